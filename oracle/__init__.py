@@ -1,0 +1,142 @@
+"""ctypes front end of the CPU oracle (oracle/dct_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The HIP library and its Python binding never
+import this package, and this package never imports them.
+
+Arrays are numpy: float32 for fp32 data, uint16 bit patterns for bf16 data
+(`as_numpy` converts a CPU torch tensor without changing a bit).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import NamedTuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dct_oracle.cpp")
+_LIB = os.path.join(_HERE, "libdct_oracle.so")
+
+F32, BF16 = 0, 1
+GE_TAU, EXACT_K = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (host code only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, u64, u32, i32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int
+        lib.oracle_select_threshold.argtypes = [vp, i32, u64, u64, vp]
+        lib.oracle_select_threshold_nth.argtypes = [vp, i32, u64, u64, vp]
+        lib.oracle_threshold_compact.argtypes = [vp, i32, u64, vp, i32, vp, vp, u64, vp]
+        lib.oracle_rowtopk_fwd.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp, vp]
+        lib.oracle_rowtopk_bwd.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp]
+        for f in (lib.oracle_select_threshold, lib.oracle_select_threshold_nth, lib.oracle_threshold_compact,
+                  lib.oracle_rowtopk_fwd, lib.oracle_rowtopk_bwd):
+            f.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+class Threshold(NamedTuple):
+    tau_key: int
+    n_gt: int
+    n_eq: int
+    tie_quota: int
+
+
+def as_numpy(t):
+    """CPU torch tensor (float32 or bfloat16) -> numpy array of the same bits."""
+    import torch
+    t = t.detach()
+    assert t.device.type == "cpu"
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def select_threshold(g: np.ndarray, k: int, method: str = "sort") -> Threshold:
+    g = np.ascontiguousarray(g)
+    assert g.ndim == 1
+    out = np.zeros(4, dtype=np.uint32)
+    fn = _load().oracle_select_threshold if method == "sort" else _load().oracle_select_threshold_nth
+    rc = fn(_ptr(g), _dtype_code(g), g.size, int(k), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle_select_threshold: invalid arguments")
+    return Threshold(*(int(v) for v in out))
+
+
+def threshold_compact(g: np.ndarray, thr: Threshold, mode: int, capacity: int | None = None):
+    """Returns (idx int32[min(count, capacity)], val[same], count)."""
+    g = np.ascontiguousarray(g)
+    assert g.ndim == 1
+    cap = g.size if capacity is None else int(capacity)
+    idx = np.full(cap, -1, dtype=np.int32)
+    val = np.zeros(cap, dtype=g.dtype)
+    count = np.zeros(1, dtype=np.uint64)
+    t = np.array(list(thr), dtype=np.uint32)
+    rc = _load().oracle_threshold_compact(_ptr(g), _dtype_code(g), g.size, _ptr(t), int(mode),
+                                          _ptr(idx), _ptr(val), cap, _ptr(count))
+    if rc != 0:
+        raise ValueError("oracle_threshold_compact: invalid arguments")
+    c = int(count[0])
+    m = min(c, cap)
+    return idx[:m], val[:m], c
+
+
+def _row_stride(x: np.ndarray) -> int:
+    assert x.ndim == 2 and x.strides[1] == x.itemsize and x.strides[0] % x.itemsize == 0
+    return x.strides[0] // x.itemsize
+
+
+def rowtopk_fwd(x: np.ndarray, k: int):
+    """x: [B, D] with unit column stride (row stride may exceed D).
+    Returns (idx int32[B,k], val[B,k], tau[B])."""
+    B, D = x.shape
+    idx = np.zeros((B, k), dtype=np.int32)
+    val = np.zeros((B, k), dtype=x.dtype)
+    tau = np.zeros(B, dtype=x.dtype)
+    rc = _load().oracle_rowtopk_fwd(_ptr(x), _dtype_code(x), B, D, _row_stride(x), int(k),
+                                    _ptr(idx), _ptr(val), _ptr(tau))
+    if rc != 0:
+        raise ValueError("oracle_rowtopk_fwd: invalid arguments")
+    return idx, val, tau
+
+
+def rowtopk_bwd(dy: np.ndarray, idx: np.ndarray):
+    B, D = dy.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    assert idx.shape[0] == B
+    k = idx.shape[1]
+    dval = np.zeros((B, k), dtype=dy.dtype)
+    rc = _load().oracle_rowtopk_bwd(_ptr(dy), _dtype_code(dy), B, D, _row_stride(dy), k, _ptr(idx), _ptr(dval))
+    if rc != 0:
+        raise ValueError(f"oracle_rowtopk_bwd: error {rc}")
+    return dval

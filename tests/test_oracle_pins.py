@@ -1,0 +1,420 @@
+"""Pins for the CPU oracle: none of the expected values below comes from the
+oracle itself or from the HIP path.
+
+  * O(N^2) rank counting on tiny inputs (every k), over random, tie-heavy and
+    special-value vectors;
+  * hand-worked fixtures of Algorithm 1 and Algorithm 2 (tests/golden/);
+  * closed forms (signed permutation of 1..N, all-equal, alternating sign);
+  * library routines on tie-free data (numpy argsort / torch.topk / kthvalue);
+  * the invariants that characterise the answer (count, tau separates kept
+    from dropped, tie rule, ascending order, bit-copied values);
+  * property tests over random sizes, k, dtypes and strides.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+from hypothesis import given, settings, strategies as st
+
+import oracle
+import synth_inputs as si
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+CPU = torch.device("cpu")
+
+
+# ------------------------------------------------------------------ helpers
+def keys_of(a: np.ndarray) -> np.ndarray:
+    """Sign-cleared bit patterns, written independently of the oracle's C++."""
+    if a.dtype == np.float32:
+        return a.view(np.uint32) & np.uint32(0x7FFFFFFF)
+    assert a.dtype == np.uint16
+    return (a & np.uint16(0x7FFF)).astype(np.uint32)
+
+
+def brute_rank(keys: np.ndarray) -> np.ndarray:
+    """rank[i] = number of positions that precede i (larger key, or equal key and
+    lower position), by counting: O(N^2)."""
+    n = keys.size
+    rank = np.zeros(n, dtype=np.int64)
+    for i in range(n):
+        c = 0
+        for j in range(n):
+            if keys[j] > keys[i] or (keys[j] == keys[i] and j < i):
+                c += 1
+        rank[i] = c
+    return rank
+
+
+def read_golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, _, rest = line.partition(":")
+            out[key.strip()] = rest.split()
+    return out
+
+
+def f32(words):
+    return np.array([float(w) for w in words], dtype=np.float32)
+
+
+def i32(words):
+    return np.array([int(w) for w in words], dtype=np.int32)
+
+
+def bits(a: np.ndarray) -> np.ndarray:
+    return a.view(np.uint32) if a.dtype == np.float32 else a.view(np.uint16)
+
+
+def to_bf16_bits(a32: np.ndarray) -> np.ndarray:
+    t = torch.from_numpy(np.ascontiguousarray(a32)).to(torch.bfloat16)
+    return oracle.as_numpy(t).copy()
+
+
+def tiny_vectors(n, seed):
+    vs = [(name, t.numpy().astype(np.float32)) for name, t in si.adversarial_vectors(n, CPU, seed)]
+    rng = np.random.default_rng(seed)
+    vs.append(("random", rng.standard_normal(n).astype(np.float32)))
+    nanv = rng.standard_normal(n).astype(np.float32)
+    if n >= 3:
+        nanv[n // 3] = np.nan
+        nanv[0] = np.inf
+    vs.append(("nan_inf", nanv))
+    return vs
+
+
+# ------------------------------------------------------------------ brute force (DP)
+@pytest.mark.parametrize("n", [1, 2, 5, 17, 40])
+def test_dp_against_rank_counting(n):
+    for name, g in tiny_vectors(n, 1000 + n):
+        for g_any in (g, to_bf16_bits(g)):
+            keys = keys_of(g_any)
+            rank = brute_rank(keys)
+            for k in range(1, n + 1):
+                exp_idx = np.nonzero(rank < k)[0]
+                tau = int(keys[np.nonzero(rank == k - 1)[0][0]])
+                thr = oracle.select_threshold(g_any, k)
+                assert thr.tau_key == tau, (name, n, k)
+                assert thr.n_gt == int((keys > tau).sum())
+                assert thr.n_eq == int((keys == tau).sum())
+                assert thr.tie_quota == k - thr.n_gt
+                assert oracle.select_threshold(g_any, k, method="nth") == thr
+                idx, val, cnt = oracle.threshold_compact(g_any, thr, oracle.EXACT_K)
+                assert cnt == k and np.array_equal(idx, exp_idx), (name, n, k)
+                assert np.array_equal(bits(val), bits(g_any[exp_idx]))
+                ge_idx = np.nonzero(keys >= tau)[0]
+                idx, val, cnt = oracle.threshold_compact(g_any, thr, oracle.GE_TAU)
+                assert cnt == ge_idx.size and np.array_equal(idx, ge_idx)
+                assert np.array_equal(bits(val), bits(g_any[ge_idx]))
+
+
+# ------------------------------------------------------------------ brute force (MP)
+@pytest.mark.parametrize("d", [1, 3, 8, 33])
+def test_mp_against_rank_counting(d):
+    B = 5
+    rng = np.random.default_rng(77 + d)
+    rows = []
+    vecs = tiny_vectors(d, 2000 + d)
+    for b in range(B):
+        rows.append(vecs[(b * 3) % len(vecs)][1])
+    x = np.stack(rows).astype(np.float32)
+    x[B - 1] = np.maximum(rng.standard_normal(d), 0).astype(np.float32)
+    dy = rng.standard_normal((B, d)).astype(np.float32)
+    for xa, dya in ((x, dy), (to_bf16_bits(x), to_bf16_bits(dy))):
+        for k in range(1, d + 1):
+            idx, val, tau = oracle.rowtopk_fwd(xa, k)
+            dval = oracle.rowtopk_bwd(dya, idx)
+            for b in range(B):
+                keys = keys_of(xa[b])
+                rank = brute_rank(keys)
+                exp = np.nonzero(rank < k)[0]
+                assert np.array_equal(idx[b], exp), (d, k, b)
+                assert np.array_equal(bits(val[b]), bits(xa[b][exp]))
+                assert int(keys_of(tau[b:b + 1])[0]) == int(keys[np.nonzero(rank == k - 1)[0][0]])
+                assert int(bits(tau[b:b + 1])[0]) == int(keys_of(tau[b:b + 1])[0])  # tau >= +0
+                assert np.array_equal(bits(dval[b]), bits(dya[b][exp]))
+
+
+# ------------------------------------------------------------------ hand-worked fixtures
+def test_golden_alg1():
+    gd = read_golden("alg1_worked.txt")
+    g = f32(gd["g"])
+    k = int(gd["k"][0])
+    thr = oracle.select_threshold(g, k)
+    tau = np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0]
+    assert tau == float(gd["tau"][0])
+    assert (thr.n_gt, thr.n_eq, thr.tie_quota) == (int(gd["n_gt"][0]), int(gd["n_eq"][0]), int(gd["tie_quota"][0]))
+    idx, val, cnt = oracle.threshold_compact(g, thr, oracle.GE_TAU)
+    assert cnt == len(gd["ge_idx"]) and np.array_equal(idx, i32(gd["ge_idx"]))
+    assert np.array_equal(bits(val), bits(f32(gd["ge_val"])))
+    idx, val, cnt = oracle.threshold_compact(g, thr, oracle.EXACT_K)
+    assert cnt == k and np.array_equal(idx, i32(gd["exact_idx"]))
+    assert np.array_equal(bits(val), bits(f32(gd["exact_val"])))
+    # same instance in bf16 (every value is exactly representable)
+    gb = to_bf16_bits(g)
+    thr_b = oracle.select_threshold(gb, k)
+    assert thr_b.tau_key == int(to_bf16_bits(np.array([1.0], dtype=np.float32))[0])
+    idx, val, cnt = oracle.threshold_compact(gb, thr_b, oracle.EXACT_K)
+    assert np.array_equal(idx, i32(gd["exact_idx"]))
+    assert np.array_equal(val, to_bf16_bits(f32(gd["exact_val"])))
+
+
+def test_golden_alg2():
+    gd = read_golden("alg2_worked.txt")
+    k = int(gd["k"][0])
+    x = np.stack([f32(gd[f"x{b}"]) for b in range(3)])
+    dy = np.stack([f32(gd[f"dy{b}"]) for b in range(3)])
+    for conv in (lambda a: a, to_bf16_bits):
+        idx, val, tau = oracle.rowtopk_fwd(conv(x), k)
+        dval = oracle.rowtopk_bwd(conv(dy), idx)
+        for b in range(3):
+            assert np.array_equal(idx[b], i32(gd[f"idx{b}"]))
+            assert np.array_equal(bits(val[b]), bits(conv(f32(gd[f"val{b}"]))))
+            assert np.array_equal(bits(dval[b]), bits(conv(f32(gd[f"dval{b}"]))))
+        assert np.array_equal(bits(tau), bits(conv(f32(gd["tau"]))))
+
+
+def test_capacity_prefix_and_zero_count():
+    gd = read_golden("alg1_worked.txt")
+    g = f32(gd["g"])
+    thr = oracle.select_threshold(g, 4)
+    idx, val, cnt = oracle.threshold_compact(g, thr, oracle.GE_TAU, capacity=2)
+    assert cnt == 5 and np.array_equal(idx, i32(gd["ge_idx"])[:2])
+    assert np.array_equal(val, f32(gd["ge_val"])[:2])
+    stale = oracle.Threshold(int(np.array([10.0], dtype=np.float32).view(np.uint32)[0]), 0, 0, 0)
+    idx, val, cnt = oracle.threshold_compact(g, stale, oracle.GE_TAU)
+    assert cnt == 0 and idx.size == 0
+
+
+def test_invalid_arguments():
+    g = np.ones(4, dtype=np.float32)
+    for k in (0, 5):
+        with pytest.raises(ValueError):
+            oracle.select_threshold(g, k)
+    with pytest.raises(ValueError):
+        oracle.rowtopk_fwd(np.ones((2, 4), dtype=np.float32), 5)
+
+
+# ------------------------------------------------------------------ closed forms
+@pytest.mark.parametrize("n,k", [(1000, 1), (1000, 10), (1000, 999), (1000, 1000), (4097, 41)])
+def test_signed_permutation_closed_form(n, k):
+    rng = np.random.default_rng(n * 7 + k)
+    mags = rng.permutation(n) + 1
+    g = (mags * rng.choice([-1, 1], n)).astype(np.float32)
+    thr = oracle.select_threshold(g, k)
+    assert np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0] == float(n - k + 1)
+    assert (thr.n_gt, thr.n_eq, thr.tie_quota) == (k - 1, 1, 1)
+    exp = np.nonzero(mags >= n - k + 1)[0]
+    for mode in (oracle.GE_TAU, oracle.EXACT_K):
+        idx, val, cnt = oracle.threshold_compact(g, thr, mode)
+        assert cnt == k and np.array_equal(idx, exp) and np.array_equal(val, g[exp])
+
+
+@pytest.mark.parametrize("value", [0.75, 0.0, -0.0])
+def test_all_equal_closed_form(value):
+    n, k = 257, 19
+    g = np.full(n, value, dtype=np.float32)
+    thr = oracle.select_threshold(g, k)
+    assert thr.tau_key == int(np.abs(g[:1]).view(np.uint32)[0])
+    assert (thr.n_gt, thr.n_eq, thr.tie_quota) == (0, n, k)
+    idx, val, cnt = oracle.threshold_compact(g, thr, oracle.EXACT_K)
+    assert cnt == k and np.array_equal(idx, np.arange(k)) and np.array_equal(bits(val), bits(g[:k]))
+    idx, _, cnt = oracle.threshold_compact(g, thr, oracle.GE_TAU)
+    assert cnt == n and np.array_equal(idx, np.arange(n))
+
+
+def test_alternating_sign_ties_resolve_by_index():
+    n, k = 64, 9
+    g = np.array([3.0 if i % 2 == 0 else -3.0 for i in range(n)], dtype=np.float32)
+    thr = oracle.select_threshold(g, k)
+    idx, val, cnt = oracle.threshold_compact(g, thr, oracle.EXACT_K)
+    assert cnt == k and np.array_equal(idx, np.arange(k)) and np.array_equal(val, g[:k])
+
+
+def test_k_equals_n_keeps_everything():
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal(513).astype(np.float32)
+    thr = oracle.select_threshold(g, g.size)
+    assert thr.tau_key == int(keys_of(g).min())
+    idx, val, cnt = oracle.threshold_compact(g, thr, oracle.EXACT_K)
+    assert cnt == g.size and np.array_equal(idx, np.arange(g.size)) and np.array_equal(bits(val), bits(g))
+
+
+# ------------------------------------------------------------------ library routines (tie-free data)
+@pytest.mark.parametrize("n,k", [(5000, 50), (65536, 656), (100003, 1)])
+def test_dp_against_library_on_distinct_magnitudes(n, k):
+    rng = np.random.default_rng(n + k)
+    g = rng.standard_normal(n + n // 8).astype(np.float32)
+    _, first = np.unique(np.abs(g), return_index=True)  # drop repeated magnitudes: tie-free data,
+    g = g[np.sort(first)[:n]]                           # so the library's tie order is irrelevant
+    mag = np.abs(g)
+    assert g.size == n and np.unique(mag).size == n
+    order = np.argsort(-mag.astype(np.float64), kind="stable")
+    exp = np.sort(order[:k])
+    thr = oracle.select_threshold(g, k)
+    tau = np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0]
+    assert tau == mag[order[k - 1]]
+    assert tau == torch.kthvalue(torch.from_numpy(mag), n - k + 1).values.item()
+    idx, val, cnt = oracle.threshold_compact(g, thr, oracle.EXACT_K)
+    assert cnt == k and np.array_equal(idx, exp) and np.array_equal(val, g[exp])
+    top = torch.topk(torch.from_numpy(mag), k).indices.numpy()
+    assert np.array_equal(np.sort(top), idx)
+
+
+def test_mp_against_library_on_distinct_magnitudes():
+    rng = np.random.default_rng(11)
+    B, D, k = 64, 300, 15
+    x = rng.standard_normal((B, D)).astype(np.float32)
+    dy = rng.standard_normal((B, D)).astype(np.float32)
+    assert all(np.unique(np.abs(r)).size == D for r in x)
+    idx, val, tau = oracle.rowtopk_fwd(x, k)
+    top = torch.topk(torch.from_numpy(np.abs(x)), k, dim=1)
+    exp = np.sort(top.indices.numpy(), axis=1)
+    assert np.array_equal(idx, exp)
+    assert np.array_equal(val, np.take_along_axis(x, exp, axis=1))
+    assert np.array_equal(tau, top.values.numpy()[:, -1])
+    dval = oracle.rowtopk_bwd(dy, idx)
+    assert np.array_equal(dval, dy[np.arange(B)[:, None], exp])
+
+
+def test_mp_row_stride():
+    rng = np.random.default_rng(12)
+    B, D, S, k = 7, 50, 64, 5
+    buf = np.full((B, S), 1e4, dtype=np.float32)
+    buf[:, :D] = rng.standard_normal((B, D)).astype(np.float32)
+    x = buf[:, :D]
+    idx, val, tau = oracle.rowtopk_fwd(x, k)
+    idx2, val2, tau2 = oracle.rowtopk_fwd(np.ascontiguousarray(x), k)
+    assert np.array_equal(idx, idx2) and np.array_equal(val, val2) and np.array_equal(tau, tau2)
+    assert np.array_equal(oracle.rowtopk_bwd(x, idx), val)
+
+
+# ------------------------------------------------------------------ invariants as properties
+def check_dp_invariants(g, k, thr, idx, val, cnt, mode):
+    keys = keys_of(g)
+    tau = thr.tau_key
+    assert np.all(np.diff(idx.astype(np.int64)) > 0)
+    assert np.array_equal(bits(val), bits(g[idx]))
+    kept = np.zeros(g.size, dtype=bool)
+    kept[idx] = True
+    assert np.all(keys[kept] >= tau) and np.all(keys[~kept] <= tau)
+    assert thr.n_gt == int((keys > tau).sum()) and thr.n_eq == int((keys == tau).sum())
+    assert 1 <= thr.tie_quota <= thr.n_eq and thr.tie_quota == k - thr.n_gt
+    if mode == oracle.EXACT_K:
+        assert cnt == k == idx.size
+        ties = np.nonzero(keys == tau)[0]
+        assert np.array_equal(np.nonzero(kept & (keys == tau))[0], ties[:thr.tie_quota])
+    else:
+        assert cnt == thr.n_gt + thr.n_eq == idx.size == int((keys >= tau).sum())
+
+
+@settings(max_examples=120, deadline=None)
+@given(n=st.integers(1, 3000), frac=st.floats(0.0, 1.0), levels=st.sampled_from([0, 2, 3, 17, 1000]),
+       seed=st.integers(0, 2 ** 31), bf16=st.booleans())
+def test_dp_invariants_property(n, frac, levels, seed, bf16):
+    rng = np.random.default_rng(seed)
+    g = rng.standard_normal(n).astype(np.float32)
+    if levels:
+        g = (np.round(g * levels / 3.0) * (3.0 / levels)).astype(np.float32)  # few distinct magnitudes
+    ga = to_bf16_bits(g) if bf16 else g
+    k = min(n, max(1, int(round(frac * n))))
+    thr = oracle.select_threshold(ga, k)
+    for mode in (oracle.GE_TAU, oracle.EXACT_K):
+        idx, val, cnt = oracle.threshold_compact(ga, thr, mode)
+        check_dp_invariants(ga, k, thr, idx, val, cnt, mode)
+    if thr.n_eq == thr.tie_quota:
+        a = oracle.threshold_compact(ga, thr, oracle.GE_TAU)
+        b = oracle.threshold_compact(ga, thr, oracle.EXACT_K)
+        assert np.array_equal(a[0], b[0]) and a[2] == b[2]
+
+
+@settings(max_examples=80, deadline=None)
+@given(B=st.integers(1, 12), D=st.integers(1, 400), frac=st.floats(0.0, 1.0), pad=st.integers(0, 9),
+       seed=st.integers(0, 2 ** 31), bf16=st.booleans(), relu=st.booleans())
+def test_mp_invariants_property(B, D, frac, pad, seed, bf16, relu):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((B, D + pad)).astype(np.float32)
+    if relu:
+        x = np.maximum(x, 0)
+    dy = rng.standard_normal((B, D + pad)).astype(np.float32)
+    xa = (to_bf16_bits(x) if bf16 else x)[:, :D]
+    dya = (to_bf16_bits(dy) if bf16 else dy)[:, :D]
+    k = min(D, max(1, int(round(frac * D))))
+    idx, val, tau = oracle.rowtopk_fwd(xa, k)
+    dval = oracle.rowtopk_bwd(dya, idx)
+    assert idx.shape == (B, k)
+    for b in range(B):
+        keys = keys_of(np.ascontiguousarray(xa[b]))
+        t = int(keys_of(tau[b:b + 1])[0])
+        assert np.all(np.diff(idx[b].astype(np.int64)) > 0) and idx[b].min() >= 0 and idx[b].max() < D
+        kept = np.zeros(D, dtype=bool)
+        kept[idx[b]] = True
+        assert np.all(keys[kept] >= t) and np.all(keys[~kept] <= t) and t in keys[kept]
+        ties = np.nonzero(keys == t)[0]
+        quota = k - int((keys > t).sum())
+        assert np.array_equal(np.nonzero(kept & (keys == t))[0], ties[:quota])
+        assert np.array_equal(bits(val[b]), bits(np.ascontiguousarray(xa[b])[idx[b]]))
+        assert np.array_equal(bits(dval[b]), bits(np.ascontiguousarray(dya[b])[idx[b]]))
+
+
+# ------------------------------------------------------------------ generators + k: statistical sanity
+def test_keep_counts():
+    assert si.C1_K == 10486 and si.C2_K == 51 and si.C3_K == 25000
+    assert si.C4_K == 1342178 and si.C4_NZ_ROWS == 209715 and si.C5_K == 204
+    assert si.C1_N - (si.C1_N * 99) // 100 == si.C1_K  # N - floor(N*eta), eta = 0.99 (Algorithm 1)
+
+
+def tau_value(thr):
+    return float(np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0])
+
+
+def test_c1_threshold_is_the_normal_quantile():
+    g, k = si.config_c1(CPU)
+    thr = oracle.select_threshold(g.numpy(), k)
+    assert abs(tau_value(thr) / 2.5758e-3 - 1) < 0.02  # two-sided 1 % point of N(0, 1e-3^2)
+    idx, _, cnt = oracle.threshold_compact(g.numpy(), thr, oracle.EXACT_K)
+    assert cnt == k
+
+
+def test_c3_threshold_is_the_student_t_quantile_and_reuse_counts_fluctuate():
+    n = 1_000_000  # c3's distribution at a size the CPU suite affords
+    k = si.ceil_frac(n, 1, 1000)
+    g0 = si.config_c3_draw(CPU, 0, n).numpy()
+    thr = oracle.select_threshold(g0, k)
+    assert abs(tau_value(thr) / 12.92e-3 - 1) < 0.08  # two-sided 0.1 % point of t(3) * 1e-3
+    g1 = si.config_c3_draw(CPU, 1, n).numpy()
+    assert not np.array_equal(g0, g1)
+    _, _, cnt = oracle.threshold_compact(g1, thr, oracle.GE_TAU)
+    assert cnt != k and abs(cnt - k) < 6 * (k ** 0.5) * 2  # stale tau: count near k, not equal
+
+
+def test_c4_structure_and_quantile():
+    rows = 1 << 16
+    g, k = si.config_c4(CPU, rows)
+    t = g.view(rows, si.C4_DIM)
+    nz_rows = (t != 0).any(dim=1).sum().item()
+    assert nz_rows == (rows * 5) // 100
+    assert (t == 0).all(dim=1).sum().item() == rows - nz_rows
+    thr = oracle.select_threshold(g.numpy(), k)
+    assert abs(tau_value(thr) / 1.645 - 1) < 0.03  # keeps 10 % of the non-zeros of N(0,1)
+
+
+def test_c2_c5_shape_sanity():
+    x, dy, k = si.config_c2(CPU)
+    assert x.shape == (si.C2_B, si.C2_D) and abs((x == 0).float().mean().item() - 0.5) < 0.01
+    _, _, tau = oracle.rowtopk_fwd(x.numpy()[:256], k)
+    assert abs(tau.mean() / 1.64 - 1) < 0.05  # 10 % point of the half-normal non-zeros
+    xb, dyb, kb = si.config_c5(CPU, b=64)
+    assert xb.dtype == torch.bfloat16 and xb.shape == (64, si.C5_D) and kb == 204
+    idx, val, taub = oracle.rowtopk_fwd(oracle.as_numpy(xb), kb)
+    tau_f = torch.from_numpy(taub.view(np.int16)).view(torch.bfloat16).float()
+    assert abs(tau_f.mean().item() / 1.64 - 1) < 0.05
+    # bf16 makes ties at tau the normal case
+    keys = keys_of(oracle.as_numpy(xb))
+    n_eq = [(keys[b] == (int(taub[b]) & 0x7FFF)).sum() for b in range(64)]
+    assert np.mean(n_eq) > 1.5
