@@ -1,0 +1,149 @@
+/* dct.h -- C ABI of libdct: the hard-thresholding hot path of Dynamic
+ * Communication Thresholding (DCT) on one MI355X (gfx950).
+ *
+ * Everything a worker does to its own data before anything goes on the wire:
+ *   DCT-DP (Algorithm 1): pick the magnitude threshold tau as the k-th largest
+ *   |W_grad| every L iterations, and every iteration keep the entries with
+ *   |W_grad| >= tau, emitted as (index, value) pairs;
+ *   DCT-MP (Algorithm 2): per sample (row) keep the k largest |X_act|, and in the
+ *   backward pass pass X_grad through the same mask.
+ * The network transfer, the parameter server and the error-feedback update are
+ * not part of this library.
+ *
+ * Conventions shared by every call
+ *   - Pointers named d_* (and g, x, dy) are DEVICE pointers on the current HIP
+ *     device; nothing is copied to or from the host.  Inputs are never modified.
+ *   - The library allocates no device memory.  The caller owns every buffer,
+ *     including workspaces (sizes from the *_workspace_bytes queries).
+ *   - Every call only enqueues kernels on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and returns without synchronising.
+ *   - Return value: a dct_status.  Argument errors are detected on the host and
+ *     nothing is enqueued.  No C++ type or exception crosses this boundary.
+ *   - Magnitude order is the unsigned order of key(x) = bit pattern of x with the
+ *     sign bit cleared (31 bits for fp32, 15 bits for bf16).  For non-NaN x this
+ *     is the order of |x|; -0 and +0 are equal; denormals are ordered exactly;
+ *     NaNs rank above infinity (deterministic, not meaningful).
+ *   - Position i precedes j when key[i] > key[j], or the keys are equal and
+ *     i < j: ties go to the lower index.
+ *   - Indices are 0-based int32; survivors are emitted in ascending index order
+ *     and values are copied bit for bit.
+ */
+#ifndef DCT_H_
+#define DCT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DCT_OK = 0,
+  DCT_ERR_INVALID = 1,   /* bad argument (null, zero size, k out of range, misaligned, ...) */
+  DCT_ERR_WORKSPACE = 2, /* workspace pointer null, misaligned or too small                 */
+  DCT_ERR_OVERFLOW = 3,  /* reported by the Python binding when count > capacity            */
+  DCT_ERR_HIP = 4        /* a kernel launch failed                                          */
+} dct_status;
+
+typedef enum { DCT_F32 = 0, DCT_BF16 = 1 } dct_dtype;
+
+typedef enum {
+  DCT_GE_TAU = 0, /* the mask of Algorithm 1: keep every key >= tau_key (count varies)      */
+  DCT_EXACT_K = 1 /* keep key > tau_key plus the tie_quota lowest-index entries with
+                     key == tau_key: exactly k survivors on the vector tau was selected on  */
+} dct_mode;
+
+/* The threshold carried from a select iteration to the following reuse
+ * iterations (Algorithm 1, "use tau from iteration k-1").  Lives in DEVICE
+ * memory, 16 bytes, 16-byte aligned, caller-owned. */
+typedef struct {
+  uint32_t tau_key;   /* key of the k-th largest magnitude; always the key of an input element */
+  uint32_t n_gt;      /* #{ i : key[i] >  tau_key }                                          */
+  uint32_t n_eq;      /* #{ i : key[i] == tau_key }                                          */
+  uint32_t tie_quota; /* k - n_gt, in [1, n_eq]                                              */
+} dct_threshold;
+
+/* Sentinel written to *d_count_out when dct_threshold_compact finds its
+ * workspace uninitialised or corrupted (no survivor is written in that case). */
+#define DCT_COUNT_WORKSPACE_ERROR UINT64_MAX
+
+/* ---------------------------------------------------------------- DCT-DP ---
+ * Algorithm 1, threshold selection ("sort |W_grad|; tau = w_floor(N*eta)"),
+ * computed exactly without sorting or copying the gradient: a radix select over
+ * the key bits with LDS histograms.  The caller passes the integer number of
+ * entries to keep, k (for a sparsity factor eta that is N - floor(N*eta)).
+ *
+ *   g          device, n elements of `dt`, contiguous, aligned to the element size
+ *   n          1 .. 2^31-1            k   1 .. n
+ *   d_thr_out  device, receives the dct_threshold
+ *   d_ws       device workspace of at least dct_select_threshold_workspace_bytes,
+ *              256-byte aligned; contents on entry are irrelevant, it is scratch
+ */
+size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n);
+int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,
+                         void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* Algorithm 1, mask and compressed gradient ("M = I(|W_grad| >= tau)",
+ * "W_hat = W_grad . M"), fused with an ordered stream compaction: one pass over
+ * g, survivors written as idx[j] (ascending) and val[j] = g[idx[j]].
+ *
+ *   d_thr        device, threshold from dct_select_threshold (possibly of an
+ *                earlier iteration: the reuse iterations of Algorithm 1)
+ *   mode         DCT_GE_TAU or DCT_EXACT_K
+ *   d_idx_out    device int32[capacity]     d_val_out  device dt[capacity]
+ *   capacity     pairs the outputs can hold (may be 0).  If more entries survive,
+ *                only the first `capacity` in index order are written and the TRUE
+ *                count is still reported; nothing is written out of bounds.
+ *   d_count_out  device uint64, receives the survivor count (8-byte aligned)
+ *   d_ws         device workspace of dct_threshold_compact_workspace_bytes,
+ *                256-byte aligned, that was initialised ONCE with
+ *                dct_threshold_compact_workspace_init.  Each call leaves it
+ *                initialised again, so it can be reused call after call on the same
+ *                stream.  Two calls that share a workspace must not overlap.
+ */
+size_t dct_threshold_compact_workspace_bytes(int dt, uint64_t n);
+int dct_threshold_compact_workspace_init(void* d_ws, size_t ws_bytes, void* hip_stream);
+int dct_threshold_compact(const void* g, int dt, uint64_t n, const dct_threshold* d_thr, int mode,
+                          int32_t* d_idx_out, void* d_val_out, uint64_t capacity, uint64_t* d_count_out,
+                          void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------- DCT-MP ---
+ * Algorithm 2, forward pass: for every row of X_act the k entries that come
+ * first in the magnitude order (exactly k per row, ties to the lower column,
+ * rows with fewer than k non-zeros are filled with their lowest-column zeros),
+ * written in ascending column order.  This is the row's mask m_i as indices plus
+ * the compressed row X_act,i . m_i.
+ *
+ *   x           device, B rows of D elements of `dt`, unit column stride,
+ *               row_stride_elems >= D elements between rows
+ *   k           1 .. D
+ *   d_idx_out   device int32[B*k] (column indices)   d_val_out  device dt[B*k]
+ *   d_tau_out   device dt[B] or NULL: tau_i = magnitude of the k-th entry of row i
+ */
+int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
+                    int32_t* d_idx_out, void* d_val_out, void* d_tau_out, void* hip_stream);
+
+/* Algorithm 2, backward pass ("X_grad . M" with the mask of the forward pass):
+ * dval[b, j] = dy[b, idx[b, j]].  No new selection takes place.  An index
+ * outside [0, D) is not dereferenced; its output element is set to zero.
+ */
+int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
+                    const int32_t* d_idx, void* d_dval_out, void* hip_stream);
+
+/* ------------------------------------------------------------ measurement ---
+ * Plain streaming kernels used by the benchmark to measure the achievable HBM
+ * rate next to the DCT kernels (not part of the method).
+ *   dct_probe_read: sums `bytes` (multiple of 16, 16-byte aligned) as uint32 words,
+ *                   writes one uint32 per workgroup into d_sink (>= 16384 bytes).
+ *   dct_probe_copy: copies `bytes` (multiple of 16) from d_src to d_dst.
+ */
+int dct_probe_read(const void* d_src, size_t bytes, void* d_sink, void* hip_stream);
+int dct_probe_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream);
+
+const char* dct_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCT_H_ */

@@ -1,0 +1,214 @@
+"""ctypes binding of libdct.so: same names as the C ABI, argument marshalling only.
+
+Tensors must be CUDA (HIP) tensors; kernels are enqueued on torch's current
+stream.  There is no CPU fallback: if the library is missing or cannot be
+loaded, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple
+
+import torch
+
+from . import build as _build
+
+DCT_OK, DCT_ERR_INVALID, DCT_ERR_WORKSPACE, DCT_ERR_OVERFLOW, DCT_ERR_HIP = range(5)
+DCT_F32, DCT_BF16 = 0, 1
+DCT_GE_TAU, DCT_EXACT_K = 0, 1
+COUNT_WORKSPACE_ERROR = (1 << 64) - 1
+
+_EXPORTS = {
+    # name: (restype, argtypes)
+    "dct_select_threshold_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64]),
+    "dct_select_threshold": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
+                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "dct_threshold_compact_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64]),
+    "dct_threshold_compact_workspace_init": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "dct_threshold_compact": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_void_p,
+                                             ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "dct_rowtopk_fwd": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
+                                       ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.c_void_p]),
+    "dct_rowtopk_bwd": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
+                                       ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p]),
+    "dct_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
+    "dct_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "dct_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+}
+
+_lib = None
+
+
+class DctError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {dct_status_string(status)}")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libdct.so (building it only if no built library is present)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build_library(force=True)
+        handle = ctypes.CDLL(_build.LIB)
+        for name, (res, args) in _EXPORTS.items():
+            fn = getattr(handle, name)  # AttributeError if the library lacks an entry point
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def dct_status_string(status: int) -> str:
+    return lib().dct_status_string(int(status)).decode()
+
+
+class Threshold(NamedTuple):
+    tau_key: int
+    n_gt: int
+    n_eq: int
+    tie_quota: int
+
+
+def _check(status: int, where: str):
+    if status != DCT_OK:
+        raise DctError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DCT_F32
+    if t.dtype == torch.bfloat16:
+        return DCT_BF16
+    raise TypeError(f"libdct takes float32 or bfloat16 tensors, got {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    return t.data_ptr()
+
+
+def _flat(t: torch.Tensor, name: str) -> int:
+    if t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1):
+        raise ValueError(f"{name} must be a contiguous 1-D tensor")
+    return _dev(t, name)
+
+
+def _rows(t: torch.Tensor, name: str):
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with unit column stride")
+    stride = t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+    return _dev(t, name), t.shape[0], t.shape[1], stride
+
+
+# ------------------------------------------------------------------ workspaces
+def dct_select_threshold_workspace_bytes(dt: int, n: int) -> int:
+    return lib().dct_select_threshold_workspace_bytes(dt, n)
+
+
+def dct_threshold_compact_workspace_bytes(dt: int, n: int) -> int:
+    return lib().dct_threshold_compact_workspace_bytes(dt, n)
+
+
+def new_select_workspace(g: torch.Tensor) -> torch.Tensor:
+    nbytes = dct_select_threshold_workspace_bytes(_dt(g), g.numel())
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=g.device)
+
+
+def dct_threshold_compact_workspace_init(ws: torch.Tensor) -> None:
+    _check(lib().dct_threshold_compact_workspace_init(_dev(ws, "ws"), ws.numel() * ws.element_size(), _stream()),
+           "dct_threshold_compact_workspace_init")
+
+
+def new_compact_workspace(g: torch.Tensor) -> torch.Tensor:
+    nbytes = dct_threshold_compact_workspace_bytes(_dt(g), g.numel())
+    ws = torch.empty(max(nbytes, 512), dtype=torch.uint8, device=g.device)
+    dct_threshold_compact_workspace_init(ws)
+    return ws
+
+
+# ------------------------------------------------------------------ DCT-DP
+def dct_select_threshold(g: torch.Tensor, k: int, thr_out: torch.Tensor, ws: torch.Tensor) -> None:
+    """thr_out: int32[4] device tensor receiving {tau_key, n_gt, n_eq, tie_quota}."""
+    _check(lib().dct_select_threshold(_flat(g, "g"), _dt(g), g.numel(), int(k), _dev(thr_out, "thr_out"),
+                                      _dev(ws, "ws"), ws.numel() * ws.element_size(), _stream()),
+           "dct_select_threshold")
+
+
+def dct_threshold_compact(g: torch.Tensor, thr: torch.Tensor, mode: int, idx_out: torch.Tensor,
+                          val_out: torch.Tensor, count_out: torch.Tensor, ws: torch.Tensor,
+                          capacity: int | None = None) -> None:
+    """idx_out int32[capacity], val_out g.dtype[capacity], count_out int64[1]; all device tensors."""
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > min(idx_out.numel(), val_out.numel()):
+        raise ValueError("capacity exceeds the output tensors")
+    if idx_out.dtype != torch.int32 or val_out.dtype != g.dtype or count_out.dtype != torch.int64:
+        raise TypeError("idx_out must be int32, val_out must match g, count_out must be int64")
+    _check(lib().dct_threshold_compact(_flat(g, "g"), _dt(g), g.numel(), _dev(thr, "thr"), int(mode),
+                                       _flat(idx_out, "idx_out") if cap else None,
+                                       _flat(val_out, "val_out") if cap else None, cap,
+                                       _dev(count_out, "count_out"), _dev(ws, "ws"),
+                                       ws.numel() * ws.element_size(), _stream()),
+           "dct_threshold_compact")
+
+
+def read_threshold(thr: torch.Tensor) -> Threshold:
+    """Synchronising host copy of a device dct_threshold."""
+    v = thr.cpu().tolist()
+    return Threshold(*(x & 0xFFFFFFFF for x in v))
+
+
+def read_count(count_out: torch.Tensor, capacity: int | None = None) -> int:
+    """Synchronising read of the survivor count; raises on a workspace error or,
+    when `capacity` is given, on overflow."""
+    c = int(count_out.cpu().item()) & ((1 << 64) - 1)
+    if c == COUNT_WORKSPACE_ERROR:
+        raise DctError(DCT_ERR_WORKSPACE, "dct_threshold_compact")
+    if capacity is not None and c > capacity:
+        raise DctError(DCT_ERR_OVERFLOW, f"dct_threshold_compact (count {c} > capacity {capacity})")
+    return c
+
+
+# ------------------------------------------------------------------ DCT-MP
+def dct_rowtopk_fwd(x: torch.Tensor, k: int, idx_out: torch.Tensor, val_out: torch.Tensor,
+                    tau_out: torch.Tensor | None = None) -> None:
+    ptr, B, D, stride = _rows(x, "x")
+    if idx_out.dtype != torch.int32 or val_out.dtype != x.dtype or not idx_out.is_contiguous() \
+            or not val_out.is_contiguous() or idx_out.numel() != B * k or val_out.numel() != B * k:
+        raise ValueError("idx_out / val_out must be contiguous [B, k] int32 / x.dtype tensors")
+    if tau_out is not None and (tau_out.dtype != x.dtype or tau_out.numel() != B or not tau_out.is_contiguous()):
+        raise ValueError("tau_out must be a contiguous [B] tensor of x.dtype")
+    _check(lib().dct_rowtopk_fwd(ptr, _dt(x), B, D, stride, int(k), _dev(idx_out, "idx_out"),
+                                 _dev(val_out, "val_out"), _dev(tau_out, "tau_out") if tau_out is not None else None,
+                                 _stream()), "dct_rowtopk_fwd")
+
+
+def dct_rowtopk_bwd(dy: torch.Tensor, idx: torch.Tensor, dval_out: torch.Tensor) -> None:
+    ptr, B, D, stride = _rows(dy, "dy")
+    if idx.dtype != torch.int32 or idx.dim() != 2 or idx.shape[0] != B or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous int32 [B, k] tensor")
+    k = idx.shape[1]
+    if dval_out.dtype != dy.dtype or dval_out.numel() != B * k or not dval_out.is_contiguous():
+        raise ValueError("dval_out must be a contiguous [B, k] tensor of dy.dtype")
+    _check(lib().dct_rowtopk_bwd(ptr, _dt(dy), B, D, stride, k, _dev(idx, "idx"), _dev(dval_out, "dval_out"),
+                                 _stream()), "dct_rowtopk_bwd")
+
+
+# ------------------------------------------------------------------ measurement helpers
+def dct_probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    _check(lib().dct_probe_read(_dev(src, "src"), src.numel() * src.element_size(), _dev(sink, "sink"), _stream()),
+           "dct_probe_read")
+
+
+def dct_probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    _check(lib().dct_probe_copy(_dev(dst, "dst"), _dev(src, "src"), src.numel() * src.element_size(), _stream()),
+           "dct_probe_copy")

@@ -1,0 +1,82 @@
+// Shared device/host helpers of libdct (gfx950 only, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dct.h"
+
+namespace dct {
+
+constexpr int kWave = 64;
+
+// Element traits: storage word, elements per 16-byte vector, key extraction.
+// key(x) = bit pattern with the sign bit cleared; unsigned order on keys is the
+// magnitude order used by Algorithm 1 ("sort |W_grad|") and Algorithm 2.
+template <int DT>
+struct Elem;
+
+template <>
+struct Elem<DCT_F32> {
+  using word_t = uint32_t;
+  static constexpr int kVec = 4;
+  static constexpr int kKeyBits = 31;
+  static constexpr uint32_t kKeyMask = 0x7FFFFFFFu;
+  __device__ static __forceinline__ uint32_t raw(const uint4& v, int e) {
+    return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+  }
+};
+
+template <>
+struct Elem<DCT_BF16> {
+  using word_t = uint16_t;
+  static constexpr int kVec = 8;
+  static constexpr int kKeyBits = 15;
+  static constexpr uint32_t kKeyMask = 0x7FFFu;
+  __device__ static __forceinline__ uint32_t raw(const uint4& v, int e) {
+    const uint32_t w = (e >> 1) == 0 ? v.x : (e >> 1) == 1 ? v.y : (e >> 1) == 2 ? v.z : v.w;
+    return (e & 1) ? (w >> 16) : (w & 0xFFFFu);
+  }
+};
+
+__device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
+
+// Number of set bits of `m` in lanes below the calling lane.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u));
+}
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
+  return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
+  return v;
+}
+
+// Agent-scope relaxed accesses for words that other workgroups poll or update.
+__device__ __forceinline__ uint64_t ld_agent(const uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? DCT_OK : DCT_ERR_HIP; }
+
+}  // namespace dct

@@ -1,0 +1,93 @@
+// Plain streaming kernels for the benchmark's "achievable HBM rate" lines and for
+// scaling the rocprof byte counters against a transfer of known size, plus the
+// status strings.  Not part of the method.
+#include "dct_common.hpp"
+
+namespace dct {
+namespace {
+
+constexpr int kPrThreads = 256;
+constexpr int kPrUnroll = 8;
+constexpr uint32_t kPrMaxGrid = 4096;
+
+__global__ __launch_bounds__(kPrThreads) void probe_read_kernel(const uint4* __restrict__ src, uint64_t n_vec,
+                                                                uint32_t* __restrict__ sink) {
+  uint32_t acc = 0;
+  const uint64_t span = static_cast<uint64_t>(kPrThreads) * kPrUnroll;
+  for (uint64_t base = blockIdx.x * span; base < n_vec; base += gridDim.x * span) {
+    uint4 v[kPrUnroll];
+#pragma unroll
+    for (int u = 0; u < kPrUnroll; ++u) {
+      const uint64_t i = base + static_cast<uint64_t>(u) * kPrThreads + threadIdx.x;
+      v[u] = i < n_vec ? src[i] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < kPrUnroll; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  acc = wave_sum_u32(acc);
+  __shared__ uint32_t s[kPrThreads / kWave];
+  if (lane_id() == 0) s[threadIdx.x / kWave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = s[0] + s[1] + s[2] + s[3];
+}
+
+__global__ __launch_bounds__(kPrThreads) void probe_copy_kernel(uint4* __restrict__ dst,
+                                                                const uint4* __restrict__ src, uint64_t n_vec) {
+  const uint64_t span = static_cast<uint64_t>(kPrThreads) * kPrUnroll;
+  for (uint64_t base = blockIdx.x * span; base < n_vec; base += gridDim.x * span) {
+    uint4 v[kPrUnroll];
+#pragma unroll
+    for (int u = 0; u < kPrUnroll; ++u) {
+      const uint64_t i = base + static_cast<uint64_t>(u) * kPrThreads + threadIdx.x;
+      if (i < n_vec) v[u] = src[i];
+    }
+#pragma unroll
+    for (int u = 0; u < kPrUnroll; ++u) {
+      const uint64_t i = base + static_cast<uint64_t>(u) * kPrThreads + threadIdx.x;
+      if (i < n_vec) dst[i] = v[u];
+    }
+  }
+}
+
+uint32_t probe_grid(uint64_t n_vec) {
+  const uint64_t span = static_cast<uint64_t>(kPrThreads) * kPrUnroll;
+  uint64_t g = (n_vec + span - 1) / span;
+  if (g > kPrMaxGrid) g = kPrMaxGrid;
+  return g ? static_cast<uint32_t>(g) : 1u;
+}
+
+}  // namespace
+}  // namespace dct
+
+using namespace dct;
+
+extern "C" int dct_probe_read(const void* d_src, size_t bytes, void* d_sink, void* hip_stream) {
+  if (!d_src || !d_sink || bytes == 0 || (bytes & 15) || !is_aligned(d_src, 16) || !is_aligned(d_sink, 4))
+    return DCT_ERR_INVALID;
+  const uint64_t n_vec = bytes / 16;
+  hipLaunchKernelGGL(probe_read_kernel, dim3(probe_grid(n_vec)), dim3(kPrThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<const uint4*>(d_src), n_vec,
+                     static_cast<uint32_t*>(d_sink));
+  return launch_status();
+}
+
+extern "C" int dct_probe_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream) {
+  if (!d_src || !d_dst || bytes == 0 || (bytes & 15) || !is_aligned(d_src, 16) || !is_aligned(d_dst, 16))
+    return DCT_ERR_INVALID;
+  const uint64_t n_vec = bytes / 16;
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(probe_grid(n_vec)), dim3(kPrThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<uint4*>(d_dst),
+                     static_cast<const uint4*>(d_src), n_vec);
+  return launch_status();
+}
+
+extern "C" const char* dct_status_string(int status) {
+  switch (status) {
+    case DCT_OK: return "DCT_OK";
+    case DCT_ERR_INVALID: return "DCT_ERR_INVALID: bad argument";
+    case DCT_ERR_WORKSPACE: return "DCT_ERR_WORKSPACE: workspace null, misaligned, too small or uninitialised";
+    case DCT_ERR_OVERFLOW: return "DCT_ERR_OVERFLOW: more survivors than the output capacity";
+    case DCT_ERR_HIP: return "DCT_ERR_HIP: kernel launch failed";
+    default: return "unknown dct_status";
+  }
+}

@@ -1,0 +1,198 @@
+// dct_rowtopk_fwd / dct_rowtopk_bwd: Algorithm 2.  Forward: per sample (row of
+// X_act) the k largest magnitudes, i.e. the mask m_i = I(|X_act,i| >= tau_i)
+// made exactly k wide (ties to the lower column), emitted as ascending column
+// indices plus the selected values.  Backward: X_grad through the same mask,
+// which is a gather of dy at the forward indices (no new selection: Sec. 2.2,
+// "the same mask is used").
+#include "dct_common.hpp"
+
+namespace dct {
+namespace {
+
+constexpr int kRtThreads = 256;
+constexpr int kRtWaves = kRtThreads / kWave;
+constexpr int kRtBins = 2048;
+
+// ---------------------------------------------------------------------------
+// Generic forward kernel: one wavefront per row, any D, any row stride, rows
+// read from memory once per radix pass (digits 11+11+9 for fp32, 8+7 for bf16)
+// plus once for the ordered emit.  Wave-synchronous: no workgroup barrier.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digit) {
+  const uint64_t act = ballot64(active);
+  if (act == 0) return;
+  const int leader = __builtin_ctzll(act);
+  const uint32_t d0 = __shfl(digit, leader, kWave);
+  const bool same = active && digit == d0;
+  const uint64_t m = ballot64(same);
+  if (static_cast<int>(lane_id()) == leader) atomicAdd(&h[d0], static_cast<uint32_t>(__popcll(m)));
+  if (active && !same) atomicAdd(&h[digit], 1u);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kRtThreads) void rowtopk_fwd_generic_kernel(
+    const typename Elem<DT>::word_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k,
+    int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out,
+    typename Elem<DT>::word_t* __restrict__ tau_out) {
+  using E = Elem<DT>;
+  __shared__ uint32_t s_hist[kRtWaves][kRtBins];
+  const int wave = threadIdx.x / kWave;
+  const uint32_t lane = lane_id();
+  constexpr int kPasses = DT == DCT_F32 ? 3 : 2;
+  constexpr int kShift[3] = {DT == DCT_F32 ? 20 : 7, DT == DCT_F32 ? 9 : 0, 0};
+  constexpr int kWidth[3] = {DT == DCT_F32 ? 11 : 8, DT == DCT_F32 ? 11 : 7, 9};
+  constexpr int kPer = kRtBins / kWave;  // bins per lane in the scan
+  uint32_t* h = s_hist[wave];
+
+  for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * kRtWaves + wave; row < B;
+       row += static_cast<uint64_t>(gridDim.x) * kRtWaves) {
+    const typename E::word_t* xr = x + row * stride;
+    uint32_t prefix = 0, k_rem = k, fixed_mask = 0;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int shift = kShift[p], width = kWidth[p];
+      const uint32_t dmask = (1u << width) - 1u;
+      for (int i = lane; i < kRtBins; i += kWave) h[i] = 0;
+      wave_lds_sync();
+      for (uint32_t c0 = 0; c0 < D; c0 += kWave) {
+        const uint32_t c = c0 + lane;
+        const bool in = c < D;
+        const uint32_t key = in ? (static_cast<uint32_t>(xr[c]) & E::kKeyMask) : 0u;
+        hist_add(h, in && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+      }
+      wave_lds_sync();
+      // lane L owns bins 2047-32L ... 2047-32L-31 (top down)
+      uint32_t sum = 0;
+      for (int j = 0; j < kPer; ++j) sum += h[kRtBins - 1 - (lane * kPer + j)];
+      uint32_t incl = sum;
+#pragma unroll
+      for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t t = __shfl_up(incl, d, kWave);
+        if (lane >= static_cast<uint32_t>(d)) incl += t;
+      }
+      uint32_t above = incl - sum;
+      const bool mine = above < k_rem && k_rem <= incl;
+      uint32_t f_bin = 0, f_above = 0;
+      if (mine) {
+        bool found = false;
+        for (int j = 0; j < kPer; ++j) {
+          const uint32_t cj = h[kRtBins - 1 - (lane * kPer + j)];
+          if (!found && above < k_rem && k_rem <= above + cj) {
+            f_bin = kRtBins - 1 - (lane * kPer + j);
+            f_above = above;
+            found = true;
+          }
+          if (!found) above += cj;
+        }
+      }
+      const int src = __builtin_ctzll(ballot64(mine));
+      f_bin = __shfl(f_bin, src, kWave);
+      f_above = __shfl(f_above, src, kWave);
+      prefix |= f_bin << shift;
+      k_rem -= f_above;
+      fixed_mask |= dmask << shift;
+      wave_lds_sync();
+    }
+    const uint32_t tau = prefix;  // key of the k-th largest magnitude of the row
+    const uint32_t quota = k_rem; // ties at tau to keep, lowest columns first
+
+    // ordered emit
+    uint32_t out = 0, ties_seen = 0;
+    int32_t* io = idx_out + row * k;
+    typename E::word_t* vo = val_out + row * k;
+    for (uint32_t c0 = 0; c0 < D; c0 += kWave) {
+      const uint32_t c = c0 + lane;
+      const bool in = c < D;
+      const uint32_t raw = in ? static_cast<uint32_t>(xr[c]) : 0u;
+      const uint32_t key = raw & E::kKeyMask;
+      const bool gt = in && key > tau;
+      const bool eq = in && key == tau;
+      const uint64_t m_eq = ballot64(eq);
+      const bool keep = gt || (eq && ties_seen + lanes_below(m_eq) < quota);
+      const uint64_t m_keep = ballot64(keep);
+      const uint32_t slot = out + lanes_below(m_keep);
+      if (keep && slot < k) {
+        io[slot] = static_cast<int32_t>(c);
+        vo[slot] = static_cast<typename E::word_t>(raw);
+      }
+      out += __popcll(m_keep);
+      ties_seen += __popcll(m_eq);
+    }
+    if (tau_out && lane == 0) tau_out[row] = static_cast<typename E::word_t>(tau);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Backward: gather through the forward indices.
+// ---------------------------------------------------------------------------
+template <typename W>
+__global__ __launch_bounds__(256) void rowtopk_bwd_gather_kernel(const W* __restrict__ dy, uint32_t B, uint32_t D,
+                                                                uint64_t stride, uint32_t k,
+                                                                const int32_t* __restrict__ idx,
+                                                                W* __restrict__ dval) {
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= k) return;
+  for (uint32_t b = blockIdx.y; b < B; b += gridDim.y) {
+    const uint64_t o = static_cast<uint64_t>(b) * k + j;
+    const uint32_t c = static_cast<uint32_t>(idx[o]);
+    dval[o] = c < D ? dy[static_cast<uint64_t>(b) * stride + c] : static_cast<W>(0);
+  }
+}
+
+}  // namespace
+}  // namespace dct
+
+using namespace dct;
+
+extern "C" int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                               uint32_t k, int32_t* d_idx_out, void* d_val_out, void* d_tau_out,
+                               void* hip_stream) {
+  if (!x || !d_idx_out || !d_val_out || B == 0 || D == 0 || k == 0 || k > D || row_stride_elems < D)
+    return DCT_ERR_INVALID;
+  if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
+  if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
+  const size_t es = dt == DCT_F32 ? 4 : 2;
+  if (!is_aligned(x, es) || !is_aligned(d_idx_out, 4) || !is_aligned(d_val_out, es) ||
+      (d_tau_out && !is_aligned(d_tau_out, es)))
+    return DCT_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
+  if (grid > 65536u * 4) grid = 65536u * 4;
+  if (dt == DCT_F32) {
+    hipLaunchKernelGGL((rowtopk_fwd_generic_kernel<DCT_F32>), dim3(grid), dim3(kRtThreads), 0, s,
+                       static_cast<const uint32_t*>(x), B, D, row_stride_elems, k, d_idx_out,
+                       static_cast<uint32_t*>(d_val_out), static_cast<uint32_t*>(d_tau_out));
+  } else {
+    hipLaunchKernelGGL((rowtopk_fwd_generic_kernel<DCT_BF16>), dim3(grid), dim3(kRtThreads), 0, s,
+                       static_cast<const uint16_t*>(x), B, D, row_stride_elems, k, d_idx_out,
+                       static_cast<uint16_t*>(d_val_out), static_cast<uint16_t*>(d_tau_out));
+  }
+  return launch_status();
+}
+
+extern "C" int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                               uint32_t k, const int32_t* d_idx, void* d_dval_out, void* hip_stream) {
+  if (!dy || !d_idx || !d_dval_out || B == 0 || D == 0 || k == 0 || k > D || row_stride_elems < D)
+    return DCT_ERR_INVALID;
+  if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
+  if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
+  const size_t es = dt == DCT_F32 ? 4 : 2;
+  if (!is_aligned(dy, es) || !is_aligned(d_idx, 4) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const dim3 grid((k + 255) / 256, B < 65535u ? B : 65535u);
+  if (dt == DCT_F32) {
+    hipLaunchKernelGGL((rowtopk_bwd_gather_kernel<uint32_t>), grid, dim3(256), 0, s,
+                       static_cast<const uint32_t*>(dy), B, D, row_stride_elems, k, d_idx,
+                       static_cast<uint32_t*>(d_dval_out));
+  } else {
+    hipLaunchKernelGGL((rowtopk_bwd_gather_kernel<uint16_t>), grid, dim3(256), 0, s,
+                       static_cast<const uint16_t*>(dy), B, D, row_stride_elems, k, d_idx,
+                       static_cast<uint16_t*>(d_dval_out));
+  }
+  return launch_status();
+}

@@ -1,0 +1,60 @@
+"""CPU-side checks of the boundary: the C-ABI library builds for gfx950, loads
+without a GPU and exports every entry point that include/dct.h declares; the
+Python binding marshals the same names.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_entry_points():
+    text = open(os.path.join(ROOT, "include", "dct.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dct_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_calls():
+    names = declared_entry_points()
+    for want in ("dct_select_threshold", "dct_threshold_compact", "dct_rowtopk_fwd", "dct_rowtopk_bwd"):
+        assert want in names
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2010_08899_amd as m
+    from paper_2010_08899_amd import binding, build
+    handle = m.lib()
+    assert os.path.exists(build.LIB)
+    raw = ctypes.CDLL(build.LIB)
+    for name in declared_entry_points():
+        assert hasattr(raw, name), name
+        assert name in binding._EXPORTS, name
+        assert hasattr(m, name), name
+    assert handle.dct_status_string(0) == b"DCT_OK"
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    import paper_2010_08899_amd as m
+    lib = m.lib()
+    assert m.dct_select_threshold_workspace_bytes(m.DCT_F32, 0) == 0
+    assert m.dct_select_threshold_workspace_bytes(m.DCT_F32, 1 << 31) == 0
+    assert m.dct_select_threshold_workspace_bytes(m.DCT_F32, 1 << 20) > 0
+    small = m.dct_threshold_compact_workspace_bytes(m.DCT_F32, 1 << 20)
+    big = m.dct_threshold_compact_workspace_bytes(m.DCT_F32, 1 << 28)
+    assert 0 < small < big < (1 << 22)
+    # null pointers and bad sizes are rejected before anything is enqueued
+    assert lib.dct_select_threshold(None, 0, 10, 1, None, None, 0, None) == 1
+    assert lib.dct_threshold_compact(None, 0, 10, None, 0, None, None, 0, None, None, 0, None) == 1
+    assert lib.dct_rowtopk_fwd(None, 0, 1, 1, 1, 1, None, None, None, None) == 1
+    assert lib.dct_rowtopk_bwd(None, 0, 1, 1, 1, 1, None, None, None) == 1
+    assert "INVALID" in m.dct_status_string(1)
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2010_08899_amd as m
+    g = torch.zeros(16)
+    with pytest.raises(ValueError):
+        m.dct_select_threshold(g, 1, torch.zeros(4, dtype=torch.int32), torch.zeros(1024, dtype=torch.uint8))

@@ -1,0 +1,296 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Everything is integer / bit-copy work, so the bar is
+bit-exact: threshold words, counts, indices and copied values (0 ULP).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dct():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2010_08899_amd as m
+    m.lib()
+    return m
+
+
+DEV = torch.device("cuda:0")
+
+
+def host(t):
+    return oracle.as_numpy(t.detach().cpu())
+
+
+def bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a.view(np.uint16)
+
+
+class DP:
+    """Buffers for one vector size; reused across calls like a training loop would."""
+
+    def __init__(self, dct, g, capacity=None):
+        self.dct, self.g = dct, g
+        n = g.numel()
+        self.cap = n if capacity is None else capacity
+        self.thr = torch.zeros(4, dtype=torch.int32, device=g.device)
+        self.idx = torch.full((max(self.cap, 1),), -7, dtype=torch.int32, device=g.device)
+        self.val = torch.zeros(max(self.cap, 1), dtype=g.dtype, device=g.device)
+        self.count = torch.zeros(1, dtype=torch.int64, device=g.device)
+        self.sel_ws = dct.new_select_workspace(g)
+        self.ws = dct.new_compact_workspace(g)
+
+    def select(self, k, g=None):
+        self.dct.dct_select_threshold(self.g if g is None else g, k, self.thr, self.sel_ws)
+        return oracle.Threshold(*self.dct.read_threshold(self.thr))
+
+    def compact(self, mode, g=None, capacity=None):
+        cap = self.cap if capacity is None else capacity
+        self.idx.fill_(-7)
+        self.dct.dct_threshold_compact(self.g if g is None else g, self.thr, mode, self.idx, self.val, self.count,
+                                       self.ws, capacity=cap)
+        c = self.dct.read_count(self.count)
+        m = min(c, cap)
+        return host(self.idx[:m]), host(self.val[:m]), c, host(self.idx[m:m + 16])
+
+
+def check_dp(dct, g, k, modes=(0, 1), select_method="sort"):
+    gh = host(g)
+    dp = DP(dct, g)
+    thr = dp.select(k)
+    exp = oracle.select_threshold(gh, k, method=select_method)
+    assert thr == exp, (thr, exp)
+    for mode in modes:
+        idx, val, cnt, guard = dp.compact(mode)
+        eidx, eval_, ecnt = oracle.threshold_compact(gh, exp, mode)
+        assert cnt == ecnt
+        assert np.array_equal(idx, eidx)
+        assert np.array_equal(bits(val), bits(eval_))
+        assert np.all(guard == -7)  # nothing written past the survivors
+    return dp, exp
+
+
+# ------------------------------------------------------------------ DP: sizes, tails, alignment
+@pytest.mark.parametrize("n", [1, 2, 5, 63, 64, 1000, 8191, 8192, 8193, 3 * 8192 + 17, 100_003, 1_000_000])
+def test_dp_sizes(dct, n):
+    g = si.gaussian_gradient(n, DEV, 100 + n)
+    for k in sorted({1, max(1, n // 100), max(1, n // 2), n}):
+        check_dp(dct, g, k)
+
+
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_dp_misaligned_base(dct, shift):
+    buf = si.gaussian_gradient(50_000 + shift, DEV, 7)
+    g = buf[shift:]
+    assert g.data_ptr() % 16 != 0
+    check_dp(dct, g, 500)
+    check_dp(dct, g[:5], 2)
+
+
+@pytest.mark.parametrize("n", [40, 20_000])
+def test_dp_adversarial_values(dct, n):
+    for name, g in si.adversarial_vectors(n, DEV, 900 + n):
+        for k in sorted({1, 3, n // 7 + 1, n // 2, n}):
+            check_dp(dct, g.contiguous(), k)
+    g = si.gaussian_gradient(n, DEV, 5)
+    g[n // 3] = float("nan")
+    g[0] = float("inf")
+    check_dp(dct, g, 3)
+
+
+def test_dp_bf16(dct):
+    for n in (10, 16384, 16385, 70_001):
+        g = si.gaussian_gradient(n, DEV, 300 + n, scale=1.0).to(torch.bfloat16)
+        for k in (1, max(1, n // 100), n):
+            check_dp(dct, g, k)
+    check_dp(dct, g[1:], 100)  # 2-byte-aligned base
+
+
+def test_dp_c1_full(dct):
+    g, k = si.config_c1(DEV)
+    dp, thr = check_dp(dct, g, k)
+    assert abs(np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0] / 2.5758e-3 - 1) < 0.02
+    # determinism: a second run gives the same bits
+    a = dp.compact(1)
+    b = dp.compact(1)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(bits(a[1]), bits(b[1])) and a[2] == b[2] == k
+
+
+def test_dp_overflow_prefix_and_empty(dct):
+    g = si.gaussian_gradient(200_000, DEV, 11)
+    gh = host(g)
+    dp = DP(dct, g)
+    thr = dp.select(2000)
+    full = oracle.threshold_compact(gh, thr, oracle.GE_TAU)
+    idx, val, cnt, guard = dp.compact(0, capacity=777)
+    assert cnt == full[2] == 2000 and np.array_equal(idx, full[0][:777]) and np.array_equal(val, full[1][:777])
+    assert np.all(guard == -7)
+    with pytest.raises(dct.DctError):
+        dct.read_count(dp.count, capacity=777)
+    idx, val, cnt, _ = dp.compact(1, capacity=0)
+    assert cnt == 2000 and idx.size == 0
+    # a stale threshold that nothing reaches: count 0, nothing written
+    dp.thr.copy_(torch.tensor([0x7F000000, 0, 0, 0], dtype=torch.int32))
+    idx, val, cnt, guard = dp.compact(0)
+    assert cnt == 0 and np.all(guard == -7)
+    # a stale threshold of zero keeps everything
+    dp.thr.zero_()
+    idx, val, cnt, _ = dp.compact(0)
+    assert cnt == g.numel() and np.array_equal(idx, np.arange(g.numel())) and np.array_equal(bits(val), bits(gh))
+
+
+def test_dp_argument_and_workspace_errors(dct):
+    g = si.gaussian_gradient(10_000, DEV, 12)
+    dp = DP(dct, g)
+    for k in (0, g.numel() + 1):
+        with pytest.raises(dct.DctError) as e:
+            dp.select(k)
+        assert e.value.status == 1
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(dct.DctError) as e:
+        dct.dct_select_threshold(g, 5, dp.thr, small)
+    assert e.value.status == 2
+    dp.select(100)
+    with pytest.raises(dct.DctError) as e:
+        dct.dct_threshold_compact(g, dp.thr, 0, dp.idx, dp.val, dp.count, small[:16])
+    assert e.value.status == 2
+    with pytest.raises(dct.DctError):
+        dct.dct_threshold_compact(g, dp.thr, 5, dp.idx, dp.val, dp.count, dp.ws)
+    # a workspace that was never initialised is reported through the count, no hang
+    raw = torch.zeros(dp.ws.numel(), dtype=torch.uint8, device=DEV)
+    dct.dct_threshold_compact(g, dp.thr, 0, dp.idx, dp.val, dp.count, raw)
+    with pytest.raises(dct.DctError) as e:
+        dct.read_count(dp.count)
+    assert e.value.status == 2
+    # and the initialised one still works afterwards
+    idx, val, cnt, _ = dp.compact(1)
+    assert cnt == 100
+
+
+# ------------------------------------------------------------------ DP: c3 (select once, reuse on fresh draws)
+@pytest.mark.parametrize("chunk", range(4))
+def test_dp_c3_reuse(dct, chunk):
+    draws_per_chunk = si.C3_DRAWS // 4
+    g0 = si.config_c3_draw(DEV, 0)
+    dp = DP(dct, g0, capacity=si.C3_CAPACITY)
+    thr = dp.select(si.C3_K)
+    if chunk == 0:
+        exp = oracle.select_threshold(host(g0), si.C3_K)
+        assert thr == exp
+        tau = np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0]
+        assert abs(tau / 12.92e-3 - 1) < 0.03
+    else:
+        assert thr == oracle.select_threshold(host(g0), si.C3_K, method="nth")
+    del g0
+    counts = []
+    for j in range(1 + chunk * draws_per_chunk, 1 + (chunk + 1) * draws_per_chunk):
+        g = si.config_c3_draw(DEV, j)
+        idx, val, cnt, guard = dp.compact(0, g=g)
+        eidx, eval_, ecnt = oracle.threshold_compact(host(g), thr, oracle.GE_TAU, capacity=si.C3_CAPACITY)
+        assert cnt == ecnt <= si.C3_CAPACITY, j
+        assert np.array_equal(idx, eidx) and np.array_equal(bits(val), bits(eval_)), j
+        counts.append(cnt)
+    counts = np.array(counts)
+    assert abs(counts.mean() / si.C3_K - 1) < 0.05 and counts.std() > 10  # fluctuates around k
+
+
+# ------------------------------------------------------------------ DP: c4 (embedding-shaped, 95 % exact zeros)
+def test_dp_c4_reduced_full_sort(dct):
+    g, k = si.config_c4(DEV, rows=1 << 18)  # N = 2^24: the oracle's full sort takes seconds
+    check_dp(dct, g, k)
+    # k larger than the number of non-zeros: tau = 0 and the lowest-index zeros fill up
+    check_dp(dct, g, g.numel() // 10, modes=(1,))
+
+
+def test_dp_c4_full(dct):
+    g, k = si.config_c4(DEV)
+    assert g.numel() == 1 << 28 and k == 1342178
+    dp, thr = check_dp(dct, g, k, modes=(1,), select_method="nth")
+    tau = np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0]
+    assert abs(tau / 1.645 - 1) < 0.01
+
+
+# ------------------------------------------------------------------ MP
+def check_mp(dct, x, dy, k, with_tau=True):
+    B, D = x.shape
+    idx = torch.full((B, k), -7, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=x.dtype, device=DEV)
+    tau = torch.zeros(B, dtype=x.dtype, device=DEV) if with_tau else None
+    dval = torch.zeros(B, k, dtype=x.dtype, device=DEV)
+    dct.dct_rowtopk_fwd(x, k, idx, val, tau)
+    dct.dct_rowtopk_bwd(dy, idx, dval)
+    xh, dyh = host(x), host(dy)
+    eidx, eval_, etau = oracle.rowtopk_fwd(xh, k)
+    edval = oracle.rowtopk_bwd(dyh, eidx)
+    assert np.array_equal(host(idx), eidx)
+    assert np.array_equal(bits(host(val)), bits(eval_))
+    if with_tau:
+        assert np.array_equal(bits(host(tau)), bits(etau))
+    assert np.array_equal(bits(host(dval)), bits(edval))
+    return idx, val, dval
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("D", [1, 3, 64, 65, 500, 1000, 1024, 2048, 4096, 5000])
+def test_mp_shapes(dct, dtype, D):
+    B = 37
+    for stride in (None, D + 3, D + 8):
+        x = si.relu_activations(B, D, DEV, 40 + D, dtype=dtype, row_stride=stride)
+        dy = si.normal_matrix(B, D, DEV, 41 + D, dtype=dtype, row_stride=stride)
+        for k in sorted({1, max(1, D // 20), max(1, D // 2), D}):
+            check_mp(dct, x, dy, k, with_tau=(k % 2 == 1))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_mp_signed_and_tie_heavy_rows(dct, dtype):
+    D = 777
+    rows = [t for _, t in si.adversarial_vectors(D, DEV, 55)]
+    x = torch.stack(rows).to(dtype)
+    dy = si.normal_matrix(x.shape[0], D, DEV, 56, dtype=dtype)
+    for k in (1, 38, 400, D):
+        check_mp(dct, x, dy, k)
+    xs = si.normal_matrix(64, 1024, DEV, 57, dtype=dtype)  # split before the activation: signed entries
+    check_mp(dct, xs, si.normal_matrix(64, 1024, DEV, 58, dtype=dtype), 51)
+
+
+def test_mp_c2_full(dct):
+    x, dy, k = si.config_c2(DEV)
+    idx, val, dval = check_mp(dct, x, dy, k)
+    idx2 = torch.zeros_like(idx)
+    val2 = torch.zeros_like(val)
+    dct.dct_rowtopk_fwd(x, k, idx2, val2, None)
+    assert torch.equal(idx, idx2) and torch.equal(val.view(torch.int32), val2.view(torch.int32))
+
+
+def test_mp_c5_full(dct):
+    x, dy, k = si.config_c5(DEV)
+    assert x.shape == (65536, 4096) and k == 204
+    check_mp(dct, x, dy, k)
+
+
+def test_mp_bwd_out_of_range_index_is_not_dereferenced(dct):
+    dy = si.normal_matrix(4, 100, DEV, 60)
+    idx = torch.tensor([[0, 5, 99], [1, 100, 2], [-1, 3, 4], [7, 8, 2 ** 31 - 1]], dtype=torch.int32, device=DEV)
+    dval = torch.full((4, 3), 9.0, device=DEV)
+    dct.dct_rowtopk_bwd(dy, idx, dval)
+    d = dval.cpu()
+    dyh = dy.cpu()
+    assert d[0].tolist() == [dyh[0, 0].item(), dyh[0, 5].item(), dyh[0, 99].item()]
+    assert d[1, 1] == 0 and d[2, 0] == 0 and d[3, 2] == 0 and d[1, 0] == dyh[1, 1]
+
+
+def test_mp_argument_errors(dct):
+    x = si.relu_activations(4, 100, DEV, 61)
+    idx = torch.zeros(4, 101, dtype=torch.int32, device=DEV)
+    val = torch.zeros(4, 101, device=DEV)
+    with pytest.raises(dct.DctError) as e:
+        dct.dct_rowtopk_fwd(x, 101, idx, val)
+    assert e.value.status == 1
+    with pytest.raises(dct.DctError):
+        dct.dct_rowtopk_fwd(x, 0, idx[:, :0].contiguous(), val[:, :0].contiguous())
