@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the DCT hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+  dct_select_threshold + dct_threshold_compact (exactly-k) on the c4 gradient
+  (embedding-shaped, N = 2^28 fp32, keep 0.5 %), then
+  dct_rowtopk_fwd + dct_rowtopk_bwd on the c5 activations
+  (65536 x 4096 bf16, k = 204).
+Inputs are resident in HBM before the timed region; two copies of every input
+alternate so that no step re-reads what the previous one left in cache.
+
+Prints ONE JSON line: whole-step throughput in elements/s, per-call times and
+HBM fractions, the roofline entry of the dominant kernel, the c3 reuse loop
+(threshold selected once, applied to fresh draws) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_calls(fn, reps, warmup=2):
+    """Average duration in microseconds of fn(i), measured with HIP events on the
+    stream the kernels are launched on (torch's current stream)."""
+    for i in range(warmup):
+        fn(i)
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(reps):
+        fn(i)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1e3 / reps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--reps", type=int, default=30, help="launches per kernel for the per-call timings")
+    ap.add_argument("--c3-draws", type=int, default=1000, help="distinct resident draws for the c3 reuse loop")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--small", action="store_true", help="shrink c4/c5 by 16x (debugging only, not a valid number)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (every box has one); --gpus N with N > 1 is not supported. "
+                 "The path shards without communication (see DESIGN.md); value is the one GPU's throughput.")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+
+    import paper_2010_08899_amd as dct
+    dct.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    shrink = 16 if args.small else 1
+
+    # ------------------------------------------------------------ inputs (resident)
+    t0 = time.time()
+    c4_rows = si.C4_ROWS // shrink
+    g4 = [None, None]
+    g4[0], k4 = si.config_c4(dev, rows=c4_rows)
+    g4[1] = si.embedding_gradient(c4_rows, si.C4_DIM, (c4_rows * 5) // 100, dev, si.BASE_SEED + 40)
+    n4 = g4[0].numel()
+    c5_b = si.C5_B // shrink
+    x5 = [None, None]
+    dy5 = [None, None]
+    x5[0], dy5[0], k5 = si.config_c5(dev, b=c5_b)
+    x5[1] = si.relu_activations(c5_b, si.C5_D, dev, si.BASE_SEED + 50, dtype=torch.bfloat16)
+    dy5[1] = si.normal_matrix(c5_b, si.C5_D, dev, si.BASE_SEED + 51, dtype=torch.bfloat16)
+    B5, D5 = x5[0].shape
+    torch.cuda.synchronize()
+    log(f"[bench] inputs resident in {time.time() - t0:.1f}s: c4 N={n4} k={k4}; c5 {B5}x{D5} bf16 k={k5}")
+
+    thr = torch.zeros(4, dtype=torch.int32, device=dev)
+    sel_ws = dct.new_select_workspace(g4[0])
+    cmp_ws = dct.new_compact_workspace(g4[0])
+    cap4 = k4
+    idx4 = torch.zeros(cap4, dtype=torch.int32, device=dev)
+    val4 = torch.zeros(cap4, dtype=torch.float32, device=dev)
+    cnt4 = torch.zeros(1, dtype=torch.int64, device=dev)
+    idx5 = torch.zeros(B5, k5, dtype=torch.int32, device=dev)
+    val5 = torch.zeros(B5, k5, dtype=torch.bfloat16, device=dev)
+    dval5 = torch.zeros(B5, k5, dtype=torch.bfloat16, device=dev)
+
+    def call_select(i):
+        dct.dct_select_threshold(g4[i & 1], k4, thr, sel_ws)
+
+    def call_compact(i):
+        dct.dct_threshold_compact(g4[i & 1], thr, dct.DCT_EXACT_K, idx4, val4, cnt4, cmp_ws)
+
+    def call_fwd(i):
+        dct.dct_rowtopk_fwd(x5[i & 1], k5, idx5, val5, None)
+
+    def call_bwd(i):
+        dct.dct_rowtopk_bwd(dy5[i & 1], idx5, dval5)
+
+    def step(i):
+        call_select(i)
+        call_compact(i)
+        call_fwd(i)
+        call_bwd(i)
+
+    # ------------------------------------------------------------ the timed steps
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    assert dct.read_count(cnt4, capacity=cap4) == k4
+    elems_per_step = n4 + B5 * D5
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = elems_per_step * args.steps / elapsed
+    log(f"[bench] {args.steps} steps: {ms_per_step:.3f} ms/step, {value:.4g} elements/s")
+
+    # ------------------------------------------------------------ per-call timings and rooflines
+    def entry(name, us, alg_bytes, elems, launches=1, extra=None):
+        gbps = alg_bytes / (us * 1e-6) / 1e9
+        e = {"call": name, "us": round(us, 2), "elements_per_s": elems / (us * 1e-6), "algorithmic_bytes": alg_bytes,
+             "GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4), "launches": launches}
+        if extra:
+            e.update(extra)
+        return e
+
+    calls = []
+    us = time_calls(call_select, args.reps)
+    sel_launches = 4
+    calls.append(entry("dct_select_threshold[c4]", us, n4 * 4 + 16, n4, launches=sel_launches))
+    call_select(0)
+    us = time_calls(call_compact, args.reps)
+    calls.append(entry("dct_threshold_compact[c4,exact_k]", us, n4 * 4 + k4 * 8 + 8, n4))
+    us = time_calls(call_fwd, args.reps)
+    calls.append(entry("dct_rowtopk_fwd[c5]", us, B5 * D5 * 2 + B5 * k5 * 6, B5 * D5))
+    us = time_calls(call_bwd, args.reps)
+    # touched-sector floor of the gather (128-byte lines and 64-byte sectors), from the indices themselves
+    idx_h = idx5[: min(B5, 2048)].cpu().numpy().astype(np.int64)
+    lines128 = np.mean([np.unique(r // 64).size for r in idx_h]) * 128
+    sect64 = np.mean([np.unique(r // 32).size for r in idx_h]) * 64
+    strict = B5 * k5 * (4 + 2 * 2)
+    gran128 = int(B5 * lines128) + B5 * k5 * 6
+    gran64 = int(B5 * sect64) + B5 * k5 * 6
+    calls.append(entry("dct_rowtopk_bwd[c5]", us, gran128, B5 * D5, extra={
+        "algorithmic_bytes_strict": strict, "GBps_strict": round(strict / (us * 1e-6) / 1e9, 1),
+        "algorithmic_bytes_64B_sectors": gran64, "GBps_64B_sectors": round(gran64 / (us * 1e-6) / 1e9, 1),
+        "note": "algorithmic_bytes counts the 128-byte lines the gather touches"}))
+
+    # plain streaming kernels: the achievable HBM rate measured in the same run
+    probe_bytes = (4 << 30) // shrink
+    probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
+    probe_dst = torch.empty(probe_bytes // 2, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(16384, dtype=torch.uint8, device=dev)
+    us_read = time_calls(lambda i: dct.dct_probe_read(probe_src, sink), 10)
+    us_copy = time_calls(lambda i: dct.dct_probe_copy(probe_dst, probe_src[: probe_bytes // 2]), 10)
+    probes = {"read_GBps": round(probe_bytes / (us_read * 1e-6) / 1e9, 1),
+              "copy_GBps": round(probe_bytes / (us_copy * 1e-6) / 1e9, 1)}
+    del probe_src, probe_dst
+    for c in calls:
+        c["frac_of_probe_read"] = round(c["GBps"] / probes["read_GBps"], 4)
+        log(f"[bench] {c['call']}: {c['us']} us, {c['GBps']} GB/s = {c['frac_of_hbm_peak']:.1%} of 8 TB/s")
+    log(f"[bench] probes: {probes}")
+
+    dom = max(calls, key=lambda c: c["us"])
+    per_launch_us = dom["us"] / dom["launches"]
+    roofline = {"bound": "hbm", "kernel": dom["call"], "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                "launch_us": round(per_launch_us, 2), "launches_per_call": dom["launches"],
+                "algorithmic_bytes_per_launch": dom["algorithmic_bytes"] // dom["launches"]}
+
+    # ------------------------------------------------------------ c3: select once, reuse on fresh draws
+    c3 = None
+    free_b, _ = torch.cuda.mem_get_info()
+    n3 = si.C3_N // shrink
+    draws = max(3, min(args.c3_draws, int(free_b * 0.8) // (n3 * 4) - 2))
+    try:
+        t0 = time.time()
+        bank = torch.empty(draws, n3, dtype=torch.float32, device=dev)
+        for j in range(draws):
+            bank[j] = si.config_c3_draw(dev, j + 1, n3)
+        g0 = si.config_c3_draw(dev, 0, n3)
+        k3 = si.ceil_frac(n3, 1, 1000)
+        cap3 = 2 * k3
+        thr3 = torch.zeros(4, dtype=torch.int32, device=dev)
+        ws3s = dct.new_select_workspace(g0)
+        ws3 = dct.new_compact_workspace(g0)
+        idx3 = torch.zeros(cap3, dtype=torch.int32, device=dev)
+        val3 = torch.zeros(cap3, dtype=torch.float32, device=dev)
+        cnt3 = torch.zeros(1, dtype=torch.int64, device=dev)
+        torch.cuda.synchronize()
+        log(f"[bench] c3: {draws} draws resident in {time.time() - t0:.1f}s")
+        us_sel3 = time_calls(lambda i: dct.dct_select_threshold(g0, k3, thr3, ws3s), 10)
+        iters = si.C3_DRAWS
+        us_c3 = time_calls(lambda i: dct.dct_threshold_compact(bank[i % draws], thr3, dct.DCT_GE_TAU, idx3, val3,
+                                                               cnt3, ws3), iters, warmup=5)
+        last = dct.read_count(cnt3, capacity=cap3)
+        alg3 = n3 * 4 + k3 * 8 + 8
+        c3 = {"n": n3, "k": k3, "distinct_draws": draws, "iterations": iters, "select_us": round(us_sel3, 2),
+              "compact_us_per_iteration": round(us_c3, 2), "elements_per_s": n3 / (us_c3 * 1e-6),
+              "GBps": round(alg3 / (us_c3 * 1e-6) / 1e9, 1),
+              "frac_of_hbm_peak": round(alg3 / (us_c3 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+              "amortised_us_per_iteration_L1000": round(us_c3 + us_sel3 / 1000.0, 2), "last_count": last}
+        log(f"[bench] c3 reuse: {c3}")
+        del bank
+    except torch.cuda.OutOfMemoryError:
+        log("[bench] c3 reuse loop skipped: not enough free HBM")
+
+    # ------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        n_s = min(n4, 1 << 24)
+        b_s = min(B5, 4096)
+        k_s = si.ceil_frac(n_s, 5, 1000)
+        gs = g4[0][:n_s].cpu().numpy()
+        xs = oracle.as_numpy(x5[0][:b_s].cpu())
+        dys = oracle.as_numpy(dy5[0][:b_s].cpu())
+        t = {}
+        t0 = time.perf_counter(); thr_s = oracle.select_threshold(gs, k_s); t["select_full_sort"] = time.perf_counter() - t0
+        t0 = time.perf_counter(); oracle.threshold_compact(gs, thr_s, oracle.EXACT_K, capacity=k_s); t["compact"] = time.perf_counter() - t0
+        t0 = time.perf_counter(); ei, _, _ = oracle.rowtopk_fwd(xs, k5); t["rowtopk_fwd"] = time.perf_counter() - t0
+        t0 = time.perf_counter(); oracle.rowtopk_bwd(dys, ei); t["rowtopk_bwd"] = time.perf_counter() - t0
+        total = sum(t.values())
+        t0 = time.perf_counter(); oracle.select_threshold(gs, k_s, method="nth"); t_nth = time.perf_counter() - t0
+        model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+        except OSError:
+            pass
+        cpu = {"value": (n_s + b_s * D5) / total, "unit": "elements/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n_s} elements of the c4 gradient (k={k_s}) + first {b_s} rows of c5; "
+                         f"one step = full-sort select + scalar compact + partial-sort row top-k + gather",
+               "seconds": {k_: round(v, 3) for k_, v in t.items()}, "select_nth_element_seconds": round(t_nth, 3),
+               "host_cpus": os.cpu_count(), "cpu_model": model}
+        log(f"[bench] cpu oracle: {cpu}")
+
+    out = {
+        "metric": "elements/s and % of HBM peak: DP threshold+compact, MP row top-k fwd/bwd",
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 keys of fp32 (DP) / u16 keys of bf16 (MP); integer compare and bit copy only",
+        "data": "synthetic",
+        "config": {"workload": "c4 DP select+compact (N=2^28 fp32, keep 0.5%) + c5 MP row top-k fwd+bwd "
+                               "(65536x4096 bf16, k=204)" + (" [SHRUNK 16x: not a valid number]" if args.small else ""),
+                   "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
+        "roofline": roofline, "calls": calls, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

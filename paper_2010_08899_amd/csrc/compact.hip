@@ -2,21 +2,35 @@
 // "W_hat = W_grad . M", as ONE pass over the gradient that writes the survivors
 // as (ascending index, value) pairs.
 //
-// Design (gfx950): the vector is cut into tiles of 32 KiB.  A workgroup of four
-// wavefronts takes the next tile from a ticket counter, loads it with 16-byte
-// coalesced loads into registers (8 per lane), counts its survivors with
-// wavefront ballots, publishes the tile count in a 64-bit descriptor and finds
-// the number of survivors in all earlier tiles by a decoupled look-back over the
-// descriptors of its predecessors.  Tickets are handed out in launch order, so
-// every tile a workgroup waits for is already running or finished.  Survivors are
-// then written straight from registers to their final slots (ballot + lane-prefix
-// ranks), so the input is read from HBM exactly once and nothing but the pairs is
-// written.  Exactly-k mode carries a second counter (ties seen so far) through the
-// same scan: a tie is kept while fewer than tie_quota ties precede it.
+// Design (gfx950).  The 8 XCDs of the chip have private L2s, so workgroups can
+// only talk to each other through the memory-side path (about a microsecond per
+// round trip, and polling hammers a few channels).  The kernel therefore keeps
+// cross-workgroup traffic to one short exchange at the very end:
+//   1. The 16-byte-aligned interior of the vector is split into one contiguous
+//      chunk per workgroup (at most 4 workgroups per CU, all resident at once);
+//      each of its four wavefronts streams a contiguous quarter with coalesced
+//      16-byte loads, 8 KiB per wavefront per iteration.
+//   2. Survivors are sparse (<= a few %), so each wavefront appends its
+//      (index, value) pairs, in index order, to its own region of LDS (ballot +
+//      lane-prefix ranks).  No workgroup waits for another while streaming.
+//   3. When a chunk is done the workgroup publishes its two counts (keys above
+//      tau, ties at tau) in a 64-bit descriptor.  Descriptors are summed in two
+//      levels (members of a group of 64 workgroups, then whole groups), which keeps
+//      every poll to one coalesced load of at most 64 descriptors.
+//   4. With its exclusive prefix known, the workgroup copies its staged pairs to
+//      their final slots; in exactly-k mode a tie is written while fewer than
+//      tie_quota ties precede it (ties are staged with a flag bit).
+// If a wavefront's LDS region overflows (dense survivors, or a tie value that
+// covers much of the vector) the workgroup still counts everything, and after the
+// scan streams its chunk a second time, writing straight to the final slots.
 //
-// The workspace holds the ticket, a completion counter and the descriptors.  The
-// workgroup that finishes last writes the survivor count and returns the
-// workspace to its initial (all-zero) state, so a call needs a single launch.
+// A workgroup only ever waits for workgroups with a lower index, which start
+// earlier; the waits are bounded all the same and a wait that runs out is reported
+// through the count.  The workspace holds two descriptor sets used by alternate
+// calls (an epoch word picks the set): every call clears the other set for its
+// successor and the last workgroup advances the epoch, so a call is one launch.
+#include <type_traits>
+
 #include "dct_common.hpp"
 
 namespace dct {
@@ -24,11 +38,18 @@ namespace {
 
 constexpr int kCtThreads = 256;
 constexpr int kCtWaves = kCtThreads / kWave;
-constexpr int kCtRows = 8;                       // 16-byte loads per lane per tile
-constexpr uint32_t kCtTileBytes = kCtThreads * kCtRows * 16;
-constexpr uint32_t kCtMagic = 0x44435431u;       // "DCT1"
+constexpr int kCtRows = 8;                              // 16-byte loads per lane per iteration
+constexpr uint32_t kCtTileVecs = kCtThreads * kCtRows;  // granule of the chunking: 32 KiB
+constexpr int kCtWgPerCu = 4;
+constexpr uint32_t kCtMaxGrid = 2048;
+constexpr uint32_t kCtGroup = 64;                       // workgroups per descriptor group
+constexpr uint32_t kCtMaxGroups = kCtMaxGrid / kCtGroup;
+static_assert(kCtMaxGroups <= kWave, "the group-level look-back is a single poll");
+constexpr uint32_t kCtStageCap = 1152;                  // staged pairs per wavefront (36 KiB of LDS per workgroup)
+constexpr uint32_t kCtMagic = 0x44435433u;              // "DCT3"
 constexpr uint32_t kCtHeaderBytes = 256;
 constexpr uint32_t kCtSpinLimit = 1u << 20;
+constexpr uint32_t kTieFlag = 0x80000000u;
 
 // Descriptor: [63:62] status, [61:31] count A (keys above the cut), [30:0] count E (ties).
 constexpr uint64_t kStAggregate = 1ull << 62;
@@ -37,294 +58,356 @@ constexpr uint64_t kPayload = (1ull << 62) - 1;
 
 struct CompactHeader {
   uint32_t magic;
-  uint32_t ticket;
-  uint32_t done;
-  uint32_t n_desc;
+  uint32_t epoch;
   uint32_t error;
-  uint32_t pad[59];
+  uint32_t pad[61];
 };
 static_assert(sizeof(CompactHeader) == kCtHeaderBytes, "header size");
+
+struct DescSet {
+  uint64_t wg[kCtMaxGrid];
+  uint64_t group[kCtGroup];
+};
+constexpr size_t kCtWsBytes = kCtHeaderBytes + 2 * sizeof(DescSet);
 
 __device__ __forceinline__ uint64_t pack(uint32_t a, uint32_t e) { return (static_cast<uint64_t>(a) << 31) | e; }
 __device__ __forceinline__ uint32_t cnt_a(uint64_t p) { return static_cast<uint32_t>((p & kPayload) >> 31); }
 __device__ __forceinline__ uint32_t cnt_e(uint64_t p) { return static_cast<uint32_t>(p & 0x7FFFFFFFu); }
 
-__global__ void compact_ws_init_kernel(uint32_t* ws, uint32_t n_words, uint32_t n_desc) {
+__global__ void compact_ws_init_kernel(uint32_t* ws, uint32_t n_words) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_words) return;
-  uint32_t v = 0;
-  if (i == 0) v = kCtMagic;
-  if (i == 3) v = n_desc;
-  ws[i] = v;
+  ws[i] = (i == 0) ? kCtMagic : 0u;
 }
 
-// Sum of the counts of all tiles before `tile`.  Called by all lanes of one
-// wavefront.  `failed` is set when a predecessor never published (only possible
-// with a corrupted workspace): the wait is bounded so the kernel always ends.
-__device__ uint64_t look_back(const uint64_t* desc, int tile, bool& failed) {
-  const int lane = lane_id();
-  uint64_t excl = 0;
-  int pos = tile - 1;
+// Bounded wait helper: returns false when the spin budget is used up or another
+// workgroup has already reported a failure.
+__device__ __forceinline__ bool keep_waiting(uint32_t& spins, const uint32_t* error_flag) {
+  ++spins;
+  if (spins > kCtSpinLimit || ((spins & 255u) == 0 && ld_agent(error_flag) != 0)) return false;
+  __builtin_amdgcn_s_sleep(1);
+  return true;
+}
+
+// Sum of the descriptors of members 0..m-1 of a group (m <= 63), once all are published.
+__device__ uint64_t sum_members(const uint64_t* first, uint32_t m, const uint32_t* error_flag, bool& failed) {
+  if (m == 0) return 0;
+  const uint32_t lane = lane_id();
   uint32_t spins = 0;
   for (;;) {
-    const int i = pos - lane;
-    const uint64_t d = (i >= 0) ? ld_agent(desc + i) : kStInclusive;
-    const uint32_t st = static_cast<uint32_t>(d >> 62);
-    const uint64_t invalid = ballot64(st == 0);
-    const uint64_t incl = ballot64(st == 2);
-    if (incl != 0) {
-      const int f = __builtin_ctzll(incl);
-      const uint64_t need = (f == 63) ? ~0ull : ((2ull << f) - 1);
-      if ((invalid & need) == 0) {
-        excl += wave_sum_u64(lane <= f ? (d & kPayload) : 0ull);
-        return excl;
-      }
-    } else if (invalid == 0) {
-      excl += wave_sum_u64(d & kPayload);
-      pos -= kWave;
-      continue;
-    }
-    if (++spins > kCtSpinLimit) {
+    const uint64_t d = lane < m ? ld_agent(first + lane) : kStAggregate;
+    if (ballot64((d >> 62) == 0) == 0) return wave_sum_u64(d & kPayload);
+    if (!keep_waiting(spins, error_flag)) {
       failed = true;
-      return excl;
+      return 0;
     }
-    __builtin_amdgcn_s_sleep(2);
   }
 }
 
-template <int DT, bool GUARDED, bool EXACT>
-__device__ __forceinline__ void process_tile(const typename Elem<DT>::word_t* __restrict__ g_al, uint32_t off,
-                                             uint32_t n_virt, uint32_t tile, uint32_t t_above, uint32_t tau,
-                                             uint32_t quota, int32_t* __restrict__ idx_out,
-                                             typename Elem<DT>::word_t* __restrict__ val_out, uint32_t capacity,
-                                             uint64_t* desc, CompactHeader* hdr, uint32_t* s_wave_a,
-                                             uint32_t* s_wave_e, uint64_t* s_excl) {
-  using E = Elem<DT>;
-  constexpr int V = E::kVec;
-  constexpr uint32_t kTileElems = kCtThreads * kCtRows * V;
+// Sum over all groups before group g (g <= 63): nearest groups first, up to and
+// including the first one that carries an inclusive prefix.
+__device__ uint64_t group_prefix(const uint64_t* gdesc, uint32_t g, const uint32_t* error_flag, bool& failed) {
+  if (g == 0) return 0;
   const int lane = lane_id();
-  const int wave = threadIdx.x / kWave;
-  // Virtual element index of this lane's first element in row 0; row r adds r * 64 * V.
-  const uint32_t v0 = tile * kTileElems + (wave * kCtRows * kWave + lane) * V;
+  uint32_t spins = 0;
+  for (;;) {
+    const int i = static_cast<int>(g) - 1 - lane;
+    const uint64_t d = i >= 0 ? ld_agent(gdesc + i) : kStInclusive;
+    const uint32_t st = static_cast<uint32_t>(d >> 62);
+    const uint64_t invalid = ballot64(st == 0);
+    const int f = __builtin_ctzll(ballot64(st == 2));  // exists: lane g reads the virtual group -1
+    const uint64_t need = (f == 63) ? ~0ull : ((2ull << f) - 1);
+    if ((invalid & need) == 0) return wave_sum_u64(lane <= f ? (d & kPayload) : 0ull);
+    if (!keep_waiting(spins, error_flag)) {
+      failed = true;
+      return 0;
+    }
+  }
+}
 
-  uint4 v[kCtRows];
-  uint32_t valid[kCtRows];  // per-element validity bits (all ones on the fast path)
+// Work description shared by all workgroups (computed on the host).
+struct CompactGeom {
+  uint32_t head;         // elements before the first 16-byte-aligned vector (< kVec)
+  uint32_t n_vec;        // full 16-byte vectors after the head
+  uint32_t tail;         // elements after the last full vector (< kVec)
+  uint32_t grid;         // workgroups
+  uint32_t vecs_per_wg;  // chunk length in vectors (multiple of kCtTileVecs)
+};
+
+template <int DT, bool EXACT>
+__global__ __launch_bounds__(kCtThreads) void compact_kernel(
+    const typename Elem<DT>::word_t* __restrict__ g, CompactGeom geo, const dct_threshold* __restrict__ thr,
+    int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out, uint32_t capacity,
+    uint64_t* __restrict__ count_out, CompactHeader* hdr) {
+  using E = Elem<DT>;
+  using word_t = typename E::word_t;
+  constexpr int V = E::kVec;
+  __shared__ uint32_t s_idx[kCtWaves][kCtStageCap];
+  __shared__ word_t s_val[kCtWaves][kCtStageCap];
+  __shared__ uint32_t s_wave_a[kCtWaves], s_wave_e[kCtWaves];
+  __shared__ uint64_t s_excl;
+
+  const uint32_t wg = blockIdx.x;
+  const uint32_t lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const bool first_wg = wg == 0, last_wg = wg == geo.grid - 1;
+
+  // ---- workspace: this call's descriptor set; the other one is cleared for the next call
+  const uint32_t magic = hdr->magic;
+  const uint32_t epoch = hdr->epoch;
+  if (magic != kCtMagic) {  // never initialised (uniform over the grid)
+    if (first_wg && threadIdx.x == 0) *count_out = DCT_COUNT_WORKSPACE_ERROR;
+    return;
+  }
+  DescSet* sets = reinterpret_cast<DescSet*>(reinterpret_cast<char*>(hdr) + kCtHeaderBytes);
+  DescSet* mine_set = sets + (epoch & 1u);
+  {
+    uint64_t* other = reinterpret_cast<uint64_t*>(sets + ((epoch & 1u) ^ 1u));
+    constexpr uint32_t kWords = sizeof(DescSet) / 8;
+    for (uint32_t i = wg * kCtThreads + threadIdx.x; i < kWords; i += geo.grid * kCtThreads) st_agent(other + i, 0ull);
+  }
+
+  const uint32_t tau = thr->tau_key;
+  const uint32_t quota = thr->tie_quota;
+  const uint32_t t_above = EXACT ? tau + 1u : tau;  // "A": key >= t_above; "E": key == tau (exactly-k only)
+
+  // ---- this wavefront's share: rows of 64 vectors [row_lo, row_hi) of the chunk [wg_lo, wg_hi)
+  const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
+  const uint32_t wg_lo = wg * geo.vecs_per_wg;
+  const uint32_t wg_hi = min(wg_lo + geo.vecs_per_wg, geo.n_vec);
+  const uint32_t rows_total = (wg_hi - wg_lo + kWave - 1) / kWave;
+  const uint32_t rows_per_wave = ((rows_total + kCtWaves - 1) / kCtWaves + kCtRows - 1) / kCtRows * kCtRows;
+  const uint32_t row_lo = min(static_cast<uint32_t>(wave) * rows_per_wave, rows_total);
+  const uint32_t row_hi = min(row_lo + rows_per_wave, rows_total);
+
+  const bool do_head = first_wg && wave == 0 && geo.head != 0;
+  const bool do_tail = last_wg && wave == kCtWaves - 1 && geo.tail != 0;
+  const uint32_t tail_base = geo.head + geo.n_vec * V;
+
+  // One pass over the wavefront's share.  DIRECT = false: stage survivors (ties
+  // flagged) in LDS and count; DIRECT = true: the exclusive counts are known, write
+  // to the final slots.  Leaves in wa / we the number of A / E elements seen.
+  uint32_t wa = 0, we = 0;
+  auto pass = [&](auto direct_tag, uint32_t a_before, uint32_t e_before) {
+    constexpr bool DIRECT = decltype(direct_tag)::value;
+    uint32_t staged = 0;  // STAGE: pairs appended so far (beyond the region they are only counted)
+    uint32_t na = 0, ne = 0;
+
+    // up to NE elements per lane: raw[e], validity, index of element 0
+    auto emit = [&](const uint32_t* raw, bool in, uint32_t index0, auto nelem_tag) {
+      constexpr int NE = decltype(nelem_tag)::value;
+      bool fa[NE], fe[NE];
+      uint32_t row_a = 0, row_e = 0;
 #pragma unroll
-  for (int r = 0; r < kCtRows; ++r) {
-    const uint32_t vi = v0 + r * kWave * V;
-    if constexpr (!GUARDED) {
-      v[r] = *reinterpret_cast<const uint4*>(g_al + vi);
-      valid[r] = (1u << V) - 1;
-    } else {
-      uint32_t w[4] = {0, 0, 0, 0};
-      uint32_t vm = 0;
+      for (int e = 0; e < NE; ++e) {
+        const uint32_t key = raw[e] & E::kKeyMask;
+        fa[e] = in && key >= t_above;
+        fe[e] = EXACT && in && key == tau;
+        row_a += __popcll(ballot64(fa[e]));
+        if constexpr (EXACT) row_e += __popcll(ballot64(fe[e]));
+      }
+      if (row_a + row_e != 0) {
+        if constexpr (!DIRECT) {
+          uint32_t slot = staged;
 #pragma unroll
-      for (int e = 0; e < V; ++e) {
-        const uint32_t ve = vi + e;
-        if (ve >= off && ve < n_virt) {
-          const uint32_t x = g_al[ve];
-          vm |= 1u << e;
-          if constexpr (V == 4) w[e] = x; else w[e >> 1] |= x << (16 * (e & 1));
+          for (int e = 0; e < NE; ++e) slot += lanes_below(ballot64(fa[e] || fe[e]));
+#pragma unroll
+          for (int e = 0; e < NE; ++e) {
+            if ((fa[e] || fe[e]) && slot < kCtStageCap) {
+              s_idx[wave][slot] = (index0 + e) | (fe[e] ? kTieFlag : 0u);
+              s_val[wave][slot] = static_cast<word_t>(raw[e]);
+            }
+            slot += (fa[e] || fe[e]) ? 1u : 0u;
+          }
+          staged += row_a + row_e;
+        } else {
+          // ties of this group that survive: those with global tie rank < quota
+          uint32_t tie_rank = e_before + ne;
+          const bool some_ties = EXACT && row_e != 0 && tie_rank < quota;
+          if (some_ties) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) tie_rank += lanes_below(ballot64(fe[e]));
+          }
+          uint32_t slot = a_before + na + (EXACT ? min(e_before + ne, quota) : 0u);
+          bool keep[NE];
+#pragma unroll
+          for (int e = 0; e < NE; ++e) {
+            keep[e] = fa[e] || (some_ties && fe[e] && tie_rank < quota);
+            tie_rank += fe[e] ? 1u : 0u;
+            slot += lanes_below(ballot64(keep[e]));
+          }
+#pragma unroll
+          for (int e = 0; e < NE; ++e) {
+            if (keep[e] && slot < capacity) {
+              idx_out[slot] = static_cast<int32_t>(index0 + e);
+              val_out[slot] = static_cast<word_t>(raw[e]);
+            }
+            slot += keep[e] ? 1u : 0u;
+          }
         }
       }
-      v[r] = make_uint4(w[0], w[1], w[2], w[3]);
-      valid[r] = vm;
-    }
-  }
+      na += row_a;
+      ne += row_e;
+    };
 
-  // ---- count survivors of this wavefront's rows
-  uint32_t wa = 0, we = 0;
-#pragma unroll
-  for (int r = 0; r < kCtRows; ++r) {
-#pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const uint32_t key = E::raw(v[r], e) & E::kKeyMask;
-      const bool ok = GUARDED ? ((valid[r] >> e) & 1u) != 0 : true;
-      wa += __popcll(ballot64(ok && key >= t_above));
-      if constexpr (EXACT) we += __popcll(ballot64(ok && key == tau));
+    if (do_head) {
+      const bool in = lane < geo.head;
+      const uint32_t raw = in ? static_cast<uint32_t>(g[lane]) : 0u;
+      emit(&raw, in, lane, std::integral_constant<int, 1>{});
     }
-  }
+    for (uint32_t row = row_lo; row < row_hi; row += kCtRows) {
+      const uint32_t vec0 = wg_lo + row * kWave + lane;
+      const bool full = wg_lo + (row + kCtRows) * kWave <= wg_hi;  // uniform
+      uint4 v[kCtRows];
+      if (full) {
+#pragma unroll
+        for (int r = 0; r < kCtRows; ++r) v[r] = gv[vec0 + r * kWave];
+      } else {
+#pragma unroll
+        for (int r = 0; r < kCtRows; ++r) {
+          const uint32_t vi = vec0 + r * kWave;
+          v[r] = vi < wg_hi ? gv[vi] : make_uint4(0, 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kCtRows; ++r) {
+        const uint32_t vi = vec0 + r * kWave;
+        uint32_t raw[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) raw[e] = E::raw(v[r], e);
+        emit(raw, full || vi < wg_hi, geo.head + vi * V, std::integral_constant<int, V>{});
+      }
+    }
+    if (do_tail) {
+      const bool in = lane < geo.tail;
+      const uint32_t raw = in ? static_cast<uint32_t>(g[tail_base + lane]) : 0u;
+      emit(&raw, in, tail_base + lane, std::integral_constant<int, 1>{});
+    }
+    wa = na;
+    we = ne;
+    return staged;
+  };
+
+  // ---- 1+2: stream the chunk, stage survivors in LDS
+  const uint32_t staged = pass(std::false_type{}, 0u, 0u);
   if (lane == 0) {
     s_wave_a[wave] = wa;
-    s_wave_e[wave] = we;
+    s_wave_e[wave] = we | (staged > kCtStageCap ? kTieFlag : 0u);  // top bit: this wavefront's region overflowed
   }
   __syncthreads();
 
-  // ---- wavefront 0: publish the tile count, look back for the exclusive prefix
+  // ---- 3: wavefront 0 publishes the counts and obtains the exclusive prefix
   if (wave == 0) {
     uint32_t ta = 0, te = 0;
 #pragma unroll
     for (int w = 0; w < kCtWaves; ++w) {
       ta += s_wave_a[w];
-      te += s_wave_e[w];
+      te += s_wave_e[w] & ~kTieFlag;
     }
     const uint64_t mine = pack(ta, te);
-    uint64_t excl = 0;
-    if (tile == 0) {
-      if (lane == 0) st_agent(desc, kStInclusive | mine);
-    } else {
-      if (lane == 0) st_agent(desc + tile, kStAggregate | mine);
-      bool failed = false;
-      excl = look_back(desc, static_cast<int>(tile), failed);
-      if (lane == 0) {
-        if (failed) atomicOr(&hdr->error, 1u);
-        st_agent(desc + tile, kStInclusive | ((excl + mine) & kPayload));
+    const uint32_t grp = wg / kCtGroup, member = wg % kCtGroup;
+    const bool leader = member == kCtGroup - 1;
+    bool failed = false;
+    if (lane == 0) st_agent(&mine_set->wg[wg], kStAggregate | mine);
+    const uint64_t before_in_group = sum_members(&mine_set->wg[grp * kCtGroup], member, &hdr->error, failed);
+    if (leader && grp != 0 && lane == 0)
+      st_agent(&mine_set->group[grp], kStAggregate | ((before_in_group + mine) & kPayload));
+    const uint64_t before_groups = group_prefix(mine_set->group, grp, &hdr->error, failed);
+    const uint64_t excl = (before_groups + before_in_group) & kPayload;
+    if (lane == 0) {
+      if (failed) {  // a predecessor never published: report it (the result of this call is void)
+        atomicOr(&hdr->error, 1u);
+        *count_out = DCT_COUNT_WORKSPACE_ERROR;
+        st_agent(&hdr->magic, 0u);
+      }
+      if (leader) st_agent(&mine_set->group[grp], kStInclusive | ((excl + mine) & kPayload));
+      s_excl = excl;
+      if (last_wg) {  // every other workgroup has read the epoch and published: finish the call
+        const uint64_t total = (excl + mine) & kPayload;
+        uint64_t c = cnt_a(total);
+        if (EXACT) c += min(cnt_e(total), quota);
+        const uint32_t err = __builtin_amdgcn_readfirstlane(ld_agent(&hdr->error));
+        if (failed || err != 0) {
+          *count_out = DCT_COUNT_WORKSPACE_ERROR;
+          st_agent(&hdr->magic, 0u);  // force a re-initialisation
+        } else {
+          *count_out = c;
+          st_agent(&hdr->epoch, epoch + 1u);
+        }
       }
     }
-    if (lane == 0) *s_excl = excl;
   }
   __syncthreads();
 
-  // ---- write survivors from registers
-  const uint64_t excl = *s_excl;
+  // ---- 4: final slots
+  const uint64_t excl = s_excl;
   uint32_t a_before = cnt_a(excl), e_before = cnt_e(excl);
-  for (int w = 0; w < wave; ++w) {
-    a_before += s_wave_a[w];
-    e_before += s_wave_e[w];
+  bool overflow = false;
+  for (int w = 0; w < kCtWaves; ++w) {
+    const uint32_t ew = s_wave_e[w];
+    overflow = overflow || (ew & kTieFlag) != 0;
+    if (w < wave) {
+      a_before += s_wave_a[w];
+      e_before += ew & ~kTieFlag;
+    }
   }
-#pragma unroll
-  for (int r = 0; r < kCtRows; ++r) {
-    bool fa[V], fe[V];
-    uint64_t ma[V], me[V];
-    uint32_t row_a = 0, row_e = 0;
-#pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const uint32_t key = E::raw(v[r], e) & E::kKeyMask;
-      const bool ok = GUARDED ? ((valid[r] >> e) & 1u) != 0 : true;
-      fa[e] = ok && key >= t_above;
-      ma[e] = ballot64(fa[e]);
-      row_a += __popcll(ma[e]);
-      if constexpr (EXACT) {
-        fe[e] = ok && key == tau;
-        me[e] = ballot64(fe[e]);
-        row_e += __popcll(me[e]);
-      } else {
-        fe[e] = false;
-        me[e] = 0;
-      }
+  if (overflow) {  // uniform over the workgroup: second pass over the chunk, straight to the outputs
+    pass(std::true_type{}, a_before, e_before);
+    return;
+  }
+  const uint32_t n_staged = wa + we;
+  const uint32_t ties_left = EXACT ? (quota > e_before ? quota - e_before : 0u) : 0u;
+  uint32_t out = a_before + (EXACT ? min(e_before, quota) : 0u);
+  uint32_t ties_seen = 0;
+  for (uint32_t j0 = 0; j0 < n_staged; j0 += kWave) {
+    const uint32_t j = j0 + lane;
+    const bool valid = j < n_staged;
+    const uint32_t ent = valid ? s_idx[wave][j] : 0u;
+    const bool is_tie = EXACT && (ent & kTieFlag) != 0;
+    const uint64_t m_tie = ballot64(is_tie);
+    const bool keep = valid && (!is_tie || ties_seen + lanes_below(m_tie) < ties_left);
+    const uint64_t m_keep = ballot64(keep);
+    const uint32_t slot = out + lanes_below(m_keep);
+    if (keep && slot < capacity) {
+      idx_out[slot] = static_cast<int32_t>(ent & ~kTieFlag);
+      val_out[slot] = s_val[wave][j];
     }
-    uint32_t out_base = a_before;
-    bool keep[V];
-    uint64_t mk[V];
-    if constexpr (EXACT) {
-      out_base += min(e_before, quota);
-      if (row_e == 0 || e_before >= quota) {          // no tie of this row survives
-#pragma unroll
-        for (int e = 0; e < V; ++e) { keep[e] = fa[e]; mk[e] = ma[e]; }
-      } else if (e_before + row_e <= quota) {          // every tie of this row survives
-#pragma unroll
-        for (int e = 0; e < V; ++e) { keep[e] = fa[e] || fe[e]; mk[e] = ma[e] | me[e]; }
-      } else {                                         // the quota runs out inside this row
-        uint32_t ties_in_lower_lanes = 0;
-#pragma unroll
-        for (int e = 0; e < V; ++e) ties_in_lower_lanes += lanes_below(me[e]);
-        uint32_t tie_rank = e_before + ties_in_lower_lanes;
-#pragma unroll
-        for (int e = 0; e < V; ++e) {
-          keep[e] = fa[e] || (fe[e] && tie_rank < quota);
-          tie_rank += fe[e] ? 1u : 0u;
-          mk[e] = ballot64(keep[e]);
-        }
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < V; ++e) { keep[e] = fa[e]; mk[e] = ma[e]; }
-    }
-    uint64_t any = 0;
-#pragma unroll
-    for (int e = 0; e < V; ++e) any |= mk[e];
-    if (any != 0) {
-      uint32_t slot = out_base;
-#pragma unroll
-      for (int e = 0; e < V; ++e) slot += lanes_below(mk[e]);
-      const uint32_t vi = v0 + r * kWave * V;
-#pragma unroll
-      for (int e = 0; e < V; ++e) {
-        if (keep[e]) {
-          if (slot < capacity) {
-            idx_out[slot] = static_cast<int32_t>(vi + e - off);
-            val_out[slot] = static_cast<typename E::word_t>(E::raw(v[r], e));
-          }
-          ++slot;
-        }
-      }
-    }
-    a_before += row_a;
-    e_before += row_e;
+    out += __popcll(m_keep);
+    ties_seen += __popcll(m_tie);
   }
 }
 
-template <int DT, bool EXACT>
-__global__ __launch_bounds__(kCtThreads) void compact_kernel(
-    const typename Elem<DT>::word_t* __restrict__ g_al, uint32_t off, uint32_t n_virt, uint32_t num_tiles,
-    const dct_threshold* __restrict__ thr, int32_t* __restrict__ idx_out,
-    typename Elem<DT>::word_t* __restrict__ val_out, uint32_t capacity, uint64_t* __restrict__ count_out,
-    CompactHeader* hdr) {
-  __shared__ uint32_t s_tile;
-  __shared__ uint32_t s_flag;
-  __shared__ uint32_t s_wave_a[kCtWaves], s_wave_e[kCtWaves];
-  __shared__ uint64_t s_excl;
-  constexpr uint32_t kTileElems = kCtThreads * kCtRows * Elem<DT>::kVec;
-  uint64_t* desc = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(hdr) + kCtHeaderBytes);
-
-  if (threadIdx.x == 0) {
-    const bool ok = hdr->magic == kCtMagic && hdr->n_desc >= num_tiles;
-    s_flag = ok ? 1u : 0u;
-    s_tile = ok ? atomicAdd(&hdr->ticket, 1u) : 0u;
+int cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
   }
-  __syncthreads();
-  if (s_flag == 0) {  // workspace was never initialised: report, touch nothing else
-    if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = DCT_COUNT_WORKSPACE_ERROR;
-    return;
-  }
-  const uint32_t tile = s_tile;
-  if (tile >= num_tiles) {  // ticket counter was not zero on entry: corrupted workspace
-    if (threadIdx.x == 0) {
-      *count_out = DCT_COUNT_WORKSPACE_ERROR;
-      st_agent(&hdr->magic, 0u);
-    }
-    return;
-  }
-  const uint32_t tau = thr->tau_key;
-  const uint32_t quota = thr->tie_quota;
-  const uint32_t t_above = EXACT ? tau + 1u : tau;
-
-  const uint32_t lo = tile * kTileElems;
-  const bool full = lo >= off && static_cast<uint64_t>(lo) + kTileElems <= n_virt;
-  if (full) {
-    process_tile<DT, false, EXACT>(g_al, off, n_virt, tile, t_above, tau, quota, idx_out, val_out, capacity, desc,
-                                   hdr, s_wave_a, s_wave_e, &s_excl);
-  } else {
-    process_tile<DT, true, EXACT>(g_al, off, n_virt, tile, t_above, tau, quota, idx_out, val_out, capacity, desc,
-                                  hdr, s_wave_a, s_wave_e, &s_excl);
-  }
-
-  // ---- completion: the workgroup that finishes last reports the count and
-  // clears the workspace for the next call.
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const uint32_t prev = __hip_atomic_fetch_add(&hdr->done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    s_flag = (prev == num_tiles - 1) ? 1u : 0u;
-  }
-  __syncthreads();
-  if (s_flag != 0) {
-    const uint64_t total = ld_agent(desc + (num_tiles - 1));
-    const bool bad = ld_agent(&hdr->error) != 0 || (total >> 62) != 2;
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < num_tiles; i += kCtThreads) st_agent(desc + i, 0ull);
-    if (threadIdx.x == 0) {
-      uint64_t c = cnt_a(total);
-      if (EXACT) c += min(cnt_e(total), quota);
-      *count_out = bad ? DCT_COUNT_WORKSPACE_ERROR : c;
-      st_agent(&hdr->ticket, 0u);
-      st_agent(&hdr->done, 0u);
-      st_agent(&hdr->error, 0u);
-      if (bad) st_agent(&hdr->magic, 0u);  // force a re-initialisation
-    }
-  }
+  return cached[dev];
 }
 
-uint32_t tile_elems(int dt) { return kCtTileBytes / (dt == DCT_F32 ? 4 : 2); }
+// Head / full vectors / tail split of n elements starting at address `addr`, and the chunking.
+CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt) {
+  const uint32_t es = dt == DCT_F32 ? 4 : 2;
+  const uint32_t vec = 16 / es;
+  CompactGeom geo;
+  uint64_t head = ((16 - (addr & 15)) & 15) / es;
+  if (head > n) head = n;
+  geo.head = static_cast<uint32_t>(head);
+  geo.n_vec = static_cast<uint32_t>((n - head) / vec);
+  geo.tail = static_cast<uint32_t>((n - head) % vec);
+  uint32_t tiles = (geo.n_vec + kCtTileVecs - 1) / kCtTileVecs;
+  if (tiles == 0) tiles = 1;
+  uint32_t max_grid = static_cast<uint32_t>(cu_count()) * kCtWgPerCu;
+  if (max_grid > kCtMaxGrid) max_grid = kCtMaxGrid;
+  const uint32_t tiles_per_wg = (tiles + max_grid - 1) / max_grid;
+  geo.grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+  geo.vecs_per_wg = tiles_per_wg * kCtTileVecs;
+  return geo;
+}
 
 }  // namespace
 }  // namespace dct
@@ -333,18 +416,14 @@ using namespace dct;
 
 extern "C" size_t dct_threshold_compact_workspace_bytes(int dt, uint64_t n) {
   if ((dt != DCT_F32 && dt != DCT_BF16) || n == 0 || n > 0x7FFFFFFFull) return 0;
-  // One descriptor per tile; +1 tile because a misaligned base shifts the tiling.
-  const uint64_t tiles = (n + 8) / tile_elems(dt) + 2;
-  return kCtHeaderBytes + tiles * sizeof(uint64_t);
+  return kCtWsBytes;
 }
 
 extern "C" int dct_threshold_compact_workspace_init(void* d_ws, size_t ws_bytes, void* hip_stream) {
-  if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < kCtHeaderBytes + 8 || ws_bytes > 0xFFFFFFFFull)
-    return DCT_ERR_WORKSPACE;
-  const uint32_t n_words = static_cast<uint32_t>(ws_bytes / 4);
-  const uint32_t n_desc = static_cast<uint32_t>((ws_bytes - kCtHeaderBytes) / 8);
+  if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < kCtWsBytes) return DCT_ERR_WORKSPACE;
+  const uint32_t n_words = static_cast<uint32_t>(kCtWsBytes / 4);
   hipLaunchKernelGGL(compact_ws_init_kernel, dim3((n_words + 255) / 256), dim3(256), 0,
-                     static_cast<hipStream_t>(hip_stream), static_cast<uint32_t*>(d_ws), n_words, n_desc);
+                     static_cast<hipStream_t>(hip_stream), static_cast<uint32_t*>(d_ws), n_words);
   return launch_status();
 }
 
@@ -358,26 +437,17 @@ extern "C" int dct_threshold_compact(const void* g, int dt, uint64_t n, const dc
   if (!is_aligned(g, es) || !is_aligned(d_thr, 16) || !is_aligned(d_count_out, 8)) return DCT_ERR_INVALID;
   if (capacity > 0 && (!d_idx_out || !d_val_out || !is_aligned(d_idx_out, 4) || !is_aligned(d_val_out, es)))
     return DCT_ERR_INVALID;
-  if (!d_ws || !is_aligned(d_ws, 256)) return DCT_ERR_WORKSPACE;
+  if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < kCtWsBytes) return DCT_ERR_WORKSPACE;
 
-  // Tiles are laid over the 16-byte-aligned address range that covers g: `off`
-  // leading virtual elements (and the ones past n) are masked out.
-  const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
-  const uint32_t off = static_cast<uint32_t>((addr & 15) / es);
-  const uint64_t n_virt = n + off;
-  const uint32_t te = tile_elems(dt);
-  const uint32_t num_tiles = static_cast<uint32_t>((n_virt + te - 1) / te);
-  if (ws_bytes < kCtHeaderBytes + static_cast<uint64_t>(num_tiles) * 8) return DCT_ERR_WORKSPACE;
-  const void* g_al = reinterpret_cast<const void*>(addr & ~static_cast<uintptr_t>(15));
+  const CompactGeom geo = make_geom(reinterpret_cast<uintptr_t>(g), n, dt);
   const uint32_t cap = capacity > 0xFFFFFFFFull ? 0xFFFFFFFFu : static_cast<uint32_t>(capacity);
   auto* hdr = static_cast<CompactHeader*>(d_ws);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const dim3 grid(num_tiles), block(kCtThreads);
+  const dim3 grid(geo.grid), block(kCtThreads);
 
-#define DCT_LAUNCH_COMPACT(DTV, EX)                                                                              \
-  hipLaunchKernelGGL((compact_kernel<DTV, EX>), grid, block, 0, s,                                               \
-                     static_cast<const Elem<DTV>::word_t*>(g_al), off, static_cast<uint32_t>(n_virt), num_tiles, \
-                     d_thr, d_idx_out, static_cast<Elem<DTV>::word_t*>(d_val_out), cap, d_count_out, hdr)
+#define DCT_LAUNCH_COMPACT(DTV, EX)                                                                          \
+  hipLaunchKernelGGL((compact_kernel<DTV, EX>), grid, block, 0, s, static_cast<const Elem<DTV>::word_t*>(g), \
+                     geo, d_thr, d_idx_out, static_cast<Elem<DTV>::word_t*>(d_val_out), cap, d_count_out, hdr)
   if (dt == DCT_F32) {
     if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_F32, true); else DCT_LAUNCH_COMPACT(DCT_F32, false);
   } else {
