@@ -377,18 +377,6 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
   }
 }
 
-int cu_count() {
-  static int cached[64] = {0};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
-}
-
 // Head / full vectors / tail split of n elements starting at address `addr`, and the chunking.
 CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt) {
   const uint32_t es = dt == DCT_F32 ? 4 : 2;
@@ -401,7 +389,7 @@ CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt) {
   geo.tail = static_cast<uint32_t>((n - head) % vec);
   uint32_t tiles = (geo.n_vec + kCtTileVecs - 1) / kCtTileVecs;
   if (tiles == 0) tiles = 1;
-  uint32_t max_grid = static_cast<uint32_t>(cu_count()) * kCtWgPerCu;
+  uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * kCtWgPerCu;
   if (max_grid > kCtMaxGrid) max_grid = kCtMaxGrid;
   const uint32_t tiles_per_wg = (tiles + max_grid - 1) / max_grid;
   geo.grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;

@@ -77,6 +77,19 @@ __device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
 
 inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Compute units of the current device (cached per device).
+inline int device_cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? DCT_OK : DCT_ERR_HIP; }
 
 }  // namespace dct

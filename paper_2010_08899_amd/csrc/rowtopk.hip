@@ -5,6 +5,7 @@
 // which is a gather of dy at the forward indices (no new selection: Sec. 2.2,
 // "the same mask is used").
 #include "dct_common.hpp"
+#include "rowtopk_fast.hpp"
 
 namespace dct {
 namespace {
@@ -163,6 +164,26 @@ extern "C" int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, ui
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
   if (grid > 65536u * 4) grid = 65536u * 4;
+  // bf16 rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, D <= 4096
+  if (dt == DCT_BF16 && D % 8 == 0 && D <= 4096 && is_aligned(x, 16) && row_stride_elems % 8 == 0) {
+    uint32_t fgrid = (B + fast::kWaves - 1) / fast::kWaves;
+    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 4u;
+    if (fgrid > resident) fgrid = resident;
+    const auto* xp = static_cast<const uint16_t*>(x);
+    auto* vp = static_cast<uint16_t*>(d_val_out);
+    auto* tp = static_cast<uint16_t*>(d_tau_out);
+    const dim3 g(fgrid), b(fast::kThreads);
+    if (D <= 512) {
+      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<1>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
+    } else if (D <= 1024) {
+      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<2>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
+    } else if (D <= 2048) {
+      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<4>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
+    } else {
+      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<8>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
+    }
+    return launch_status();
+  }
   if (dt == DCT_F32) {
     hipLaunchKernelGGL((rowtopk_fwd_generic_kernel<DCT_F32>), dim3(grid), dim3(kRtThreads), 0, s,
                        static_cast<const uint32_t*>(x), B, D, row_stride_elems, k, d_idx_out,

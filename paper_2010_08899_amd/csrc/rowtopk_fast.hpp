@@ -1,0 +1,283 @@
+// Fast forward kernel of dct_rowtopk_fwd for bf16 rows of up to 4096 columns
+// (Algorithm 2, forward loop: per row the k largest |X_act,i|).
+//
+// One wavefront owns one row at a time and keeps it on chip:
+//   1. the row is loaded once with coalesced 16-byte loads and written to a
+//      padded LDS buffer; every lane then reads back ITS 64 (or fewer) contiguous
+//      columns, so that column order is (lane, position in lane);
+//   2. keys (sign-cleared bit patterns) stay packed two per register with bit 15
+//      of each half set, so that one packed 16-bit subtract compares two keys with
+//      a threshold (the borrow lands in bit 15 / 31);
+//   3. tau_i is found exactly.  Rows of one matrix have similar thresholds, so the
+//      previous row's tau predicts a window of 64 key values: two packed compare
+//      sweeps give the per-lane bitmaps of the keys at or above the window's ends,
+//      the few keys inside the window are histogrammed (one LDS bin per lane) and
+//      a wave scan over the bins locates the k-th largest key.  If the window does
+//      not contain it (or there is no previous row) a bisection over the upper key
+//      bits narrows the range to 64 values first;
+//   4. ties at tau_i are resolved by column order with one wave scan of per-lane
+//      tie counts; survivors are then written from the per-lane bitmaps, the slot of
+//      each being (survivors in lower lanes) + (survivors at lower columns of the
+//      same lane).
+// Everything is integer work on the key bits; values are copied from the LDS copy
+// of the row bit for bit.
+#pragma once
+
+#include "dct_common.hpp"
+
+namespace dct {
+namespace fast {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr uint32_t kWindow = 64;
+
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, a) - __builtin_bit_cast(ushort2_t, b));
+}
+__device__ __forceinline__ uint32_t pk_add_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, a) + __builtin_bit_cast(ushort2_t, b));
+}
+__device__ __forceinline__ uint32_t pk_lshr15_u16(uint32_t a) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, a) >> static_cast<unsigned short>(15));
+}
+
+// Inclusive prefix sum over the 64 lanes with DPP row shifts and row broadcasts.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+  uint32_t v = x;
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_total(uint32_t x) {
+  return __builtin_amdgcn_readlane(wave_incl_scan(x), 63);
+}
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// NV = 16-byte vectors per lane: the lane owns columns [lane*NV*8, (lane+1)*NV*8).
+template <int NV>
+__global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
+    const uint16_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k,
+    int32_t* __restrict__ idx_out, uint16_t* __restrict__ val_out, uint16_t* __restrict__ tau_out) {
+  constexpr int REGS = 4 * NV;                      // packed registers per lane (2 columns each)
+  constexpr int RPW = REGS < 16 ? REGS : 16;        // registers per bitmap word
+  constexpr int WORDS = (REGS + 15) / 16;
+  constexpr int COLS = NV * 8;                      // columns per lane
+  constexpr int CHUNK = (NV + 1) * 16;              // LDS bytes per lane chunk (16 bytes of padding)
+  __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
+  __shared__ uint32_t s_hist[kWaves][kWave];
+
+  const int wave = threadIdx.x / kWave;
+  const uint32_t lane = lane_id();
+  char* row_lds = reinterpret_cast<char*>(s_row[wave]);
+  uint32_t* hist = s_hist[wave];
+  const uint32_t n_vec = D / 8;                     // the host guarantees D % 8 == 0
+
+  // bit (w, q) of a bitmap <-> register 16w + (q & 15), half q >> 4 <-> local column 2*reg + half
+  auto local_col = [](int w, uint32_t q) { return 2u * (16u * w + (q & 15u)) + (q >> 4); };
+  // bits of word m that belong to lower local columns than bit q of the same word
+  auto rank_in_word = [](uint32_t m, uint32_t q) {
+    const uint32_t i = q & 15u, odd = q >> 4;
+    return static_cast<uint32_t>(__popc((m & 0xFFFFu) & ((1u << (i + odd)) - 1u)) + __popc((m >> 16) & ((1u << i) - 1u)));
+  };
+  auto key_at = [&](uint32_t lc) {
+    return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(row_lds + lane * CHUNK + lc * 2));
+  };
+
+  uint32_t guess = 0xFFFFFFFFu;  // tau of the previous row of this wavefront; none yet
+
+  for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * kWaves + wave; row < B;
+       row += static_cast<uint64_t>(gridDim.x) * kWaves) {
+    // ---- 1. row -> LDS (padded) -> registers, lane-contiguous
+    const uint4* xr = reinterpret_cast<const uint4*>(x + row * stride);
+    wave_lds_fence();  // the previous row's readers are done with the buffer
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const uint32_t q = j * kWave + lane;
+      const uint4 v = q < n_vec ? xr[q] : make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<uint4*>(row_lds + (q / NV) * CHUNK + (q % NV) * 16) = v;
+    }
+    wave_lds_fence();
+    uint32_t K[REGS];
+#pragma unroll
+    for (int m = 0; m < NV; ++m) {
+      const uint4 v = *reinterpret_cast<const uint4*>(row_lds + lane * CHUNK + m * 16);
+      K[4 * m + 0] = (v.x & 0x7FFF7FFFu) | 0x80008000u;
+      K[4 * m + 1] = (v.y & 0x7FFF7FFFu) | 0x80008000u;
+      K[4 * m + 2] = (v.z & 0x7FFF7FFFu) | 0x80008000u;
+      K[4 * m + 3] = (v.w & 0x7FFF7FFFu) | 0x80008000u;
+    }
+
+    // per-lane bitmap of the keys >= t (t <= 0x8000)
+    auto ge_bitmap = [&](uint32_t t, uint32_t* out) {
+      const uint32_t t2 = t * 0x00010001u;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) {
+        uint32_t a = 0;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) a = (a >> 1) | (pk_sub_u16(K[16 * w + i], t2) & 0x80008000u);
+        out[w] = a >> (16 - RPW);
+      }
+    };
+    // number of keys >= t in the row
+    auto count_ge = [&](uint32_t t) {
+      const uint32_t t2 = t * 0x00010001u;
+      uint32_t acc = 0;
+#pragma unroll
+      for (int i = 0; i < REGS; ++i) acc = pk_add_u16(acc, pk_lshr15_u16(pk_sub_u16(K[i], t2)));
+      return wave_total((acc & 0xFFFFu) + (acc >> 16));
+    };
+
+    // ---- 3. locate tau
+    uint32_t above[WORDS], inwin[WORDS];
+    uint32_t wlo = 0, n_above = 0, n_win = 0;
+    bool hit = false;
+    if (guess != 0xFFFFFFFFu) {
+      wlo = guess >= kWindow / 2 ? guess - kWindow / 2 : 0u;
+      wlo = min(wlo, 0x8000u - kWindow);
+      uint32_t lo_bits[WORDS];
+      ge_bitmap(wlo, lo_bits);
+      ge_bitmap(wlo + kWindow, above);
+      uint32_t ca = 0, cw = 0;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) {
+        inwin[w] = lo_bits[w] & ~above[w];
+        ca += __popc(above[w]);
+        cw += __popc(inwin[w]);
+      }
+      n_above = wave_total(ca);
+      n_win = wave_total(cw);
+      hit = n_above < k && k <= n_above + n_win;
+    }
+    if (!hit) {
+      // bisection over the key bits above the window width: the largest multiple of
+      // 64 with at least k keys at or above it
+      uint32_t t = 0;
+      for (int bit = 14; bit >= 6; --bit) {
+        const uint32_t cand = t | (1u << bit);
+        if (count_ge(cand) >= k) t = cand;
+      }
+      wlo = t;  // a multiple of 64 below 0x8000, so wlo + 64 <= 0x8000
+      uint32_t lo_bits[WORDS];
+      ge_bitmap(wlo, lo_bits);
+      ge_bitmap(wlo + kWindow, above);
+      uint32_t ca = 0, cw = 0;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) {
+        inwin[w] = lo_bits[w] & ~above[w];
+        ca += __popc(above[w]);
+        cw += __popc(inwin[w]);
+      }
+      n_above = wave_total(ca);
+      n_win = wave_total(cw);
+    }
+
+    // histogram of the keys inside the window: bin = key - wlo, one bin per lane
+    hist[lane] = 0;
+    wave_lds_fence();
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) {
+      uint32_t m = inwin[w];
+      while (ballot64(m != 0) != 0) {
+        if (m != 0) {
+          const uint32_t q = __builtin_ctz(m);
+          m &= m - 1;
+          atomicAdd(&hist[(key_at(local_col(w, q)) & 0x7FFFu) - wlo], 1u);
+        }
+      }
+    }
+    wave_lds_fence();
+    const uint32_t c = hist[lane];
+    const uint32_t incl = wave_incl_scan(c);
+    const uint32_t suffix = n_win - incl + c;  // keys in bins >= lane
+    const uint64_t reach = ballot64(n_above + suffix >= k);  // non-empty: bin 0 reaches n_above + n_win >= k
+    const int bstar = 63 - __builtin_clzll(reach);
+    const uint32_t tau = wlo + bstar;
+    const uint32_t n_eq = __builtin_amdgcn_readlane(c, bstar);
+    const uint32_t n_gt = n_above + __builtin_amdgcn_readlane(suffix, bstar) - n_eq;
+    const uint32_t quota = k - n_gt;  // ties at tau to keep, lowest columns first
+    guess = tau;
+
+    // ---- keep / tie bitmaps: above the window, plus the window keys compared with tau
+    uint32_t keep[WORDS], tie[WORDS];
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) {
+      keep[w] = above[w];
+      tie[w] = 0;
+      uint32_t m = inwin[w];
+      while (ballot64(m != 0) != 0) {
+        if (m != 0) {
+          const uint32_t q = __builtin_ctz(m);
+          m &= m - 1;
+          const uint32_t key = key_at(local_col(w, q)) & 0x7FFFu;
+          if (key > tau) keep[w] |= 1u << q;
+          if (key == tau) tie[w] |= 1u << q;
+        }
+      }
+    }
+
+    // ---- 4. ties: the `quota` lowest columns among the n_eq ties survive
+    if (quota >= n_eq) {
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) keep[w] |= tie[w];
+    } else {
+      uint32_t tc = 0;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
+      const uint32_t before = wave_incl_scan(tc) - tc;     // ties in lower lanes
+      const uint32_t allowed = quota > before ? quota - before : 0u;  // ties this lane may keep
+      uint32_t seen = 0;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) {
+        uint32_t m = tie[w];
+        while (ballot64(m != 0) != 0) {
+          if (m != 0) {
+            const uint32_t q = __builtin_ctz(m);
+            m &= m - 1;
+            if (seen + rank_in_word(tie[w], q) < allowed) keep[w] |= 1u << q;
+          }
+        }
+        seen += __popc(tie[w]);
+      }
+    }
+
+    // ---- write the survivors: slot = survivors in lower lanes + survivors at lower columns of this lane
+    uint32_t kc = 0;
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
+    uint32_t base = wave_incl_scan(kc) - kc;
+    int32_t* io = idx_out + row * k;
+    uint16_t* vo = val_out + row * k;
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) {
+      uint32_t m = keep[w];
+      while (ballot64(m != 0) != 0) {
+        if (m != 0) {
+          const uint32_t q = __builtin_ctz(m);
+          m &= m - 1;
+          const uint32_t lc = local_col(w, q);
+          const uint32_t slot = base + rank_in_word(keep[w], q);
+          if (slot < k) {
+            io[slot] = static_cast<int32_t>(lane * COLS + lc);
+            vo[slot] = static_cast<uint16_t>(key_at(lc));
+          }
+        }
+      }
+      base += __popc(keep[w]);
+    }
+    if (tau_out && lane == 0) tau_out[row] = static_cast<uint16_t>(tau);
+  }
+}
+
+}  // namespace fast
+}  // namespace dct
