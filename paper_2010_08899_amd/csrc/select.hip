@@ -3,49 +3,85 @@
 // gradient (the copy-and-sort routine is what Sec. 3.3 measures as the cost of
 // recomputing the threshold every iteration).
 //
-// Radix select over the key bits, most significant digit first (11 + 11 + 9 bits
-// for fp32, 8 + 7 for bf16).  Each pass streams the vector with 16-byte loads,
-// histograms the current digit of the keys that match the digits fixed so far
-// into a per-workgroup LDS histogram, and merges it into a global one.  The
-// workgroup that finishes a pass last walks the histogram from the top bin down,
-// finds the bin that holds the k-th largest key and narrows the search state for
-// the next pass; after the last pass it writes the dct_threshold.  All arithmetic
-// is on integers.
+// The exact part is a radix select over the key bits, most significant digit
+// first (11 + 11 + 9 bits for fp32, 8 + 7 for bf16): each pass histograms one
+// digit of the keys that match the digits fixed so far (LDS histogram per
+// workgroup, merged into a global one), and the next kernel walks the histogram
+// from the top bin down to find the bin of the k-th largest key.
+//
+// For large vectors the radix passes do not run over the vector.  A first kernel
+// reads a stratified sample of 16384 keys and takes two of its order statistics
+// as bounds lo <= tau <= hi that hold with overwhelming probability.  One
+// streaming pass over the vector (coalesced 16-byte loads, one contiguous chunk
+// per workgroup) counts the keys above hi and appends the keys in [lo, hi] --
+// well under 1 % of the vector -- to a candidate buffer through LDS staging.  The
+// radix passes then run over the candidates only, so the vector is read from HBM
+// once.  The counts tell exactly whether the bounds held (n_above < k <= n_above
+// + n_candidates, no buffer overflow); if they did not, the same radix passes run
+// over the whole vector instead, decided on the device, so the result is always
+// the exact order statistic.  All arithmetic is on integers.
 #include "dct_common.hpp"
 
 namespace dct {
 namespace {
 
 constexpr int kSelThreads = 256;
+constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelBins = 2048;
 constexpr int kSelMaxPasses = 3;
-constexpr int kSelUnroll = 4;  // 16-byte loads in flight per lane
+constexpr int kSelUnroll = 4;                   // 16-byte loads in flight per lane in the radix passes
+constexpr uint32_t kSelMaxGrid = 4096;
+
+constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes run over the vector itself
+constexpr int kSampleThreads = 1024;
+constexpr uint32_t kSampleSize = 16384;         // 64 KiB of LDS
+constexpr int kPartRows = 8;                    // 16-byte loads per lane per iteration of the partition pass
+constexpr uint32_t kPartStage = 1024;           // staged candidate keys per wavefront
+constexpr uint32_t kPartTileVecs = kSelThreads * kPartRows;
 
 struct SelState {
-  uint32_t prefix;  // digits fixed so far, in place
-  uint32_t k_rem;   // rank still to find inside the matching keys (1-based from the top)
-  uint32_t n_gt;    // keys known to be above every matching key
-  uint32_t pad;
+  uint32_t prefix;     // digits fixed so far, in place
+  uint32_t k_rem;      // rank still to find among the matching keys (1-based from the top)
+  uint32_t n_gt;       // keys known to be above every matching key
+  uint32_t from_cand;  // 1: the passes read the candidate buffer, 0: the vector
+  uint32_t n_src;      // keys in the source
+  uint32_t pad[3];
 };
 
 struct SelWs {
-  SelState state[kSelMaxPasses + 1];
-  uint32_t done[kSelMaxPasses];
-  uint32_t pad[13];
+  unsigned long long counts;  // partition pass: keys > hi (high word), keys in [lo, hi] (low word; may exceed the buffer)
+  uint32_t lo, hi;     // bounds from the sample
+  uint32_t sampled;    // 1 when the sample / partition kernels ran
+  uint32_t cand_cap;
+  uint32_t pad[2];
+  SelState state[kSelMaxPasses + 1];  // state[p]: search state at the start of pass p
   uint32_t hist[kSelMaxPasses][kSelBins];
+  uint32_t cand[4];    // candidate keys follow (cand_cap of them)
 };
 
-__global__ void select_init_kernel(SelWs* ws, uint32_t k) {
-  uint32_t* w = reinterpret_cast<uint32_t*>(ws);
-  const uint32_t n_words = sizeof(SelWs) / 4;
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) w[i] = 0;
-  __syncthreads();
-  if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[0].k_rem = k;  // block 0 owns word 1 (i < 256)
+struct PassDigits {
+  int n_pass;
+  int shift[kSelMaxPasses];
+  int width[kSelMaxPasses];
+};
+__host__ __device__ inline PassDigits pass_digits(int dt) {
+  PassDigits d;
+  if (dt == DCT_F32) {
+    d.n_pass = 3;
+    d.shift[0] = 20; d.shift[1] = 9; d.shift[2] = 0;
+    d.width[0] = 11; d.width[1] = 11; d.width[2] = 9;
+  } else {
+    d.n_pass = 2;
+    d.shift[0] = 7; d.shift[1] = 0; d.shift[2] = 0;
+    d.width[0] = 8; d.width[1] = 7; d.width[2] = 0;
+  }
+  return d;
 }
 
 // One histogram update.  Lanes whose digit equals the first active lane's digit
 // are counted with one ballot and a single LDS add (skewed data such as a mostly
-// zero gradient would otherwise serialise on one bin); the others add directly.
+// zero gradient, or candidates that share their top digits, would otherwise
+// serialise on one bin); the others add directly.
 __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digit) {
   const uint64_t act = ballot64(active);
   if (act == 0) return;
@@ -57,124 +93,395 @@ __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digi
   if (active && !same) atomicAdd(&h[digit], 1u);
 }
 
-template <int DT>
-__global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
-    const typename Elem<DT>::word_t* __restrict__ g_al, uint32_t off, uint32_t n_virt, SelWs* ws, int pass,
-    int shift, int width, uint32_t fixed_mask, int last_pass, dct_threshold* __restrict__ thr_out) {
-  using E = Elem<DT>;
-  constexpr int V = E::kVec;
-  __shared__ uint32_t h[kSelBins];
-  __shared__ uint32_t s_scan[kSelThreads];
-  __shared__ uint32_t s_last;
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) h[i] = 0;
-  const SelState st = ws->state[pass];
-  const uint32_t prefix = st.prefix;
-  const uint32_t dmask = (1u << width) - 1u;
-  __syncthreads();
+// Inclusive prefix sum over the lanes of a wavefront (DPP row shifts + broadcasts).
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+  uint32_t v = x;
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);
+  return v;
+}
 
-  // Vectors [v_lo, v_hi) are entirely inside the data; at most one vector on each
-  // side straddles an end and is read element by element by workgroup 0.
-  const uint32_t v_lo = off ? 1u : 0u;
-  const uint32_t v_hi = n_virt / V;
-  const uint4* gv = reinterpret_cast<const uint4*>(g_al);
-  const uint32_t span = kSelThreads * kSelUnroll;
-  for (uint32_t base = v_lo + blockIdx.x * span; base < v_hi; base += gridDim.x * span) {
-    uint4 v[kSelUnroll];
-    bool in[kSelUnroll];
-#pragma unroll
-    for (int u = 0; u < kSelUnroll; ++u) {
-      const uint32_t vi = base + u * kSelThreads + threadIdx.x;
-      in[u] = vi < v_hi;
-      v[u] = in[u] ? gv[vi] : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < kSelUnroll; ++u) {
-#pragma unroll
-      for (int e = 0; e < V; ++e) {
-        const uint32_t key = E::raw(v[u], e) & E::kKeyMask;
-        hist_add(h, in[u] && (key & fixed_mask) == prefix, (key >> shift) & dmask);
-      }
-    }
-  }
-  if (blockIdx.x == 0) {
-    // head elements [off, min(V, n_virt)) when the base is misaligned, tail elements [v_hi*V, n_virt)
-    const uint32_t t = threadIdx.x;
-    uint32_t ve = 0xFFFFFFFFu;
-    if (t < static_cast<uint32_t>(V)) {
-      if (off && t >= off && t < n_virt) ve = t;
-    } else if (t < 2u * V) {
-      const uint32_t c = v_hi * V + (t - V);
-      if (c < n_virt && (c >= static_cast<uint32_t>(V) || !off)) ve = c;
-    }
-    const bool act = ve != 0xFFFFFFFFu;
-    const uint32_t key = act ? (static_cast<uint32_t>(g_al[ve]) & E::kKeyMask) : 0u;
-    if (t < kWave) hist_add(h, act && (key & fixed_mask) == prefix, (key >> shift) & dmask);
-  }
-  __syncthreads();
-
-  // merge into the global histogram of this pass
-  uint32_t* gh = ws->hist[pass];
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) {
-    const uint32_t c = h[i];
-    if (c) atomicAdd(&gh[i], c);
-  }
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const uint32_t prev = __hip_atomic_fetch_add(&ws->done[pass], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (prev == gridDim.x - 1) ? 1u : 0u;
-  }
-  __syncthreads();
-  if (s_last == 0) return;
-
-  // ---- last workgroup: find the bin of the k_rem-th largest matching key.
-  // Thread t owns the 8 bins [2047-8t-7, 2047-8t], walked from the top down.
-  constexpr int kPer = kSelBins / kSelThreads;
+// Walk a 2048-bin histogram from the top bin down and find the bin that holds the
+// k_rem-th largest key.  Called by all THREADS threads of a workgroup (THREADS a
+// multiple of 64 that divides 2048); s_tmp needs THREADS / 64 + 4 words.  Returns
+// {bin, keys in higher bins, keys in the bin} to every thread.
+struct BinHit {
+  uint32_t bin, above, count;
+};
+template <int THREADS, typename LoadBin>
+__device__ BinHit find_bin(LoadBin load_bin, uint32_t k_rem, uint32_t* s_tmp) {
+  constexpr int kPer = kSelBins / THREADS;
+  constexpr int kW = THREADS / kWave;
+  const uint32_t t = threadIdx.x;
   uint32_t c[kPer];
   uint32_t sum = 0;
 #pragma unroll
   for (int j = 0; j < kPer; ++j) {
-    c[j] = ld_agent(&gh[kSelBins - 1 - (threadIdx.x * kPer + j)]);
+    c[j] = load_bin(kSelBins - 1 - (t * kPer + j));
     sum += c[j];
   }
-  s_scan[threadIdx.x] = sum;
+  const uint32_t incl_w = wave_incl_scan(sum);
+  if (lane_id() == kWave - 1) s_tmp[t / kWave] = incl_w;
   __syncthreads();
-  // inclusive scan over threads (Hillis-Steele, 256 entries)
-  for (int d = 1; d < kSelThreads; d <<= 1) {
-    const uint32_t add = threadIdx.x >= static_cast<uint32_t>(d) ? s_scan[threadIdx.x - d] : 0u;
-    __syncthreads();
-    s_scan[threadIdx.x] += add;
-    __syncthreads();
-  }
-  const uint32_t incl = s_scan[threadIdx.x];
-  uint32_t above = incl - sum;  // matching keys in bins above this thread's bins
-  const uint32_t k_rem = st.k_rem;
+  uint32_t before_waves = 0;
+  for (uint32_t w = 0; w < t / kWave; ++w) before_waves += s_tmp[w];
+  const uint32_t incl = before_waves + incl_w;
+  uint32_t above = incl - sum;
   if (above < k_rem && k_rem <= incl) {
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
       if (above < k_rem && k_rem <= above + c[j]) {
-        const uint32_t bin = kSelBins - 1 - (threadIdx.x * kPer + j);
-        const uint32_t new_prefix = prefix | (bin << shift);
-        if (last_pass) {
-          thr_out->tau_key = new_prefix;
-          thr_out->n_gt = st.n_gt + above;
-          thr_out->n_eq = c[j];
-          thr_out->tie_quota = k_rem - above;
-        } else {
-          SelState nx;
-          nx.prefix = new_prefix;
-          nx.k_rem = k_rem - above;
-          nx.n_gt = st.n_gt + above;
-          nx.pad = 0;
-          ws->state[pass + 1] = nx;
-        }
-        above = 0xFFFFFFFFu;  // found: stop matching the following bins
+        s_tmp[kW + 0] = kSelBins - 1 - (t * kPer + j);
+        s_tmp[kW + 1] = above;
+        s_tmp[kW + 2] = c[j];
+        above = 0xFFFFFFFFu;
       } else if (above != 0xFFFFFFFFu) {
         above += c[j];
       }
     }
   }
+  __syncthreads();
+  BinHit r;
+  r.bin = s_tmp[kW + 0];
+  r.above = s_tmp[kW + 1];
+  r.count = s_tmp[kW + 2];
+  __syncthreads();
+  return r;
 }
+
+// ------------------------------------------------------------------ kernel 1a
+// Clears the workspace for the direct (no sample) path.
+__global__ void select_init_kernel(SelWs* ws, uint32_t k, uint32_t n) {
+  uint32_t* w = reinterpret_cast<uint32_t*>(ws);
+  const uint32_t n_words = offsetof(SelWs, cand) / 4;
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) w[i] = 0;
+}
+
+// ------------------------------------------------------------------ kernel 1b
+// One workgroup: clear the workspace, read a stratified sample of the keys into
+// LDS and select two order statistics of it as bounds for tau.
+template <int DT>
+__global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
+    const typename Elem<DT>::word_t* __restrict__ g, uint32_t n, uint32_t k, SelWs* ws, uint32_t cand_cap) {
+  using E = Elem<DT>;
+  __shared__ uint32_t s_keys[kSampleSize];
+  __shared__ uint32_t s_hist[kSelBins];
+  __shared__ uint32_t s_tmp[kSampleThreads / kWave + 4];
+  const uint32_t t = threadIdx.x;
+  {
+    uint32_t* w = reinterpret_cast<uint32_t*>(ws);
+    const uint32_t n_words = offsetof(SelWs, cand) / 4;
+    for (uint32_t i = t; i < n_words; i += kSampleThreads) w[i] = 0;
+  }
+  // stratum i covers [i*n/S, (i+1)*n/S); one key at a hashed offset inside it
+  const uint64_t stratum = n / kSampleSize;  // >= 256 by the choice of kSampleMinN
+  for (uint32_t i = t; i < kSampleSize; i += kSampleThreads) {
+    const uint64_t start = static_cast<uint64_t>(i) * n / kSampleSize;
+    const uint32_t h = (i * 2654435761u) ^ ((i * 40503u) >> 7);
+    const uint64_t pos = start + h % stratum;
+    s_keys[i] = static_cast<uint32_t>(g[pos]) & E::kKeyMask;
+  }
+  __syncthreads();
+
+  // sample ranks (1-based from the top) that bracket rank k of the vector with a
+  // margin of six standard deviations of the sample count, plus slack
+  const uint64_t r = static_cast<uint64_t>(k) * kSampleSize / n;
+  uint32_t sq = 0;
+  while (static_cast<uint64_t>(sq + 1) * (sq + 1) <= r) ++sq;
+  const uint64_t delta = 6ull * (sq + 1) + 16;
+  const uint64_t rank_hi = r > delta ? r - delta : 0;                     // 0: no upper bound
+  const uint64_t rank_lo = r + delta + 1 <= kSampleSize ? r + delta + 1 : 0;  // 0: no lower bound
+
+  const PassDigits dg = pass_digits(DT);
+  uint32_t bound[2] = {E::kKeyMask, 0u};  // {hi, lo}
+  for (int which = 0; which < 2; ++which) {
+    const uint32_t rank = static_cast<uint32_t>(which == 0 ? rank_hi : rank_lo);
+    if (rank == 0) continue;  // uniform
+    uint32_t prefix = 0, fixed_mask = 0, k_rem = rank;
+    for (int p = 0; p < dg.n_pass; ++p) {
+      const int shift = dg.shift[p];
+      const uint32_t dmask = (1u << dg.width[p]) - 1u;
+      for (uint32_t i = t; i < kSelBins; i += kSampleThreads) s_hist[i] = 0;
+      __syncthreads();
+      for (uint32_t i = t; i < kSampleSize; i += kSampleThreads) {
+        const uint32_t key = s_keys[i];
+        hist_add(s_hist, (key & fixed_mask) == prefix, (key >> shift) & dmask);
+      }
+      __syncthreads();
+      const BinHit hit = find_bin<kSampleThreads>([&](uint32_t b) { return s_hist[b]; }, k_rem, s_tmp);
+      prefix |= hit.bin << shift;
+      fixed_mask |= dmask << shift;
+      k_rem -= hit.above;
+    }
+    bound[which] = prefix;
+  }
+  if (t == 0) {
+    ws->hi = bound[0];
+    ws->lo = bound[1];
+    ws->sampled = 1;
+    ws->cand_cap = cand_cap;
+  }
+}
+
+// ------------------------------------------------------------------ kernel 2
+// Streaming partition pass: count keys > hi, append keys in [lo, hi] to the
+// candidate buffer.  One contiguous chunk per workgroup, a contiguous quarter per
+// wavefront; candidates are staged in LDS and flushed with one slot reservation
+// per flush (their order is irrelevant: only the multiset of keys matters).
+struct PartGeom {
+  uint32_t head, n_vec, tail, grid, vecs_per_wg;
+};
+
+template <int DT>
+__global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
+    const typename Elem<DT>::word_t* __restrict__ g, PartGeom geo, SelWs* ws) {
+  using E = Elem<DT>;
+  constexpr int V = E::kVec;
+  __shared__ uint32_t s_stage[kSelWaves][kPartStage];
+  const uint32_t lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const uint32_t wg = blockIdx.x;
+  const uint32_t lo = ws->lo, hi = ws->hi, cand_cap = ws->cand_cap;
+  const uint32_t span = hi - lo;  // lo <= key <= hi  <=>  key - lo <= span (unsigned)
+  uint32_t* stage = s_stage[wave];
+  uint32_t staged = 0, above = 0;
+  __shared__ uint32_t s_cnt[kSelWaves], s_abv[kSelWaves], s_base;
+
+  // Mid-chunk flush of one wavefront's staging region (only when it fills up).
+  auto flush = [&]() {
+    if (staged == 0) return;
+    uint32_t base = 0;
+    if (lane == 0) base = static_cast<uint32_t>(atomicAdd(&ws->counts, static_cast<unsigned long long>(staged)));
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (uint32_t i = lane; i < staged; i += kWave)
+      if (base + i < cand_cap) ws->cand[base + i] = stage[i];
+    staged = 0;
+  };
+  // NE keys per lane
+  auto take = [&](const uint32_t* raw, bool in, auto ne_tag) {
+    constexpr int NE = decltype(ne_tag)::value;
+    bool c[NE];
+    uint32_t n_c = 0;
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      const uint32_t key = raw[e] & E::kKeyMask;
+      above += __popcll(ballot64(in && key > hi));
+      c[e] = in && key - lo <= span;
+      n_c += __popcll(ballot64(c[e]));
+    }
+    if (n_c != 0) {
+      if (staged + n_c > kPartStage) flush();  // n_c <= 64 * NE <= 512 <= kPartStage
+      uint32_t slot = staged;
+#pragma unroll
+      for (int e = 0; e < NE; ++e) slot += lanes_below(ballot64(c[e]));
+#pragma unroll
+      for (int e = 0; e < NE; ++e) {
+        if (c[e]) stage[slot] = raw[e] & E::kKeyMask;
+        slot += c[e] ? 1u : 0u;
+      }
+      staged += n_c;
+    }
+  };
+
+  const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
+  const uint32_t wg_lo = wg * geo.vecs_per_wg;
+  const uint32_t wg_hi = min(wg_lo + geo.vecs_per_wg, geo.n_vec);
+  const uint32_t rows_total = (wg_hi - wg_lo + kWave - 1) / kWave;
+  const uint32_t rows_per_wave = ((rows_total + kSelWaves - 1) / kSelWaves + kPartRows - 1) / kPartRows * kPartRows;
+  const uint32_t row_lo = min(static_cast<uint32_t>(wave) * rows_per_wave, rows_total);
+  const uint32_t row_hi = min(row_lo + rows_per_wave, rows_total);
+
+  if (wg == 0 && wave == 0 && geo.head != 0) {
+    const bool in = lane < geo.head;
+    const uint32_t raw = in ? static_cast<uint32_t>(g[lane]) : 0u;
+    take(&raw, in, std::integral_constant<int, 1>{});
+  }
+  for (uint32_t row = row_lo; row < row_hi; row += kPartRows) {
+    const uint32_t vec0 = wg_lo + row * kWave + lane;
+    const bool full = wg_lo + (row + kPartRows) * kWave <= wg_hi;  // uniform
+    uint4 v[kPartRows];
+    if (full) {
+#pragma unroll
+      for (int r = 0; r < kPartRows; ++r) v[r] = gv[vec0 + r * kWave];
+    } else {
+#pragma unroll
+      for (int r = 0; r < kPartRows; ++r) {
+        const uint32_t vi = vec0 + r * kWave;
+        v[r] = vi < wg_hi ? gv[vi] : make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < kPartRows; ++r) {
+      uint32_t raw[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) raw[e] = E::raw(v[r], e);
+      take(raw, full || vec0 + r * kWave < wg_hi, std::integral_constant<int, V>{});
+    }
+  }
+  if (wg == geo.grid - 1 && wave == kSelWaves - 1 && geo.tail != 0) {
+    const bool in = lane < geo.tail;
+    const uint32_t raw = in ? static_cast<uint32_t>(g[geo.head + geo.n_vec * V + lane]) : 0u;
+    take(&raw, in, std::integral_constant<int, 1>{});
+  }
+  // end of the chunk: one reservation for the whole workgroup (both counts in one 64-bit add)
+  if (lane == 0) {
+    s_cnt[wave] = staged;
+    s_abv[wave] = above;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t c = 0, a = 0;
+    for (int w = 0; w < kSelWaves; ++w) {
+      c += s_cnt[w];
+      a += s_abv[w];
+    }
+    uint32_t base = 0;
+    if (c != 0 || a != 0)
+      base = static_cast<uint32_t>(atomicAdd(&ws->counts, (static_cast<unsigned long long>(a) << 32) | c));
+    s_base = base;
+  }
+  __syncthreads();
+  uint32_t base = s_base;
+  for (int w = 0; w < wave; ++w) base += s_cnt[w];
+  for (uint32_t i = lane; i < staged; i += kWave)
+    if (base + i < cand_cap) ws->cand[base + i] = stage[i];
+}
+
+// ------------------------------------------------------------------ kernel 3
+// One radix pass.  Every workgroup first derives the search state of this pass
+// (from the partition counts for pass 0, from the previous pass's histogram
+// otherwise), then histograms its part of the source.
+template <int DT>
+__global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
+    const typename Elem<DT>::word_t* __restrict__ g_al, uint32_t off, uint32_t n_virt, uint32_t k, SelWs* ws,
+    int pass, int shift, int width, int prev_shift) {
+  using E = Elem<DT>;
+  constexpr int V = E::kVec;
+  __shared__ uint32_t h[kSelBins];
+  __shared__ uint32_t s_tmp[kSelWaves + 4];
+  const uint32_t span = kSelThreads * kSelUnroll;  // vectors per workgroup per iteration
+
+  // ---- search state at the start of this pass
+  SelState st;
+  if (pass == 0) {
+    const unsigned long long counts = ws->counts;
+    const uint32_t n_above = static_cast<uint32_t>(counts >> 32), n_cand = static_cast<uint32_t>(counts);
+    const bool ok = ws->sampled != 0 && n_cand <= ws->cand_cap && n_above < k && k <= n_above + n_cand;
+    st.prefix = 0;
+    st.k_rem = ok ? k - n_above : k;
+    st.n_gt = ok ? n_above : 0u;
+    st.from_cand = ok ? 1u : 0u;
+    st.n_src = ok ? n_cand : n_virt - off;
+  } else {
+    st = ws->state[pass - 1];
+  }
+  // vectors of the source; a workgroup with nothing to read leaves at once
+  const uint32_t src_vecs = st.from_cand ? (st.n_src + 3) / 4 : n_virt / V + 1;
+  if (blockIdx.x != 0 && blockIdx.x * span >= src_vecs) return;
+  if (pass != 0) {
+    const uint32_t* prev = ws->hist[pass - 1];
+    const BinHit hit = find_bin<kSelThreads>([&](uint32_t b) { return prev[b]; }, st.k_rem, s_tmp);
+    st.prefix |= hit.bin << prev_shift;
+    st.k_rem -= hit.above;
+    st.n_gt += hit.above;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[pass] = st;
+
+  const uint32_t dmask = (1u << width) - 1u;
+  const uint32_t fixed_mask = E::kKeyMask & ~((1u << (shift + width)) - 1u);
+  const uint32_t prefix = st.prefix;
+  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) h[i] = 0;
+  __syncthreads();
+
+  if (st.from_cand) {
+    // candidate keys: u32, 16-byte-aligned buffer, n_src of them
+    const uint4* cv = reinterpret_cast<const uint4*>(ws->cand);
+    const uint32_t n_src = st.n_src;
+    for (uint32_t base = blockIdx.x * span; base < src_vecs; base += gridDim.x * span) {
+      uint4 v[kSelUnroll];
+#pragma unroll
+      for (int u = 0; u < kSelUnroll; ++u) {
+        const uint32_t vi = base + u * kSelThreads + threadIdx.x;
+        v[u] = vi < src_vecs ? cv[vi] : make_uint4(0, 0, 0, 0);  // the buffer is padded to whole vectors
+      }
+#pragma unroll
+      for (int u = 0; u < kSelUnroll; ++u) {
+        const uint32_t e0 = (base + u * kSelThreads + threadIdx.x) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t key = Elem<DCT_F32>::raw(v[u], e);
+          hist_add(h, e0 + e < n_src && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+        }
+      }
+    }
+  } else {
+    // the vector itself.  Vectors [v_lo, v_hi) are entirely inside the data; at most one
+    // vector on each side straddles an end and is read element by element by workgroup 0.
+    const uint32_t v_lo = off ? 1u : 0u;
+    const uint32_t v_hi = n_virt / V;
+    const uint4* gv = reinterpret_cast<const uint4*>(g_al);
+    for (uint32_t base = v_lo + blockIdx.x * span; base < v_hi; base += gridDim.x * span) {
+      uint4 v[kSelUnroll];
+      bool in[kSelUnroll];
+#pragma unroll
+      for (int u = 0; u < kSelUnroll; ++u) {
+        const uint32_t vi = base + u * kSelThreads + threadIdx.x;
+        in[u] = vi < v_hi;
+        v[u] = in[u] ? gv[vi] : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < kSelUnroll; ++u) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const uint32_t key = E::raw(v[u], e) & E::kKeyMask;
+          hist_add(h, in[u] && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+        }
+      }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < kWave) {
+      // head elements [off, min(V, n_virt)) of a misaligned base, tail elements [v_hi*V, n_virt)
+      const uint32_t t = threadIdx.x;
+      uint32_t ve = 0xFFFFFFFFu;
+      if (t < static_cast<uint32_t>(V)) {
+        if (off && t >= off && t < n_virt) ve = t;
+      } else if (t < 2u * V) {
+        const uint32_t c = v_hi * V + (t - V);
+        if (c < n_virt && (c >= static_cast<uint32_t>(V) || !off)) ve = c;
+      }
+      const bool act = ve != 0xFFFFFFFFu;
+      const uint32_t key = act ? (static_cast<uint32_t>(g_al[ve]) & E::kKeyMask) : 0u;
+      hist_add(h, act && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = ws->hist[pass];
+  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) {
+    const uint32_t c = h[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+}
+
+// ------------------------------------------------------------------ kernel 4
+// One workgroup: the last histogram fixes the remaining digits; write the result.
+__global__ __launch_bounds__(kSelThreads) void select_finish_kernel(SelWs* ws, int last, int last_shift,
+                                                                    dct_threshold* __restrict__ out) {
+  __shared__ uint32_t s_tmp[kSelWaves + 4];
+  const SelState st = ws->state[last];
+  const uint32_t* hist = ws->hist[last];
+  const BinHit hit = find_bin<kSelThreads>([&](uint32_t b) { return hist[b]; }, st.k_rem, s_tmp);
+  if (threadIdx.x == 0) {
+    out->tau_key = st.prefix | (hit.bin << last_shift);
+    out->n_gt = st.n_gt + hit.above;
+    out->n_eq = hit.count;
+    out->tie_quota = st.k_rem - hit.above;
+  }
+}
+
+uint32_t cand_capacity(uint64_t n) { return n >= kSampleMinN ? static_cast<uint32_t>(n / 64 + 65536) : 0u; }
 
 }  // namespace
 }  // namespace dct
@@ -183,7 +490,7 @@ using namespace dct;
 
 extern "C" size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n) {
   if ((dt != DCT_F32 && dt != DCT_BF16) || n == 0 || n > 0x7FFFFFFFull) return 0;
-  return sizeof(SelWs);
+  return sizeof(SelWs) + static_cast<size_t>(cand_capacity(n)) * 4;
 }
 
 extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,
@@ -192,45 +499,68 @@ extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t 
   if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
   const size_t es = dt == DCT_F32 ? 4 : 2;
   if (!is_aligned(g, es) || !is_aligned(d_thr_out, 16)) return DCT_ERR_INVALID;
-  if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < sizeof(SelWs)) return DCT_ERR_WORKSPACE;
+  const uint32_t cand_cap = cand_capacity(n);
+  if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < sizeof(SelWs) + static_cast<size_t>(cand_cap) * 4)
+    return DCT_ERR_WORKSPACE;
 
   const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
-  const uint32_t off = static_cast<uint32_t>((addr & 15) / es);
-  const uint32_t n_virt = static_cast<uint32_t>(n + off);
-  const void* g_al = reinterpret_cast<const void*>(addr & ~static_cast<uintptr_t>(15));
+  const int vec = dt == DCT_F32 ? 4 : 8;
   auto* ws = static_cast<SelWs*>(d_ws);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint32_t n32 = static_cast<uint32_t>(n), k32 = static_cast<uint32_t>(k);
 
-  hipLaunchKernelGGL(select_init_kernel, dim3((sizeof(SelWs) / 4 + 255) / 256), dim3(256), 0, s, ws,
-                     static_cast<uint32_t>(k));
+  if (cand_cap != 0) {
+    // sample -> bounds, then the streaming partition pass
+    PartGeom geo;
+    uint64_t head = ((16 - (addr & 15)) & 15) / es;
+    if (head > n) head = n;
+    geo.head = static_cast<uint32_t>(head);
+    geo.n_vec = static_cast<uint32_t>((n - head) / vec);
+    geo.tail = static_cast<uint32_t>((n - head) % vec);
+    uint32_t tiles = (geo.n_vec + kPartTileVecs - 1) / kPartTileVecs;
+    if (tiles == 0) tiles = 1;
+    uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * 8u;
+    if (max_grid > kSelMaxGrid) max_grid = kSelMaxGrid;
+    const uint32_t tiles_per_wg = (tiles + max_grid - 1) / max_grid;
+    geo.grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+    geo.vecs_per_wg = tiles_per_wg * kPartTileVecs;
+    if (dt == DCT_F32) {
+      hipLaunchKernelGGL((select_sample_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s,
+                         static_cast<const uint32_t*>(g), n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_partition_kernel<DCT_F32>), dim3(geo.grid), dim3(kSelThreads), 0, s,
+                         static_cast<const uint32_t*>(g), geo, ws);
+    } else {
+      hipLaunchKernelGGL((select_sample_kernel<DCT_BF16>), dim3(1), dim3(kSampleThreads), 0, s,
+                         static_cast<const uint16_t*>(g), n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_partition_kernel<DCT_BF16>), dim3(geo.grid), dim3(kSelThreads), 0, s,
+                         static_cast<const uint16_t*>(g), geo, ws);
+    }
+  } else {
+    hipLaunchKernelGGL(select_init_kernel, dim3(32), dim3(256), 0, s, ws, k32, n32);
+  }
   if (hipGetLastError() != hipSuccess) return DCT_ERR_HIP;
 
-  const int vec = dt == DCT_F32 ? 4 : 8;
-  const uint32_t n_vec = n_virt / vec + 1;
+  // radix passes (over the candidates, or over the vector: decided on the device)
+  const uint32_t off = static_cast<uint32_t>((addr & 15) / es);
+  const uint32_t n_virt = n32 + off;
+  const void* g_al = reinterpret_cast<const void*>(addr & ~static_cast<uintptr_t>(15));
+  const uint32_t n_vec_all = n_virt / vec + 1;
   const uint32_t span = kSelThreads * kSelUnroll;
-  uint32_t grid = (n_vec + span - 1) / span;
-  if (grid > 4096) grid = 4096;
-  if (grid == 0) grid = 1;
-
-  const int n_pass = dt == DCT_F32 ? 3 : 2;
-  const int shifts_f32[3] = {20, 9, 0}, widths_f32[3] = {11, 11, 9};
-  const int shifts_bf16[2] = {7, 0}, widths_bf16[2] = {8, 7};
-  for (int p = 0; p < n_pass; ++p) {
-    const int shift = dt == DCT_F32 ? shifts_f32[p] : shifts_bf16[p];
-    const int width = dt == DCT_F32 ? widths_f32[p] : widths_bf16[p];
-    const uint32_t key_mask = dt == DCT_F32 ? 0x7FFFFFFFu : 0x7FFFu;
-    const uint32_t fixed_mask = key_mask & ~((1u << (shift + width)) - 1u);
-    const int last = p == n_pass - 1;
+  uint32_t grid = (n_vec_all + span - 1) / span;
+  if (grid > kSelMaxGrid) grid = kSelMaxGrid;
+  const PassDigits dg = pass_digits(dt);
+  for (int p = 0; p < dg.n_pass; ++p) {
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((select_pass_kernel<DCT_F32>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint32_t*>(g_al), off, n_virt, ws, p, shift, width, fixed_mask, last,
-                         d_thr_out);
+                         static_cast<const uint32_t*>(g_al), off, n_virt, k32, ws, p, dg.shift[p], dg.width[p],
+                         p ? dg.shift[p - 1] : 0);
     } else {
       hipLaunchKernelGGL((select_pass_kernel<DCT_BF16>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint16_t*>(g_al), off, n_virt, ws, p, shift, width, fixed_mask, last,
-                         d_thr_out);
+                         static_cast<const uint16_t*>(g_al), off, n_virt, k32, ws, p, dg.shift[p], dg.width[p],
+                         p ? dg.shift[p - 1] : 0);
     }
-    if (hipGetLastError() != hipSuccess) return DCT_ERR_HIP;
   }
-  return DCT_OK;
+  hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kSelThreads), 0, s, ws, dg.n_pass - 1,
+                     dg.shift[dg.n_pass - 1], d_thr_out);
+  return launch_status();
 }
