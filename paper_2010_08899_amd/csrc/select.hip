@@ -31,10 +31,12 @@ constexpr int kSelBins = 2048;
 constexpr int kSelMaxPasses = 3;
 constexpr int kSelUnroll = 4;                   // 16-byte loads in flight per lane in the radix passes
 constexpr uint32_t kSelMaxGrid = 4096;
+constexpr uint32_t kCandGrid = 256;
 
 constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes run over the vector itself
 constexpr int kSampleThreads = 1024;
 constexpr uint32_t kSampleSize = 16384;         // 64 KiB of LDS
+constexpr int kGatherThreads = 256;
 constexpr int kPartRows = 8;                    // 16-byte loads per lane per iteration of the partition pass
 constexpr uint32_t kPartStage = 1024;           // staged candidate keys per wavefront
 constexpr uint32_t kPartTileVecs = kSelThreads * kPartRows;
@@ -45,8 +47,12 @@ struct SelState {
   uint32_t n_gt;       // keys known to be above every matching key
   uint32_t from_cand;  // 1: the passes read the candidate buffer, 0: the vector
   uint32_t n_src;      // keys in the source
-  uint32_t pad[3];
+  uint32_t rem_bits;   // low key bits not fixed yet
+  uint32_t width;      // digit width of this pass (0: nothing left to do)
+  uint32_t last_count; // keys that match the prefix
 };
+
+constexpr uint32_t kDigitBits = 11;
 
 struct SelWs {
   unsigned long long counts;  // partition pass: keys > hi (high word), keys in [lo, hi] (low word; may exceed the buffer)
@@ -56,6 +62,7 @@ struct SelWs {
   uint32_t pad[2];
   SelState state[kSelMaxPasses + 1];  // state[p]: search state at the start of pass p
   uint32_t hist[kSelMaxPasses][kSelBins];
+  uint32_t sample[kSampleSize];       // keys of the stratified sample
   uint32_t cand[4];    // candidate keys follow (cand_cap of them)
 };
 
@@ -157,33 +164,44 @@ __device__ BinHit find_bin(LoadBin load_bin, uint32_t k_rem, uint32_t* s_tmp) {
 // Clears the workspace for the direct (no sample) path.
 __global__ void select_init_kernel(SelWs* ws, uint32_t k, uint32_t n) {
   uint32_t* w = reinterpret_cast<uint32_t*>(ws);
-  const uint32_t n_words = offsetof(SelWs, cand) / 4;
+  const uint32_t n_words = offsetof(SelWs, sample) / 4;
   for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) w[i] = 0;
 }
 
 // ------------------------------------------------------------------ kernel 1b
-// One workgroup: clear the workspace, read a stratified sample of the keys into
-// LDS and select two order statistics of it as bounds for tau.
+// Clear the workspace and gather a stratified sample of the keys: stratum i covers
+// [i*n/S, (i+1)*n/S) and contributes one key at a hashed offset.  One key per
+// thread, spread over many CUs (a single CU cannot keep enough scattered loads in
+// flight).
 template <int DT>
-__global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
-    const typename Elem<DT>::word_t* __restrict__ g, uint32_t n, uint32_t k, SelWs* ws, uint32_t cand_cap) {
+__global__ __launch_bounds__(kGatherThreads) void select_gather_kernel(
+    const typename Elem<DT>::word_t* __restrict__ g, uint32_t n, SelWs* ws) {
+  const uint32_t i = blockIdx.x * kGatherThreads + threadIdx.x;  // the grid has exactly kSampleSize threads
+  const uint32_t stratum = n / kSampleSize;                      // >= 256 by the choice of kSampleMinN
+  const uint64_t start = static_cast<uint64_t>(i) * n / kSampleSize;
+  const uint32_t h = (i * 2654435761u) ^ ((i * 40503u) >> 7);
+  const uint32_t raw = static_cast<uint32_t>(g[start + h % stratum]);
+  uint32_t* w = reinterpret_cast<uint32_t*>(ws);
+  const uint32_t n_words = offsetof(SelWs, sample) / 4;
+  if (i < n_words) w[i] = 0;
+  ws->sample[i] = raw & Elem<DT>::kKeyMask;
+}
+static_assert(offsetof(SelWs, sample) / 4 <= kSampleSize, "the gather grid also clears the workspace header");
+
+// ------------------------------------------------------------------ kernel 1c
+// One workgroup: select two order statistics of the sample as bounds for tau.
+template <int DT>
+__global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t n, uint32_t k, SelWs* ws,
+                                                                       uint32_t cand_cap) {
   using E = Elem<DT>;
   __shared__ uint32_t s_keys[kSampleSize];
-  __shared__ uint32_t s_hist[kSelBins];
+  __shared__ uint32_t s_hist[2 * kSelBins];
   __shared__ uint32_t s_tmp[kSampleThreads / kWave + 4];
   const uint32_t t = threadIdx.x;
   {
-    uint32_t* w = reinterpret_cast<uint32_t*>(ws);
-    const uint32_t n_words = offsetof(SelWs, cand) / 4;
-    for (uint32_t i = t; i < n_words; i += kSampleThreads) w[i] = 0;
-  }
-  // stratum i covers [i*n/S, (i+1)*n/S); one key at a hashed offset inside it
-  const uint64_t stratum = n / kSampleSize;  // >= 256 by the choice of kSampleMinN
-  for (uint32_t i = t; i < kSampleSize; i += kSampleThreads) {
-    const uint64_t start = static_cast<uint64_t>(i) * n / kSampleSize;
-    const uint32_t h = (i * 2654435761u) ^ ((i * 40503u) >> 7);
-    const uint64_t pos = start + h % stratum;
-    s_keys[i] = static_cast<uint32_t>(g[pos]) & E::kKeyMask;
+    const uint4* src = reinterpret_cast<const uint4*>(ws->sample);
+    uint4* dst = reinterpret_cast<uint4*>(s_keys);
+    for (uint32_t i = t; i < kSampleSize / 4; i += kSampleThreads) dst[i] = src[i];
   }
   __syncthreads();
 
@@ -196,29 +214,35 @@ __global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
   const uint64_t rank_hi = r > delta ? r - delta : 0;                     // 0: no upper bound
   const uint64_t rank_lo = r + delta + 1 <= kSampleSize ? r + delta + 1 : 0;  // 0: no lower bound
 
+  // Both order statistics are searched together: while their fixed digits agree
+  // (the usual case until the last pass) one histogram serves both.
   const PassDigits dg = pass_digits(DT);
-  uint32_t bound[2] = {E::kKeyMask, 0u};  // {hi, lo}
-  for (int which = 0; which < 2; ++which) {
-    const uint32_t rank = static_cast<uint32_t>(which == 0 ? rank_hi : rank_lo);
-    if (rank == 0) continue;  // uniform
-    uint32_t prefix = 0, fixed_mask = 0, k_rem = rank;
-    for (int p = 0; p < dg.n_pass; ++p) {
-      const int shift = dg.shift[p];
-      const uint32_t dmask = (1u << dg.width[p]) - 1u;
-      for (uint32_t i = t; i < kSelBins; i += kSampleThreads) s_hist[i] = 0;
-      __syncthreads();
-      for (uint32_t i = t; i < kSampleSize; i += kSampleThreads) {
-        const uint32_t key = s_keys[i];
-        hist_add(s_hist, (key & fixed_mask) == prefix, (key >> shift) & dmask);
-      }
-      __syncthreads();
-      const BinHit hit = find_bin<kSampleThreads>([&](uint32_t b) { return s_hist[b]; }, k_rem, s_tmp);
-      prefix |= hit.bin << shift;
-      fixed_mask |= dmask << shift;
-      k_rem -= hit.above;
+  const uint32_t rank[2] = {static_cast<uint32_t>(rank_hi), static_cast<uint32_t>(rank_lo)};
+  uint32_t prefix[2] = {0, 0}, k_rem[2] = {rank[0], rank[1]};
+  uint32_t fixed_mask = 0;
+  for (int p = 0; p < dg.n_pass; ++p) {
+    const int shift = dg.shift[p];
+    const uint32_t dmask = (1u << dg.width[p]) - 1u;
+    const bool shared = rank[0] != 0 && rank[1] != 0 && prefix[0] == prefix[1];  // uniform
+    for (uint32_t i = t; i < 2 * kSelBins; i += kSampleThreads) s_hist[i] = 0;
+    __syncthreads();
+    for (uint32_t i = t; i < kSampleSize; i += kSampleThreads) {
+      const uint32_t key = s_keys[i];
+      const uint32_t digit = (key >> shift) & dmask;
+      if (rank[0] != 0) hist_add(s_hist, (key & fixed_mask) == prefix[0], digit);
+      if (rank[1] != 0 && !shared) hist_add(s_hist + kSelBins, (key & fixed_mask) == prefix[1], digit);
     }
-    bound[which] = prefix;
+    __syncthreads();
+    for (int which = 0; which < 2; ++which) {
+      if (rank[which] == 0) continue;  // uniform
+      const uint32_t* hsel = (which == 1 && !shared) ? s_hist + kSelBins : s_hist;
+      const BinHit hit = find_bin<kSampleThreads>([&](uint32_t b) { return hsel[b]; }, k_rem[which], s_tmp);
+      prefix[which] |= hit.bin << shift;
+      k_rem[which] -= hit.above;
+    }
+    fixed_mask |= dmask << shift;
   }
+  const uint32_t bound[2] = {rank[0] != 0 ? prefix[0] : E::kKeyMask, rank[1] != 0 ? prefix[1] : 0u};  // {hi, lo}
   if (t == 0) {
     ws->hi = bound[0];
     ws->lo = bound[1];
@@ -287,22 +311,18 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
     }
   };
 
+  // Tiles of 32 KiB are dealt round-robin to the workgroups, so that at any time the
+  // grid reads one contiguous window of the vector (order is irrelevant here).
   const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
-  const uint32_t wg_lo = wg * geo.vecs_per_wg;
-  const uint32_t wg_hi = min(wg_lo + geo.vecs_per_wg, geo.n_vec);
-  const uint32_t rows_total = (wg_hi - wg_lo + kWave - 1) / kWave;
-  const uint32_t rows_per_wave = ((rows_total + kSelWaves - 1) / kSelWaves + kPartRows - 1) / kPartRows * kPartRows;
-  const uint32_t row_lo = min(static_cast<uint32_t>(wave) * rows_per_wave, rows_total);
-  const uint32_t row_hi = min(row_lo + rows_per_wave, rows_total);
-
+  const uint32_t tiles = (geo.n_vec + kPartTileVecs - 1) / kPartTileVecs;
   if (wg == 0 && wave == 0 && geo.head != 0) {
     const bool in = lane < geo.head;
     const uint32_t raw = in ? static_cast<uint32_t>(g[lane]) : 0u;
     take(&raw, in, std::integral_constant<int, 1>{});
   }
-  for (uint32_t row = row_lo; row < row_hi; row += kPartRows) {
-    const uint32_t vec0 = wg_lo + row * kWave + lane;
-    const bool full = wg_lo + (row + kPartRows) * kWave <= wg_hi;  // uniform
+  for (uint32_t tile = wg; tile < tiles; tile += geo.grid) {
+    const uint32_t vec0 = tile * kPartTileVecs + wave * kPartRows * kWave + lane;
+    const bool full = (tile + 1) * kPartTileVecs <= geo.n_vec;  // uniform
     uint4 v[kPartRows];
     if (full) {
 #pragma unroll
@@ -311,7 +331,7 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
 #pragma unroll
       for (int r = 0; r < kPartRows; ++r) {
         const uint32_t vi = vec0 + r * kWave;
-        v[r] = vi < wg_hi ? gv[vi] : make_uint4(0, 0, 0, 0);
+        v[r] = vi < geo.n_vec ? gv[vi] : make_uint4(0, 0, 0, 0);
       }
     }
 #pragma unroll
@@ -319,7 +339,7 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
       uint32_t raw[V];
 #pragma unroll
       for (int e = 0; e < V; ++e) raw[e] = E::raw(v[r], e);
-      take(raw, full || vec0 + r * kWave < wg_hi, std::integral_constant<int, V>{});
+      take(raw, full || vec0 + r * kWave < geo.n_vec, std::integral_constant<int, V>{});
     }
   }
   if (wg == geo.grid - 1 && wave == kSelWaves - 1 && geo.tail != 0) {
@@ -355,10 +375,25 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
 // One radix pass.  Every workgroup first derives the search state of this pass
 // (from the partition counts for pass 0, from the previous pass's histogram
 // otherwise), then histograms its part of the source.
+// Search state after the pass whose state was `prev` and whose histogram is `hist`.
+__device__ SelState advance_state(const SelState& prev, const uint32_t* hist, uint32_t* s_tmp) {
+  SelState st = prev;
+  if (prev.width != 0) {  // uniform
+    const BinHit hit = find_bin<kSelThreads>([&](uint32_t b) { return hist[b]; }, prev.k_rem, s_tmp);
+    st.rem_bits = prev.rem_bits - prev.width;
+    st.prefix = prev.prefix | (hit.bin << st.rem_bits);
+    st.k_rem = prev.k_rem - hit.above;
+    st.n_gt = prev.n_gt + hit.above;
+    st.last_count = hit.count;
+  }
+  st.width = min(kDigitBits, st.rem_bits);
+  return st;
+}
+
 template <int DT>
 __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     const typename Elem<DT>::word_t* __restrict__ g_al, uint32_t off, uint32_t n_virt, uint32_t k, SelWs* ws,
-    int pass, int shift, int width, int prev_shift) {
+    int pass) {
   using E = Elem<DT>;
   constexpr int V = E::kVec;
   __shared__ uint32_t h[kSelBins];
@@ -371,28 +406,31 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     const unsigned long long counts = ws->counts;
     const uint32_t n_above = static_cast<uint32_t>(counts >> 32), n_cand = static_cast<uint32_t>(counts);
     const bool ok = ws->sampled != 0 && n_cand <= ws->cand_cap && n_above < k && k <= n_above + n_cand;
-    st.prefix = 0;
     st.k_rem = ok ? k - n_above : k;
     st.n_gt = ok ? n_above : 0u;
     st.from_cand = ok ? 1u : 0u;
     st.n_src = ok ? n_cand : n_virt - off;
+    st.last_count = st.n_src;
+    // candidates share the leading bits on which lo and hi agree
+    const uint32_t diff = ok ? (ws->lo ^ ws->hi) : E::kKeyMask;
+    st.rem_bits = diff ? 32u - __builtin_clz(diff) : 0u;
+    st.prefix = ok ? (ws->lo & ~((st.rem_bits >= 32u ? 0u : (1u << st.rem_bits)) - 1u)) : 0u;
+    st.width = min(kDigitBits, st.rem_bits);
   } else {
     st = ws->state[pass - 1];
   }
   // vectors of the source; a workgroup with nothing to read leaves at once
+  // (the candidate passes use at most kCandGrid workgroups: fewer histogram merges)
   const uint32_t src_vecs = st.from_cand ? (st.n_src + 3) / 4 : n_virt / V + 1;
-  if (blockIdx.x != 0 && blockIdx.x * span >= src_vecs) return;
-  if (pass != 0) {
-    const uint32_t* prev = ws->hist[pass - 1];
-    const BinHit hit = find_bin<kSelThreads>([&](uint32_t b) { return prev[b]; }, st.k_rem, s_tmp);
-    st.prefix |= hit.bin << prev_shift;
-    st.k_rem -= hit.above;
-    st.n_gt += hit.above;
-  }
+  const uint32_t n_wg = st.from_cand ? min(gridDim.x, kCandGrid) : gridDim.x;
+  if (blockIdx.x != 0 && (blockIdx.x >= n_wg || blockIdx.x * span >= src_vecs)) return;
+  if (pass != 0) st = advance_state(st, ws->hist[pass - 1], s_tmp);
   if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[pass] = st;
+  if (st.width == 0) return;  // every digit is fixed already
 
-  const uint32_t dmask = (1u << width) - 1u;
-  const uint32_t fixed_mask = E::kKeyMask & ~((1u << (shift + width)) - 1u);
+  const uint32_t shift = st.rem_bits - st.width;
+  const uint32_t dmask = (1u << st.width) - 1u;
+  const uint32_t fixed_mask = E::kKeyMask & ~((1u << st.rem_bits) - 1u);
   const uint32_t prefix = st.prefix;
   for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) h[i] = 0;
   __syncthreads();
@@ -401,7 +439,7 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     // candidate keys: u32, 16-byte-aligned buffer, n_src of them
     const uint4* cv = reinterpret_cast<const uint4*>(ws->cand);
     const uint32_t n_src = st.n_src;
-    for (uint32_t base = blockIdx.x * span; base < src_vecs; base += gridDim.x * span) {
+    for (uint32_t base = blockIdx.x * span; base < src_vecs; base += n_wg * span) {
       uint4 v[kSelUnroll];
 #pragma unroll
       for (int u = 0; u < kSelUnroll; ++u) {
@@ -467,17 +505,15 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
 
 // ------------------------------------------------------------------ kernel 4
 // One workgroup: the last histogram fixes the remaining digits; write the result.
-__global__ __launch_bounds__(kSelThreads) void select_finish_kernel(SelWs* ws, int last, int last_shift,
+__global__ __launch_bounds__(kSelThreads) void select_finish_kernel(SelWs* ws, int last,
                                                                     dct_threshold* __restrict__ out) {
   __shared__ uint32_t s_tmp[kSelWaves + 4];
-  const SelState st = ws->state[last];
-  const uint32_t* hist = ws->hist[last];
-  const BinHit hit = find_bin<kSelThreads>([&](uint32_t b) { return hist[b]; }, st.k_rem, s_tmp);
+  const SelState st = advance_state(ws->state[last], ws->hist[last], s_tmp);
   if (threadIdx.x == 0) {
-    out->tau_key = st.prefix | (hit.bin << last_shift);
-    out->n_gt = st.n_gt + hit.above;
-    out->n_eq = hit.count;
-    out->tie_quota = st.k_rem - hit.above;
+    out->tau_key = st.prefix;
+    out->n_gt = st.n_gt;
+    out->n_eq = st.last_count;
+    out->tie_quota = st.k_rem;
   }
 }
 
@@ -521,17 +557,20 @@ extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t 
     if (tiles == 0) tiles = 1;
     uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * 8u;
     if (max_grid > kSelMaxGrid) max_grid = kSelMaxGrid;
-    const uint32_t tiles_per_wg = (tiles + max_grid - 1) / max_grid;
-    geo.grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;
-    geo.vecs_per_wg = tiles_per_wg * kPartTileVecs;
+    geo.grid = tiles < max_grid ? tiles : max_grid;
+    geo.vecs_per_wg = 0;
     if (dt == DCT_F32) {
-      hipLaunchKernelGGL((select_sample_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s,
-                         static_cast<const uint32_t*>(g), n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_gather_kernel<DCT_F32>), dim3(kSampleSize / kGatherThreads), dim3(kGatherThreads), 0,
+                         s, static_cast<const uint32_t*>(g), n32, ws);
+      hipLaunchKernelGGL((select_bounds_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws,
+                         cand_cap);
       hipLaunchKernelGGL((select_partition_kernel<DCT_F32>), dim3(geo.grid), dim3(kSelThreads), 0, s,
                          static_cast<const uint32_t*>(g), geo, ws);
     } else {
-      hipLaunchKernelGGL((select_sample_kernel<DCT_BF16>), dim3(1), dim3(kSampleThreads), 0, s,
-                         static_cast<const uint16_t*>(g), n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_gather_kernel<DCT_BF16>), dim3(kSampleSize / kGatherThreads), dim3(kGatherThreads), 0,
+                         s, static_cast<const uint16_t*>(g), n32, ws);
+      hipLaunchKernelGGL((select_bounds_kernel<DCT_BF16>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws,
+                         cand_cap);
       hipLaunchKernelGGL((select_partition_kernel<DCT_BF16>), dim3(geo.grid), dim3(kSelThreads), 0, s,
                          static_cast<const uint16_t*>(g), geo, ws);
     }
@@ -548,19 +587,19 @@ extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t 
   const uint32_t span = kSelThreads * kSelUnroll;
   uint32_t grid = (n_vec_all + span - 1) / span;
   if (grid > kSelMaxGrid) grid = kSelMaxGrid;
+  // After a partition pass the radix passes normally see the candidates only: a small grid
+  // (it still covers the whole vector, more slowly, should the bounds have failed).
+  if (cand_cap != 0 && grid > kCandGrid) grid = kCandGrid;
   const PassDigits dg = pass_digits(dt);
   for (int p = 0; p < dg.n_pass; ++p) {
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((select_pass_kernel<DCT_F32>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint32_t*>(g_al), off, n_virt, k32, ws, p, dg.shift[p], dg.width[p],
-                         p ? dg.shift[p - 1] : 0);
+                         static_cast<const uint32_t*>(g_al), off, n_virt, k32, ws, p);
     } else {
       hipLaunchKernelGGL((select_pass_kernel<DCT_BF16>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint16_t*>(g_al), off, n_virt, k32, ws, p, dg.shift[p], dg.width[p],
-                         p ? dg.shift[p - 1] : 0);
+                         static_cast<const uint16_t*>(g_al), off, n_virt, k32, ws, p);
     }
   }
-  hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kSelThreads), 0, s, ws, dg.n_pass - 1,
-                     dg.shift[dg.n_pass - 1], d_thr_out);
+  hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kSelThreads), 0, s, ws, dg.n_pass - 1, d_thr_out);
   return launch_status();
 }
