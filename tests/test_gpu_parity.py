@@ -173,6 +173,36 @@ def test_dp_argument_and_workspace_errors(dct):
     assert cnt == 100
 
 
+# ------------------------------------------------------------------ DP: large vectors (sampled select) and its fallback
+@pytest.mark.parametrize("case", ["gauss", "k1", "kn", "all_equal", "few_levels", "spike_block", "misaligned"])
+def test_dp_sampled_select_and_fallback(dct, case):
+    # n is above the size from which the threshold is bracketed from a sample and the radix passes
+    # run over the candidates; several cases make the bracket fail (ties wider than the candidate
+    # buffer, k = n) so that the device-side fallback to passes over the whole vector is taken.
+    n = (1 << 22) + 12345
+    g = si.gaussian_gradient(n, DEV, 4242)
+    k = n // 200
+    sel = "nth"
+    if case == "k1":
+        k = 1
+    elif case == "kn":
+        k = n
+    elif case == "all_equal":
+        g = torch.full((n,), -0.125, device=DEV)
+    elif case == "few_levels":
+        g = (torch.randint(0, 5, (n,), device=DEV, generator=torch.Generator(device=DEV).manual_seed(7)).float() - 2.0)
+        k = n // 3
+    elif case == "spike_block":
+        # the k largest magnitudes all sit in one short block that a stratified sample barely sees
+        g = g * 1e-3
+        g[1_000_000:1_000_000 + 3000] = 5.0 + torch.arange(3000, device=DEV) * 1e-3
+        k = 2500
+    elif case == "misaligned":
+        g = g[3:]
+    dp, thr = check_dp(dct, g.contiguous() if case != "misaligned" else g, k, select_method=sel)
+    assert thr == oracle.select_threshold(host(g), k, method="sort")
+
+
 # ------------------------------------------------------------------ DP: c3 (select once, reuse on fresh draws)
 @pytest.mark.parametrize("chunk", range(4))
 def test_dp_c3_reuse(dct, chunk):
@@ -257,6 +287,30 @@ def test_mp_signed_and_tie_heavy_rows(dct, dtype):
         check_mp(dct, x, dy, k)
     xs = si.normal_matrix(64, 1024, DEV, 57, dtype=dtype)  # split before the activation: signed entries
     check_mp(dct, xs, si.normal_matrix(64, 1024, DEV, 58, dtype=dtype), 51)
+
+
+@pytest.mark.parametrize("D", [1024, 4096])
+def test_mp_bf16_on_chip_kernel_hard_rows(dct, D):
+    # rows that defeat the previous-row threshold prediction of the on-chip bf16 kernel (wildly
+    # different scales from row to row), rows of ties, zeros, infinities and NaNs, fewer than k non-zeros
+    rows = [t for _, t in si.adversarial_vectors(D, DEV, 71)]
+    scales = [1e-30, 1e30, 1.0, 1e-3, 3e4, 1e-10]
+    gen = torch.Generator(device=DEV).manual_seed(72)
+    for s_ in scales:
+        rows.append(torch.randn(D, device=DEV, generator=gen) * s_)
+    sparse = torch.zeros(D, device=DEV)
+    sparse[5::97] = 2.0
+    rows.append(sparse)
+    nanrow = torch.randn(D, device=DEV, generator=gen)
+    nanrow[7] = float("nan")
+    nanrow[D - 1] = float("nan")
+    rows.append(nanrow)
+    rows.append(torch.full((D,), float("nan"), device=DEV))
+    x = torch.stack(rows * 3).to(torch.bfloat16)
+    x = x[torch.randperm(x.shape[0], device=DEV, generator=gen)].contiguous()
+    dy = si.normal_matrix(x.shape[0], D, DEV, 73, dtype=torch.bfloat16)
+    for k in (1, 7, D // 20, D // 2, D):
+        check_mp(dct, x, dy, k)
 
 
 def test_mp_c2_full(dct):
