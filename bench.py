@@ -33,6 +33,32 @@ import synth_inputs as si  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
 
+# kernels behind each timed call (names as rocprofv3 prints them) and launches per call
+CALL_KERNELS = {
+    "dct_select_threshold[c4]": [("dct::select_gather_kernel<0>", 1), ("dct::select_bounds_kernel<0>", 1),
+                                 ("dct::select_partition_kernel<0> [c4]", 1), ("dct::select_pass_kernel<0>", 3),
+                                 ("dct::select_finish_kernel", 1)],
+    "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true>", 1)],
+    "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_bf16_kernel<8>", 1)],
+    "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_gather_kernel<unsigned short>", 1)],
+}
+
+
+def measured_traffic(call):
+    """HBM bytes per call from the committed rocprofv3 counter summary (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+    try:
+        table = {}
+        with open(path) as f:
+            for line in f:
+                if line.startswith("#") or not line.strip():
+                    continue
+                name, fb, wb = line.rstrip("\n").split("\t")
+                table[name] = float(fb) + float(wb)
+        return int(sum(table[k] * n for k, n in CALL_KERNELS[call]))
+    except (OSError, KeyError, ValueError):
+        return None
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -148,7 +174,7 @@ def main():
 
     calls = []
     us = time_calls(call_select, args.reps)
-    sel_launches = 4
+    sel_launches = sum(n for _, n in CALL_KERNELS["dct_select_threshold[c4]"])
     calls.append(entry("dct_select_threshold[c4]", us, n4 * 4 + 16, n4, launches=sel_launches))
     call_select(0)
     us = time_calls(call_compact, args.reps)
@@ -184,11 +210,15 @@ def main():
     log(f"[bench] probes: {probes}")
 
     dom = max(calls, key=lambda c: c["us"])
-    per_launch_us = dom["us"] / dom["launches"]
-    roofline = {"bound": "hbm", "kernel": dom["call"], "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
-                "launch_us": round(per_launch_us, 2), "launches_per_call": dom["launches"],
-                "algorithmic_bytes_per_launch": dom["algorithmic_bytes"] // dom["launches"]}
+    roofline = {"bound": "hbm", "kernel": " + ".join(k for k, _ in CALL_KERNELS[dom["call"]]), "call": dom["call"],
+                "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom["call"]),
+                "algorithmic_bytes": dom["algorithmic_bytes"], "call_us": dom["us"],
+                "launches_per_call": dom["launches"],
+                "note": "achieved = algorithmic bytes of the call / HIP-event time of the call; traffic = scaled "
+                        "FETCH_SIZE + WRITE_SIZE of its kernels from profiles/bench_hbm_counters.txt"}
+    for c in calls:
+        c["traffic"] = measured_traffic(c["call"])
 
     # ------------------------------------------------------------ c3: select once, reuse on fresh draws
     c3 = None
@@ -231,8 +261,8 @@ def main():
     cpu = None
     if not args.no_cpu:
         import oracle
-        n_s = min(n4, 1 << 24)
-        b_s = min(B5, 4096)
+        n_s = min(n4, 1 << 27)
+        b_s = min(B5, 32768)
         k_s = si.ceil_frac(n_s, 5, 1000)
         gs = g4[0][:n_s].cpu().numpy()
         xs = oracle.as_numpy(x5[0][:b_s].cpu())

@@ -7,7 +7,9 @@
 //      columns, so that column order is (lane, position in lane);
 //   2. keys (sign-cleared bit patterns) stay packed two per register with bit 15
 //      of each half set, so that one packed 16-bit subtract compares two keys with
-//      a threshold (the borrow lands in bit 15 / 31);
+//      a threshold (the borrow lands in bit 15 / 31).  Register i of a group of 16
+//      pairs column i with column 16 + i, so that shifting those two bits into an
+//      accumulator yields a per-lane bitmap in plain column order;
 //   3. tau_i is found exactly.  Rows of one matrix have similar thresholds, so the
 //      previous row's tau predicts a window of 64 key values: two packed compare
 //      sweeps give the per-lane bitmaps of the keys at or above the window's ends,
@@ -16,9 +18,9 @@
 //      not contain it (or there is no previous row) a bisection over the upper key
 //      bits narrows the range to 64 values first;
 //   4. ties at tau_i are resolved by column order with one wave scan of per-lane
-//      tie counts; survivors are then written from the per-lane bitmaps, the slot of
-//      each being (survivors in lower lanes) + (survivors at lower columns of the
-//      same lane).
+//      tie counts; the survivors' columns are then listed in order in the padding of
+//      the LDS row buffer (slot = survivors in lower lanes + survivors at lower
+//      columns of the lane) and written out with coalesced stores.
 // Everything is integer work on the key bits; values are copied from the LDS copy
 // of the row bit for bit.
 #pragma once
@@ -30,7 +32,8 @@ namespace fast {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr uint32_t kWindow = 64;
+constexpr uint32_t kWindow = 32;
+constexpr int kWindowLog2 = 5;
 
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
@@ -83,39 +86,62 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
   uint32_t* hist = s_hist[wave];
   const uint32_t n_vec = D / 8;                     // the host guarantees D % 8 == 0
 
-  // bit (w, q) of a bitmap <-> register 16w + (q & 15), half q >> 4 <-> local column 2*reg + half
-  auto local_col = [](int w, uint32_t q) { return 2u * (16u * w + (q & 15u)) + (q >> 4); };
-  // bits of word m that belong to lower local columns than bit q of the same word
-  auto rank_in_word = [](uint32_t m, uint32_t q) {
-    const uint32_t i = q & 15u, odd = q >> 4;
-    return static_cast<uint32_t>(__popc((m & 0xFFFFu) & ((1u << (i + odd)) - 1u)) + __popc((m >> 16) & ((1u << i) - 1u)));
-  };
+  // bit q of bitmap word w <-> local column kColsPerWord * w + q of the lane
+  constexpr int kColsPerWord = 2 * RPW;
   auto key_at = [&](uint32_t lc) {
     return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(row_lds + lane * CHUNK + lc * 2));
+  };
+  // the 16 padding bytes of every lane chunk hold the ordered list of surviving columns
+  constexpr uint32_t kStageSlots = kWave * 8;
+  auto stage_at = [&](uint32_t slot) {
+    return reinterpret_cast<uint16_t*>(row_lds + (slot >> 3) * CHUNK + NV * 16 + (slot & 7u) * 2);
   };
 
   uint32_t guess = 0xFFFFFFFFu;  // tau of the previous row of this wavefront; none yet
 
-  for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * kWaves + wave; row < B;
-       row += static_cast<uint64_t>(gridDim.x) * kWaves) {
+  // The next row's loads are issued while the current row is processed.
+  const uint64_t row_step = static_cast<uint64_t>(gridDim.x) * kWaves;
+  uint64_t row = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
+  uint4 nxt[NV];
+  auto load_row = [&](uint64_t r) {
+    const uint4* xr = reinterpret_cast<const uint4*>(x + r * stride);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const uint32_t q = j * kWave + lane;
+      nxt[j] = q < n_vec ? xr[q] : make_uint4(0, 0, 0, 0);
+    }
+  };
+  if (row < B) load_row(row);
+
+  for (; row < B; row += row_step) {
     // ---- 1. row -> LDS (padded) -> registers, lane-contiguous
-    const uint4* xr = reinterpret_cast<const uint4*>(x + row * stride);
     wave_lds_fence();  // the previous row's readers are done with the buffer
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const uint32_t q = j * kWave + lane;
-      const uint4 v = q < n_vec ? xr[q] : make_uint4(0, 0, 0, 0);
-      *reinterpret_cast<uint4*>(row_lds + (q / NV) * CHUNK + (q % NV) * 16) = v;
+      *reinterpret_cast<uint4*>(row_lds + (q / NV) * CHUNK + (q % NV) * 16) = nxt[j];
     }
     wave_lds_fence();
-    uint32_t K[REGS];
+    if (row + row_step < B) load_row(row + row_step);
+    uint32_t R[REGS];  // R[r] = columns (2r, 2r+1) of the lane
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
       const uint4 v = *reinterpret_cast<const uint4*>(row_lds + lane * CHUNK + m * 16);
-      K[4 * m + 0] = (v.x & 0x7FFF7FFFu) | 0x80008000u;
-      K[4 * m + 1] = (v.y & 0x7FFF7FFFu) | 0x80008000u;
-      K[4 * m + 2] = (v.z & 0x7FFF7FFFu) | 0x80008000u;
-      K[4 * m + 3] = (v.w & 0x7FFF7FFFu) | 0x80008000u;
+      R[4 * m + 0] = v.x;
+      R[4 * m + 1] = v.y;
+      R[4 * m + 2] = v.z;
+      R[4 * m + 3] = v.w;
+    }
+    // K[RPW*w + i] = keys of columns (2*RPW*w + i, 2*RPW*w + RPW + i), bit 15 of each half set
+    uint32_t K[REGS];
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) {
+#pragma unroll
+      for (int i = 0; i < RPW; ++i) {
+        const uint32_t a = R[RPW * w + i / 2], b2 = R[RPW * w + RPW / 2 + i / 2];
+        const uint32_t pair = (i & 1) ? ((a >> 16) | (b2 & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b2 << 16));
+        K[RPW * w + i] = (pair & 0x7FFF7FFFu) | 0x80008000u;
+      }
     }
 
     // per-lane bitmap of the keys >= t (t <= 0x8000)
@@ -126,7 +152,8 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         uint32_t a = 0;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) a = (a >> 1) | (pk_sub_u16(K[16 * w + i], t2) & 0x80008000u);
-        out[w] = a >> (16 - RPW);
+        // flags sit at bits [16-RPW, 16) and [32-RPW, 32): close the gap
+        out[w] = RPW == 16 ? a : (((a & 0xFFFFu) >> (16 - RPW)) | ((a >> (32 - 2 * RPW)) & ~((1u << RPW) - 1u)));
       }
     };
     // number of keys >= t in the row
@@ -136,6 +163,25 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
 #pragma unroll
       for (int i = 0; i < REGS; ++i) acc = pk_add_u16(acc, pk_lshr15_u16(pk_sub_u16(K[i], t2)));
       return wave_total((acc & 0xFFFFu) + (acc >> 16));
+    };
+
+    // Bit loops run two independent streams per step so that their LDS round trips overlap:
+    // with two bitmap words, stream A walks word 0 and stream B word 1 (both upwards); with one
+    // word, A takes the lowest and B the highest remaining bit.  c = local column of the bit.
+    constexpr int wB = WORDS - 1;
+    auto pop2 = [&](uint32_t& mA, uint32_t& mB, bool& vA, uint32_t& cA, bool& vB, uint32_t& cB) {
+      vA = mA != 0;
+      cA = vA ? __builtin_ctz(mA) : 0u;
+      mA &= mA - 1;
+      if constexpr (WORDS == 2) {
+        vB = mB != 0;
+        cB = kColsPerWord + (vB ? __builtin_ctz(mB) : 0u);
+        mB &= mB - 1;
+      } else {
+        vB = mA != 0;
+        cB = vB ? 31u - __builtin_clz(mA) : 0u;
+        mA &= ~(vB ? (1u << cB) : 0u);
+      }
     };
 
     // ---- 3. locate tau
@@ -161,13 +207,13 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     }
     if (!hit) {
       // bisection over the key bits above the window width: the largest multiple of
-      // 64 with at least k keys at or above it
+      // the window width with at least k keys at or above it
       uint32_t t = 0;
-      for (int bit = 14; bit >= 6; --bit) {
+      for (int bit = 14; bit >= kWindowLog2; --bit) {
         const uint32_t cand = t | (1u << bit);
         if (count_ge(cand) >= k) t = cand;
       }
-      wlo = t;  // a multiple of 64 below 0x8000, so wlo + 64 <= 0x8000
+      wlo = t;  // a multiple of the window width below 0x8000, so wlo + width <= 0x8000
       uint32_t lo_bits[WORDS];
       ge_bitmap(wlo, lo_bits);
       ge_bitmap(wlo + kWindow, above);
@@ -185,15 +231,15 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     // histogram of the keys inside the window: bin = key - wlo, one bin per lane
     hist[lane] = 0;
     wave_lds_fence();
-#pragma unroll
-    for (int w = 0; w < WORDS; ++w) {
-      uint32_t m = inwin[w];
-      while (ballot64(m != 0) != 0) {
-        if (m != 0) {
-          const uint32_t q = __builtin_ctz(m);
-          m &= m - 1;
-          atomicAdd(&hist[(key_at(local_col(w, q)) & 0x7FFFu) - wlo], 1u);
-        }
+    {
+      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+      while (ballot64((mA | mB) != 0) != 0) {
+        bool vA, vB;
+        uint32_t cA, cB;
+        pop2(mA, mB, vA, cA, vB, cB);
+        const uint32_t kA = key_at(cA) & 0x7FFFu, kB = key_at(cB) & 0x7FFFu;
+        if (vA) atomicAdd(&hist[kA - wlo], 1u);
+        if (vB) atomicAdd(&hist[kB - wlo], 1u);
       }
     }
     wave_lds_fence();
@@ -214,15 +260,19 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     for (int w = 0; w < WORDS; ++w) {
       keep[w] = above[w];
       tie[w] = 0;
-      uint32_t m = inwin[w];
-      while (ballot64(m != 0) != 0) {
-        if (m != 0) {
-          const uint32_t q = __builtin_ctz(m);
-          m &= m - 1;
-          const uint32_t key = key_at(local_col(w, q)) & 0x7FFFu;
-          if (key > tau) keep[w] |= 1u << q;
-          if (key == tau) tie[w] |= 1u << q;
-        }
+    }
+    {
+      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+      while (ballot64((mA | mB) != 0) != 0) {
+        bool vA, vB;
+        uint32_t cA, cB;
+        pop2(mA, mB, vA, cA, vB, cB);
+        const uint32_t kA = key_at(cA) & 0x7FFFu, kB = key_at(cB) & 0x7FFFu;
+        const uint32_t bA = 1u << cA, bB = 1u << (cB & 31u);
+        keep[0] |= (vA && kA > tau) ? bA : 0u;
+        tie[0] |= (vA && kA == tau) ? bA : 0u;
+        keep[wB] |= (vB && kB > tau) ? bB : 0u;
+        tie[wB] |= (vB && kB == tau) ? bB : 0u;
       }
     }
 
@@ -244,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
           if (m != 0) {
             const uint32_t q = __builtin_ctz(m);
             m &= m - 1;
-            if (seen + rank_in_word(tie[w], q) < allowed) keep[w] |= 1u << q;
+            if (seen + __popc(tie[w] & ((1u << q) - 1u)) < allowed) keep[w] |= 1u << q;
           }
         }
         seen += __popc(tie[w]);
@@ -255,25 +305,48 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     uint32_t kc = 0;
 #pragma unroll
     for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
-    uint32_t base = wave_incl_scan(kc) - kc;
+    uint32_t slot = wave_incl_scan(kc) - kc;
     int32_t* io = idx_out + row * k;
     uint16_t* vo = val_out + row * k;
+    if (k <= kStageSlots) {
+      // list the surviving columns in order in LDS, then write idx / val with coalesced stores
+      {
+        uint32_t mA = keep[0], mB = WORDS == 2 ? keep[wB] : 0u;
+        uint32_t slotA = slot, slotB = WORDS == 2 ? slot + __popc(keep[0]) : slot + kc - 1u;
+        while (ballot64((mA | mB) != 0) != 0) {
+          bool vA, vB;
+          uint32_t cA, cB;
+          pop2(mA, mB, vA, cA, vB, cB);
+          if (vA && slotA < k) *stage_at(slotA) = static_cast<uint16_t>(lane * COLS + cA);
+          if (vB && slotB < k) *stage_at(slotB) = static_cast<uint16_t>(lane * COLS + cB);
+          ++slotA;
+          slotB += WORDS == 2 ? 1u : 0xFFFFFFFFu;
+        }
+      }
+      wave_lds_fence();
+      for (uint32_t j = lane; j < k; j += kWave) {
+        const uint32_t col = *stage_at(j);
+        const uint32_t raw = *reinterpret_cast<const uint16_t*>(row_lds + (col / COLS) * CHUNK + (col % COLS) * 2);
+        io[j] = static_cast<int32_t>(col);
+        vo[j] = static_cast<uint16_t>(raw);
+      }
+    } else {
 #pragma unroll
-    for (int w = 0; w < WORDS; ++w) {
-      uint32_t m = keep[w];
-      while (ballot64(m != 0) != 0) {
-        if (m != 0) {
-          const uint32_t q = __builtin_ctz(m);
-          m &= m - 1;
-          const uint32_t lc = local_col(w, q);
-          const uint32_t slot = base + rank_in_word(keep[w], q);
-          if (slot < k) {
-            io[slot] = static_cast<int32_t>(lane * COLS + lc);
-            vo[slot] = static_cast<uint16_t>(key_at(lc));
+      for (int w = 0; w < WORDS; ++w) {
+        uint32_t m = keep[w];
+        while (ballot64(m != 0) != 0) {
+          if (m != 0) {
+            const uint32_t q = __builtin_ctz(m);
+            m &= m - 1;
+            const uint32_t lc = kColsPerWord * w + q;
+            if (slot < k) {
+              io[slot] = static_cast<int32_t>(lane * COLS + lc);
+              vo[slot] = static_cast<uint16_t>(key_at(lc));
+            }
+            ++slot;
           }
         }
       }
-      base += __popc(keep[w]);
     }
     if (tau_out && lane == 0) tau_out[row] = static_cast<uint16_t>(tau);
   }
