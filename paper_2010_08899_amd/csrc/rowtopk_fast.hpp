@@ -139,7 +139,8 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
 #pragma unroll
       for (int i = 0; i < RPW; ++i) {
         const uint32_t a = R[RPW * w + i / 2], b2 = R[RPW * w + RPW / 2 + i / 2];
-        const uint32_t pair = (i & 1) ? ((a >> 16) | (b2 & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b2 << 16));
+        // v_perm_b32 picks bytes from {b2, a}: the two low halves (i even) or the two high halves (i odd)
+        const uint32_t pair = __builtin_amdgcn_perm(b2, a, (i & 1) ? 0x07060302u : 0x05040100u);
         K[RPW * w + i] = (pair & 0x7FFF7FFFu) | 0x80008000u;
       }
     }
@@ -151,7 +152,8 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
       for (int w = 0; w < WORDS; ++w) {
         uint32_t a = 0;
 #pragma unroll
-        for (int i = 0; i < RPW; ++i) a = (a >> 1) | (pk_sub_u16(K[16 * w + i], t2) & 0x80008000u);
+        for (int i = 0; i < RPW; ++i)  // shift the accumulator, insert the two borrow bits (one v_bfi_b32)
+          a = ((a >> 1) & ~0x80008000u) | (pk_sub_u16(K[RPW * w + i], t2) & 0x80008000u);
         // flags sit at bits [16-RPW, 16) and [32-RPW, 32): close the gap
         out[w] = RPW == 16 ? a : (((a & 0xFFFFu) >> (16 - RPW)) | ((a >> (32 - 2 * RPW)) & ~((1u << RPW) - 1u)));
       }
@@ -231,15 +233,27 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     // histogram of the keys inside the window: bin = key - wlo, one bin per lane
     hist[lane] = 0;
     wave_lds_fence();
+    // The bins (key - wlo, 5 bits) of the window keys are also remembered per stream in pop order,
+    // six per stream, so that the second walk below needs no LDS reads.
+    uint32_t listA = 0, listB = 0;
+    bool list_full = false;
     {
       uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+      uint32_t sh = 0;
       while (ballot64((mA | mB) != 0) != 0) {
         bool vA, vB;
         uint32_t cA, cB;
         pop2(mA, mB, vA, cA, vB, cB);
-        const uint32_t kA = key_at(cA) & 0x7FFFu, kB = key_at(cB) & 0x7FFFu;
-        if (vA) atomicAdd(&hist[kA - wlo], 1u);
-        if (vB) atomicAdd(&hist[kB - wlo], 1u);
+        const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
+        if (vA) atomicAdd(&hist[bA], 1u);
+        if (vB) atomicAdd(&hist[bB], 1u);
+        if (sh < 30u) {
+          listA |= (vA ? bA : 0u) << sh;
+          listB |= (vB ? bB : 0u) << sh;
+        } else {
+          list_full = true;
+        }
+        sh += 5u;
       }
     }
     wave_lds_fence();
@@ -263,16 +277,26 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     }
     {
       uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+      uint32_t sh = 0;
+      const uint32_t bs = static_cast<uint32_t>(bstar);
       while (ballot64((mA | mB) != 0) != 0) {
         bool vA, vB;
         uint32_t cA, cB;
         pop2(mA, mB, vA, cA, vB, cB);
-        const uint32_t kA = key_at(cA) & 0x7FFFu, kB = key_at(cB) & 0x7FFFu;
-        const uint32_t bA = 1u << cA, bB = 1u << (cB & 31u);
-        keep[0] |= (vA && kA > tau) ? bA : 0u;
-        tie[0] |= (vA && kA == tau) ? bA : 0u;
-        keep[wB] |= (vB && kB > tau) ? bB : 0u;
-        tie[wB] |= (vB && kB == tau) ? bB : 0u;
+        uint32_t bA, bB;  // bins of the two keys
+        if (!list_full) {  // uniform: same pop order as the first walk
+          bA = (listA >> sh) & 31u;
+          bB = (listB >> sh) & 31u;
+          sh += 5u;
+        } else {
+          bA = (key_at(cA) & 0x7FFFu) - wlo;
+          bB = (key_at(cB) & 0x7FFFu) - wlo;
+        }
+        const uint32_t mkA = 1u << cA, mkB = 1u << (cB & 31u);
+        keep[0] |= (vA && bA > bs) ? mkA : 0u;
+        tie[0] |= (vA && bA == bs) ? mkA : 0u;
+        keep[wB] |= (vB && bB > bs) ? mkB : 0u;
+        tie[wB] |= (vB && bB == bs) ? mkB : 0u;
       }
     }
 
