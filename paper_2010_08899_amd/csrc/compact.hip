@@ -169,7 +169,6 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
 
   const uint32_t tau = thr->tau_key;
   const uint32_t quota = thr->tie_quota;
-  const uint32_t t_above = EXACT ? tau + 1u : tau;  // "A": key >= t_above; "E": key == tau (exactly-k only)
 
   // ---- this wavefront's share: rows of 64 vectors [row_lo, row_hi) of the chunk [wg_lo, wg_hi)
   const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
@@ -196,17 +195,26 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     // up to NE elements per lane: raw[e], validity, index of element 0
     auto emit = [&](const uint32_t* raw, bool in, uint32_t index0, auto nelem_tag) {
       constexpr int NE = decltype(nelem_tag)::value;
+      // Cheap common case first: one compare per element against tau (keys >= tau are the
+      // survivors and, in exactly-k mode, the ties); most groups of rows have none.
+      bool ge[NE];
+      uint64_t any = 0;
+#pragma unroll
+      for (int e = 0; e < NE; ++e) {
+        ge[e] = in && (raw[e] & E::kKeyMask) >= tau;
+        any |= ballot64(ge[e]);
+      }
+      if (any == 0) return;
       bool fa[NE], fe[NE];
       uint32_t row_a = 0, row_e = 0;
 #pragma unroll
       for (int e = 0; e < NE; ++e) {
-        const uint32_t key = raw[e] & E::kKeyMask;
-        fa[e] = in && key >= t_above;
-        fe[e] = EXACT && in && key == tau;
+        fe[e] = EXACT && ge[e] && (raw[e] & E::kKeyMask) == tau;
+        fa[e] = ge[e] && !fe[e];
         row_a += __popcll(ballot64(fa[e]));
         if constexpr (EXACT) row_e += __popcll(ballot64(fe[e]));
       }
-      if (row_a + row_e != 0) {
+      {
         if constexpr (!DIRECT) {
           uint32_t slot = staged;
 #pragma unroll
@@ -255,27 +263,45 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
       const uint32_t raw = in ? static_cast<uint32_t>(g[lane]) : 0u;
       emit(&raw, in, lane, std::integral_constant<int, 1>{});
     }
-    for (uint32_t row = row_lo; row < row_hi; row += kCtRows) {
+    // Two register buffers: the loads of the next 8 rows are in flight while the current 8 are
+    // processed, so a wavefront always has requests outstanding.
+    auto load_rows = [&](uint4 (&buf)[kCtRows], uint32_t row) {
       const uint32_t vec0 = wg_lo + row * kWave + lane;
-      const bool full = wg_lo + (row + kCtRows) * kWave <= wg_hi;  // uniform
-      uint4 v[kCtRows];
-      if (full) {
+      if (wg_lo + (row + kCtRows) * kWave <= wg_hi) {  // uniform: all 8 rows inside the chunk
 #pragma unroll
-        for (int r = 0; r < kCtRows; ++r) v[r] = gv[vec0 + r * kWave];
+        for (int r = 0; r < kCtRows; ++r) buf[r] = gv[vec0 + r * kWave];
       } else {
 #pragma unroll
         for (int r = 0; r < kCtRows; ++r) {
           const uint32_t vi = vec0 + r * kWave;
-          v[r] = vi < wg_hi ? gv[vi] : make_uint4(0, 0, 0, 0);
+          buf[r] = vi < wg_hi ? gv[vi] : make_uint4(0, 0, 0, 0);
         }
       }
+    };
+    auto process_rows = [&](const uint4 (&buf)[kCtRows], uint32_t row) {
+      const uint32_t vec0 = wg_lo + row * kWave + lane;
+      const bool full = wg_lo + (row + kCtRows) * kWave <= wg_hi;
 #pragma unroll
       for (int r = 0; r < kCtRows; ++r) {
         const uint32_t vi = vec0 + r * kWave;
         uint32_t raw[V];
 #pragma unroll
-        for (int e = 0; e < V; ++e) raw[e] = E::raw(v[r], e);
+        for (int e = 0; e < V; ++e) raw[e] = E::raw(buf[r], e);
         emit(raw, full || vi < wg_hi, geo.head + vi * V, std::integral_constant<int, V>{});
+      }
+    };
+    {
+      uint4 va[kCtRows], vb[kCtRows];
+      uint32_t row = row_lo;
+      if (row < row_hi) load_rows(va, row);
+      while (row < row_hi) {
+        if (row + kCtRows < row_hi) load_rows(vb, row + kCtRows);
+        process_rows(va, row);
+        row += kCtRows;
+        if (row >= row_hi) break;
+        if (row + kCtRows < row_hi) load_rows(va, row + kCtRows);
+        process_rows(vb, row);
+        row += kCtRows;
       }
     }
     if (do_tail) {

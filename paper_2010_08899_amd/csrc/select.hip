@@ -270,7 +270,6 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
   const int wave = threadIdx.x / kWave;
   const uint32_t wg = blockIdx.x;
   const uint32_t lo = ws->lo, hi = ws->hi, cand_cap = ws->cand_cap;
-  const uint32_t span = hi - lo;  // lo <= key <= hi  <=>  key - lo <= span (unsigned)
   uint32_t* stage = s_stage[wave];
   uint32_t staged = 0, above = 0;
   __shared__ uint32_t s_cnt[kSelWaves], s_abv[kSelWaves], s_base;
@@ -288,13 +287,22 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
   // NE keys per lane
   auto take = [&](const uint32_t* raw, bool in, auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
+    // one compare per element in the common case: keys >= lo are rare
+    bool ge[NE];
+    uint64_t any = 0;
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      ge[e] = in && (raw[e] & E::kKeyMask) >= lo;
+      any |= ballot64(ge[e]);
+    }
+    if (any == 0) return;
     bool c[NE];
     uint32_t n_c = 0;
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
       const uint32_t key = raw[e] & E::kKeyMask;
-      above += __popcll(ballot64(in && key > hi));
-      c[e] = in && key - lo <= span;
+      above += __popcll(ballot64(ge[e] && key > hi));
+      c[e] = ge[e] && key <= hi;
       n_c += __popcll(ballot64(c[e]));
     }
     if (n_c != 0) {
@@ -320,26 +328,43 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
     const uint32_t raw = in ? static_cast<uint32_t>(g[lane]) : 0u;
     take(&raw, in, std::integral_constant<int, 1>{});
   }
-  for (uint32_t tile = wg; tile < tiles; tile += geo.grid) {
+  // two register buffers: the next tile's loads are in flight while the current one is processed
+  auto load_tile = [&](uint4 (&buf)[kPartRows], uint32_t tile) {
     const uint32_t vec0 = tile * kPartTileVecs + wave * kPartRows * kWave + lane;
-    const bool full = (tile + 1) * kPartTileVecs <= geo.n_vec;  // uniform
-    uint4 v[kPartRows];
-    if (full) {
+    if ((tile + 1) * kPartTileVecs <= geo.n_vec) {  // uniform
 #pragma unroll
-      for (int r = 0; r < kPartRows; ++r) v[r] = gv[vec0 + r * kWave];
+      for (int r = 0; r < kPartRows; ++r) buf[r] = gv[vec0 + r * kWave];
     } else {
 #pragma unroll
       for (int r = 0; r < kPartRows; ++r) {
         const uint32_t vi = vec0 + r * kWave;
-        v[r] = vi < geo.n_vec ? gv[vi] : make_uint4(0, 0, 0, 0);
+        buf[r] = vi < geo.n_vec ? gv[vi] : make_uint4(0, 0, 0, 0);
       }
     }
+  };
+  auto process_tile = [&](const uint4 (&buf)[kPartRows], uint32_t tile) {
+    const uint32_t vec0 = tile * kPartTileVecs + wave * kPartRows * kWave + lane;
+    const bool full = (tile + 1) * kPartTileVecs <= geo.n_vec;
 #pragma unroll
     for (int r = 0; r < kPartRows; ++r) {
       uint32_t raw[V];
 #pragma unroll
-      for (int e = 0; e < V; ++e) raw[e] = E::raw(v[r], e);
+      for (int e = 0; e < V; ++e) raw[e] = E::raw(buf[r], e);
       take(raw, full || vec0 + r * kWave < geo.n_vec, std::integral_constant<int, V>{});
+    }
+  };
+  {
+    uint4 va[kPartRows], vb[kPartRows];
+    uint32_t tile = wg;
+    if (tile < tiles) load_tile(va, tile);
+    while (tile < tiles) {
+      if (tile + geo.grid < tiles) load_tile(vb, tile + geo.grid);
+      process_tile(va, tile);
+      tile += geo.grid;
+      if (tile >= tiles) break;
+      if (tile + geo.grid < tiles) load_tile(va, tile + geo.grid);
+      process_tile(vb, tile);
+      tile += geo.grid;
     }
   }
   if (wg == geo.grid - 1 && wave == kSelWaves - 1 && geo.tail != 0) {
