@@ -92,7 +92,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every box has one); --gpus N with N > 1 is not supported. "
-                 "The path shards without communication (see DESIGN.md); value is the one GPU's throughput.")
+                 "Every worker runs this same path on its own data with no communication; value is the one GPU's throughput.")
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
 

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
   __shared__ uint32_t s_hist[kWaves][kWave];
 
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: row numbers stay scalar
   const uint32_t lane = lane_id();
   char* row_lds = reinterpret_cast<char*>(s_row[wave]);
   uint32_t* hist = s_hist[wave];
@@ -103,12 +103,15 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
   const uint64_t row_step = static_cast<uint64_t>(gridDim.x) * kWaves;
   uint64_t row = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
   uint4 nxt[NV];
+  const bool full_width = n_vec == static_cast<uint32_t>(NV * kWave);  // no lane runs past the row's end
   auto load_row = [&](uint64_t r) {
-    const uint4* xr = reinterpret_cast<const uint4*>(x + r * stride);
+    const uint4* xr = reinterpret_cast<const uint4*>(x + r * stride) + lane;
+    if (full_width) {
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      const uint32_t q = j * kWave + lane;
-      nxt[j] = q < n_vec ? xr[q] : make_uint4(0, 0, 0, 0);
+      for (int j = 0; j < NV; ++j) nxt[j] = xr[j * kWave];
+    } else {
+#pragma unroll
+      for (int j = 0; j < NV; ++j) nxt[j] = j * kWave + lane < n_vec ? xr[j * kWave] : make_uint4(0, 0, 0, 0);
     }
   };
   if (row < B) load_row(row);
@@ -203,8 +206,9 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         ca += __popc(above[w]);
         cw += __popc(inwin[w]);
       }
-      n_above = wave_total(ca);
-      n_win = wave_total(cw);
+      const uint32_t both = wave_total(ca | (cw << 16));  // each count is at most 4096
+      n_above = both & 0xFFFFu;
+      n_win = both >> 16;
       hit = n_above < k && k <= n_above + n_win;
     }
     if (!hit) {
@@ -226,8 +230,9 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         ca += __popc(above[w]);
         cw += __popc(inwin[w]);
       }
-      n_above = wave_total(ca);
-      n_win = wave_total(cw);
+      const uint32_t both = wave_total(ca | (cw << 16));
+      n_above = both & 0xFFFFu;
+      n_win = both >> 16;
     }
 
     // histogram of the keys inside the window: bin = key - wlo, one bin per lane
@@ -275,23 +280,35 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
       keep[w] = above[w];
       tie[w] = 0;
     }
-    {
+    const uint32_t bs = static_cast<uint32_t>(bstar);
+    if (!list_full) {
+      // every stream popped at most six keys: replay the pops from the remembered bins, straight-line
       uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
-      uint32_t sh = 0;
-      const uint32_t bs = static_cast<uint32_t>(bstar);
+#pragma unroll
+      for (int j = 0; j < 6; ++j) {
+        const uint32_t bitA = mA & (0u - mA);  // 0 once the stream is exhausted: contributes nothing
+        mA ^= bitA;
+        uint32_t bitB;
+        if constexpr (WORDS == 2) {
+          bitB = mB & (0u - mB);
+          mB ^= bitB;
+        } else {
+          bitB = mA != 0 ? 0x80000000u >> __builtin_clz(mA) : 0u;
+          mA ^= bitB;
+        }
+        const uint32_t bA = (listA >> (5 * j)) & 31u, bB = (listB >> (5 * j)) & 31u;
+        keep[0] |= bA > bs ? bitA : 0u;
+        tie[0] |= bA == bs ? bitA : 0u;
+        keep[wB] |= bB > bs ? bitB : 0u;
+        tie[wB] |= bB == bs ? bitB : 0u;
+      }
+    } else {
+      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
       while (ballot64((mA | mB) != 0) != 0) {
         bool vA, vB;
         uint32_t cA, cB;
         pop2(mA, mB, vA, cA, vB, cB);
-        uint32_t bA, bB;  // bins of the two keys
-        if (!list_full) {  // uniform: same pop order as the first walk
-          bA = (listA >> sh) & 31u;
-          bB = (listB >> sh) & 31u;
-          sh += 5u;
-        } else {
-          bA = (key_at(cA) & 0x7FFFu) - wlo;
-          bB = (key_at(cB) & 0x7FFFu) - wlo;
-        }
+        const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
         const uint32_t mkA = 1u << cA, mkB = 1u << (cB & 31u);
         keep[0] |= (vA && bA > bs) ? mkA : 0u;
         tie[0] |= (vA && bA == bs) ? mkA : 0u;
@@ -310,19 +327,21 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
       for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
       const uint32_t before = wave_incl_scan(tc) - tc;     // ties in lower lanes
       const uint32_t allowed = quota > before ? quota - before : 0u;  // ties this lane may keep
-      uint32_t seen = 0;
+      // lanes below the boundary keep all their ties, lanes above it none; the one lane on the
+      // boundary drops its highest columns until `allowed` ties are left
+      uint32_t t[WORDS];
 #pragma unroll
-      for (int w = 0; w < WORDS; ++w) {
-        uint32_t m = tie[w];
-        while (ballot64(m != 0) != 0) {
-          if (m != 0) {
-            const uint32_t q = __builtin_ctz(m);
-            m &= m - 1;
-            if (seen + __popc(tie[w] & ((1u << q) - 1u)) < allowed) keep[w] |= 1u << q;
-          }
+      for (int w = 0; w < WORDS; ++w) t[w] = allowed != 0 ? tie[w] : 0u;
+      if (allowed != 0 && allowed < tc) {
+        for (uint32_t drop = tc - allowed; drop != 0; --drop) {
+          if (WORDS == 2 && t[wB] != 0)
+            t[wB] ^= 0x80000000u >> __builtin_clz(t[wB]);
+          else
+            t[0] ^= 0x80000000u >> __builtin_clz(t[0]);
         }
-        seen += __popc(tie[w]);
       }
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) keep[w] |= t[w];
     }
 
     // ---- write the survivors: slot = survivors in lower lanes + survivors at lower columns of this lane
@@ -348,11 +367,29 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         }
       }
       wave_lds_fence();
-      for (uint32_t j = lane; j < k; j += kWave) {
-        const uint32_t col = *stage_at(j);
-        const uint32_t raw = *reinterpret_cast<const uint16_t*>(row_lds + (col / COLS) * CHUNK + (col % COLS) * 2);
-        io[j] = static_cast<int32_t>(col);
-        vo[j] = static_cast<uint16_t>(raw);
+      if (k <= 4 * kWave) {
+        // up to four outputs per lane: all list reads first, then all value reads, then the stores
+        uint32_t col[4], raw[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) col[j] = j * kWave + lane < k ? *stage_at(j * kWave + lane) : 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          raw[j] = *reinterpret_cast<const uint16_t*>(row_lds + (col[j] / COLS) * CHUNK + (col[j] % COLS) * 2);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t o = j * kWave + lane;
+          if (o < k) {
+            io[o] = static_cast<int32_t>(col[j]);
+            vo[o] = static_cast<uint16_t>(raw[j]);
+          }
+        }
+      } else {
+        for (uint32_t j = lane; j < k; j += kWave) {
+          const uint32_t col = *stage_at(j);
+          const uint32_t raw = *reinterpret_cast<const uint16_t*>(row_lds + (col / COLS) * CHUNK + (col % COLS) * 2);
+          io[j] = static_cast<int32_t>(col);
+          vo[j] = static_cast<uint16_t>(raw);
+        }
       }
     } else {
 #pragma unroll
