@@ -46,6 +46,11 @@ def _load():
         lib.oracle_threshold_compact.argtypes = [vp, i32, u64, vp, i32, vp, vp, u64, vp]
         lib.oracle_rowtopk_fwd.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp, vp]
         lib.oracle_rowtopk_bwd.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp]
+        lib.oracle_ef_accumulate.argtypes = [vp, vp, u64, vp]
+        lib.oracle_ef_select_threshold.argtypes = [vp, vp, u64, u64, vp]
+        lib.oracle_ef_threshold_compact.argtypes = [vp, vp, u64, vp, i32, vp, vp, u64, vp, vp]
+        for f in (lib.oracle_ef_accumulate, lib.oracle_ef_select_threshold, lib.oracle_ef_threshold_compact):
+            f.restype = ctypes.c_int
         for f in (lib.oracle_select_threshold, lib.oracle_select_threshold_nth, lib.oracle_threshold_compact,
                   lib.oracle_rowtopk_fwd, lib.oracle_rowtopk_bwd):
             f.restype = ctypes.c_int
@@ -140,3 +145,48 @@ def rowtopk_bwd(dy: np.ndarray, idx: np.ndarray):
     if rc != 0:
         raise ValueError(f"oracle_rowtopk_bwd: error {rc}")
     return dval
+
+
+# ---- Algorithm 1 with error feedback (fp32 only) ----------------------------
+def _f32_pair(g: np.ndarray, e: np.ndarray):
+    g = np.ascontiguousarray(g)
+    e = np.ascontiguousarray(e)
+    if g.dtype != np.float32 or e.dtype != np.float32:
+        raise TypeError("error feedback is defined for float32")
+    assert g.ndim == 1 and g.shape == e.shape
+    return g, e
+
+
+def ef_accumulate(g: np.ndarray, e: np.ndarray) -> np.ndarray:
+    """w = g + e, one binary32 addition per element."""
+    g, e = _f32_pair(g, e)
+    w = np.zeros_like(g)
+    if _load().oracle_ef_accumulate(_ptr(g), _ptr(e), g.size, _ptr(w)) != 0:
+        raise ValueError("oracle_ef_accumulate: invalid arguments")
+    return w
+
+
+def ef_select_threshold(g: np.ndarray, e: np.ndarray, k: int) -> Threshold:
+    g, e = _f32_pair(g, e)
+    out = np.zeros(4, dtype=np.uint32)
+    if _load().oracle_ef_select_threshold(_ptr(g), _ptr(e), g.size, int(k), _ptr(out)) != 0:
+        raise ValueError("oracle_ef_select_threshold: invalid arguments")
+    return Threshold(*(int(v) for v in out))
+
+
+def ef_threshold_compact(g: np.ndarray, e: np.ndarray, thr: Threshold, mode: int, capacity: int | None = None):
+    """Returns (idx, val, count, e_out): survivors of w = g + e and the new residual."""
+    g, e = _f32_pair(g, e)
+    cap = g.size if capacity is None else int(capacity)
+    idx = np.full(cap, -1, dtype=np.int32)
+    val = np.zeros(cap, dtype=np.float32)
+    e_out = np.zeros_like(g)
+    count = np.zeros(1, dtype=np.uint64)
+    t = np.array(list(thr), dtype=np.uint32)
+    rc = _load().oracle_ef_threshold_compact(_ptr(g), _ptr(e), g.size, _ptr(t), int(mode), _ptr(idx), _ptr(val),
+                                             cap, _ptr(count), _ptr(e_out))
+    if rc != 0:
+        raise ValueError("oracle_ef_threshold_compact: invalid arguments")
+    c = int(count[0])
+    m = min(c, cap)
+    return idx[:m], val[:m], c, e_out

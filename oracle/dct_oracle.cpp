@@ -12,6 +12,11 @@
 //     per row, the k largest magnitudes by a partial sort; the backward pass
 //     reuses the forward mask (Sec. 2.2: "the same mask").
 //
+//   * Error feedback (Algorithm 1, "W_grad = W_grad + E_grad" before the
+//     selection and "E_grad = W_grad - W_hat_grad" after the mask; Fig. 3): the
+//     *_ef functions add the residual first, select / filter the sum, and return
+//     the new residual.
+//
 // Readings fixed where the paper is silent (listed in the design notes too):
 //   * the caller passes the integer number kept, k; no fraction is rounded here;
 //   * magnitude order is the order of key(x) = bit pattern of x with the sign bit
@@ -23,7 +28,12 @@
 //     mode EXACT keeps key > tau plus the first tie_quota ties in index order
 //     (exactly k survivors on the vector tau was selected from);
 //   * survivors are emitted as (int32 index, value) in ascending index order,
-//     values copied bit for bit.
+//     values copied bit for bit;
+//   * error feedback is defined for fp32: w[i] = g[i] + e[i] is one IEEE-754
+//     binary32 addition, round to nearest even, denormals kept.  The new residual
+//     is the part of w that was not delivered: +0 where (i, w[i]) was written to
+//     the output, w[i] (bit for bit) everywhere else -- this includes entries that
+//     pass the mask but do not fit into `capacity`, which therefore are not lost.
 //
 // Parity status: every function below is pinned by tests that do not call it to
 // produce their expected values (O(N^2) rank counting on tiny inputs, closed
@@ -209,6 +219,72 @@ int oracle_rowtopk_bwd(const void* dy, int dtype, uint32_t B, uint32_t D, uint64
             std::memcpy(static_cast<unsigned char*>(dval_out) + es * o, row + es * static_cast<uint32_t>(c), es);
         }
     }
+    return 0;
+}
+
+// ---- Algorithm 1 with error feedback (fp32) --------------------------------
+
+// "W_grad = W_grad + E_grad": one binary32 addition per element.  The sum is
+// formed in binary64, where it is exact or correctly rounded with far more than
+// 2*24+2 digits, and rounded once to binary32: the same value as a single
+// round-to-nearest-even binary32 addition.
+int oracle_ef_accumulate(const float* g, const float* e, uint64_t n, float* w) {
+    if (!g || !e || !w || n == 0 || n > 0x7FFFFFFFull) return 1;
+    for (uint64_t i = 0; i < n; ++i) {
+        const double wide = static_cast<double>(g[i]) + static_cast<double>(e[i]);
+        w[i] = static_cast<float>(wide);
+    }
+    return 0;
+}
+
+// Threshold selection on the corrected gradient: tau = k-th largest |g + e|.
+int oracle_ef_select_threshold(const float* g, const float* e, uint64_t n, uint64_t k, uint32_t* out) {
+    if (!g || !e || !out || n == 0 || n > 0x7FFFFFFFull) return 1;
+    std::vector<float> w(n);
+    if (oracle_ef_accumulate(g, e, n, w.data()) != 0) return 1;
+    return oracle_select_threshold(w.data(), ORACLE_F32, n, k, out);
+}
+
+// Mask, compressed gradient and new residual ("E_grad = W_grad - W_hat_grad"):
+// filter w = g + e in index order exactly as oracle_threshold_compact filters g;
+// e_out[i] = +0 where the pair (i, w[i]) was written, w[i] otherwise.
+int oracle_ef_threshold_compact(const float* g, const float* e_in, uint64_t n, const uint32_t* thr, int mode,
+                                int32_t* idx_out, float* val_out, uint64_t capacity, uint64_t* count,
+                                float* e_out) {
+    if (!g || !e_in || !e_out || !thr || !count || n == 0 || n > 0x7FFFFFFFull) return 1;
+    if (mode != ORACLE_GE_TAU && mode != ORACLE_EXACT_K) return 1;
+    if (capacity > 0 && (!idx_out || !val_out)) return 1;
+    std::vector<float> w(n);
+    if (oracle_ef_accumulate(g, e_in, n, w.data()) != 0) return 1;
+    const uint32_t tau = thr[0];
+    const uint32_t quota = thr[3];
+    uint64_t kept = 0;
+    uint32_t ties_kept = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint32_t key = key_at(w.data(), ORACLE_F32, i);
+        bool keep;
+        if (mode == ORACLE_GE_TAU) {
+            keep = key >= tau;
+        } else if (key > tau) {
+            keep = true;
+        } else if (key == tau && ties_kept < quota) {
+            keep = true;
+            ++ties_kept;
+        } else {
+            keep = false;
+        }
+        bool written = false;
+        if (keep) {
+            if (kept < capacity) {
+                idx_out[kept] = static_cast<int32_t>(i);
+                val_out[kept] = w[i];
+                written = true;
+            }
+            ++kept;
+        }
+        e_out[i] = written ? 0.0f : w[i];
+    }
+    *count = kept;
     return 0;
 }
 

@@ -8,7 +8,10 @@ oracle itself or from the HIP path.
   * library routines on tie-free data (numpy argsort / torch.topk / kthvalue);
   * the invariants that characterise the answer (count, tau separates kept
     from dropped, tie rule, ascending order, bit-copied values);
-  * property tests over random sizes, k, dtypes and strides.
+  * property tests over random sizes, k, dtypes and strides;
+  * error feedback: a hand-worked two-iteration fixture with hand-rounded sums,
+    numpy's float32 addition, rank counting on the summed vector, and the
+    conservation law (delivered + residual == corrected gradient, bit for bit).
 """
 import os
 
@@ -61,6 +64,16 @@ def read_golden(name):
 
 def f32(words):
     return np.array([float(w) for w in words], dtype=np.float32)
+
+
+def f32x(words):
+    """Like f32, but also reads C99 hexadecimal floats (exact by construction)."""
+    def one(w):
+        return float.fromhex(w) if "0x" in w else float(w)
+    vals = [one(w) for w in words]
+    out = np.array(vals, dtype=np.float32)
+    assert all(float(o) == v or (v != v) for o, v in zip(out, vals)), "fixture value is not a binary32 number"
+    return out
 
 
 def i32(words):
@@ -418,3 +431,141 @@ def test_c2_c5_shape_sanity():
     keys = keys_of(oracle.as_numpy(xb))
     n_eq = [(keys[b] == (int(taub[b]) & 0x7FFF)).sum() for b in range(64)]
     assert np.mean(n_eq) > 1.5
+
+
+# ------------------------------------------------------------------ error feedback (Algorithm 1 with E_grad)
+def scatter(n, idx, val):
+    out = np.zeros(n, dtype=np.float32)
+    out[idx] = val
+    return out
+
+
+def test_golden_error_feedback_two_iterations():
+    gd = read_golden("alg1_error_feedback_worked.txt")
+    g1, e0, g2 = f32x(gd["g1"]), f32x(gd["e0"]), f32x(gd["g2"])
+    k = int(gd["k"][0])
+    # iteration 1: add the residual, select, mask, new residual
+    assert np.array_equal(bits(oracle.ef_accumulate(g1, e0)), bits(f32x(gd["w1"])))
+    thr = oracle.ef_select_threshold(g1, e0, k)
+    tau = np.array([thr.tau_key], dtype=np.uint32).view(np.float32)[0]
+    assert tau == float(gd["tau"][0])
+    assert (thr.n_gt, thr.n_eq, thr.tie_quota) == (int(gd["n_gt"][0]), int(gd["n_eq"][0]), int(gd["tie_quota"][0]))
+    for mode in (oracle.GE_TAU, oracle.EXACT_K):
+        idx, val, cnt, e1 = oracle.ef_threshold_compact(g1, e0, thr, mode)
+        assert cnt == k and np.array_equal(idx, i32(gd["idx1"]))
+        assert np.array_equal(bits(val), bits(f32x(gd["val1"])))
+        assert np.array_equal(bits(e1), bits(f32x(gd["e1"])))
+    # iteration 2 reuses the threshold of iteration 1
+    assert np.array_equal(bits(oracle.ef_accumulate(g2, e1)), bits(f32x(gd["w2"])))
+    idx, val, cnt, e2 = oracle.ef_threshold_compact(g2, e1, thr, oracle.GE_TAU)
+    assert cnt == len(gd["ge_idx2"]) and np.array_equal(idx, i32(gd["ge_idx2"]))
+    assert np.array_equal(bits(val), bits(f32x(gd["ge_val2"])))
+    assert np.array_equal(bits(e2), bits(f32x(gd["ge_e2"])))
+    idx, val, cnt, e2 = oracle.ef_threshold_compact(g2, e1, thr, oracle.EXACT_K)
+    assert np.array_equal(idx, i32(gd["exact_idx2"]))
+    assert np.array_equal(bits(val), bits(f32x(gd["exact_val2"])))
+    assert np.array_equal(bits(e2), bits(f32x(gd["exact_e2"])))
+    # survivors that do not fit stay in the residual
+    idx, val, cnt, e2 = oracle.ef_threshold_compact(g2, e1, thr, oracle.GE_TAU, capacity=2)
+    assert cnt == int(gd["cap2_count"][0]) and np.array_equal(idx, i32(gd["cap2_idx"]))
+    assert np.array_equal(bits(e2), bits(f32x(gd["cap2_e2"])))
+
+
+def test_golden_error_feedback_rounding():
+    gd = read_golden("alg1_error_feedback_worked.txt")
+    g, e, w = f32x(gd["round_g"]), f32x(gd["round_e"]), f32x(gd["round_w"])
+    assert np.array_equal(bits(oracle.ef_accumulate(g, e)), bits(w))
+    assert np.array_equal(bits(oracle.ef_accumulate(e, g)), bits(w))  # the sum is commutative
+
+
+def ef_vectors(n, seed):
+    """(g, e) pairs with cancellation, wide exponent ranges, denormals and exact ties in the sum."""
+    rng = np.random.default_rng(seed)
+    out = []
+    g = rng.standard_normal(n).astype(np.float32)
+    out.append(("normal", g, (0.3 * rng.standard_normal(n)).astype(np.float32)))
+    out.append(("cancelling", g, (-g + (rng.integers(-2, 3, n) * 2.0 ** -20).astype(np.float32)).astype(np.float32)))
+    scale = (2.0 ** rng.integers(-40, 40, n)).astype(np.float32)
+    out.append(("wide_exponents", (g * scale).astype(np.float32),
+                (rng.standard_normal(n) * 2.0 ** rng.integers(-40, 40, n)).astype(np.float32)))
+    den = rng.integers(1, 1 << 22, n).astype(np.uint32).view(np.float32)
+    out.append(("denormals", den * np.where(rng.random(n) < 0.5, -1, 1).astype(np.float32),
+                rng.integers(0, 1 << 22, n).astype(np.uint32).view(np.float32)))
+    q = rng.integers(-3, 4, n).astype(np.float32) * 0.25
+    out.append(("quantised_ties", q, rng.integers(-3, 4, n).astype(np.float32) * 0.25))
+    out.append(("zero_residual", g, np.zeros(n, dtype=np.float32)))
+    return out
+
+
+@pytest.mark.parametrize("n", [1, 7, 33])
+def test_error_feedback_against_rank_counting(n):
+    for name, g, e in ef_vectors(n, 100 + n):
+        w = g + e  # numpy's float32 addition: an IEEE-754 library routine, not the oracle's code
+        assert np.array_equal(bits(oracle.ef_accumulate(g, e)), bits(w)), name
+        keys = keys_of(w)
+        rank = brute_rank(keys)
+        for k in sorted({1, (n + 1) // 2, n}):
+            thr = oracle.ef_select_threshold(g, e, k)
+            tau = int(keys[np.nonzero(rank == k - 1)[0][0]])
+            assert thr.tau_key == tau, (name, k)
+            assert thr.n_gt == int((keys > tau).sum()) and thr.n_eq == int((keys == tau).sum())
+            idx, val, cnt, e_out = oracle.ef_threshold_compact(g, e, thr, oracle.EXACT_K)
+            want = np.nonzero(rank < k)[0]
+            assert cnt == k and np.array_equal(idx, want.astype(np.int32)), (name, k)
+            assert np.array_equal(bits(val), bits(w[want]))
+            expect_e = w.copy()
+            expect_e[want] = 0.0
+            assert np.array_equal(bits(e_out), bits(expect_e)), (name, k)
+            idx, val, cnt, e_out = oracle.ef_threshold_compact(g, e, thr, oracle.GE_TAU)
+            want = np.nonzero(keys >= tau)[0]
+            assert cnt == want.size and np.array_equal(idx, want.astype(np.int32))
+            expect_e = w.copy()
+            expect_e[want] = 0.0
+            assert np.array_equal(bits(e_out), bits(expect_e)), (name, k)
+
+
+@settings(max_examples=40, deadline=None)
+@given(n=st.integers(1, 3000), frac=st.floats(0.001, 1.0), seed=st.integers(0, 2**31 - 1),
+       which=st.integers(0, 5), cap_frac=st.floats(0.0, 1.5))
+def test_error_feedback_conservation_property(n, frac, seed, which, cap_frac):
+    """Nothing is lost and nothing is invented: what is delivered plus what stays
+    in the residual is the corrected gradient, bit for bit, at every position; a
+    delivered position has residual +0; with zero residual the result is that of
+    the plain path."""
+    name, g, e = ef_vectors(n, seed)[which]
+    w = g + e
+    k = max(1, min(n, int(round(frac * n))))
+    thr = oracle.ef_select_threshold(g, e, k)
+    assert thr == oracle.select_threshold(w, k)
+    cap = int(cap_frac * n)
+    for mode in (oracle.GE_TAU, oracle.EXACT_K):
+        idx, val, cnt, e_out = oracle.ef_threshold_compact(g, e, thr, mode, capacity=cap)
+        pidx, pval, pcnt = oracle.threshold_compact(w, thr, mode, capacity=cap)
+        assert cnt == pcnt and np.array_equal(idx, pidx) and np.array_equal(bits(val), bits(pval))
+        delivered = np.zeros(n, dtype=bool)
+        delivered[idx] = True
+        assert np.all(bits(e_out)[delivered] == 0)
+        assert np.array_equal(bits(e_out)[~delivered], bits(w)[~delivered])
+        assert np.array_equal(bits(val), bits(w[idx]))
+        finite = np.isfinite(w)
+        total = scatter(n, idx, val) + e_out  # one of the two terms is +0 at every position
+        assert np.array_equal(total[finite], w[finite])
+
+
+def test_error_feedback_residual_is_eventually_delivered():
+    """The point of the residual (Fig. 3): a coordinate whose gradient is always
+    below the threshold is still delivered once its accumulated value crosses it."""
+    n, k = 64, 4
+    g = np.full(n, 0.125, dtype=np.float32)
+    g[:4] = 1.0                       # four large coordinates fix tau = 1.0
+    e = np.zeros(n, dtype=np.float32)
+    thr = oracle.ef_select_threshold(g, e, k)
+    assert thr.tau_key == int(np.float32(1.0).view(np.uint32))
+    first_delivery = None
+    for it in range(1, 10):
+        idx, val, cnt, e = oracle.ef_threshold_compact(g, e, thr, oracle.GE_TAU)
+        if first_delivery is None and cnt > 4:
+            first_delivery = it
+            assert cnt == n and np.all(val[4:] == 1.0)   # 8 * 0.125, summed exactly
+            assert np.all(e == 0.0)
+    assert first_delivery == 8
