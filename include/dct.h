@@ -7,8 +7,10 @@
  *   |W_grad| >= tau, emitted as (index, value) pairs;
  *   DCT-MP (Algorithm 2): per sample (row) keep the k largest |X_act|, and in the
  *   backward pass pass X_grad through the same mask.
- * The network transfer, the parameter server and the error-feedback update are
- * not part of this library.
+ * The dct_ef_* calls are the same two DCT-DP steps with the error-feedback update
+ * of Algorithm 1 fused in (the residual is added before, and refreshed after, the
+ * compression).  The network transfer and the parameter server are not part of
+ * this library.
  *
  * Conventions shared by every call
  *   - Pointers named d_* (and g, x, dy) are DEVICE pointers on the current HIP
@@ -107,6 +109,37 @@ int dct_threshold_compact_workspace_init(void* d_ws, size_t ws_bytes, void* hip_
 int dct_threshold_compact(const void* g, int dt, uint64_t n, const dct_threshold* d_thr, int mode,
                           int32_t* d_idx_out, void* d_val_out, uint64_t capacity, uint64_t* d_count_out,
                           void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* ------------------------------------------- DCT-DP with error feedback ---
+ * Algorithm 1 keeps what compression drops: "W_grad = W_grad + E_grad" before
+ * the selection, "E_grad = W_grad - W_hat_grad" after the mask (Fig. 3).  These
+ * two calls are dct_select_threshold and dct_threshold_compact applied to the
+ * corrected gradient w = g + e, which is never materialised on its own.
+ *
+ *   dt     DCT_F32 only (anything else: DCT_ERR_INVALID).  w[i] = g[i] + e[i] is
+ *          one IEEE-754 binary32 addition, round to nearest even, denormals kept.
+ *          A NaN sum has an unspecified payload.
+ *   e / e_in / e_out   device, n floats.  They must sit at the same offset within
+ *          16 bytes as g (e.g. all 16-byte aligned), else DCT_ERR_INVALID.
+ *
+ * dct_ef_select_threshold: tau = k-th largest |g + e|; reads g and e, writes only
+ * the threshold record.  Workspace as for dct_select_threshold.
+ *
+ * dct_ef_threshold_compact: survivors of w under `mode`, as (index, w[index])
+ * pairs in ascending index order, and the new residual:
+ *     e_out[i] = +0    if the pair (i, w[i]) was written to the outputs,
+ *     e_out[i] = w[i]  otherwise (bit for bit).
+ * An entry that passes the mask but finds no room (count > capacity) is therefore
+ * kept in the residual, not lost.  e_out may be the same buffer as e_in (update in
+ * place); otherwise the two must not overlap, and g must not overlap e_out.
+ * Workspace, count and capacity as for dct_threshold_compact (same workspace).
+ */
+int dct_ef_select_threshold(const void* g, const void* e, int dt, uint64_t n, uint64_t k,
+                            dct_threshold* d_thr_out, void* d_ws, size_t ws_bytes, void* hip_stream);
+int dct_ef_threshold_compact(const void* g, const void* e_in, void* e_out, int dt, uint64_t n,
+                             const dct_threshold* d_thr, int mode, int32_t* d_idx_out, void* d_val_out,
+                             uint64_t capacity, uint64_t* d_count_out, void* d_ws, size_t ws_bytes,
+                             void* hip_stream);
 
 /* ---------------------------------------------------------------- DCT-MP ---
  * Algorithm 2, forward pass: for every row of X_act the k entries that come

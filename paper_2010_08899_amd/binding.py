@@ -29,6 +29,13 @@ _EXPORTS = {
     "dct_threshold_compact": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_void_p,
                                              ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "dct_ef_select_threshold": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64,
+                                               ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                               ctypes.c_void_p]),
+    "dct_ef_threshold_compact": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                                ctypes.c_uint64, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_size_t, ctypes.c_void_p]),
     "dct_rowtopk_fwd": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
                                        ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_void_p]),
@@ -159,6 +166,37 @@ def dct_threshold_compact(g: torch.Tensor, thr: torch.Tensor, mode: int, idx_out
                                        _dev(count_out, "count_out"), _dev(ws, "ws"),
                                        ws.numel() * ws.element_size(), _stream()),
            "dct_threshold_compact")
+
+
+def dct_ef_select_threshold(g: torch.Tensor, e: torch.Tensor, k: int, thr_out: torch.Tensor,
+                            ws: torch.Tensor) -> None:
+    """Threshold of the corrected gradient g + e (float32 tensors of equal length)."""
+    if e.dtype != g.dtype or e.numel() != g.numel():
+        raise ValueError("e must have the dtype and length of g")
+    _check(lib().dct_ef_select_threshold(_flat(g, "g"), _flat(e, "e"), _dt(g), g.numel(), int(k),
+                                         _dev(thr_out, "thr_out"), _dev(ws, "ws"), ws.numel() * ws.element_size(),
+                                         _stream()),
+           "dct_ef_select_threshold")
+
+
+def dct_ef_threshold_compact(g: torch.Tensor, e_in: torch.Tensor, e_out: torch.Tensor, thr: torch.Tensor, mode: int,
+                             idx_out: torch.Tensor, val_out: torch.Tensor, count_out: torch.Tensor,
+                             ws: torch.Tensor, capacity: int | None = None) -> None:
+    """Survivors of g + e_in and the new residual e_out (which may be e_in itself)."""
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > min(idx_out.numel(), val_out.numel()):
+        raise ValueError("capacity exceeds the output tensors")
+    if idx_out.dtype != torch.int32 or val_out.dtype != g.dtype or count_out.dtype != torch.int64:
+        raise TypeError("idx_out must be int32, val_out must match g, count_out must be int64")
+    if e_in.dtype != g.dtype or e_out.dtype != g.dtype or e_in.numel() != g.numel() or e_out.numel() != g.numel():
+        raise ValueError("e_in and e_out must have the dtype and length of g")
+    _check(lib().dct_ef_threshold_compact(_flat(g, "g"), _flat(e_in, "e_in"), _flat(e_out, "e_out"), _dt(g),
+                                          g.numel(), _dev(thr, "thr"), int(mode),
+                                          _flat(idx_out, "idx_out") if cap else None,
+                                          _flat(val_out, "val_out") if cap else None, cap,
+                                          _dev(count_out, "count_out"), _dev(ws, "ws"),
+                                          ws.numel() * ws.element_size(), _stream()),
+           "dct_ef_threshold_compact")
 
 
 def read_threshold(thr: torch.Tensor) -> Threshold:

@@ -24,6 +24,15 @@
 // covers much of the vector) the workgroup still counts everything, and after the
 // scan streams its chunk a second time, writing straight to the final slots.
 //
+// Error feedback (Algorithm 1, "W_grad = W_grad + E_grad" before the mask and
+// "E_grad = W_grad - W_hat_grad" after it) rides on the same pass: the EF variant
+// streams g and the residual together, forms w = g + e with one fp32 addition per
+// element, writes w as the new residual with full 16-byte stores and compacts w.
+// The residual of a pair that is actually written out is then overwritten with
+// +0 in step 4 (a 4-byte store per survivor), so an entry that finds no room in
+// the outputs keeps its value in the residual.  The second-pass fallback re-reads
+// w from the new residual, which also makes updating the residual in place safe.
+//
 // A workgroup only ever waits for workgroups with a lower index, which start
 // earlier; the waits are bounded all the same and a wait that runs out is reported
 // through the count.  The workspace holds two descriptor sets used by alternate
@@ -134,14 +143,18 @@ struct CompactGeom {
   uint32_t vecs_per_wg;  // chunk length in vectors (multiple of kCtTileVecs)
 };
 
-template <int DT, bool EXACT>
+// EF: g is W_grad, e_in the residual E_grad (may be the same buffer as e_out), e_out the new residual.
+template <int DT, bool EXACT, bool EF>
 __global__ __launch_bounds__(kCtThreads) void compact_kernel(
-    const typename Elem<DT>::word_t* __restrict__ g, CompactGeom geo, const dct_threshold* __restrict__ thr,
+    const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* e_in,
+    typename Elem<DT>::word_t* e_out, CompactGeom geo, const dct_threshold* __restrict__ thr,
     int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out, uint32_t capacity,
     uint64_t* __restrict__ count_out, CompactHeader* hdr) {
+  static_assert(!EF || DT == DCT_F32, "error feedback is an fp32 addition");
   using E = Elem<DT>;
   using word_t = typename E::word_t;
   constexpr int V = E::kVec;
+  constexpr int ROWS = EF ? kCtRows / 2 : kCtRows;  // two input streams: half the rows per iteration
   __shared__ uint32_t s_idx[kCtWaves][kCtStageCap];
   __shared__ word_t s_val[kCtWaves][kCtStageCap];
   __shared__ uint32_t s_wave_a[kCtWaves], s_wave_e[kCtWaves];
@@ -249,6 +262,7 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
             if (keep[e] && slot < capacity) {
               idx_out[slot] = static_cast<int32_t>(index0 + e);
               val_out[slot] = static_cast<word_t>(raw[e]);
+              if constexpr (EF) e_out[index0 + e] = 0;  // delivered: nothing is left behind
             }
             slot += keep[e] ? 1u : 0u;
           }
@@ -258,55 +272,88 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
       ne += row_e;
     };
 
+    // One element of the head or tail: the corrected gradient in the first pass (stored as the
+    // new residual), the new residual itself in the second.
+    auto edge_element = [&](bool in, uint32_t i) -> uint32_t {
+      if (!in) return 0u;
+      if constexpr (!EF) {
+        return static_cast<uint32_t>(g[i]);
+      } else if constexpr (DIRECT) {
+        return static_cast<uint32_t>(e_out[i]);
+      } else {
+        const uint32_t w = __float_as_uint(__uint_as_float(g[i]) + __uint_as_float(e_in[i]));
+        e_out[i] = w;
+        return w;
+      }
+    };
     if (do_head) {
       const bool in = lane < geo.head;
-      const uint32_t raw = in ? static_cast<uint32_t>(g[lane]) : 0u;
+      const uint32_t raw = edge_element(in, lane);
       emit(&raw, in, lane, std::integral_constant<int, 1>{});
     }
-    // Two register buffers: the loads of the next 8 rows are in flight while the current 8 are
-    // processed, so a wavefront always has requests outstanding.
-    auto load_rows = [&](uint4 (&buf)[kCtRows], uint32_t row) {
+    // Two register buffers: the loads of the next group of rows are in flight while the current
+    // group is processed, so a wavefront always has requests outstanding.
+    struct Rows {
+      uint4 a[ROWS];               // g (or, in the second pass with error feedback, the new residual)
+      uint4 b[EF ? ROWS : 1];      // the residual
+    };
+    const uint4* av = (EF && DIRECT) ? reinterpret_cast<const uint4*>(e_out + geo.head) : gv;
+    const uint4* bv = EF ? reinterpret_cast<const uint4*>(e_in + geo.head) : nullptr;
+    uint4* wv = EF ? reinterpret_cast<uint4*>(e_out + geo.head) : nullptr;
+    constexpr bool kAdd = EF && !DIRECT;
+    auto load_rows = [&](Rows& buf, uint32_t row) {
       const uint32_t vec0 = wg_lo + row * kWave + lane;
-      if (wg_lo + (row + kCtRows) * kWave <= wg_hi) {  // uniform: all 8 rows inside the chunk
+      if (wg_lo + (row + ROWS) * kWave <= wg_hi) {  // uniform: all rows inside the chunk
 #pragma unroll
-        for (int r = 0; r < kCtRows; ++r) buf[r] = gv[vec0 + r * kWave];
+        for (int r = 0; r < ROWS; ++r) {
+          buf.a[r] = av[vec0 + r * kWave];
+          if constexpr (kAdd) buf.b[r] = bv[vec0 + r * kWave];
+        }
       } else {
 #pragma unroll
-        for (int r = 0; r < kCtRows; ++r) {
+        for (int r = 0; r < ROWS; ++r) {
           const uint32_t vi = vec0 + r * kWave;
-          buf[r] = vi < wg_hi ? gv[vi] : make_uint4(0, 0, 0, 0);
+          buf.a[r] = vi < wg_hi ? av[vi] : make_uint4(0, 0, 0, 0);
+          if constexpr (kAdd) buf.b[r] = vi < wg_hi ? bv[vi] : make_uint4(0, 0, 0, 0);
         }
       }
     };
-    auto process_rows = [&](const uint4 (&buf)[kCtRows], uint32_t row) {
+    auto process_rows = [&](const Rows& buf, uint32_t row) {
       const uint32_t vec0 = wg_lo + row * kWave + lane;
-      const bool full = wg_lo + (row + kCtRows) * kWave <= wg_hi;
+      const bool full = wg_lo + (row + ROWS) * kWave <= wg_hi;
 #pragma unroll
-      for (int r = 0; r < kCtRows; ++r) {
+      for (int r = 0; r < ROWS; ++r) {
         const uint32_t vi = vec0 + r * kWave;
+        const bool in = full || vi < wg_hi;
         uint32_t raw[V];
 #pragma unroll
-        for (int e = 0; e < V; ++e) raw[e] = E::raw(buf[r], e);
-        emit(raw, full || vi < wg_hi, geo.head + vi * V, std::integral_constant<int, V>{});
+        for (int e = 0; e < V; ++e) raw[e] = E::raw(buf.a[r], e);
+        if constexpr (kAdd) {
+#pragma unroll
+          for (int e = 0; e < V; ++e)
+            raw[e] = __float_as_uint(__uint_as_float(raw[e]) + __uint_as_float(E::raw(buf.b[r], e)));
+          if (in) wv[vi] = make_uint4(raw[0], raw[1], raw[2], raw[3]);
+        }
+        emit(raw, in, geo.head + vi * V, std::integral_constant<int, V>{});
       }
     };
     {
-      uint4 va[kCtRows], vb[kCtRows];
+      Rows va, vb;
       uint32_t row = row_lo;
       if (row < row_hi) load_rows(va, row);
       while (row < row_hi) {
-        if (row + kCtRows < row_hi) load_rows(vb, row + kCtRows);
+        if (row + ROWS < row_hi) load_rows(vb, row + ROWS);
         process_rows(va, row);
-        row += kCtRows;
+        row += ROWS;
         if (row >= row_hi) break;
-        if (row + kCtRows < row_hi) load_rows(va, row + kCtRows);
+        if (row + ROWS < row_hi) load_rows(va, row + ROWS);
         process_rows(vb, row);
-        row += kCtRows;
+        row += ROWS;
       }
     }
     if (do_tail) {
       const bool in = lane < geo.tail;
-      const uint32_t raw = in ? static_cast<uint32_t>(g[tail_base + lane]) : 0u;
+      const uint32_t raw = edge_element(in, tail_base + lane);
       emit(&raw, in, tail_base + lane, std::integral_constant<int, 1>{});
     }
     wa = na;
@@ -378,6 +425,9 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     }
   }
   if (overflow) {  // uniform over the workgroup: second pass over the chunk, straight to the outputs
+    // With error feedback the second pass reads back what the first one stored (the barriers
+    // above have waited for those stores): drop this CU's cached copies of the old lines first.
+    if constexpr (EF) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     pass(std::true_type{}, a_before, e_before);
     return;
   }
@@ -397,6 +447,7 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     if (keep && slot < capacity) {
       idx_out[slot] = static_cast<int32_t>(ent & ~kTieFlag);
       val_out[slot] = s_val[wave][j];
+      if constexpr (EF) e_out[ent & ~kTieFlag] = 0;  // delivered: nothing is left behind
     }
     out += __popcll(m_keep);
     ties_seen += __popcll(m_tie);
@@ -441,9 +492,12 @@ extern "C" int dct_threshold_compact_workspace_init(void* d_ws, size_t ws_bytes,
   return launch_status();
 }
 
-extern "C" int dct_threshold_compact(const void* g, int dt, uint64_t n, const dct_threshold* d_thr, int mode,
-                                     int32_t* d_idx_out, void* d_val_out, uint64_t capacity, uint64_t* d_count_out,
-                                     void* d_ws, size_t ws_bytes, void* hip_stream) {
+namespace {
+
+int launch_compact(const void* g, const void* e_in, void* e_out, int dt, uint64_t n, const dct_threshold* d_thr,
+                   int mode, int32_t* d_idx_out, void* d_val_out, uint64_t capacity, uint64_t* d_count_out,
+                   void* d_ws, size_t ws_bytes, void* hip_stream) {
+  const bool ef = e_out != nullptr;
   if (!g || !d_thr || !d_count_out || n == 0 || n > 0x7FFFFFFFull) return DCT_ERR_INVALID;
   if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
   if (mode != DCT_GE_TAU && mode != DCT_EXACT_K) return DCT_ERR_INVALID;
@@ -451,6 +505,16 @@ extern "C" int dct_threshold_compact(const void* g, int dt, uint64_t n, const dc
   if (!is_aligned(g, es) || !is_aligned(d_thr, 16) || !is_aligned(d_count_out, 8)) return DCT_ERR_INVALID;
   if (capacity > 0 && (!d_idx_out || !d_val_out || !is_aligned(d_idx_out, 4) || !is_aligned(d_val_out, es)))
     return DCT_ERR_INVALID;
+  if (ef) {
+    if (dt != DCT_F32 || !e_in) return DCT_ERR_INVALID;
+    const uintptr_t ga = reinterpret_cast<uintptr_t>(g), ia = reinterpret_cast<uintptr_t>(e_in),
+                    oa = reinterpret_cast<uintptr_t>(e_out);
+    // the three vectors are walked with the same 16-byte vectors: same offset within 16 bytes
+    if (!is_aligned(e_in, es) || (ia & 15) != (ga & 15) || (oa & 15) != (ga & 15)) return DCT_ERR_INVALID;
+    const uintptr_t bytes = static_cast<uintptr_t>(n) * es;
+    if (ga < oa + bytes && oa < ga + bytes) return DCT_ERR_INVALID;              // g must not overlap e_out
+    if (ia != oa && ia < oa + bytes && oa < ia + bytes) return DCT_ERR_INVALID;  // e_in: identical or disjoint
+  }
   if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < kCtWsBytes) return DCT_ERR_WORKSPACE;
 
   const CompactGeom geo = make_geom(reinterpret_cast<uintptr_t>(g), n, dt);
@@ -459,14 +523,36 @@ extern "C" int dct_threshold_compact(const void* g, int dt, uint64_t n, const dc
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const dim3 grid(geo.grid), block(kCtThreads);
 
-#define DCT_LAUNCH_COMPACT(DTV, EX)                                                                          \
-  hipLaunchKernelGGL((compact_kernel<DTV, EX>), grid, block, 0, s, static_cast<const Elem<DTV>::word_t*>(g), \
-                     geo, d_thr, d_idx_out, static_cast<Elem<DTV>::word_t*>(d_val_out), cap, d_count_out, hdr)
-  if (dt == DCT_F32) {
-    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_F32, true); else DCT_LAUNCH_COMPACT(DCT_F32, false);
+#define DCT_LAUNCH_COMPACT(DTV, EX, EFV)                                                                        \
+  hipLaunchKernelGGL((compact_kernel<DTV, EX, EFV>), grid, block, 0, s,                                         \
+                     static_cast<const Elem<DTV>::word_t*>(g), static_cast<const Elem<DTV>::word_t*>(e_in),     \
+                     static_cast<Elem<DTV>::word_t*>(e_out), geo, d_thr, d_idx_out,                             \
+                     static_cast<Elem<DTV>::word_t*>(d_val_out), cap, d_count_out, hdr)
+  if (ef) {
+    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_F32, true, true); else DCT_LAUNCH_COMPACT(DCT_F32, false, true);
+  } else if (dt == DCT_F32) {
+    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_F32, true, false); else DCT_LAUNCH_COMPACT(DCT_F32, false, false);
   } else {
-    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_BF16, true); else DCT_LAUNCH_COMPACT(DCT_BF16, false);
+    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_BF16, true, false); else DCT_LAUNCH_COMPACT(DCT_BF16, false, false);
   }
 #undef DCT_LAUNCH_COMPACT
   return launch_status();
+}
+
+}  // namespace
+
+extern "C" int dct_threshold_compact(const void* g, int dt, uint64_t n, const dct_threshold* d_thr, int mode,
+                                     int32_t* d_idx_out, void* d_val_out, uint64_t capacity, uint64_t* d_count_out,
+                                     void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return launch_compact(g, nullptr, nullptr, dt, n, d_thr, mode, d_idx_out, d_val_out, capacity, d_count_out, d_ws,
+                        ws_bytes, hip_stream);
+}
+
+extern "C" int dct_ef_threshold_compact(const void* g, const void* e_in, void* e_out, int dt, uint64_t n,
+                                        const dct_threshold* d_thr, int mode, int32_t* d_idx_out, void* d_val_out,
+                                        uint64_t capacity, uint64_t* d_count_out, void* d_ws, size_t ws_bytes,
+                                        void* hip_stream) {
+  if (!e_in || !e_out) return DCT_ERR_INVALID;
+  return launch_compact(g, e_in, e_out, dt, n, d_thr, mode, d_idx_out, d_val_out, capacity, d_count_out, d_ws,
+                        ws_bytes, hip_stream);
 }

@@ -20,6 +20,11 @@
 // + n_candidates, no buffer overflow); if they did not, the same radix passes run
 // over the whole vector instead, decided on the device, so the result is always
 // the exact order statistic.  All arithmetic is on integers.
+//
+// With error feedback (Algorithm 1, "W_grad = W_grad + E_grad" precedes the
+// sort) the EF variants of the kernels that read the vector read g and the
+// residual e together and select on w = g + e, one fp32 addition per element,
+// without storing w: dct_ef_threshold_compact forms the same sums again.
 #include "dct_common.hpp"
 
 namespace dct {
@@ -83,6 +88,24 @@ __host__ __device__ inline PassDigits pass_digits(int dt) {
     d.width[0] = 8; d.width[1] = 7; d.width[2] = 0;
   }
   return d;
+}
+
+// Element i of the vector the selection runs on: g, or g + e with error feedback.
+template <int DT, bool EF>
+__device__ __forceinline__ uint32_t elem_raw(const typename Elem<DT>::word_t* g, const typename Elem<DT>::word_t* e,
+                                             uint64_t i) {
+  if constexpr (EF) {
+    return __float_as_uint(__uint_as_float(g[i]) + __uint_as_float(e[i]));
+  } else {
+    return static_cast<uint32_t>(g[i]);
+  }
+}
+// Four fp32 sums (error feedback only).
+__device__ __forceinline__ uint4 add4(const uint4& a, const uint4& b) {
+  return make_uint4(__float_as_uint(__uint_as_float(a.x) + __uint_as_float(b.x)),
+                    __float_as_uint(__uint_as_float(a.y) + __uint_as_float(b.y)),
+                    __float_as_uint(__uint_as_float(a.z) + __uint_as_float(b.z)),
+                    __float_as_uint(__uint_as_float(a.w) + __uint_as_float(b.w)));
 }
 
 // One histogram update.  Lanes whose digit equals the first active lane's digit
@@ -173,14 +196,15 @@ __global__ void select_init_kernel(SelWs* ws, uint32_t k, uint32_t n) {
 // [i*n/S, (i+1)*n/S) and contributes one key at a hashed offset.  One key per
 // thread, spread over many CUs (a single CU cannot keep enough scattered loads in
 // flight).
-template <int DT>
+template <int DT, bool EF>
 __global__ __launch_bounds__(kGatherThreads) void select_gather_kernel(
-    const typename Elem<DT>::word_t* __restrict__ g, uint32_t n, SelWs* ws) {
+    const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* __restrict__ e, uint32_t n,
+    SelWs* ws) {
   const uint32_t i = blockIdx.x * kGatherThreads + threadIdx.x;  // the grid has exactly kSampleSize threads
   const uint32_t stratum = n / kSampleSize;                      // >= 256 by the choice of kSampleMinN
   const uint64_t start = static_cast<uint64_t>(i) * n / kSampleSize;
   const uint32_t h = (i * 2654435761u) ^ ((i * 40503u) >> 7);
-  const uint32_t raw = static_cast<uint32_t>(g[start + h % stratum]);
+  const uint32_t raw = elem_raw<DT, EF>(g, e, start + h % stratum);
   uint32_t* w = reinterpret_cast<uint32_t*>(ws);
   const uint32_t n_words = offsetof(SelWs, sample) / 4;
   if (i < n_words) w[i] = 0;
@@ -260,11 +284,15 @@ struct PartGeom {
   uint32_t head, n_vec, tail, grid, vecs_per_wg;
 };
 
-template <int DT>
+template <int DT, bool EF>
 __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
-    const typename Elem<DT>::word_t* __restrict__ g, PartGeom geo, SelWs* ws) {
+    const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* __restrict__ e, PartGeom geo,
+    SelWs* ws) {
+  static_assert(!EF || DT == DCT_F32, "error feedback is an fp32 addition");
   using E = Elem<DT>;
   constexpr int V = E::kVec;
+  constexpr int ROWS = EF ? kPartRows / 2 : kPartRows;  // two input streams: half a tile per step
+  constexpr uint32_t PARTS = kPartRows / ROWS;
   __shared__ uint32_t s_stage[kSelWaves][kPartStage];
   const uint32_t lane = lane_id();
   const int wave = threadIdx.x / kWave;
@@ -325,51 +353,70 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
   const uint32_t tiles = (geo.n_vec + kPartTileVecs - 1) / kPartTileVecs;
   if (wg == 0 && wave == 0 && geo.head != 0) {
     const bool in = lane < geo.head;
-    const uint32_t raw = in ? static_cast<uint32_t>(g[lane]) : 0u;
+    const uint32_t raw = in ? elem_raw<DT, EF>(g, e, lane) : 0u;
     take(&raw, in, std::integral_constant<int, 1>{});
   }
-  // two register buffers: the next tile's loads are in flight while the current one is processed
-  auto load_tile = [&](uint4 (&buf)[kPartRows], uint32_t tile) {
-    const uint32_t vec0 = tile * kPartTileVecs + wave * kPartRows * kWave + lane;
-    if ((tile + 1) * kPartTileVecs <= geo.n_vec) {  // uniform
+  // Two register buffers: the next step's loads are in flight while the current one is processed.
+  // Step q of a workgroup covers part q % PARTS of its (q / PARTS)-th tile.
+  struct Rows {
+    uint4 a[ROWS];
+    uint4 b[EF ? ROWS : 1];
+  };
+  const uint4* ev = EF ? reinterpret_cast<const uint4*>(e + geo.head) : nullptr;
+  const uint32_t my_tiles = wg < tiles ? (tiles - wg + geo.grid - 1) / geo.grid : 0u;
+  const uint32_t steps = my_tiles * PARTS;
+  auto first_vec = [&](uint32_t q) {
+    const uint32_t tile = wg + (q / PARTS) * geo.grid;
+    return tile * kPartTileVecs + (wave * kPartRows + (q % PARTS) * ROWS) * kWave + lane;
+  };
+  auto tile_is_full = [&](uint32_t q) { return (wg + (q / PARTS) * geo.grid + 1) * kPartTileVecs <= geo.n_vec; };
+  auto load_step = [&](Rows& buf, uint32_t q) {
+    const uint32_t vec0 = first_vec(q);
+    if (tile_is_full(q)) {  // uniform
 #pragma unroll
-      for (int r = 0; r < kPartRows; ++r) buf[r] = gv[vec0 + r * kWave];
+      for (int r = 0; r < ROWS; ++r) {
+        buf.a[r] = gv[vec0 + r * kWave];
+        if constexpr (EF) buf.b[r] = ev[vec0 + r * kWave];
+      }
     } else {
 #pragma unroll
-      for (int r = 0; r < kPartRows; ++r) {
+      for (int r = 0; r < ROWS; ++r) {
         const uint32_t vi = vec0 + r * kWave;
-        buf[r] = vi < geo.n_vec ? gv[vi] : make_uint4(0, 0, 0, 0);
+        buf.a[r] = vi < geo.n_vec ? gv[vi] : make_uint4(0, 0, 0, 0);
+        if constexpr (EF) buf.b[r] = vi < geo.n_vec ? ev[vi] : make_uint4(0, 0, 0, 0);
       }
     }
   };
-  auto process_tile = [&](const uint4 (&buf)[kPartRows], uint32_t tile) {
-    const uint32_t vec0 = tile * kPartTileVecs + wave * kPartRows * kWave + lane;
-    const bool full = (tile + 1) * kPartTileVecs <= geo.n_vec;
+  auto process_step = [&](const Rows& buf, uint32_t q) {
+    const uint32_t vec0 = first_vec(q);
+    const bool full = tile_is_full(q);
 #pragma unroll
-    for (int r = 0; r < kPartRows; ++r) {
+    for (int r = 0; r < ROWS; ++r) {
+      uint4 v = buf.a[r];
+      if constexpr (EF) v = add4(v, buf.b[r]);
       uint32_t raw[V];
 #pragma unroll
-      for (int e = 0; e < V; ++e) raw[e] = E::raw(buf[r], e);
+      for (int i = 0; i < V; ++i) raw[i] = E::raw(v, i);
       take(raw, full || vec0 + r * kWave < geo.n_vec, std::integral_constant<int, V>{});
     }
   };
   {
-    uint4 va[kPartRows], vb[kPartRows];
-    uint32_t tile = wg;
-    if (tile < tiles) load_tile(va, tile);
-    while (tile < tiles) {
-      if (tile + geo.grid < tiles) load_tile(vb, tile + geo.grid);
-      process_tile(va, tile);
-      tile += geo.grid;
-      if (tile >= tiles) break;
-      if (tile + geo.grid < tiles) load_tile(va, tile + geo.grid);
-      process_tile(vb, tile);
-      tile += geo.grid;
+    Rows va, vb;
+    uint32_t q = 0;
+    if (q < steps) load_step(va, q);
+    while (q < steps) {
+      if (q + 1 < steps) load_step(vb, q + 1);
+      process_step(va, q);
+      ++q;
+      if (q >= steps) break;
+      if (q + 1 < steps) load_step(va, q + 1);
+      process_step(vb, q);
+      ++q;
     }
   }
   if (wg == geo.grid - 1 && wave == kSelWaves - 1 && geo.tail != 0) {
     const bool in = lane < geo.tail;
-    const uint32_t raw = in ? static_cast<uint32_t>(g[geo.head + geo.n_vec * V + lane]) : 0u;
+    const uint32_t raw = in ? elem_raw<DT, EF>(g, e, geo.head + geo.n_vec * V + lane) : 0u;
     take(&raw, in, std::integral_constant<int, 1>{});
   }
   // end of the chunk: one reservation for the whole workgroup (both counts in one 64-bit add)
@@ -415,10 +462,11 @@ __device__ SelState advance_state(const SelState& prev, const uint32_t* hist, ui
   return st;
 }
 
-template <int DT>
+template <int DT, bool EF>
 __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
-    const typename Elem<DT>::word_t* __restrict__ g_al, uint32_t off, uint32_t n_virt, uint32_t k, SelWs* ws,
-    int pass) {
+    const typename Elem<DT>::word_t* __restrict__ g_al, const typename Elem<DT>::word_t* __restrict__ e_al,
+    uint32_t off, uint32_t n_virt, uint32_t k, SelWs* ws, int pass) {
+  static_assert(!EF || DT == DCT_F32, "error feedback is an fp32 addition");
   using E = Elem<DT>;
   constexpr int V = E::kVec;
   __shared__ uint32_t h[kSelBins];
@@ -487,17 +535,20 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     const uint32_t v_lo = off ? 1u : 0u;
     const uint32_t v_hi = n_virt / V;
     const uint4* gv = reinterpret_cast<const uint4*>(g_al);
+    const uint4* ev = reinterpret_cast<const uint4*>(e_al);
     for (uint32_t base = v_lo + blockIdx.x * span; base < v_hi; base += gridDim.x * span) {
-      uint4 v[kSelUnroll];
+      uint4 v[kSelUnroll], ve4[EF ? kSelUnroll : 1];
       bool in[kSelUnroll];
 #pragma unroll
       for (int u = 0; u < kSelUnroll; ++u) {
         const uint32_t vi = base + u * kSelThreads + threadIdx.x;
         in[u] = vi < v_hi;
         v[u] = in[u] ? gv[vi] : make_uint4(0, 0, 0, 0);
+        if constexpr (EF) ve4[u] = in[u] ? ev[vi] : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
       for (int u = 0; u < kSelUnroll; ++u) {
+        if constexpr (EF) v[u] = add4(v[u], ve4[u]);
 #pragma unroll
         for (int e = 0; e < V; ++e) {
           const uint32_t key = E::raw(v[u], e) & E::kKeyMask;
@@ -516,7 +567,7 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
         if (c < n_virt && (c >= static_cast<uint32_t>(V) || !off)) ve = c;
       }
       const bool act = ve != 0xFFFFFFFFu;
-      const uint32_t key = act ? (static_cast<uint32_t>(g_al[ve]) & E::kKeyMask) : 0u;
+      const uint32_t key = act ? (elem_raw<DT, EF>(g_al, e_al, ve) & E::kKeyMask) : 0u;
       hist_add(h, act && (key & fixed_mask) == prefix, (key >> shift) & dmask);
     }
   }
@@ -554,21 +605,30 @@ extern "C" size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n) {
   return sizeof(SelWs) + static_cast<size_t>(cand_capacity(n)) * 4;
 }
 
-extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,
-                                    void* d_ws, size_t ws_bytes, void* hip_stream) {
+namespace {
+
+int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out, void* d_ws,
+                  size_t ws_bytes, void* hip_stream) {
+  const bool ef = e != nullptr;
   if (!g || !d_thr_out || n == 0 || n > 0x7FFFFFFFull || k == 0 || k > n) return DCT_ERR_INVALID;
   if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
   const size_t es = dt == DCT_F32 ? 4 : 2;
   if (!is_aligned(g, es) || !is_aligned(d_thr_out, 16)) return DCT_ERR_INVALID;
+  const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
+  const uintptr_t eaddr = reinterpret_cast<uintptr_t>(e);
+  // both vectors are walked with the same 16-byte vectors: same offset within 16 bytes
+  if (ef && (dt != DCT_F32 || !is_aligned(e, es) || (eaddr & 15) != (addr & 15))) return DCT_ERR_INVALID;
   const uint32_t cand_cap = cand_capacity(n);
   if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < sizeof(SelWs) + static_cast<size_t>(cand_cap) * 4)
     return DCT_ERR_WORKSPACE;
 
-  const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
   const int vec = dt == DCT_F32 ? 4 : 8;
   auto* ws = static_cast<SelWs*>(d_ws);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t n32 = static_cast<uint32_t>(n), k32 = static_cast<uint32_t>(k);
+  const auto* g32 = static_cast<const uint32_t*>(g);
+  const auto* e32 = static_cast<const uint32_t*>(e);
+  const auto* g16 = static_cast<const uint16_t*>(g);
 
   if (cand_cap != 0) {
     // sample -> bounds, then the streaming partition pass
@@ -584,20 +644,19 @@ extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t 
     if (max_grid > kSelMaxGrid) max_grid = kSelMaxGrid;
     geo.grid = tiles < max_grid ? tiles : max_grid;
     geo.vecs_per_wg = 0;
-    if (dt == DCT_F32) {
-      hipLaunchKernelGGL((select_gather_kernel<DCT_F32>), dim3(kSampleSize / kGatherThreads), dim3(kGatherThreads), 0,
-                         s, static_cast<const uint32_t*>(g), n32, ws);
-      hipLaunchKernelGGL((select_bounds_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws,
-                         cand_cap);
-      hipLaunchKernelGGL((select_partition_kernel<DCT_F32>), dim3(geo.grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint32_t*>(g), geo, ws);
+    const dim3 ggrid(kSampleSize / kGatherThreads), gblock(kGatherThreads), pgrid(geo.grid), pblock(kSelThreads);
+    if (ef) {
+      hipLaunchKernelGGL((select_gather_kernel<DCT_F32, true>), ggrid, gblock, 0, s, g32, e32, n32, ws);
+      hipLaunchKernelGGL((select_bounds_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_partition_kernel<DCT_F32, true>), pgrid, pblock, 0, s, g32, e32, geo, ws);
+    } else if (dt == DCT_F32) {
+      hipLaunchKernelGGL((select_gather_kernel<DCT_F32, false>), ggrid, gblock, 0, s, g32, nullptr, n32, ws);
+      hipLaunchKernelGGL((select_bounds_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_partition_kernel<DCT_F32, false>), pgrid, pblock, 0, s, g32, nullptr, geo, ws);
     } else {
-      hipLaunchKernelGGL((select_gather_kernel<DCT_BF16>), dim3(kSampleSize / kGatherThreads), dim3(kGatherThreads), 0,
-                         s, static_cast<const uint16_t*>(g), n32, ws);
-      hipLaunchKernelGGL((select_bounds_kernel<DCT_BF16>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws,
-                         cand_cap);
-      hipLaunchKernelGGL((select_partition_kernel<DCT_BF16>), dim3(geo.grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint16_t*>(g), geo, ws);
+      hipLaunchKernelGGL((select_gather_kernel<DCT_BF16, false>), ggrid, gblock, 0, s, g16, nullptr, n32, ws);
+      hipLaunchKernelGGL((select_bounds_kernel<DCT_BF16>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_partition_kernel<DCT_BF16, false>), pgrid, pblock, 0, s, g16, nullptr, geo, ws);
     }
   } else {
     hipLaunchKernelGGL(select_init_kernel, dim3(32), dim3(256), 0, s, ws, k32, n32);
@@ -608,6 +667,7 @@ extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t 
   const uint32_t off = static_cast<uint32_t>((addr & 15) / es);
   const uint32_t n_virt = n32 + off;
   const void* g_al = reinterpret_cast<const void*>(addr & ~static_cast<uintptr_t>(15));
+  const void* e_al = reinterpret_cast<const void*>(eaddr & ~static_cast<uintptr_t>(15));
   const uint32_t n_vec_all = n_virt / vec + 1;
   const uint32_t span = kSelThreads * kSelUnroll;
   uint32_t grid = (n_vec_all + span - 1) / span;
@@ -617,14 +677,30 @@ extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t 
   if (cand_cap != 0 && grid > kCandGrid) grid = kCandGrid;
   const PassDigits dg = pass_digits(dt);
   for (int p = 0; p < dg.n_pass; ++p) {
-    if (dt == DCT_F32) {
-      hipLaunchKernelGGL((select_pass_kernel<DCT_F32>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint32_t*>(g_al), off, n_virt, k32, ws, p);
+    if (ef) {
+      hipLaunchKernelGGL((select_pass_kernel<DCT_F32, true>), dim3(grid), dim3(kSelThreads), 0, s,
+                         static_cast<const uint32_t*>(g_al), static_cast<const uint32_t*>(e_al), off, n_virt, k32, ws, p);
+    } else if (dt == DCT_F32) {
+      hipLaunchKernelGGL((select_pass_kernel<DCT_F32, false>), dim3(grid), dim3(kSelThreads), 0, s,
+                         static_cast<const uint32_t*>(g_al), nullptr, off, n_virt, k32, ws, p);
     } else {
-      hipLaunchKernelGGL((select_pass_kernel<DCT_BF16>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint16_t*>(g_al), off, n_virt, k32, ws, p);
+      hipLaunchKernelGGL((select_pass_kernel<DCT_BF16, false>), dim3(grid), dim3(kSelThreads), 0, s,
+                         static_cast<const uint16_t*>(g_al), nullptr, off, n_virt, k32, ws, p);
     }
   }
   hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kSelThreads), 0, s, ws, dg.n_pass - 1, d_thr_out);
   return launch_status();
+}
+
+}  // namespace
+
+extern "C" int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,
+                                    void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return launch_select(g, nullptr, dt, n, k, d_thr_out, d_ws, ws_bytes, hip_stream);
+}
+
+extern "C" int dct_ef_select_threshold(const void* g, const void* e, int dt, uint64_t n, uint64_t k,
+                                       dct_threshold* d_thr_out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  if (!e) return DCT_ERR_INVALID;
+  return launch_select(g, e, dt, n, k, d_thr_out, d_ws, ws_bytes, hip_stream);
 }

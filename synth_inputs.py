@@ -141,6 +141,37 @@ def config_c5(device, b: int = C5_B):
     return x, dy, C5_K
 
 
+# ---------------------------------------------------------------- residuals (error feedback)
+def residual_vector(n: int, device, seed: int, scale: float = 1e-3, clip: float = 2.0) -> torch.Tensor:
+    """A residual E_grad as it looks in steady state: what earlier iterations
+    dropped, i.e. values below the threshold.  N(0, scale^2) clipped to
+    +-clip*scale (about the 1 % threshold of a N(0, scale^2) gradient)."""
+    e = torch.randn(n, device=device, dtype=torch.float32, generator=_gen(device, seed))
+    return e.clamp_(-clip, clip).mul_(scale)
+
+
+def error_feedback_pairs(n: int, device, seed: int):
+    """(name, g, e) fp32 pairs whose SUM is awkward: cancellation to exact zeros,
+    exponents far apart, denormal sums, many exactly equal sums."""
+    gen = _gen(device, seed)
+    g = torch.randn(n, device=device, generator=gen)
+    out = [("normal", g * 1e-3, residual_vector(n, device, seed + 1))]
+    steps = torch.randint(-2, 3, (n,), device=device, generator=gen).float() * 2.0 ** -20
+    out.append(("cancelling", g, steps - g))
+    ex_g = torch.randint(-40, 40, (n,), device=device, generator=gen).float()
+    ex_e = torch.randint(-40, 40, (n,), device=device, generator=gen).float()
+    out.append(("wide_exponents", g * torch.exp2(ex_g), torch.randn(n, device=device, generator=gen) * torch.exp2(ex_e)))
+    den_g = torch.randint(1, 1 << 22, (n,), device=device, generator=gen, dtype=torch.int32).view(torch.float32)
+    den_e = torch.randint(0, 1 << 22, (n,), device=device, generator=gen, dtype=torch.int32).view(torch.float32)
+    sign = torch.where(torch.rand(n, device=device, generator=gen) < 0.5, -1.0, 1.0)
+    out.append(("denormals", den_g * sign, den_e))
+    q_g = torch.randint(-3, 4, (n,), device=device, generator=gen).float() * 0.25
+    q_e = torch.randint(-3, 4, (n,), device=device, generator=gen).float() * 0.25
+    out.append(("quantised_ties", q_g, q_e))
+    out.append(("zero_residual", g * 1e-3, torch.zeros(n, device=device)))
+    return [(name, a.contiguous(), b.contiguous()) for name, a, b in out]
+
+
 # ---------------------------------------------------------------- adversarial sets
 def adversarial_vectors(n: int, device, seed: int):
     """Tie-heavy and special-value fp32 vectors of length n, as (name, tensor)."""

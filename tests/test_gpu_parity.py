@@ -348,3 +348,174 @@ def test_mp_argument_errors(dct):
     assert e.value.status == 1
     with pytest.raises(dct.DctError):
         dct.dct_rowtopk_fwd(x, 0, idx[:, :0].contiguous(), val[:, :0].contiguous())
+
+
+# ------------------------------------------------------------------ DP with error feedback
+class EF:
+    """Buffers of the error-feedback calls for one vector size."""
+
+    def __init__(self, dct, n, capacity=None, device=DEV):
+        self.dct, self.n = dct, n
+        self.cap = n if capacity is None else capacity
+        self.thr = torch.zeros(4, dtype=torch.int32, device=device)
+        self.idx = torch.full((max(self.cap, 1),), -7, dtype=torch.int32, device=device)
+        self.val = torch.zeros(max(self.cap, 1), dtype=torch.float32, device=device)
+        self.count = torch.zeros(1, dtype=torch.int64, device=device)
+        proto = torch.empty(n, dtype=torch.float32, device=device)
+        self.sel_ws = dct.new_select_workspace(proto)
+        self.ws = dct.new_compact_workspace(proto)
+
+    def select(self, g, e, k):
+        self.dct.dct_ef_select_threshold(g, e, k, self.thr, self.sel_ws)
+        return oracle.Threshold(*self.dct.read_threshold(self.thr))
+
+    def compact(self, g, e_in, e_out, mode, capacity=None):
+        cap = self.cap if capacity is None else capacity
+        self.idx.fill_(-7)
+        self.dct.dct_ef_threshold_compact(g, e_in, e_out, self.thr, mode, self.idx, self.val, self.count, self.ws,
+                                          capacity=cap)
+        c = self.dct.read_count(self.count)
+        m = min(c, cap)
+        return host(self.idx[:m]), host(self.val[:m]), c, host(self.idx[m:m + 16])
+
+
+def check_ef(dct, g, e, k, modes=(0, 1), capacity=None, in_place=True):
+    """Select and compact g + e on the GPU and on the oracle; the residual is
+    written to a fresh buffer and, in a second run, over e itself."""
+    gh, eh = host(g), host(e)
+    ef = EF(dct, g.numel(), capacity)
+    thr = ef.select(g, e, k)
+    exp = oracle.ef_select_threshold(gh, eh, k)
+    assert thr == exp, (thr, exp)
+    for mode in modes:
+        eidx, eval_, ecnt, e_exp = oracle.ef_threshold_compact(gh, eh, exp, mode, capacity=capacity)
+        for place in ((False, True) if in_place else (False,)):
+            off = (g.data_ptr() % 16) // 4  # all three vectors sit at the same offset within 16 bytes
+            e_in = torch.empty(g.numel() + off, device=g.device)[off:].copy_(e)
+            e_out = e_in if place else torch.full((g.numel() + off,), 123.0, device=g.device)[off:]
+            idx, val, cnt, guard = ef.compact(g, e_in, e_out, mode)
+            assert cnt == ecnt
+            assert np.array_equal(idx, eidx)
+            assert np.array_equal(bits(val), bits(eval_))
+            assert np.all(guard == -7)
+            assert np.array_equal(bits(host(e_out)), bits(e_exp)), (mode, place)
+            if not place:
+                assert torch.equal(e_in.view(torch.int32), e.view(torch.int32))  # the input residual is untouched
+    return ef, exp
+
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 63, 64, 1000, 8191, 8193, 3 * 8192 + 17, 100_003, 1_000_000])
+def test_dp_ef_sizes(dct, n):
+    g = si.gaussian_gradient(n, DEV, 400 + n)
+    e = si.residual_vector(n, DEV, 500 + n)
+    for k in sorted({1, max(1, n // 100), max(1, n // 2), n}):
+        check_ef(dct, g, e, k)
+
+
+@pytest.mark.parametrize("n", [40, 30_000])
+def test_dp_ef_awkward_sums(dct, n):
+    """Cancellation to zero, exponents far apart, denormal sums (not flushed), many equal sums."""
+    for name, g, e in si.error_feedback_pairs(n, DEV, 700 + n):
+        for k in sorted({1, 3, n // 7 + 1, n // 2, n}):
+            check_ef(dct, g, e, k)
+
+
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_dp_ef_misaligned_base(dct, shift):
+    n = 50_000
+    gb, eb = si.gaussian_gradient(n + shift, DEV, 17), si.residual_vector(n + shift, DEV, 18)
+    g, e = gb[shift:], eb[shift:]
+    assert g.data_ptr() % 16 != 0 and g.data_ptr() % 16 == e.data_ptr() % 16
+    ef = EF(dct, n)
+    gh, eh = host(g), host(e)
+    thr = ef.select(g, e, 500)
+    exp = oracle.ef_select_threshold(gh, eh, 500)
+    assert thr == exp
+    ob = torch.full((n + shift,), 5.0, device=DEV)
+    idx, val, cnt, _ = ef.compact(g, e, ob[shift:], 1)
+    eidx, eval_, ecnt, e_exp = oracle.ef_threshold_compact(gh, eh, exp, 1)
+    assert cnt == ecnt and np.array_equal(idx, eidx) and np.array_equal(bits(val), bits(eval_))
+    assert np.array_equal(bits(host(ob[shift:])), bits(e_exp))
+    assert torch.all(ob[:shift] == 5.0)  # nothing written before the vector
+    # vectors at different offsets within 16 bytes are refused
+    with pytest.raises(dct.DctError):
+        ef.select(g, eb[:n], 500)
+    with pytest.raises(dct.DctError):
+        ef.compact(g, e, ob[:n], 1)
+
+
+def test_dp_ef_capacity_keeps_the_rest_in_the_residual(dct):
+    n = 200_000
+    g, e = si.gaussian_gradient(n, DEV, 21), si.residual_vector(n, DEV, 22)
+    check_ef(dct, g, e, 2000, capacity=777)
+    check_ef(dct, g, e, 2000, capacity=0)
+
+
+def test_dp_ef_dense_survivors_second_pass(dct):
+    """More survivors than the on-chip staging holds: the kernel re-reads the
+    corrected gradient from the new residual, also when that overwrites e_in."""
+    n = 3_000_000
+    g, e = si.gaussian_gradient(n, DEV, 31), si.residual_vector(n, DEV, 32)
+    check_ef(dct, g, e, n // 2)
+    check_ef(dct, g, e, n // 3, capacity=n // 10)
+    q = (torch.randint(-1, 2, (n,), device=DEV, generator=si._gen(DEV, 33)).float() * 0.5)
+    check_ef(dct, q, q.roll(1), n // 3)  # sums in {-1, -.5, 0, .5, 1}: a tie value covers much of the vector
+
+
+def test_dp_ef_sampled_select(dct):
+    """Large enough for the sampled selection (the partition pass reads both vectors)."""
+    n = 6_000_011
+    g = si.student_t3_gradient(n, DEV, 41)
+    e = si.residual_vector(n, DEV, 42)
+    check_ef(dct, g, e, n // 1000, in_place=False)
+    check_ef(dct, g[1:], e[1:], n // 50, modes=(1,), in_place=False)
+    name, qg, qe = si.error_feedback_pairs(n, DEV, 43)[4]   # quantised: the bounds collapse onto one key
+    check_ef(dct, qg, qe, n // 10, modes=(1,), in_place=False)
+
+
+def test_dp_ef_training_loop_with_reuse(dct):
+    """Five iterations of Algorithm 1 at a reduced c3 size: iteration 0 selects,
+    the others reuse tau; the residual is updated in place on the GPU and carried
+    from iteration to iteration on both sides."""
+    n, k = 2_500_000, 2_500
+    ef = EF(dct, n, capacity=4 * k)
+    e_gpu = torch.zeros(n, device=DEV)
+    e_ref = np.zeros(n, dtype=np.float32)
+    counts = []
+    for it in range(5):
+        g = si.config_c3_draw(DEV, it, n)
+        gh = host(g)
+        if it == 0:
+            thr = ef.select(g, e_gpu, k)
+            exp = oracle.ef_select_threshold(gh, e_ref, k)
+            assert thr == exp
+        idx, val, cnt, guard = ef.compact(g, e_gpu, e_gpu, 0)
+        eidx, eval_, ecnt, e_ref = oracle.ef_threshold_compact(gh, e_ref, exp, 0, capacity=4 * k)
+        assert cnt == ecnt and np.array_equal(idx, eidx) and np.array_equal(bits(val), bits(eval_))
+        assert np.array_equal(bits(host(e_gpu)), bits(e_ref)), it
+        counts.append(cnt)
+    assert counts[0] == k and counts[1] > counts[0]  # the carried residual pushes more entries over tau
+
+
+def test_dp_ef_argument_errors(dct):
+    n = 4096
+    g, e = si.gaussian_gradient(n, DEV, 51), si.residual_vector(n, DEV, 52)
+    ef = EF(dct, n)
+    ef.select(g, e, 10)
+    lib = dct.lib()
+    args = lambda gg, ei, eo, dt: lib.dct_ef_threshold_compact(  # noqa: E731
+        gg, ei, eo, dt, n, ef.thr.data_ptr(), 0, ef.idx.data_ptr(), ef.val.data_ptr(), n, ef.count.data_ptr(),
+        ef.ws.data_ptr(), ef.ws.numel(), None)
+    out = torch.zeros(n, device=DEV)
+    assert args(g.data_ptr(), e.data_ptr(), out.data_ptr(), 0) == 0
+    assert args(g.data_ptr(), e.data_ptr(), out.data_ptr(), 1) == 1       # bf16: not defined
+    assert args(g.data_ptr(), None, out.data_ptr(), 0) == 1
+    assert args(g.data_ptr(), e.data_ptr(), None, 0) == 1
+    assert args(g.data_ptr(), e.data_ptr(), g.data_ptr(), 0) == 1         # g overlaps e_out
+    assert args(g.data_ptr(), e.data_ptr(), e.data_ptr() + 16, 0) == 1    # e_in partially overlaps e_out
+    assert lib.dct_ef_select_threshold(g.data_ptr(), None, 0, n, 10, ef.thr.data_ptr(), ef.sel_ws.data_ptr(),
+                                       ef.sel_ws.numel(), None) == 1
+    assert lib.dct_ef_select_threshold(g.data_ptr(), e.data_ptr(), 1, n, 10, ef.thr.data_ptr(),
+                                       ef.sel_ws.data_ptr(), ef.sel_ws.numel(), None) == 1
+    torch.cuda.synchronize()
