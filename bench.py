@@ -11,8 +11,9 @@ alternate so that no step re-reads what the previous one left in cache.
 
 Prints ONE JSON line: whole-step throughput in elements/s, per-call times and
 HBM fractions, the roofline entry of the dominant kernel, the c3 reuse loop
-(threshold selected once, applied to fresh draws) and the CPU oracle timed on a
-bounded sample of the same workload.
+(threshold selected once, applied to fresh draws), the two DCT-DP calls with
+error feedback fused in (timed on the same c4 gradients; not part of the step)
+and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -35,12 +36,16 @@ HBM_PEAK_GBPS = 8000.0
 
 # kernels behind each timed call (names as rocprofv3 prints them) and launches per call
 CALL_KERNELS = {
-    "dct_select_threshold[c4]": [("dct::select_gather_kernel<0>", 1), ("dct::select_bounds_kernel<0>", 1),
-                                 ("dct::select_partition_kernel<0> [c4]", 1), ("dct::select_pass_kernel<0>", 3),
-                                 ("dct::select_finish_kernel", 1)],
-    "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true>", 1)],
+    "dct_select_threshold[c4]": [("dct::select_gather_kernel<0, false>", 1), ("dct::select_bounds_kernel<0>", 1),
+                                 ("dct::select_partition_kernel<0, false> [c4]", 1),
+                                 ("dct::select_pass_kernel<0, false>", 3), ("dct::select_finish_kernel", 1)],
+    "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false>", 1)],
     "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_bf16_kernel<8>", 1)],
     "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_gather_kernel<unsigned short>", 1)],
+    "dct_ef_select_threshold[c4]": [("dct::select_gather_kernel<0, true>", 1), ("dct::select_bounds_kernel<0>", 1),
+                                    ("dct::select_partition_kernel<0, true>", 1),
+                                    ("dct::select_pass_kernel<0, true>", 3), ("dct::select_finish_kernel", 1)],
+    "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true>", 1)],
 }
 
 
@@ -194,6 +199,26 @@ def main():
         "algorithmic_bytes_64B_sectors": gran64, "GBps_64B_sectors": round(gran64 / (us * 1e-6) / 1e9, 1),
         "note": "algorithmic_bytes counts the 128-byte lines the gather touches"}))
 
+    # ------------------------------------------------------------ error feedback fused in (not part of the step)
+    # Same c4 gradients plus a resident residual per copy; the new residual goes to a third buffer so
+    # that every repetition sees the same sums.
+    ef_calls = []
+    e4 = [si.residual_vector(n4, dev, si.BASE_SEED + 60 + j) for j in range(2)]
+    e4_out = torch.empty(n4, dtype=torch.float32, device=dev)
+    cap4e = 2 * k4
+    idx4e = torch.zeros(cap4e, dtype=torch.int32, device=dev)
+    val4e = torch.zeros(cap4e, dtype=torch.float32, device=dev)
+    us = time_calls(lambda i: dct.dct_ef_select_threshold(g4[i & 1], e4[i & 1], k4, thr, sel_ws), args.reps)
+    ef_calls.append(entry("dct_ef_select_threshold[c4]", us, 2 * n4 * 4 + 16, n4, launches=sel_launches))
+    dct.dct_ef_select_threshold(g4[0], e4[0], k4, thr, sel_ws)
+    us = time_calls(lambda i: dct.dct_ef_threshold_compact(g4[0], e4[0], e4_out, thr, dct.DCT_GE_TAU, idx4e, val4e,
+                                                           cnt4, cmp_ws), args.reps)
+    c4e = dct.read_count(cnt4, capacity=cap4e)
+    ef_calls.append(entry("dct_ef_threshold_compact[c4,ge_tau]", us, 3 * n4 * 4 + c4e * 12 + 8, n4,
+                          extra={"survivors": c4e}))
+    del e4, e4_out, idx4e, val4e
+    call_select(0)
+
     # plain streaming kernels: the achievable HBM rate measured in the same run
     probe_bytes = (4 << 30) // shrink
     probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -204,7 +229,7 @@ def main():
     probes = {"read_GBps": round(probe_bytes / (us_read * 1e-6) / 1e9, 1),
               "copy_GBps": round(probe_bytes / (us_copy * 1e-6) / 1e9, 1)}
     del probe_src, probe_dst
-    for c in calls:
+    for c in calls + ef_calls:
         c["frac_of_probe_read"] = round(c["GBps"] / probes["read_GBps"], 4)
         log(f"[bench] {c['call']}: {c['us']} us, {c['GBps']} GB/s = {c['frac_of_hbm_peak']:.1%} of 8 TB/s")
     log(f"[bench] probes: {probes}")
@@ -217,7 +242,7 @@ def main():
                 "launches_per_call": dom["launches"],
                 "note": "achieved = algorithmic bytes of the call / HIP-event time of the call; traffic = scaled "
                         "FETCH_SIZE + WRITE_SIZE of its kernels from profiles/bench_hbm_counters.txt"}
-    for c in calls:
+    for c in calls + ef_calls:
         c["traffic"] = measured_traffic(c["call"])
 
     # ------------------------------------------------------------ c3: select once, reuse on fresh draws
@@ -296,7 +321,7 @@ def main():
         "config": {"workload": "c4 DP select+compact (N=2^28 fp32, keep 0.5%) + c5 MP row top-k fwd+bwd "
                                "(65536x4096 bf16, k=204)" + (" [SHRUNK 16x: not a valid number]" if args.small else ""),
                    "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
-        "roofline": roofline, "calls": calls, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
+        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 

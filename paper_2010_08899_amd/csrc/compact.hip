@@ -306,8 +306,8 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
       if (wg_lo + (row + ROWS) * kWave <= wg_hi) {  // uniform: all rows inside the chunk
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-          buf.a[r] = av[vec0 + r * kWave];
-          if constexpr (kAdd) buf.b[r] = bv[vec0 + r * kWave];
+          buf.a[r] = ld_stream(&av[vec0 + r * kWave]);
+          if constexpr (kAdd) buf.b[r] = ld_stream(&bv[vec0 + r * kWave]);
         }
       } else {
 #pragma unroll
@@ -332,7 +332,7 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
 #pragma unroll
           for (int e = 0; e < V; ++e)
             raw[e] = __float_as_uint(__uint_as_float(raw[e]) + __uint_as_float(E::raw(buf.b[r], e)));
-          if (in) wv[vi] = make_uint4(raw[0], raw[1], raw[2], raw[3]);
+          if (in) st_stream(&wv[vi], raw[0], raw[1], raw[2], raw[3]);
         }
         emit(raw, in, geo.head + vi * V, std::integral_constant<int, V>{});
       }

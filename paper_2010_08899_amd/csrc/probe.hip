@@ -19,7 +19,7 @@ __global__ __launch_bounds__(kPrThreads) void probe_read_kernel(const uint4* __r
 #pragma unroll
     for (int u = 0; u < kPrUnroll; ++u) {
       const uint64_t i = base + static_cast<uint64_t>(u) * kPrThreads + threadIdx.x;
-      v[u] = i < n_vec ? src[i] : make_uint4(0, 0, 0, 0);
+      v[u] = i < n_vec ? ld_stream(&src[i]) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int u = 0; u < kPrUnroll; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
@@ -39,12 +39,12 @@ __global__ __launch_bounds__(kPrThreads) void probe_copy_kernel(uint4* __restric
 #pragma unroll
     for (int u = 0; u < kPrUnroll; ++u) {
       const uint64_t i = base + static_cast<uint64_t>(u) * kPrThreads + threadIdx.x;
-      if (i < n_vec) v[u] = src[i];
+      if (i < n_vec) v[u] = ld_stream(&src[i]);
     }
 #pragma unroll
     for (int u = 0; u < kPrUnroll; ++u) {
       const uint64_t i = base + static_cast<uint64_t>(u) * kPrThreads + threadIdx.x;
-      if (i < n_vec) dst[i] = v[u];
+      if (i < n_vec) st_stream(&dst[i], v[u].x, v[u].y, v[u].z, v[u].w);
     }
   }
 }

@@ -108,10 +108,11 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     const uint4* xr = reinterpret_cast<const uint4*>(x + r * stride) + lane;
     if (full_width) {
 #pragma unroll
-      for (int j = 0; j < NV; ++j) nxt[j] = xr[j * kWave];
+      for (int j = 0; j < NV; ++j) nxt[j] = ld_stream(&xr[j * kWave]);
     } else {
 #pragma unroll
-      for (int j = 0; j < NV; ++j) nxt[j] = j * kWave + lane < n_vec ? xr[j * kWave] : make_uint4(0, 0, 0, 0);
+      for (int j = 0; j < NV; ++j)
+        nxt[j] = j * kWave + lane < n_vec ? ld_stream(&xr[j * kWave]) : make_uint4(0, 0, 0, 0);
     }
   };
   if (row < B) load_row(row);

@@ -42,7 +42,7 @@ constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes r
 constexpr int kSampleThreads = 1024;
 constexpr uint32_t kSampleSize = 16384;         // 64 KiB of LDS
 constexpr int kGatherThreads = 256;
-constexpr int kPartRows = 8;                    // 16-byte loads per lane per iteration of the partition pass
+constexpr int kPartRows = 4;                    // 16-byte loads per lane per step of the partition pass
 constexpr uint32_t kPartStage = 1024;           // staged candidate keys per wavefront
 constexpr uint32_t kPartTileVecs = kSelThreads * kPartRows;
 
@@ -285,7 +285,7 @@ struct PartGeom {
 };
 
 template <int DT, bool EF>
-__global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
+__global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* __restrict__ e, PartGeom geo,
     SelWs* ws) {
   static_assert(!EF || DT == DCT_F32, "error feedback is an fp32 addition");
@@ -347,7 +347,7 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
     }
   };
 
-  // Tiles of 32 KiB are dealt round-robin to the workgroups, so that at any time the
+  // Tiles of 16 KiB are dealt round-robin to the workgroups, so that at any time the
   // grid reads one contiguous window of the vector (order is irrelevant here).
   const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
   const uint32_t tiles = (geo.n_vec + kPartTileVecs - 1) / kPartTileVecs;
@@ -375,8 +375,8 @@ __global__ __launch_bounds__(kSelThreads) void select_partition_kernel(
     if (tile_is_full(q)) {  // uniform
 #pragma unroll
       for (int r = 0; r < ROWS; ++r) {
-        buf.a[r] = gv[vec0 + r * kWave];
-        if constexpr (EF) buf.b[r] = ev[vec0 + r * kWave];
+        buf.a[r] = ld_stream(&gv[vec0 + r * kWave]);
+        if constexpr (EF) buf.b[r] = ld_stream(&ev[vec0 + r * kWave]);
       }
     } else {
 #pragma unroll
