@@ -240,11 +240,14 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
 
   // Both order statistics are searched together: while their fixed digits agree
   // (the usual case until the last pass) one histogram serves both.
+  // The bounds only have to bracket tau, so the digits below the second pass are not
+  // resolved: lo takes zeros there and hi ones (a relative widening of 2^-14 for fp32).
   const PassDigits dg = pass_digits(DT);
+  const int n_pass = dg.n_pass < 2 ? dg.n_pass : 2;
   const uint32_t rank[2] = {static_cast<uint32_t>(rank_hi), static_cast<uint32_t>(rank_lo)};
   uint32_t prefix[2] = {0, 0}, k_rem[2] = {rank[0], rank[1]};
   uint32_t fixed_mask = 0;
-  for (int p = 0; p < dg.n_pass; ++p) {
+  for (int p = 0; p < n_pass; ++p) {
     const int shift = dg.shift[p];
     const uint32_t dmask = (1u << dg.width[p]) - 1u;
     const bool shared = rank[0] != 0 && rank[1] != 0 && prefix[0] == prefix[1];  // uniform
@@ -266,7 +269,9 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
     }
     fixed_mask |= dmask << shift;
   }
-  const uint32_t bound[2] = {rank[0] != 0 ? prefix[0] : E::kKeyMask, rank[1] != 0 ? prefix[1] : 0u};  // {hi, lo}
+  const uint32_t open_bits = E::kKeyMask & ~fixed_mask;
+  const uint32_t bound[2] = {rank[0] != 0 ? (prefix[0] | open_bits) : E::kKeyMask,
+                             rank[1] != 0 ? prefix[1] : 0u};  // {hi, lo}
   if (t == 0) {
     ws->hi = bound[0];
     ws->lo = bound[1];
