@@ -33,7 +33,7 @@ namespace fast {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr uint32_t kWindow = 32;
-constexpr int kWindowLog2 = 5;
+constexpr int kSampleRegs = 4;  // packed registers per lane in the first row's sample (8 keys per lane)
 
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
@@ -191,12 +191,11 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     };
 
     // ---- 3. locate tau
+    // window [wlo, wlo + kWindow): bitmaps of the keys at or above its two ends and their counts
     uint32_t above[WORDS], inwin[WORDS];
     uint32_t wlo = 0, n_above = 0, n_win = 0;
-    bool hit = false;
-    if (guess != 0xFFFFFFFFu) {
-      wlo = guess >= kWindow / 2 ? guess - kWindow / 2 : 0u;
-      wlo = min(wlo, 0x8000u - kWindow);
+    auto window_at = [&](uint32_t lo_end) {
+      wlo = lo_end;
       uint32_t lo_bits[WORDS];
       ge_bitmap(wlo, lo_bits);
       ge_bitmap(wlo + kWindow, above);
@@ -210,30 +209,66 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
       const uint32_t both = wave_total(ca | (cw << 16));  // each count is at most 4096
       n_above = both & 0xFFFFu;
       n_win = both >> 16;
+    };
+    // Brackets in units of the window width: count_ge(lo_u * width) >= k > count_ge(hi_u * width).
+    uint32_t lo_u = 0, hi_u = 0x8000u / kWindow;
+    if (guess == 0xFFFFFFFFu && REGS > kSampleRegs) {
+      // no previous row: estimate tau as the matching order statistic of a sample of the row
+      // (kSampleRegs registers of every lane), by bisection over all 15 key bits
+      const uint32_t ks = max(1u, (k * kSampleRegs + REGS - 1) / REGS);
+      uint32_t t = 0;
+      for (int bit = 14; bit >= 0; --bit) {
+        const uint32_t cand = t | (1u << bit);
+        const uint32_t t2 = cand * 0x00010001u;
+        uint32_t acc = 0;
+#pragma unroll
+        for (int i = 0; i < kSampleRegs; ++i) acc = pk_add_u16(acc, pk_lshr15_u16(pk_sub_u16(K[i], t2)));
+        if (wave_total((acc & 0xFFFFu) + (acc >> 16)) >= ks) t = cand;
+      }
+      guess = t;
+    }
+    bool hit = false;
+    if (guess != 0xFFFFFFFFu) {
+      uint32_t lo_end = guess >= kWindow / 2 ? guess - kWindow / 2 : 0u;
+      lo_end = min(lo_end, 0x8000u - kWindow);
+      window_at(lo_end);
       hit = n_above < k && k <= n_above + n_win;
+      if (!hit) {
+        // gallop away from the failed window in the direction the counts point to
+        if (n_above >= k) {  // tau is at or above the window's upper end
+          lo_u = (wlo + kWindow) / kWindow;  // rounded down: still has >= k keys at or above it
+          for (uint32_t step = 1;; step *= 2) {
+            const uint32_t probe = min(lo_u + step, hi_u);
+            if (probe == hi_u) break;
+            if (count_ge(probe * kWindow) >= k) {
+              lo_u = probe;
+            } else {
+              hi_u = probe;
+              break;
+            }
+          }
+        } else {             // fewer than k keys at or above the window's lower end
+          hi_u = (wlo + kWindow - 1) / kWindow;  // rounded up: still has < k keys at or above it
+          for (uint32_t step = 1;; step *= 2) {
+            const uint32_t probe = hi_u > step ? hi_u - step : 0u;
+            if (probe == 0u) break;
+            if (count_ge(probe * kWindow) < k) {
+              hi_u = probe;
+            } else {
+              lo_u = probe;
+              break;
+            }
+          }
+        }
+      }
     }
     if (!hit) {
-      // bisection over the key bits above the window width: the largest multiple of
-      // the window width with at least k keys at or above it
-      uint32_t t = 0;
-      for (int bit = 14; bit >= kWindowLog2; --bit) {
-        const uint32_t cand = t | (1u << bit);
-        if (count_ge(cand) >= k) t = cand;
+      // bisection between the brackets, in units of the window width
+      while (hi_u - lo_u > 1) {
+        const uint32_t mid = (lo_u + hi_u) / 2;
+        if (count_ge(mid * kWindow) >= k) lo_u = mid; else hi_u = mid;
       }
-      wlo = t;  // a multiple of the window width below 0x8000, so wlo + width <= 0x8000
-      uint32_t lo_bits[WORDS];
-      ge_bitmap(wlo, lo_bits);
-      ge_bitmap(wlo + kWindow, above);
-      uint32_t ca = 0, cw = 0;
-#pragma unroll
-      for (int w = 0; w < WORDS; ++w) {
-        inwin[w] = lo_bits[w] & ~above[w];
-        ca += __popc(above[w]);
-        cw += __popc(inwin[w]);
-      }
-      const uint32_t both = wave_total(ca | (cw << 16));
-      n_above = both & 0xFFFFu;
-      n_win = both >> 16;
+      window_at(lo_u * kWindow);  // count_ge(wlo) >= k > count_ge(wlo + width): tau is inside
     }
 
     // histogram of the keys inside the window: bin = key - wlo, one bin per lane
