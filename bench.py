@@ -70,19 +70,18 @@ def log(*a):
 
 
 def time_calls(fn, reps, warmup=2):
-    """Average duration in microseconds of fn(i), measured with HIP events on the
-    stream the kernels are launched on (torch's current stream)."""
+    """Median duration in microseconds of fn(i) over `reps` back-to-back calls, each bracketed by HIP
+    events on the stream the kernels are launched on (torch's current stream)."""
     for i in range(warmup):
         fn(i)
-    start = torch.cuda.Event(enable_timing=True)
-    stop = torch.cuda.Event(enable_timing=True)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     torch.cuda.synchronize()
-    start.record()
+    ev[0].record()
     for i in range(reps):
         fn(i)
-    stop.record()
+        ev[i + 1].record()
     torch.cuda.synchronize()
-    return start.elapsed_time(stop) * 1e3 / reps
+    return float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)])) * 1e3
 
 
 def main():
