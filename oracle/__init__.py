@@ -49,6 +49,9 @@ def _load():
         lib.oracle_ef_accumulate.argtypes = [vp, vp, u64, vp]
         lib.oracle_ef_select_threshold.argtypes = [vp, vp, u64, u64, vp]
         lib.oracle_ef_threshold_compact.argtypes = [vp, vp, u64, vp, i32, vp, vp, u64, vp, vp]
+        lib.oracle_scatter.argtypes = [vp, vp, u64, i32, u64, vp, i32]
+        lib.oracle_rowscatter.argtypes = [vp, vp, i32, u32, u32, u32, vp, u64]
+        lib.oracle_scatter.restype = lib.oracle_rowscatter.restype = ctypes.c_int
         for f in (lib.oracle_ef_accumulate, lib.oracle_ef_select_threshold, lib.oracle_ef_threshold_compact):
             f.restype = ctypes.c_int
         for f in (lib.oracle_select_threshold, lib.oracle_select_threshold_nth, lib.oracle_threshold_compact,
@@ -190,3 +193,37 @@ def ef_threshold_compact(g: np.ndarray, e: np.ndarray, thr: Threshold, mode: int
     c = int(count[0])
     m = min(c, cap)
     return idx[:m], val[:m], c, e_out
+
+
+# ---- receiver side: decompression --------------------------------------------
+SCATTER_ASSIGN, SCATTER_ADD = 0, 1
+
+
+def scatter(idx: np.ndarray, val: np.ndarray, n: int, out: np.ndarray | None = None, mode: int = SCATTER_ASSIGN):
+    """Dense vector of n elements from (idx, val) pairs.  ASSIGN ignores the
+    contents of `out` (a fresh array if None); ADD updates `out` (float32)."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    val = np.ascontiguousarray(val)
+    assert idx.shape == val.shape and idx.ndim == 1
+    if out is None:
+        out = np.full(n, 7, dtype=val.dtype)  # ASSIGN must overwrite every element
+    assert out.dtype == val.dtype and out.size == n and out.flags.c_contiguous
+    rc = _load().oracle_scatter(_ptr(idx), _ptr(val), idx.size, _dtype_code(val), n, _ptr(out), int(mode))
+    if rc != 0:
+        raise ValueError("oracle_scatter: invalid arguments")
+    return out
+
+
+def rowscatter(idx: np.ndarray, val: np.ndarray, D: int, out: np.ndarray | None = None):
+    """Dense [B, D] matrix from per-row (idx, val) lists; `out` may have a row stride above D."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    val = np.ascontiguousarray(val)
+    B, k = idx.shape
+    assert val.shape == idx.shape
+    if out is None:
+        out = np.full((B, D), 7, dtype=val.dtype)
+    assert out.dtype == val.dtype and out.shape == (B, D)
+    rc = _load().oracle_rowscatter(_ptr(idx), _ptr(val), _dtype_code(val), B, D, k, _ptr(out), _row_stride(out))
+    if rc != 0:
+        raise ValueError("oracle_rowscatter: invalid arguments")
+    return out

@@ -17,6 +17,10 @@
 //     *_ef functions add the residual first, select / filter the sum, and return
 //     the new residual.
 //
+//   * Receiver side (Sec. 2.1 "compression and decompression"; Algorithm 2: the
+//     next worker consumes X_act . M): oracle_scatter / oracle_rowscatter put the
+//     pairs back into a dense tensor, by assignment into zeros or (fp32) by addition.
+//
 // Readings fixed where the paper is silent (listed in the design notes too):
 //   * the caller passes the integer number kept, k; no fraction is rounded here;
 //   * magnitude order is the order of key(x) = bit pattern of x with the sign bit
@@ -285,6 +289,60 @@ int oracle_ef_threshold_compact(const float* g, const float* e_in, uint64_t n, c
         e_out[i] = written ? 0.0f : w[i];
     }
     *count = kept;
+    return 0;
+}
+
+// ---- receiver side: decompression -------------------------------------------
+// What the next worker / the parameter server does with a compressed message
+// (Sec. 2.1 counts "compression and decompression" as the overhead of DCT; in
+// Algorithm 2 the next worker consumes X_act . M): put the pairs back into a
+// dense tensor.  mode 0 (assign): out = 0, then out[idx[j]] = val[j];
+// mode 1 (add, fp32 only): out[idx[j]] = out[idx[j]] + val[j], one binary32
+// addition each (the server-side sum of the workers' sparse gradients).
+// Pairs are applied in order j = 0 .. count-1; an index outside [0, n) is skipped.
+int oracle_scatter(const int32_t* idx, const void* val, uint64_t count, int dtype, uint64_t n, void* out,
+                   int mode) {
+    if (!out || n == 0 || (count > 0 && (!idx || !val))) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (mode != 0 && !(mode == 1 && dtype == ORACLE_F32)) return 1;
+    const size_t es = elem_size(dtype);
+    if (mode == 0) std::memset(out, 0, es * n);
+    for (uint64_t j = 0; j < count; ++j) {
+        const int32_t i = idx[j];
+        if (i < 0 || static_cast<uint64_t>(i) >= n) continue;
+        unsigned char* dst = static_cast<unsigned char*>(out) + es * static_cast<uint64_t>(i);
+        const unsigned char* src = static_cast<const unsigned char*>(val) + es * j;
+        if (mode == 0) {
+            std::memcpy(dst, src, es);
+        } else {
+            float a, b;
+            std::memcpy(&a, dst, 4);
+            std::memcpy(&b, src, 4);
+            const float sum = static_cast<float>(static_cast<double>(a) + static_cast<double>(b));
+            std::memcpy(dst, &sum, 4);
+        }
+    }
+    return 0;
+}
+
+// Dense [B, D] matrix (row stride out_stride elements) from the per-row lists
+// of Algorithm 2: zero everywhere, out[b, idx[b, j]] = val[b, j].  Elements
+// between D and out_stride are not touched.  A column outside [0, D) is skipped.
+int oracle_rowscatter(const int32_t* idx, const void* val, int dtype, uint32_t B, uint32_t D, uint32_t k,
+                      void* out, uint64_t out_stride) {
+    if (!idx || !val || !out || B == 0 || D == 0 || k == 0 || out_stride < D) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    const size_t es = elem_size(dtype);
+    for (uint32_t b = 0; b < B; ++b) {
+        unsigned char* row = static_cast<unsigned char*>(out) + es * out_stride * b;
+        std::memset(row, 0, es * D);
+        for (uint32_t j = 0; j < k; ++j) {
+            const uint64_t o = static_cast<uint64_t>(b) * k + j;
+            const int32_t c = idx[o];
+            if (c < 0 || static_cast<uint32_t>(c) >= D) continue;
+            std::memcpy(row + es * static_cast<uint32_t>(c), static_cast<const unsigned char*>(val) + es * o, es);
+        }
+    }
     return 0;
 }
 

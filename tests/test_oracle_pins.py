@@ -569,3 +569,93 @@ def test_error_feedback_residual_is_eventually_delivered():
             assert cnt == n and np.all(val[4:] == 1.0)   # 8 * 0.125, summed exactly
             assert np.all(e == 0.0)
     assert first_delivery == 8
+
+
+# ------------------------------------------------------------------ receiver side: decompression
+def test_scatter_hand_worked():
+    """The message of iteration 1 of the error-feedback fixture, put back into a dense vector."""
+    out = oracle.scatter(i32(["1", "4"]), f32(["-1.5", "-1.25"]), 8)
+    assert np.array_equal(bits(out), bits(f32("0 -1.5 0 0 -1.25 0 0 0".split())))
+    # server-side accumulation of two workers' messages (distinct positions, then a shared one)
+    acc = np.zeros(8, dtype=np.float32)
+    oracle.scatter(i32(["1", "4"]), f32(["-1.5", "-1.25"]), 8, out=acc, mode=oracle.SCATTER_ADD)
+    oracle.scatter(i32(["0", "4", "7"]), f32(["0.5", "0.25", "2"]), 8, out=acc, mode=oracle.SCATTER_ADD)
+    assert np.array_equal(bits(acc), bits(f32("0.5 -1.5 0 0 -1.0 0 0 2".split())))
+    # nothing to deliver: all zeros; indices outside the vector are skipped
+    assert np.all(bits(oracle.scatter(i32([]), f32([]), 5)) == 0)
+    out = oracle.scatter(i32(["-1", "2", "5"]), f32(["9", "3", "9"]), 5)
+    assert np.array_equal(out, f32("0 0 3 0 0".split()))
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_scatter_against_numpy_indexing(bf16):
+    rng = np.random.default_rng(5)
+    for n, c in [(1, 1), (10, 3), (1000, 0), (1000, 1000), (70_001, 700)]:
+        idx = np.sort(rng.choice(n, size=c, replace=False)).astype(np.int32)
+        val = rng.standard_normal(c).astype(np.float32)
+        if bf16:
+            val = to_bf16_bits(val)
+        want = np.zeros(n, dtype=val.dtype)
+        want[idx] = val  # numpy fancy indexing: a library routine
+        assert np.array_equal(bits(oracle.scatter(idx, val, n)), bits(want))
+        if not bf16:
+            base = rng.standard_normal(n).astype(np.float32)
+            want = base.copy()
+            want[idx] += val
+            got = oracle.scatter(idx, val, n, out=base.copy(), mode=oracle.SCATTER_ADD)
+            assert np.array_equal(bits(got), bits(want))
+    with pytest.raises(ValueError):
+        oracle.scatter(i32(["0"]), to_bf16_bits(f32(["1"])), 4, out=np.zeros(4, dtype=np.uint16),
+                       mode=oracle.SCATTER_ADD)
+
+
+@settings(max_examples=30, deadline=None)
+@given(n=st.integers(1, 3000), frac=st.floats(0.001, 1.0), seed=st.integers(0, 2**31 - 1), bf16=st.booleans())
+def test_compress_then_decompress_is_the_masked_gradient(n, frac, seed, bf16):
+    """Decompressing the message gives W_grad . M, and with error feedback the
+    decompressed message plus the new residual is the corrected gradient."""
+    rng = np.random.default_rng(seed)
+    g = (rng.integers(-6, 7, n) * 0.25).astype(np.float32) if seed % 2 else rng.standard_normal(n).astype(np.float32)
+    gq = to_bf16_bits(g) if bf16 else g
+    k = max(1, min(n, int(round(frac * n))))
+    thr = oracle.select_threshold(gq, k)
+    idx, val, cnt = oracle.threshold_compact(gq, thr, oracle.GE_TAU)
+    mask = keys_of(gq) >= thr.tau_key
+    want = np.where(mask, gq, np.zeros_like(gq))
+    assert np.array_equal(bits(oracle.scatter(idx, val, n)), bits(want))
+    if not bf16:
+        e = (0.5 * rng.standard_normal(n)).astype(np.float32)
+        thr = oracle.ef_select_threshold(g, e, k)
+        idx, val, cnt, e_out = oracle.ef_threshold_compact(g, e, thr, oracle.EXACT_K)
+        assert np.array_equal(oracle.scatter(idx, val, n) + e_out, g + e)
+
+
+def test_rowscatter_against_numpy_and_round_trip():
+    rng = np.random.default_rng(9)
+    B, D, k = 7, 40, 6
+    x = np.maximum(rng.standard_normal((B, D)), 0).astype(np.float32)
+    x[3, :] = 0
+    x[3, 5] = -2.0
+    for xq in (x, to_bf16_bits(x.reshape(-1)).reshape(B, D)):
+        idx, val, tau = oracle.rowtopk_fwd(xq, k)
+        want = np.zeros_like(xq)
+        np.put_along_axis(want, idx.astype(np.int64), val, axis=1)  # library routine
+        got = oracle.rowscatter(idx, val, D)
+        assert np.array_equal(bits(got.reshape(-1)), bits(want.reshape(-1)))
+        # the dense result is X_act . M: kept entries equal x, the rest is zero
+        keep = np.zeros((B, D), dtype=bool)
+        np.put_along_axis(keep, idx.astype(np.int64), True, axis=1)
+        assert np.array_equal(bits(got[keep]), bits(xq[keep])) and np.all(bits(got[~keep]) == 0)
+        # gathering the dense result through the same mask returns the values
+        assert np.array_equal(bits(oracle.rowtopk_bwd(got, idx).reshape(-1)), bits(val.reshape(-1)))
+    # a wider output buffer: the padding is not touched; columns outside [0, D) are skipped
+    buf = np.full((B, D + 8), 7, dtype=np.float32)
+    idx, val, _ = oracle.rowtopk_fwd(x, k)
+    idx2 = idx.copy()
+    idx2[0, 0] = D + 3
+    oracle.rowscatter(idx2, val, D, out=buf[:, :D])
+    assert np.all(buf[:, D:] == 7)
+    want = np.zeros((B, D), dtype=np.float32)
+    np.put_along_axis(want, idx.astype(np.int64), val, axis=1)
+    want[0, idx[0, 0]] = 0
+    assert np.array_equal(buf[:, :D], want)
