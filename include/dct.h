@@ -164,6 +164,37 @@ int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_
 int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
                     const int32_t* d_idx, void* d_dval_out, void* hip_stream);
 
+/* ------------------------------------------------------------ receiver side ---
+ * Decompression of the two message formats above (Sec. 2.1 counts "compression
+ * and decompression" as the overhead of the method; in Algorithm 2 the next
+ * worker consumes X_act . M; the parameter server sums sparse gradients).
+ *
+ * dct_scatter: (idx, val) pairs -> dense vector of n elements.
+ *   d_idx, d_val  device, `capacity` pairs as written by dct_threshold_compact:
+ *                 indices ascending and distinct.  An index outside [0, n) is
+ *                 skipped.  (If the order is violated the result is unspecified;
+ *                 nothing is written out of bounds.)
+ *   d_count       device uint64 or NULL.  The number of pairs applied is
+ *                 min(*d_count, capacity), read on the device (capacity if NULL;
+ *                 0 if *d_count is DCT_COUNT_WORKSPACE_ERROR): the count written by
+ *                 the compaction can be passed on without a host round trip.
+ *   mode          DCT_SCATTER_ASSIGN: d_out = 0 everywhere, then d_out[idx[j]] = val[j]
+ *                 (bit copies; every element of d_out is written exactly once when
+ *                 d_out is 16-byte aligned).
+ *                 DCT_SCATTER_ADD (DCT_F32 only): d_out[idx[j]] = d_out[idx[j]] + val[j],
+ *                 one binary32 addition each; all other elements are left alone.
+ *
+ * dct_rowtopk_scatter: per-row lists of dct_rowtopk_fwd -> dense rows:
+ *   d_out[b, 0..D) = 0, then d_out[b, idx[b, j]] = val[b, j]; elements between D and
+ *   the row stride are not touched; a column outside [0, D) is skipped; columns of a
+ *   row must be distinct.
+ */
+typedef enum { DCT_SCATTER_ASSIGN = 0, DCT_SCATTER_ADD = 1 } dct_scatter_mode;
+int dct_scatter(const int32_t* d_idx, const void* d_val, const uint64_t* d_count, uint64_t capacity, int dt,
+                void* d_out, uint64_t n, int mode, void* hip_stream);
+int dct_rowtopk_scatter(const int32_t* d_idx, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k,
+                        void* d_out, uint64_t out_row_stride_elems, void* hip_stream);
+
 /* ------------------------------------------------------------ measurement ---
  * Plain streaming kernels used by the benchmark to measure the achievable HBM
  * rate next to the DCT kernels (not part of the method).

@@ -17,6 +17,7 @@ from . import build as _build
 DCT_OK, DCT_ERR_INVALID, DCT_ERR_WORKSPACE, DCT_ERR_OVERFLOW, DCT_ERR_HIP = range(5)
 DCT_F32, DCT_BF16 = 0, 1
 DCT_GE_TAU, DCT_EXACT_K = 0, 1
+DCT_SCATTER_ASSIGN, DCT_SCATTER_ADD = 0, 1
 COUNT_WORKSPACE_ERROR = (1 << 64) - 1
 
 _EXPORTS = {
@@ -42,6 +43,11 @@ _EXPORTS = {
     "dct_rowtopk_bwd": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
                                        ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p]),
+    "dct_scatter": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
+                                   ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]),
+    "dct_rowtopk_scatter": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32,
+                                           ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
+                                           ctypes.c_void_p]),
     "dct_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
     "dct_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "dct_status_string": (ctypes.c_char_p, [ctypes.c_int]),
@@ -239,6 +245,31 @@ def dct_rowtopk_bwd(dy: torch.Tensor, idx: torch.Tensor, dval_out: torch.Tensor)
         raise ValueError("dval_out must be a contiguous [B, k] tensor of dy.dtype")
     _check(lib().dct_rowtopk_bwd(ptr, _dt(dy), B, D, stride, k, _dev(idx, "idx"), _dev(dval_out, "dval_out"),
                                  _stream()), "dct_rowtopk_bwd")
+
+
+# ------------------------------------------------------------------ receiver side
+def dct_scatter(idx: torch.Tensor, val: torch.Tensor, count: torch.Tensor | None, out: torch.Tensor,
+                mode: int = DCT_SCATTER_ASSIGN, capacity: int | None = None) -> None:
+    """Pairs -> dense vector `out`; `count` is the device int64[1] written by the compaction (or None)."""
+    cap = min(idx.numel(), val.numel()) if capacity is None else int(capacity)
+    if cap > min(idx.numel(), val.numel()):
+        raise ValueError("capacity exceeds the pair tensors")
+    if idx.dtype != torch.int32 or val.dtype != out.dtype or (count is not None and count.dtype != torch.int64):
+        raise TypeError("idx must be int32, val must match out, count must be int64")
+    _check(lib().dct_scatter(_flat(idx, "idx") if cap else None, _flat(val, "val") if cap else None,
+                             _dev(count, "count") if count is not None else None, cap, _dt(out),
+                             _flat(out, "out"), out.numel(), int(mode), _stream()), "dct_scatter")
+
+
+def dct_rowtopk_scatter(idx: torch.Tensor, val: torch.Tensor, out: torch.Tensor) -> None:
+    """Per-row lists [B, k] -> dense rows of `out` ([B, D], unit column stride)."""
+    ptr, B, D, stride = _rows(out, "out")
+    if idx.dtype != torch.int32 or idx.dim() != 2 or idx.shape[0] != B or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous int32 [B, k] tensor")
+    if val.dtype != out.dtype or val.shape != idx.shape or not val.is_contiguous():
+        raise ValueError("val must be a contiguous [B, k] tensor of out.dtype")
+    _check(lib().dct_rowtopk_scatter(_dev(idx, "idx"), _dev(val, "val"), _dt(out), B, D, idx.shape[1], ptr, stride,
+                                     _stream()), "dct_rowtopk_scatter")
 
 
 # ------------------------------------------------------------------ measurement helpers

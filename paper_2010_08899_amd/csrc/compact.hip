@@ -363,6 +363,9 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
 
   // ---- 1+2: stream the chunk, stage survivors in LDS
   const uint32_t staged = pass(std::false_type{}, 0u, 0u);
+  // the residual stores of this pass have landed before anything (the +0 of a delivered pair, the
+  // second pass's loads) touches the same addresses again
+  if constexpr (EF) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (lane == 0) {
     s_wave_a[wave] = wa;
     s_wave_e[wave] = we | (staged > kCtStageCap ? kTieFlag : 0u);  // top bit: this wavefront's region overflowed

@@ -519,3 +519,121 @@ def test_dp_ef_argument_errors(dct):
     assert lib.dct_ef_select_threshold(g.data_ptr(), e.data_ptr(), 1, n, 10, ef.thr.data_ptr(),
                                        ef.sel_ws.data_ptr(), ef.sel_ws.numel(), None) == 1
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ receiver side: decompression
+def check_scatter(dct, g, k, mode=0, capacity=None, shift=0):
+    """compress on the GPU, decompress on the GPU (the count stays on the device), compare the dense
+    result with the oracle's decompression of the oracle's message."""
+    n = g.numel()
+    dp = DP(dct, g, capacity=capacity)
+    thr = dp.select(k)
+    idx, val, cnt, _ = dp.compact(mode)
+    gh = host(g)
+    eidx, eval_, ecnt = oracle.threshold_compact(gh, thr, mode, capacity=capacity)
+    buf = torch.full((n + shift,), 3.0, device=DEV).to(g.dtype)
+    out = buf[shift:]
+    dct.dct_scatter(dp.idx, dp.val, dp.count, out, dct.DCT_SCATTER_ASSIGN, capacity=dp.cap)
+    want = oracle.scatter(eidx, eval_, n)
+    assert np.array_equal(bits(host(out)), bits(want))
+    if shift:
+        assert torch.all(buf[:shift] == 3.0)
+    return dp
+
+
+@pytest.mark.parametrize("n", [1, 5, 4095, 4096, 4097, 100_003, 1_000_000, 5_000_011])
+def test_scatter_sizes(dct, n):
+    g = si.gaussian_gradient(n, DEV, 600 + n)
+    for k in sorted({1, max(1, n // 100), max(1, n // 2), n}):
+        check_scatter(dct, g, k)
+    check_scatter(dct, g.to(torch.bfloat16), max(1, n // 50), mode=1)
+
+
+def test_scatter_structure_and_edges(dct):
+    g, k = si.config_c4(DEV, rows=si.C4_ROWS // 64)   # clustered survivors: whole tiles without any pair
+    check_scatter(dct, g, k // 64 + 1, mode=1)
+    g = si.gaussian_gradient(300_000, DEV, 61)
+    check_scatter(dct, g, 3000, capacity=777)          # count > capacity: only the written pairs are applied
+    check_scatter(dct, g, 3000, capacity=0)            # nothing delivered: all zeros
+    for shift in (1, 2, 3):                             # output not 16-byte aligned
+        check_scatter(dct, g, 3000, shift=shift)
+    dp = check_scatter(dct, g, 3000)
+    # a failed compaction (error sentinel in the count) decompresses to zeros; no count pointer = all pairs
+    out = torch.full((g.numel(),), 3.0, device=DEV)
+    dp.count.fill_(-1)
+    dct.dct_scatter(dp.idx, dp.val, dp.count, out)
+    assert torch.all(out.view(torch.int32) == 0)
+    idx = torch.tensor([2, 5, 400_000, -3, 7], dtype=torch.int32, device=DEV)   # out-of-range indices are skipped
+    val = torch.tensor([1.0, 2.0, 9.0, 9.0, 3.0], device=DEV)
+    out = torch.full((10,), 3.0, device=DEV)
+    dct.dct_scatter(idx, val, None, out, dct.DCT_SCATTER_ADD)
+    assert host(out).tolist() == [3, 3, 4, 3, 3, 5, 3, 6, 3, 3]
+
+
+def test_scatter_add_server_accumulate(dct):
+    """Two workers' sparse gradients summed into one dense fp32 vector, against the oracle."""
+    n = 700_001
+    acc = si.gaussian_gradient(n, DEV, 71)
+    ref = host(acc).copy()
+    for w in range(2):
+        g = si.gaussian_gradient(n, DEV, 72 + w)
+        dp = DP(dct, g)
+        thr = dp.select(n // 100)
+        dp.compact(0)
+        dct.dct_scatter(dp.idx, dp.val, dp.count, acc, dct.DCT_SCATTER_ADD)
+        eidx, eval_, _ = oracle.threshold_compact(host(g), thr, 0)
+        oracle.scatter(eidx, eval_, n, out=ref, mode=oracle.SCATTER_ADD)
+        assert np.array_equal(bits(host(acc)), bits(ref))
+    lib = dct.lib()
+    bf = acc.to(torch.bfloat16)
+    assert lib.dct_scatter(dp.idx.data_ptr(), bf.data_ptr(), None, 8, 1, bf.data_ptr(), n, 1, None) == 1  # bf16 add
+    assert lib.dct_scatter(dp.idx.data_ptr(), acc.data_ptr(), None, 8, 0, None, n, 0, None) == 1
+    assert lib.dct_scatter(dp.idx.data_ptr(), acc.data_ptr(), None, 8, 0, acc.data_ptr(), n, 2, None) == 1
+
+
+def test_scatter_after_error_feedback_conserves_the_gradient(dct):
+    n, k = 1_200_000, 6000
+    g, e = si.gaussian_gradient(n, DEV, 81), si.residual_vector(n, DEV, 82)
+    ef = EF(dct, n)
+    ef.select(g, e, k)
+    e_out = torch.empty_like(e)
+    ef.compact(g, e, e_out, 1)
+    dense = torch.empty_like(g)
+    dct.dct_scatter(ef.idx, ef.val, ef.count, dense)
+    w = host(g) + host(e)
+    assert np.array_equal(host(dense) + host(e_out), w)
+
+
+@pytest.mark.parametrize("dtype,B,D,k,pad", [
+    (torch.float32, 33, 1024, 51, 0), (torch.float32, 5, 40, 6, 0), (torch.float32, 9, 1000, 50, 24),
+    (torch.bfloat16, 64, 4096, 204, 0), (torch.bfloat16, 7, 520, 26, 8), (torch.bfloat16, 3, 12_000, 600, 0),
+    (torch.float32, 3, 5000, 250, 0), (torch.bfloat16, 10, 33, 33, 1)])
+def test_rowtopk_scatter(dct, dtype, B, D, k, pad):
+    x = si.relu_activations(B, D, DEV, 900 + D, dtype=dtype)
+    idx = torch.zeros(B, k, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=dtype, device=DEV)
+    dct.dct_rowtopk_fwd(x, k, idx, val, None)
+    buf = torch.full((B, D + pad), 3.0, device=DEV).to(dtype)
+    out = buf[:, :D]
+    dct.dct_rowtopk_scatter(idx, val, out)
+    want = oracle.rowscatter(host(idx), host(val), D)
+    assert np.array_equal(bits(host(out.contiguous()).reshape(-1)), bits(want.reshape(-1)))
+    if pad:
+        assert torch.all(buf[:, D:] == 3.0)
+    # the dense rows gathered through the same mask give the values back
+    dval = torch.zeros_like(val)
+    dct.dct_rowtopk_bwd(out, idx, dval)
+    assert torch.equal(dval.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                       val.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+
+
+def test_rowtopk_scatter_c5_block(dct):
+    x, dy, k = si.config_c5(DEV, b=2048)
+    B, D = x.shape
+    idx = torch.zeros(B, k, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=x.dtype, device=DEV)
+    dct.dct_rowtopk_fwd(x, k, idx, val, None)
+    out = torch.empty_like(x)
+    dct.dct_rowtopk_scatter(idx, val, out)
+    want = oracle.rowscatter(host(idx), host(val), D)
+    assert np.array_equal(host(out), want)
