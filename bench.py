@@ -12,8 +12,8 @@ alternate so that no step re-reads what the previous one left in cache.
 Prints ONE JSON line: whole-step throughput in elements/s, per-call times and
 HBM fractions, the roofline entry of the dominant kernel, the c3 reuse loop
 (threshold selected once, applied to fresh draws), the two DCT-DP calls with
-error feedback fused in (timed on the same c4 gradients; not part of the step)
-and the CPU oracle timed on a bounded sample of the same workload.
+error feedback fused in and the receiver-side decompression calls (timed on the
+same c4 / c5 data; not part of the step) and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -46,6 +46,9 @@ CALL_KERNELS = {
                                     ("dct::select_partition_kernel<0, true>", 1),
                                     ("dct::select_pass_kernel<0, true>", 3), ("dct::select_finish_kernel", 1)],
     "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true>", 1)],
+    "dct_scatter[c4,assign]": [("dct::scatter_assign_kernel<unsigned int>", 1)],
+    "dct_scatter[c4,add]": [("dct::scatter_pairs_kernel<unsigned int, true>", 1)],
+    "dct_rowtopk_scatter[c5]": [("dct::rowscatter_lds_kernel<unsigned short>", 1)],
 }
 
 
@@ -218,6 +221,25 @@ def main():
     del e4, e4_out, idx4e, val4e
     call_select(0)
 
+    # ------------------------------------------------------------ receiver side: decompression (not part of the step)
+    # The messages of the step (c4 pairs with their device-side count, c5 row lists) put back into
+    # dense tensors; two output buffers alternate.
+    call_compact(0)
+    rx_calls = []
+    d4 = [torch.empty(n4, dtype=torch.float32, device=dev) for _ in range(2)]
+    us = time_calls(lambda i: dct.dct_scatter(idx4, val4, cnt4, d4[i & 1]), args.reps)
+    rx_calls.append(entry("dct_scatter[c4,assign]", us, n4 * 4 + k4 * 8 + 8, n4))
+    d4[0].zero_()
+    us = time_calls(lambda i: dct.dct_scatter(idx4, val4, cnt4, d4[0], dct.DCT_SCATTER_ADD), args.reps)
+    rx_calls.append(entry("dct_scatter[c4,add]", us, k4 * 16 + 8, k4, extra={
+        "note": "strict bytes (idx, val, read-modify-write of the touched floats); the touched sectors are larger"}))
+    del d4
+    d5 = [torch.empty(B5, D5, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    call_fwd(0)
+    us = time_calls(lambda i: dct.dct_rowtopk_scatter(idx5, val5, d5[i & 1]), args.reps)
+    rx_calls.append(entry("dct_rowtopk_scatter[c5]", us, B5 * D5 * 2 + B5 * k5 * 6, B5 * D5))
+    del d5
+
     # plain streaming kernels: the achievable HBM rate measured in the same run
     probe_bytes = (4 << 30) // shrink
     probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -228,7 +250,7 @@ def main():
     probes = {"read_GBps": round(probe_bytes / (us_read * 1e-6) / 1e9, 1),
               "copy_GBps": round(probe_bytes / (us_copy * 1e-6) / 1e9, 1)}
     del probe_src, probe_dst
-    for c in calls + ef_calls:
+    for c in calls + ef_calls + rx_calls:
         c["frac_of_probe_read"] = round(c["GBps"] / probes["read_GBps"], 4)
         log(f"[bench] {c['call']}: {c['us']} us, {c['GBps']} GB/s = {c['frac_of_hbm_peak']:.1%} of 8 TB/s")
     log(f"[bench] probes: {probes}")
@@ -241,7 +263,7 @@ def main():
                 "launches_per_call": dom["launches"],
                 "note": "achieved = algorithmic bytes of the call / HIP-event time of the call; traffic = scaled "
                         "FETCH_SIZE + WRITE_SIZE of its kernels from profiles/bench_hbm_counters.txt"}
-    for c in calls + ef_calls:
+    for c in calls + ef_calls + rx_calls:
         c["traffic"] = measured_traffic(c["call"])
 
     # ------------------------------------------------------------ c3: select once, reuse on fresh draws
@@ -320,7 +342,8 @@ def main():
         "config": {"workload": "c4 DP select+compact (N=2^28 fp32, keep 0.5%) + c5 MP row top-k fwd+bwd "
                                "(65536x4096 bf16, k=204)" + (" [SHRUNK 16x: not a valid number]" if args.small else ""),
                    "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
-        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
+        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls,
+        "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 
