@@ -164,6 +164,44 @@ int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_
 int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
                     const int32_t* d_idx, void* d_dval_out, void* hip_stream);
 
+/* ------------------------------------------------------ DCT-DP, many tensors ---
+ * Layer-wise compression (Sec. 2.1: every layer's gradient is compressed on its
+ * own, with its own threshold) for many tensors with a fixed number of launches:
+ * a tensor of a million elements is about a microsecond of memory traffic, so one
+ * call per layer is launch latency and nothing else.  The tensors are segments of
+ * one address range, described by a table in HOST memory that is read during the
+ * call only (it reaches the device as kernel arguments).
+ *
+ * Per segment s the results are exactly those of dct_select_threshold(g + offset,
+ * n, k) and dct_threshold_compact(g + offset, n, thr[s], mode, idx + out_offset,
+ * val + out_offset, capacity): indices are relative to the segment's first element.
+ * Meant for tensors that sit in cache (the compaction reads each twice); a tensor of
+ * hundreds of MB is better served by the single-tensor calls.
+ *
+ *   g           device base pointer, aligned to the element size
+ *   h_segs      host, n_seg entries (1 .. 1024); n in 1 .. 2^31-1, k in 1 .. n
+ *               (k is ignored by the compaction); the output ranges
+ *               [out_offset, out_offset + capacity) must not overlap
+ *   d_thr_out / d_thr   device, n_seg threshold records (16-byte aligned)
+ *   d_count_out device uint64[n_seg]: the true survivor count of every segment
+ *   d_ws        device, dct_batched_workspace_bytes(dt, h_segs, n_seg) bytes, 256-byte
+ *               aligned, scratch (no initialisation needed); one workspace serves both
+ *               calls, which must not overlap in time on it
+ */
+typedef struct {
+  uint64_t offset;     /* first element of the tensor, in elements from g                   */
+  uint64_t n;          /* elements                                                          */
+  uint64_t k;          /* entries to keep (selection)                                       */
+  uint64_t out_offset; /* first slot of this tensor's survivors in d_idx_out / d_val_out    */
+  uint64_t capacity;   /* slots this tensor may fill (may be 0)                             */
+} dct_segment;
+size_t dct_batched_workspace_bytes(int dt, const dct_segment* h_segs, uint32_t n_seg);
+int dct_select_threshold_batched(const void* g, int dt, const dct_segment* h_segs, uint32_t n_seg,
+                                 dct_threshold* d_thr_out, void* d_ws, size_t ws_bytes, void* hip_stream);
+int dct_threshold_compact_batched(const void* g, int dt, const dct_segment* h_segs, uint32_t n_seg,
+                                  const dct_threshold* d_thr, int mode, int32_t* d_idx_out, void* d_val_out,
+                                  uint64_t* d_count_out, void* d_ws, size_t ws_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------ receiver side ---
  * Decompression of the two message formats above (Sec. 2.1 counts "compression
  * and decompression" as the overhead of the method; in Algorithm 2 the next

@@ -8,5 +8,6 @@ from .binding import (  # noqa: F401
     dct_ef_select_threshold, dct_ef_threshold_compact, dct_rowtopk_bwd, dct_rowtopk_fwd, dct_rowtopk_scatter, dct_scatter, dct_select_threshold, dct_select_threshold_workspace_bytes,
     dct_status_string, dct_threshold_compact, dct_threshold_compact_workspace_bytes,
     dct_threshold_compact_workspace_init, lib, new_compact_workspace, new_select_workspace, read_count,
-    read_threshold,
+    read_threshold, Segment, segment_table, dct_batched_workspace_bytes, new_batched_workspace,
+    dct_select_threshold_batched, dct_threshold_compact_batched,
 )

@@ -43,6 +43,14 @@ _EXPORTS = {
     "dct_rowtopk_bwd": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
                                        ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p]),
+    "dct_batched_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32]),
+    "dct_select_threshold_batched": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32,
+                                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                                    ctypes.c_void_p]),
+    "dct_threshold_compact_batched": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32,
+                                                     ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                                     ctypes.c_void_p]),
     "dct_scatter": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
                                    ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]),
     "dct_rowtopk_scatter": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32,
@@ -245,6 +253,65 @@ def dct_rowtopk_bwd(dy: torch.Tensor, idx: torch.Tensor, dval_out: torch.Tensor)
         raise ValueError("dval_out must be a contiguous [B, k] tensor of dy.dtype")
     _check(lib().dct_rowtopk_bwd(ptr, _dt(dy), B, D, stride, k, _dev(idx, "idx"), _dev(dval_out, "dval_out"),
                                  _stream()), "dct_rowtopk_bwd")
+
+
+# ------------------------------------------------------------------ DCT-DP, many tensors
+class Segment(ctypes.Structure):
+    """One tensor of a batched call (dct_segment): all fields in elements / slots."""
+    _fields_ = [("offset", ctypes.c_uint64), ("n", ctypes.c_uint64), ("k", ctypes.c_uint64),
+                ("out_offset", ctypes.c_uint64), ("capacity", ctypes.c_uint64)]
+
+
+def segment_table(segments):
+    """ctypes array of dct_segment from (offset, n, k, out_offset, capacity) tuples."""
+    arr = (Segment * len(segments))()
+    for i, sgm in enumerate(segments):
+        arr[i] = Segment(*(int(v) for v in sgm))
+    return arr
+
+
+def dct_batched_workspace_bytes(dt: int, table) -> int:
+    return lib().dct_batched_workspace_bytes(dt, ctypes.cast(table, ctypes.c_void_p), len(table))
+
+
+def new_batched_workspace(g: torch.Tensor, table) -> torch.Tensor:
+    nbytes = dct_batched_workspace_bytes(_dt(g), table)
+    if nbytes == 0:
+        raise DctError(DCT_ERR_INVALID, "dct_batched_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=g.device)
+
+
+def dct_select_threshold_batched(g: torch.Tensor, table, thr_out: torch.Tensor, ws: torch.Tensor) -> None:
+    """thr_out: int32[n_seg, 4] device tensor; `table` from segment_table()."""
+    if thr_out.dtype != torch.int32 or thr_out.numel() != 4 * len(table) or not thr_out.is_contiguous():
+        raise ValueError("thr_out must be a contiguous int32 [n_seg, 4] tensor")
+    for sgm in table:
+        if sgm.offset + sgm.n > g.numel():
+            raise ValueError("a segment exceeds g")
+    _check(lib().dct_select_threshold_batched(_flat(g, "g"), _dt(g), ctypes.cast(table, ctypes.c_void_p), len(table),
+                                              _dev(thr_out, "thr_out"), _dev(ws, "ws"),
+                                              ws.numel() * ws.element_size(), _stream()),
+           "dct_select_threshold_batched")
+
+
+def dct_threshold_compact_batched(g: torch.Tensor, table, thr: torch.Tensor, mode: int, idx_out: torch.Tensor,
+                                  val_out: torch.Tensor, count_out: torch.Tensor, ws: torch.Tensor) -> None:
+    """count_out: int64[n_seg]; every segment's out_offset + capacity must lie inside idx_out / val_out."""
+    if idx_out.dtype != torch.int32 or val_out.dtype != g.dtype or count_out.dtype != torch.int64:
+        raise TypeError("idx_out must be int32, val_out must match g, count_out must be int64")
+    if count_out.numel() != len(table) or thr.numel() != 4 * len(table):
+        raise ValueError("count_out / thr must have one entry per segment")
+    room = min(idx_out.numel(), val_out.numel())
+    for sgm in table:
+        if sgm.out_offset + sgm.capacity > room:
+            raise ValueError("a segment's output range exceeds the output tensors")
+        if sgm.offset + sgm.n > g.numel():
+            raise ValueError("a segment exceeds g")
+    _check(lib().dct_threshold_compact_batched(_flat(g, "g"), _dt(g), ctypes.cast(table, ctypes.c_void_p), len(table),
+                                               _dev(thr, "thr"), int(mode), _flat(idx_out, "idx_out"),
+                                               _flat(val_out, "val_out"), _dev(count_out, "count_out"),
+                                               _dev(ws, "ws"), ws.numel() * ws.element_size(), _stream()),
+           "dct_threshold_compact_batched")
 
 
 # ------------------------------------------------------------------ receiver side

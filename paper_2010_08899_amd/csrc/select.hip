@@ -26,13 +26,11 @@
 // residual e together and select on w = g + e, one fp32 addition per element,
 // without storing w: dct_ef_threshold_compact forms the same sums again.
 #include "dct_common.hpp"
+#include "radix_select.hpp"
 
 namespace dct {
 namespace {
 
-constexpr int kSelThreads = 256;
-constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kSelBins = 2048;
 constexpr int kSelMaxPasses = 3;
 constexpr int kSelUnroll = 4;                   // 16-byte loads in flight per lane in the radix passes
 constexpr uint32_t kSelMaxGrid = 4096;
@@ -45,19 +43,6 @@ constexpr int kGatherThreads = 256;
 constexpr int kPartRows = 4;                    // 16-byte loads per lane per step of the partition pass
 constexpr uint32_t kPartStage = 1024;           // staged candidate keys per wavefront
 constexpr uint32_t kPartTileVecs = kSelThreads * kPartRows;
-
-struct SelState {
-  uint32_t prefix;     // digits fixed so far, in place
-  uint32_t k_rem;      // rank still to find among the matching keys (1-based from the top)
-  uint32_t n_gt;       // keys known to be above every matching key
-  uint32_t from_cand;  // 1: the passes read the candidate buffer, 0: the vector
-  uint32_t n_src;      // keys in the source
-  uint32_t rem_bits;   // low key bits not fixed yet
-  uint32_t width;      // digit width of this pass (0: nothing left to do)
-  uint32_t last_count; // keys that match the prefix
-};
-
-constexpr uint32_t kDigitBits = 11;
 
 struct SelWs {
   unsigned long long counts;  // partition pass: keys > hi (high word), keys in [lo, hi] (low word; may exceed the buffer)
@@ -106,81 +91,6 @@ __device__ __forceinline__ uint4 add4(const uint4& a, const uint4& b) {
                     __float_as_uint(__uint_as_float(a.y) + __uint_as_float(b.y)),
                     __float_as_uint(__uint_as_float(a.z) + __uint_as_float(b.z)),
                     __float_as_uint(__uint_as_float(a.w) + __uint_as_float(b.w)));
-}
-
-// One histogram update.  Lanes whose digit equals the first active lane's digit
-// are counted with one ballot and a single LDS add (skewed data such as a mostly
-// zero gradient, or candidates that share their top digits, would otherwise
-// serialise on one bin); the others add directly.
-__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digit) {
-  const uint64_t act = ballot64(active);
-  if (act == 0) return;
-  const int leader = __builtin_ctzll(act);
-  const uint32_t d0 = __shfl(digit, leader, kWave);
-  const bool same = active && digit == d0;
-  const uint64_t m = ballot64(same);
-  if (static_cast<int>(lane_id()) == leader) atomicAdd(&h[d0], static_cast<uint32_t>(__popcll(m)));
-  if (active && !same) atomicAdd(&h[digit], 1u);
-}
-
-// Inclusive prefix sum over the lanes of a wavefront (DPP row shifts + broadcasts).
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
-  uint32_t v = x;
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);
-  return v;
-}
-
-// Walk a 2048-bin histogram from the top bin down and find the bin that holds the
-// k_rem-th largest key.  Called by all THREADS threads of a workgroup (THREADS a
-// multiple of 64 that divides 2048); s_tmp needs THREADS / 64 + 4 words.  Returns
-// {bin, keys in higher bins, keys in the bin} to every thread.
-struct BinHit {
-  uint32_t bin, above, count;
-};
-template <int THREADS, typename LoadBin>
-__device__ BinHit find_bin(LoadBin load_bin, uint32_t k_rem, uint32_t* s_tmp) {
-  constexpr int kPer = kSelBins / THREADS;
-  constexpr int kW = THREADS / kWave;
-  const uint32_t t = threadIdx.x;
-  uint32_t c[kPer];
-  uint32_t sum = 0;
-#pragma unroll
-  for (int j = 0; j < kPer; ++j) {
-    c[j] = load_bin(kSelBins - 1 - (t * kPer + j));
-    sum += c[j];
-  }
-  const uint32_t incl_w = wave_incl_scan(sum);
-  if (lane_id() == kWave - 1) s_tmp[t / kWave] = incl_w;
-  __syncthreads();
-  uint32_t before_waves = 0;
-  for (uint32_t w = 0; w < t / kWave; ++w) before_waves += s_tmp[w];
-  const uint32_t incl = before_waves + incl_w;
-  uint32_t above = incl - sum;
-  if (above < k_rem && k_rem <= incl) {
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-      if (above < k_rem && k_rem <= above + c[j]) {
-        s_tmp[kW + 0] = kSelBins - 1 - (t * kPer + j);
-        s_tmp[kW + 1] = above;
-        s_tmp[kW + 2] = c[j];
-        above = 0xFFFFFFFFu;
-      } else if (above != 0xFFFFFFFFu) {
-        above += c[j];
-      }
-    }
-  }
-  __syncthreads();
-  BinHit r;
-  r.bin = s_tmp[kW + 0];
-  r.above = s_tmp[kW + 1];
-  r.count = s_tmp[kW + 2];
-  __syncthreads();
-  return r;
 }
 
 // ------------------------------------------------------------------ kernel 1a
@@ -452,21 +362,6 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
 // One radix pass.  Every workgroup first derives the search state of this pass
 // (from the partition counts for pass 0, from the previous pass's histogram
 // otherwise), then histograms its part of the source.
-// Search state after the pass whose state was `prev` and whose histogram is `hist`.
-__device__ SelState advance_state(const SelState& prev, const uint32_t* hist, uint32_t* s_tmp) {
-  SelState st = prev;
-  if (prev.width != 0) {  // uniform
-    const BinHit hit = find_bin<kSelThreads>([&](uint32_t b) { return hist[b]; }, prev.k_rem, s_tmp);
-    st.rem_bits = prev.rem_bits - prev.width;
-    st.prefix = prev.prefix | (hit.bin << st.rem_bits);
-    st.k_rem = prev.k_rem - hit.above;
-    st.n_gt = prev.n_gt + hit.above;
-    st.last_count = hit.count;
-  }
-  st.width = min(kDigitBits, st.rem_bits);
-  return st;
-}
-
 template <int DT, bool EF>
 __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     const typename Elem<DT>::word_t* __restrict__ g_al, const typename Elem<DT>::word_t* __restrict__ e_al,

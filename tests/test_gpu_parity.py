@@ -637,3 +637,107 @@ def test_rowtopk_scatter_c5_block(dct):
     dct.dct_rowtopk_scatter(idx, val, out)
     want = oracle.rowscatter(host(idx), host(val), D)
     assert np.array_equal(host(out), want)
+
+
+# ------------------------------------------------------------------ DCT-DP, many tensors per call
+def make_segments(sizes, ks, caps, gap=3):
+    """Segments laid out one after another with `gap` unused elements between them (odd offsets)."""
+    segs, off, out = [], 1, 0
+    for n, k, cap in zip(sizes, ks, caps):
+        segs.append((off, n, k, out, cap))
+        off += n + gap
+        out += cap + 2          # two guard slots after every segment's range
+    return segs, off, out
+
+
+def check_batched(dct, g, segs, out_len, modes=(0, 1)):
+    table = dct.segment_table(segs)
+    ws = dct.new_batched_workspace(g, table)
+    n_seg = len(segs)
+    thr = torch.zeros(n_seg, 4, dtype=torch.int32, device=DEV)
+    dct.dct_select_threshold_batched(g, table, thr, ws)
+    thr_h = thr.cpu().numpy().view(np.uint32)
+    gh = host(g)
+    exp_thr = []
+    for s, (off, n, k, out_off, cap) in enumerate(segs):
+        e = oracle.select_threshold(gh[off:off + n], k)
+        assert tuple(int(v) for v in thr_h[s]) == tuple(e), (s, n, k)
+        exp_thr.append(e)
+    for mode in modes:
+        idx = torch.full((out_len,), -7, dtype=torch.int32, device=DEV)
+        val = torch.zeros(out_len, dtype=g.dtype, device=DEV)
+        cnt = torch.zeros(n_seg, dtype=torch.int64, device=DEV)
+        dct.dct_threshold_compact_batched(g, table, thr, mode, idx, val, cnt, ws)
+        idx_h, val_h, cnt_h = host(idx), host(val), cnt.cpu().numpy()
+        written = np.zeros(out_len, dtype=bool)
+        for s, (off, n, k, out_off, cap) in enumerate(segs):
+            eidx, eval_, ecnt = oracle.threshold_compact(gh[off:off + n], exp_thr[s], mode, capacity=cap)
+            assert int(cnt_h[s]) == ecnt, (s, mode)
+            m = min(ecnt, cap)
+            assert np.array_equal(idx_h[out_off:out_off + m], eidx), (s, mode)
+            assert np.array_equal(bits(val_h[out_off:out_off + m]), bits(eval_)), (s, mode)
+            written[out_off:out_off + m] = True
+        assert np.all(idx_h[~written] == -7)  # nothing outside the survivors' slots
+    return thr
+
+
+def test_batched_layers_like_a_small_model(dct):
+    """Tensors from a few elements to a few million, odd offsets, 1 % kept (sizes of FC weights and biases)."""
+    sizes = [512 * 256, 256, 1024 * 1024, 1024, 8191, 65536, 65537, 1, 5, 3_000_001, 13 * 64]
+    ks = [max(1, n // 100) for n in sizes]
+    caps = [2 * k for k in ks]
+    segs, total, out_len = make_segments(sizes, ks, caps)
+    g = si.gaussian_gradient(total, DEV, 1234)
+    thr = check_batched(dct, g, segs, out_len)
+    # every segment agrees with the single-tensor call on the same slice
+    for s in (0, 2, 9):
+        off, n, k, _, _ = segs[s]
+        dp = DP(dct, g[off:off + n])
+        assert dp.select(k) == oracle.Threshold(*(int(v) & 0xFFFFFFFF for v in thr[s].cpu().tolist()))
+
+
+def test_batched_ties_overflow_and_many_segments(dct):
+    # heavy ties and special values per segment; capacities that cut the output short or are zero
+    vecs = [v for _, v in si.adversarial_vectors(20_000, DEV, 77)] + [v for _, v in si.adversarial_vectors(40, DEV, 78)]
+    sizes = [v.numel() for v in vecs]
+    ks = [max(1, n // 7) for n in sizes]
+    caps = [(0 if i % 5 == 0 else (k // 2 if i % 3 == 0 else n)) for i, (n, k) in enumerate(zip(sizes, ks))]
+    segs, total, out_len = make_segments(sizes, ks, caps, gap=1)
+    g = torch.zeros(total, device=DEV)
+    for (off, n, *_), v in zip(segs, vecs):
+        g[off:off + n] = v
+    check_batched(dct, g, segs, out_len)
+    # more segments than one table upload carries
+    sizes = [17 + 37 * (i % 11) for i in range(150)]
+    ks = [1 + (i % 5) for i in range(150)]
+    segs, total, out_len = make_segments(sizes, ks, [n for n in sizes], gap=0)
+    check_batched(dct, si.gaussian_gradient(total, DEV, 4321), segs, out_len)
+
+
+def test_batched_bf16(dct):
+    sizes = [70_001, 16384, 3, 262_144]
+    ks = [max(1, n // 50) for n in sizes]
+    segs, total, out_len = make_segments(sizes, ks, [3 * k for k in ks])
+    g = si.gaussian_gradient(total, DEV, 99, scale=1.0).to(torch.bfloat16)
+    check_batched(dct, g, segs, out_len)
+
+
+def test_batched_argument_errors(dct):
+    g = si.gaussian_gradient(10_000, DEV, 5)
+    lib = dct.lib()
+    import ctypes
+    ok = dct.segment_table([(0, 5000, 50, 0, 100), (5000, 5000, 50, 100, 100)])
+    ws = dct.new_batched_workspace(g, ok)
+    thr = torch.zeros(2, 4, dtype=torch.int32, device=DEV)
+    call = lambda tab, n_seg, wsb: lib.dct_select_threshold_batched(  # noqa: E731
+        g.data_ptr(), 0, ctypes.cast(tab, ctypes.c_void_p), n_seg, thr.data_ptr(), ws.data_ptr(), wsb, None)
+    assert call(ok, 2, ws.numel()) == 0
+    assert call(ok, 0, ws.numel()) == 1
+    assert call(ok, 2000, ws.numel()) == 1
+    assert call(dct.segment_table([(0, 0, 1, 0, 0)]), 1, ws.numel()) == 1       # empty segment
+    assert call(dct.segment_table([(0, 10, 11, 0, 0)]), 1, ws.numel()) == 1     # k > n
+    assert call(ok, 2, 256) == 2                                                  # workspace too small
+    assert lib.dct_batched_workspace_bytes(0, None, 1) == 0
+    with pytest.raises(ValueError):
+        dct.dct_select_threshold_batched(g, dct.segment_table([(9000, 5000, 5, 0, 0)]), thr[:1], ws)
+    torch.cuda.synchronize()
