@@ -5,7 +5,7 @@
 // so one call per layer is pure launch latency.  Here the layers are segments
 // of one address range described by a table:
 //   select  : table upload (+ workspace clear), one launch per radix digit over
-//             all segments (a workgroup histograms 64 Ki elements of one segment
+//             all segments (a workgroup histograms 16 Ki elements of one segment
 //             into that segment's histogram), one finish launch that writes every
 //             segment's threshold record;
 //   compact : table upload, a count launch (one workgroup per 8 Ki-element tile:
@@ -26,7 +26,7 @@ namespace dct {
 namespace {
 
 constexpr uint32_t kBtMaxSeg = 1024;
-constexpr uint32_t kBtUnit = 65536;     // elements per workgroup in a select pass
+constexpr uint32_t kBtUnit = 16384;     // elements per workgroup in a select pass
 constexpr uint32_t kBtTile = 8192;      // elements per workgroup in the compaction kernels
 constexpr int kBtThreads = kSelThreads;  // 256 (find_bin is instantiated for it)
 constexpr uint32_t kBtPerThread = kBtTile / kBtThreads;  // 32
