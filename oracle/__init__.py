@@ -52,6 +52,11 @@ def _load():
         lib.oracle_scatter.argtypes = [vp, vp, u64, i32, u64, vp, i32]
         lib.oracle_rowscatter.argtypes = [vp, vp, i32, u32, u32, u32, vp, u64]
         lib.oracle_scatter.restype = lib.oracle_rowscatter.restype = ctypes.c_int
+        lib.oracle_rowtopk_fwd_bitmask.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp, vp]
+        lib.oracle_rowtopk_bwd_bitmask.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp]
+        lib.oracle_rowscatter_bitmask.argtypes = [vp, vp, i32, u32, u32, u32, vp, u64]
+        for f in (lib.oracle_rowtopk_fwd_bitmask, lib.oracle_rowtopk_bwd_bitmask, lib.oracle_rowscatter_bitmask):
+            f.restype = ctypes.c_int
         for f in (lib.oracle_ef_accumulate, lib.oracle_ef_select_threshold, lib.oracle_ef_threshold_compact):
             f.restype = ctypes.c_int
         for f in (lib.oracle_select_threshold, lib.oracle_select_threshold_nth, lib.oracle_threshold_compact,
@@ -226,4 +231,42 @@ def rowscatter(idx: np.ndarray, val: np.ndarray, D: int, out: np.ndarray | None 
     rc = _load().oracle_rowscatter(_ptr(idx), _ptr(val), _dtype_code(val), B, D, k, _ptr(out), _row_stride(out))
     if rc != 0:
         raise ValueError("oracle_rowscatter: invalid arguments")
+    return out
+
+
+# ---- Algorithm 2 with the mask as a bitmap ------------------------------------
+def rowtopk_fwd_bitmask(x: np.ndarray, k: int):
+    """Returns (mask uint32[B, ceil(D/32)], val[B,k], tau[B]); bit c%32 of word c//32 = column c kept."""
+    B, D = x.shape
+    mask = np.zeros((B, (D + 31) // 32), dtype=np.uint32)
+    val = np.zeros((B, k), dtype=x.dtype)
+    tau = np.zeros(B, dtype=x.dtype)
+    rc = _load().oracle_rowtopk_fwd_bitmask(_ptr(x), _dtype_code(x), B, D, _row_stride(x), int(k),
+                                            _ptr(mask), _ptr(val), _ptr(tau))
+    if rc != 0:
+        raise ValueError("oracle_rowtopk_fwd_bitmask: invalid arguments")
+    return mask, val, tau
+
+
+def rowtopk_bwd_bitmask(dy: np.ndarray, mask: np.ndarray, k: int):
+    B, D = dy.shape
+    mask = np.ascontiguousarray(mask, dtype=np.uint32)
+    assert mask.shape == (B, (D + 31) // 32)
+    dval = np.zeros((B, k), dtype=dy.dtype)
+    rc = _load().oracle_rowtopk_bwd_bitmask(_ptr(dy), _dtype_code(dy), B, D, _row_stride(dy), int(k), _ptr(mask),
+                                            _ptr(dval))
+    if rc != 0:
+        raise ValueError("oracle_rowtopk_bwd_bitmask: invalid arguments")
+    return dval
+
+
+def rowscatter_bitmask(mask: np.ndarray, val: np.ndarray, D: int):
+    mask = np.ascontiguousarray(mask, dtype=np.uint32)
+    val = np.ascontiguousarray(val)
+    B, k = val.shape
+    assert mask.shape == (B, (D + 31) // 32)
+    out = np.full((B, D), 7, dtype=val.dtype)
+    rc = _load().oracle_rowscatter_bitmask(_ptr(mask), _ptr(val), _dtype_code(val), B, D, k, _ptr(out), D)
+    if rc != 0:
+        raise ValueError("oracle_rowscatter_bitmask: invalid arguments")
     return out

@@ -346,4 +346,72 @@ int oracle_rowscatter(const int32_t* idx, const void* val, int dtype, uint32_t B
     return 0;
 }
 
+// ---- Algorithm 2 with the mask sent as a bitmap -------------------------------
+// Algorithm 2 sends "X_act . M and the mask M".  Here M travels literally as a
+// bitmap: ceil(D/32) 32-bit words per row, bit (c mod 32) of word (c div 32) set
+// iff column c is kept, plus the k kept values in ascending column order.  The
+// kept set is the one oracle_rowtopk_fwd computes; only the encoding differs.
+int oracle_rowtopk_fwd_bitmask(const void* x, int dtype, uint32_t B, uint32_t D, uint64_t row_stride, uint32_t k,
+                               uint32_t* mask_out, void* val_out, void* tau_out) {
+    if (!mask_out) return 1;
+    std::vector<int32_t> idx(static_cast<size_t>(B) * k);
+    const int rc = oracle_rowtopk_fwd(x, dtype, B, D, row_stride, k, idx.data(), val_out, tau_out);
+    if (rc != 0) return rc;
+    const uint32_t words = (D + 31) / 32;
+    for (uint32_t b = 0; b < B; ++b) {
+        uint32_t* m = mask_out + static_cast<size_t>(b) * words;
+        for (uint32_t w = 0; w < words; ++w) m[w] = 0;
+        for (uint32_t j = 0; j < k; ++j) {
+            const uint32_t c = static_cast<uint32_t>(idx[static_cast<size_t>(b) * k + j]);
+            m[c / 32] |= 1u << (c % 32);
+        }
+    }
+    return 0;
+}
+
+// Backward through a bitmap mask: dval[b, j] = dy[b, column of the j-th set bit
+// of row b's mask] for j < min(k, set bits); the rest of the row's k slots are 0.
+int oracle_rowtopk_bwd_bitmask(const void* dy, int dtype, uint32_t B, uint32_t D, uint64_t row_stride, uint32_t k,
+                               const uint32_t* mask, void* dval_out) {
+    if (!dy || !mask || !dval_out || B == 0 || D == 0 || k == 0 || k > D || row_stride < D) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    const size_t es = elem_size(dtype);
+    const uint32_t words = (D + 31) / 32;
+    for (uint32_t b = 0; b < B; ++b) {
+        const unsigned char* row = static_cast<const unsigned char*>(dy) + es * row_stride * b;
+        unsigned char* out = static_cast<unsigned char*>(dval_out) + es * static_cast<size_t>(b) * k;
+        std::memset(out, 0, es * k);
+        uint32_t j = 0;
+        for (uint32_t c = 0; c < D && j < k; ++c) {
+            if ((mask[static_cast<size_t>(b) * words + c / 32] >> (c % 32)) & 1u) {
+                std::memcpy(out + es * j, row + es * c, es);
+                ++j;
+            }
+        }
+    }
+    return 0;
+}
+
+// Receiver side for the bitmap encoding: dense row = zeros with the j-th value
+// at the column of the j-th set bit (j < k).
+int oracle_rowscatter_bitmask(const uint32_t* mask, const void* val, int dtype, uint32_t B, uint32_t D, uint32_t k,
+                              void* out, uint64_t out_stride) {
+    if (!mask || !val || !out || B == 0 || D == 0 || k == 0 || out_stride < D) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    const size_t es = elem_size(dtype);
+    const uint32_t words = (D + 31) / 32;
+    for (uint32_t b = 0; b < B; ++b) {
+        unsigned char* row = static_cast<unsigned char*>(out) + es * out_stride * b;
+        std::memset(row, 0, es * D);
+        uint32_t j = 0;
+        for (uint32_t c = 0; c < D && j < k; ++c) {
+            if ((mask[static_cast<size_t>(b) * words + c / 32] >> (c % 32)) & 1u) {
+                std::memcpy(row + es * c, static_cast<const unsigned char*>(val) + es * (static_cast<size_t>(b) * k + j), es);
+                ++j;
+            }
+        }
+    }
+    return 0;
+}
+
 }  // extern "C"

@@ -659,3 +659,52 @@ def test_rowscatter_against_numpy_and_round_trip():
     np.put_along_axis(want, idx.astype(np.int64), val, axis=1)
     want[0, idx[0, 0]] = 0
     assert np.array_equal(buf[:, :D], want)
+
+
+# ------------------------------------------------------------------ Algorithm 2 with the mask as a bitmap
+def test_bitmask_hand_worked():
+    """Rows of the Algorithm 2 fixture: the mask words follow from the kept columns by hand."""
+    gd = read_golden("alg2_worked.txt")
+    k = int(gd["k"][0])
+    x = np.stack([f32(gd[f"x{b}"]) for b in range(3)])
+    mask, val, tau = oracle.rowtopk_fwd_bitmask(x, k)
+    assert mask.shape == (3, 1)
+    for b in range(3):
+        cols = [int(c) for c in gd[f"idx{b}"]]
+        word = 0
+        for c in cols:            # bit c of the row's only word (D <= 32 in the fixture)
+            word |= 1 << c
+        assert int(mask[b, 0]) == word, b
+        assert np.array_equal(bits(val[b]), bits(f32(gd[f"val{b}"])))
+    # a row of 40 columns with columns 0, 31, 32 and 39 kept: words 0x80000001 and 0x00000081
+    x = np.zeros((1, 40), dtype=np.float32)
+    x[0, [0, 31, 32, 39]] = [4.0, -3.0, 2.0, 1.0]
+    mask, val, _ = oracle.rowtopk_fwd_bitmask(x, 4)
+    assert [int(w) for w in mask[0]] == [0x80000001, 0x00000081]
+    assert val[0].tolist() == [4.0, -3.0, 2.0, 1.0]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_bitmask_against_numpy_packbits_and_index_form(bf16):
+    rng = np.random.default_rng(17)
+    for B, D, k in [(5, 33, 7), (4, 64, 64), (6, 1000, 50), (3, 4096, 204)]:
+        x = np.maximum(rng.standard_normal((B, D)), 0).astype(np.float32)
+        dy = rng.standard_normal((B, D)).astype(np.float32)
+        if bf16:
+            x = to_bf16_bits(x.reshape(-1)).reshape(B, D)
+            dy = to_bf16_bits(dy.reshape(-1)).reshape(B, D)
+        idx, val, tau = oracle.rowtopk_fwd(x, k)
+        mask, mval, mtau = oracle.rowtopk_fwd_bitmask(x, k)
+        keep = np.zeros((B, ((D + 31) // 32) * 32), dtype=np.uint8)
+        np.put_along_axis(keep, idx.astype(np.int64), 1, axis=1)
+        want = np.packbits(keep, axis=1, bitorder="little").view(np.uint32)  # library routine
+        assert np.array_equal(mask, want)
+        assert np.array_equal(bits(mval.reshape(-1)), bits(val.reshape(-1))) and np.array_equal(mtau, tau)
+        assert np.all(np.unpackbits(mask.view(np.uint8), axis=1).sum(axis=1) == k)
+        # backward and decompression agree with the index form
+        assert np.array_equal(oracle.rowtopk_bwd_bitmask(dy, mask, k), oracle.rowtopk_bwd(dy, idx))
+        assert np.array_equal(oracle.rowscatter_bitmask(mask, mval, D), oracle.rowscatter(idx, val, D))
+    # a mask with fewer set bits than k: the remaining slots are zero
+    m = np.array([[0b1010]], dtype=np.uint32)
+    d = oracle.rowtopk_bwd_bitmask(f32("1 2 3 4 5".split()).reshape(1, 5), m, 3)
+    assert d.tolist() == [[2.0, 4.0, 0.0]]
