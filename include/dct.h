@@ -164,6 +164,29 @@ int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_
 int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
                     const int32_t* d_idx, void* d_dval_out, void* hip_stream);
 
+/* ------------------------------------------- DCT-MP, the mask as a bitmap ---
+ * Algorithm 2 sends "X_act . M and the mask M".  These calls carry M literally,
+ * as a bitmap, instead of k column indices: ceil(D/32) 32-bit words per row, bit
+ * (c mod 32) of word (c div 32) set iff column c is kept, plus the k kept values in
+ * ascending column order.  For bf16 and k = D/20 that is 2.25 bytes per kept entry
+ * on the wire instead of 6.  The kept set is exactly that of dct_rowtopk_fwd.
+ *
+ *   dct_rowtopk_fwd_bitmask      x -> d_mask_out uint32[B * ceil(D/32)], d_val_out dt[B*k],
+ *                                optional d_tau_out (as dct_rowtopk_fwd)
+ *   dct_rowtopk_bwd_bitmask      dval[b, j] = dy[b, column of the j-th set bit of row b];
+ *                                if a row's mask has fewer than k set bits the remaining
+ *                                slots are zero, more than k: the first k count
+ *   dct_rowtopk_scatter_bitmask  receiver side: out[b, 0..D) = zeros with val[b, j] at the
+ *                                column of the j-th set bit (j < k); the padding between D
+ *                                and the row stride is not touched
+ */
+int dct_rowtopk_fwd_bitmask(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
+                            uint32_t* d_mask_out, void* d_val_out, void* d_tau_out, void* hip_stream);
+int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
+                            const uint32_t* d_mask, void* d_dval_out, void* hip_stream);
+int dct_rowtopk_scatter_bitmask(const uint32_t* d_mask, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k,
+                                void* d_out, uint64_t out_row_stride_elems, void* hip_stream);
+
 /* ------------------------------------------------------ DCT-DP, many tensors ---
  * Layer-wise compression (Sec. 2.1: every layer's gradient is compressed on its
  * own, with its own threshold) for many tensors with a fixed number of launches:

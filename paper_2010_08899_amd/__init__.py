@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     dct_status_string, dct_threshold_compact, dct_threshold_compact_workspace_bytes,
     dct_threshold_compact_workspace_init, lib, new_compact_workspace, new_select_workspace, read_count,
     read_threshold, Segment, segment_table, dct_batched_workspace_bytes, new_batched_workspace,
-    dct_select_threshold_batched, dct_threshold_compact_batched,
+    dct_select_threshold_batched, dct_threshold_compact_batched, dct_rowtopk_fwd_bitmask,
+    dct_rowtopk_bwd_bitmask, dct_rowtopk_scatter_bitmask,
 )

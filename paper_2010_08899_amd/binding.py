@@ -43,6 +43,15 @@ _EXPORTS = {
     "dct_rowtopk_bwd": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
                                        ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p]),
+    "dct_rowtopk_fwd_bitmask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
+                                               ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_void_p]),
+    "dct_rowtopk_bwd_bitmask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
+                                               ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p]),
+    "dct_rowtopk_scatter_bitmask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32,
+                                                   ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
+                                                   ctypes.c_void_p]),
     "dct_batched_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32]),
     "dct_select_threshold_batched": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32,
                                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -253,6 +262,44 @@ def dct_rowtopk_bwd(dy: torch.Tensor, idx: torch.Tensor, dval_out: torch.Tensor)
         raise ValueError("dval_out must be a contiguous [B, k] tensor of dy.dtype")
     _check(lib().dct_rowtopk_bwd(ptr, _dt(dy), B, D, stride, k, _dev(idx, "idx"), _dev(dval_out, "dval_out"),
                                  _stream()), "dct_rowtopk_bwd")
+
+
+# ------------------------------------------------------------------ DCT-MP, the mask as a bitmap
+def _mask_ok(mask: torch.Tensor, B: int, D: int) -> None:
+    if mask.dtype != torch.int32 or mask.numel() != B * ((D + 31) // 32) or not mask.is_contiguous():
+        raise ValueError("mask must be a contiguous int32 [B, ceil(D/32)] tensor")
+
+
+def dct_rowtopk_fwd_bitmask(x: torch.Tensor, k: int, mask_out: torch.Tensor, val_out: torch.Tensor,
+                            tau_out: torch.Tensor | None = None) -> None:
+    ptr, B, D, stride = _rows(x, "x")
+    _mask_ok(mask_out, B, D)
+    if val_out.dtype != x.dtype or not val_out.is_contiguous() or val_out.numel() != B * k:
+        raise ValueError("val_out must be a contiguous [B, k] tensor of x.dtype")
+    if tau_out is not None and (tau_out.dtype != x.dtype or tau_out.numel() != B or not tau_out.is_contiguous()):
+        raise ValueError("tau_out must be a contiguous [B] tensor of x.dtype")
+    _check(lib().dct_rowtopk_fwd_bitmask(ptr, _dt(x), B, D, stride, int(k), _dev(mask_out, "mask_out"),
+                                         _dev(val_out, "val_out"),
+                                         _dev(tau_out, "tau_out") if tau_out is not None else None, _stream()),
+           "dct_rowtopk_fwd_bitmask")
+
+
+def dct_rowtopk_bwd_bitmask(dy: torch.Tensor, mask: torch.Tensor, dval_out: torch.Tensor) -> None:
+    ptr, B, D, stride = _rows(dy, "dy")
+    _mask_ok(mask, B, D)
+    if dval_out.dtype != dy.dtype or dval_out.dim() != 2 or dval_out.shape[0] != B or not dval_out.is_contiguous():
+        raise ValueError("dval_out must be a contiguous [B, k] tensor of dy.dtype")
+    _check(lib().dct_rowtopk_bwd_bitmask(ptr, _dt(dy), B, D, stride, dval_out.shape[1], _dev(mask, "mask"),
+                                         _dev(dval_out, "dval_out"), _stream()), "dct_rowtopk_bwd_bitmask")
+
+
+def dct_rowtopk_scatter_bitmask(mask: torch.Tensor, val: torch.Tensor, out: torch.Tensor) -> None:
+    ptr, B, D, stride = _rows(out, "out")
+    _mask_ok(mask, B, D)
+    if val.dtype != out.dtype or val.dim() != 2 or val.shape[0] != B or not val.is_contiguous():
+        raise ValueError("val must be a contiguous [B, k] tensor of out.dtype")
+    _check(lib().dct_rowtopk_scatter_bitmask(_dev(mask, "mask"), _dev(val, "val"), _dt(out), B, D, val.shape[1],
+                                             ptr, stride, _stream()), "dct_rowtopk_scatter_bitmask")
 
 
 # ------------------------------------------------------------------ DCT-DP, many tensors

@@ -4,6 +4,8 @@
 // indices plus the selected values.  Backward: X_grad through the same mask,
 // which is a gather of dy at the forward indices (no new selection: Sec. 2.2,
 // "the same mask is used").
+#include <algorithm>
+
 #include "dct_common.hpp"
 #include "rowtopk_fast.hpp"
 
@@ -35,7 +37,9 @@ __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digi
   if (active && !same) atomicAdd(&h[digit], 1u);
 }
 
-template <int DT>
+// MASK: the row's mask goes out as a bitmap (through `idx_out`, ceil(D/32) words per row)
+// instead of column indices.
+template <int DT, bool MASK>
 __global__ __launch_bounds__(kRtThreads) void rowtopk_fwd_generic_kernel(
     const typename Elem<DT>::word_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k,
     int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out,
@@ -118,8 +122,14 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_fwd_generic_kernel(
       const uint64_t m_keep = ballot64(keep);
       const uint32_t slot = out + lanes_below(m_keep);
       if (keep && slot < k) {
-        io[slot] = static_cast<int32_t>(c);
+        if constexpr (!MASK) io[slot] = static_cast<int32_t>(c);
         vo[slot] = static_cast<typename E::word_t>(raw);
+      }
+      if constexpr (MASK) {  // the ballot is the mask of these 64 columns
+        const uint32_t n_words = (D + 31) / 32;
+        uint32_t* mo = reinterpret_cast<uint32_t*>(idx_out) + row * n_words;
+        const uint32_t w = c0 / 32 + lane;
+        if (lane < 2 && w < n_words) mo[w] = static_cast<uint32_t>(m_keep >> (32 * lane));
       }
       out += __popcll(m_keep);
       ties_seen += __popcll(m_eq);
@@ -145,23 +155,64 @@ __global__ __launch_bounds__(256) void rowtopk_bwd_gather_kernel(const W* __rest
   }
 }
 
+// ---------------------------------------------------------------------------
+// Consumers of the bitmap form, one wavefront per row: column c of a 64-column
+// group belongs to lane c % 64; a ballot of the mask bits ranks the kept columns.
+// GATHER: dval[b, j] = dy[b, column of the j-th set bit] (slots past the set bits
+// are zeroed); otherwise: out[b, :] = zeros with val[b, j] at that column.
+// ---------------------------------------------------------------------------
+template <typename W, bool GATHER>
+__global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_kernel(const W* __restrict__ src, uint32_t B, uint32_t D,
+                                                                     uint64_t stride, uint32_t k,
+                                                                     const uint32_t* __restrict__ mask,
+                                                                     W* __restrict__ dst, uint64_t dst_stride) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane = lane_id();
+  const uint32_t n_words = (D + 31) / 32;
+  for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * kRtWaves + wave; row < B;
+       row += static_cast<uint64_t>(gridDim.x) * kRtWaves) {
+    const uint32_t* mr = mask + row * n_words;
+    uint32_t base = 0;
+    for (uint32_t c0 = 0; c0 < D; c0 += kWave) {
+      const uint32_t c = c0 + lane;
+      const uint32_t w = c0 / 32 + lane / 32;
+      const uint32_t word = w < n_words ? mr[w] : 0u;
+      const bool set = c < D && ((word >> (lane % 32)) & 1u);
+      const uint64_t m = ballot64(set);
+      const uint32_t slot = base + lanes_below(m);
+      if constexpr (GATHER) {
+        if (set && slot < k) dst[row * k + slot] = src[row * stride + c];
+      } else {
+        if (c < D) dst[row * dst_stride + c] = (set && slot < k) ? src[row * k + slot] : static_cast<W>(0);
+      }
+      base += __popcll(m);
+    }
+    if constexpr (GATHER) {
+      for (uint32_t j = base + lane; j < k; j += kWave) dst[row * k + j] = 0;
+    }
+  }
+}
+
 }  // namespace
 }  // namespace dct
 
 using namespace dct;
 
-extern "C" int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
-                               uint32_t k, int32_t* d_idx_out, void* d_val_out, void* d_tau_out,
-                               void* hip_stream) {
-  if (!x || !d_idx_out || !d_val_out || B == 0 || D == 0 || k == 0 || k > D || row_stride_elems < D)
+namespace {
+
+// idx_or_mask: int32[B*k] column indices, or (mask = true) uint32[B*ceil(D/32)] bitmap words.
+int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
+               void* idx_or_mask, void* d_val_out, void* d_tau_out, bool mask, void* hip_stream) {
+  if (!x || !idx_or_mask || !d_val_out || B == 0 || D == 0 || k == 0 || k > D || row_stride_elems < D)
     return DCT_ERR_INVALID;
   if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
   if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
   const size_t es = dt == DCT_F32 ? 4 : 2;
-  if (!is_aligned(x, es) || !is_aligned(d_idx_out, 4) || !is_aligned(d_val_out, es) ||
+  if (!is_aligned(x, es) || !is_aligned(idx_or_mask, 4) || !is_aligned(d_val_out, es) ||
       (d_tau_out && !is_aligned(d_tau_out, es)))
     return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  auto* io = static_cast<int32_t*>(idx_or_mask);
   uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
   if (grid > 65536u * 4) grid = 65536u * 4;
   // bf16 rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, D <= 4096
@@ -173,25 +224,91 @@ extern "C" int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, ui
     auto* vp = static_cast<uint16_t*>(d_val_out);
     auto* tp = static_cast<uint16_t*>(d_tau_out);
     const dim3 g(fgrid), b(fast::kThreads);
-    if (D <= 512) {
-      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<1>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
-    } else if (D <= 1024) {
-      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<2>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
-    } else if (D <= 2048) {
-      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<4>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
-    } else {
-      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<8>), g, b, 0, s, xp, B, D, row_stride_elems, k, d_idx_out, vp, tp);
-    }
+#define DCT_LAUNCH_FAST(NVV)                                                                                   \
+  do {                                                                                                         \
+    if (mask)                                                                                                  \
+      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<NVV, true>), g, b, 0, s, xp, B, D, row_stride_elems, k, \
+                         io, vp, tp);                                                                          \
+    else                                                                                                       \
+      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<NVV, false>), g, b, 0, s, xp, B, D, row_stride_elems,  \
+                         k, io, vp, tp);                                                                       \
+  } while (0)
+    if (D <= 512) DCT_LAUNCH_FAST(1);
+    else if (D <= 1024) DCT_LAUNCH_FAST(2);
+    else if (D <= 2048) DCT_LAUNCH_FAST(4);
+    else DCT_LAUNCH_FAST(8);
+#undef DCT_LAUNCH_FAST
     return launch_status();
   }
+#define DCT_LAUNCH_GENERIC(DTV, MK)                                                                       \
+  hipLaunchKernelGGL((rowtopk_fwd_generic_kernel<DTV, MK>), dim3(grid), dim3(kRtThreads), 0, s,            \
+                     static_cast<const Elem<DTV>::word_t*>(x), B, D, row_stride_elems, k, io,              \
+                     static_cast<Elem<DTV>::word_t*>(d_val_out), static_cast<Elem<DTV>::word_t*>(d_tau_out))
   if (dt == DCT_F32) {
-    hipLaunchKernelGGL((rowtopk_fwd_generic_kernel<DCT_F32>), dim3(grid), dim3(kRtThreads), 0, s,
-                       static_cast<const uint32_t*>(x), B, D, row_stride_elems, k, d_idx_out,
-                       static_cast<uint32_t*>(d_val_out), static_cast<uint32_t*>(d_tau_out));
+    if (mask) DCT_LAUNCH_GENERIC(DCT_F32, true); else DCT_LAUNCH_GENERIC(DCT_F32, false);
   } else {
-    hipLaunchKernelGGL((rowtopk_fwd_generic_kernel<DCT_BF16>), dim3(grid), dim3(kRtThreads), 0, s,
-                       static_cast<const uint16_t*>(x), B, D, row_stride_elems, k, d_idx_out,
-                       static_cast<uint16_t*>(d_val_out), static_cast<uint16_t*>(d_tau_out));
+    if (mask) DCT_LAUNCH_GENERIC(DCT_BF16, true); else DCT_LAUNCH_GENERIC(DCT_BF16, false);
+  }
+#undef DCT_LAUNCH_GENERIC
+  return launch_status();
+}
+
+}  // namespace
+
+extern "C" int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                               uint32_t k, int32_t* d_idx_out, void* d_val_out, void* d_tau_out,
+                               void* hip_stream) {
+  return launch_fwd(x, dt, B, D, row_stride_elems, k, d_idx_out, d_val_out, d_tau_out, false, hip_stream);
+}
+
+extern "C" int dct_rowtopk_fwd_bitmask(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                                       uint32_t k, uint32_t* d_mask_out, void* d_val_out, void* d_tau_out,
+                                       void* hip_stream) {
+  return launch_fwd(x, dt, B, D, row_stride_elems, k, d_mask_out, d_val_out, d_tau_out, true, hip_stream);
+}
+
+extern "C" int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                                       uint32_t k, const uint32_t* d_mask, void* d_dval_out, void* hip_stream) {
+  if (!dy || !d_mask || !d_dval_out || B == 0 || D == 0 || k == 0 || k > D || row_stride_elems < D)
+    return DCT_ERR_INVALID;
+  if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
+  if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
+  const size_t es = dt == DCT_F32 ? 4 : 2;
+  if (!is_aligned(dy, es) || !is_aligned(d_mask, 4) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
+  const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
+  if (dt == DCT_F32) {
+    hipLaunchKernelGGL((rowtopk_bitmask_kernel<uint32_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
+                       static_cast<const uint32_t*>(dy), B, D, row_stride_elems, k, d_mask,
+                       static_cast<uint32_t*>(d_dval_out), static_cast<uint64_t>(k));
+  } else {
+    hipLaunchKernelGGL((rowtopk_bitmask_kernel<uint16_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
+                       static_cast<const uint16_t*>(dy), B, D, row_stride_elems, k, d_mask,
+                       static_cast<uint16_t*>(d_dval_out), static_cast<uint64_t>(k));
+  }
+  return launch_status();
+}
+
+extern "C" int dct_rowtopk_scatter_bitmask(const uint32_t* d_mask, const void* d_val, int dt, uint32_t B, uint32_t D,
+                                           uint32_t k, void* d_out, uint64_t out_row_stride_elems, void* hip_stream) {
+  if (!d_mask || !d_val || !d_out || B == 0 || D == 0 || k == 0 || k > D || out_row_stride_elems < D)
+    return DCT_ERR_INVALID;
+  if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
+  if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
+  const size_t es = dt == DCT_F32 ? 4 : 2;
+  if (!is_aligned(d_mask, 4) || !is_aligned(d_val, es) || !is_aligned(d_out, es)) return DCT_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
+  const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
+  if (dt == DCT_F32) {
+    hipLaunchKernelGGL((rowtopk_bitmask_kernel<uint32_t, false>), dim3(grid), dim3(kRtThreads), 0, s,
+                       static_cast<const uint32_t*>(d_val), B, D, static_cast<uint64_t>(k), k, d_mask,
+                       static_cast<uint32_t*>(d_out), out_row_stride_elems);
+  } else {
+    hipLaunchKernelGGL((rowtopk_bitmask_kernel<uint16_t, false>), dim3(grid), dim3(kRtThreads), 0, s,
+                       static_cast<const uint16_t*>(d_val), B, D, static_cast<uint64_t>(k), k, d_mask,
+                       static_cast<uint16_t*>(d_out), out_row_stride_elems);
   }
   return launch_status();
 }

@@ -68,7 +68,9 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // NV = 16-byte vectors per lane: the lane owns columns [lane*NV*8, (lane+1)*NV*8).
-template <int NV>
+// MASK: the row's mask is written as a bitmap (ceil(D/32) words per row, bit c%32 of word c/32 =
+// column c kept) through `idx_out` instead of k column indices; the values are written either way.
+template <int NV, bool MASK>
 __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     const uint16_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k,
     int32_t* __restrict__ idx_out, uint16_t* __restrict__ val_out, uint16_t* __restrict__ tau_out) {
@@ -387,6 +389,22 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     uint32_t slot = wave_incl_scan(kc) - kc;
     int32_t* io = idx_out + row * k;
     uint16_t* vo = val_out + row * k;
+    if constexpr (MASK) {
+      // the per-lane bitmaps ARE the mask: COLS bits per lane, packed into 32-bit words
+      const uint32_t n_words = (D + 31) / 32;
+      uint32_t* mo = reinterpret_cast<uint32_t*>(idx_out) + row * n_words;
+      if constexpr (COLS >= 32) {
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w)
+          if (lane * WORDS + w < n_words) mo[lane * WORDS + w] = keep[w];
+      } else {
+        constexpr uint32_t kLanesPerWord = 32 / COLS;  // 2 or 4 neighbouring lanes share a word
+        uint32_t v = keep[0] << ((lane % kLanesPerWord) * COLS);
+#pragma unroll
+        for (uint32_t d = 1; d < kLanesPerWord; d <<= 1) v |= __shfl_xor(v, d, kWave);
+        if (lane % kLanesPerWord == 0 && lane / kLanesPerWord < n_words) mo[lane / kLanesPerWord] = v;
+      }
+    }
     if (k <= kStageSlots) {
       // list the surviving columns in order in LDS, then write idx / val with coalesced stores
       {
@@ -415,7 +433,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         for (int j = 0; j < 4; ++j) {
           const uint32_t o = j * kWave + lane;
           if (o < k) {
-            io[o] = static_cast<int32_t>(col[j]);
+            if constexpr (!MASK) io[o] = static_cast<int32_t>(col[j]);
             vo[o] = static_cast<uint16_t>(raw[j]);
           }
         }
@@ -423,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         for (uint32_t j = lane; j < k; j += kWave) {
           const uint32_t col = *stage_at(j);
           const uint32_t raw = *reinterpret_cast<const uint16_t*>(row_lds + (col / COLS) * CHUNK + (col % COLS) * 2);
-          io[j] = static_cast<int32_t>(col);
+          if constexpr (!MASK) io[j] = static_cast<int32_t>(col);
           vo[j] = static_cast<uint16_t>(raw);
         }
       }
@@ -437,7 +455,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
             m &= m - 1;
             const uint32_t lc = kColsPerWord * w + q;
             if (slot < k) {
-              io[slot] = static_cast<int32_t>(lane * COLS + lc);
+              if constexpr (!MASK) io[slot] = static_cast<int32_t>(lane * COLS + lc);
               vo[slot] = static_cast<uint16_t>(key_at(lc));
             }
             ++slot;

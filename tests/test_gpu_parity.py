@@ -741,3 +741,81 @@ def test_batched_argument_errors(dct):
     with pytest.raises(ValueError):
         dct.dct_select_threshold_batched(g, dct.segment_table([(9000, 5000, 5, 0, 0)]), thr[:1], ws)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ DCT-MP, the mask as a bitmap
+@pytest.mark.parametrize("dtype,B,D,k,pad", [
+    (torch.bfloat16, 70, 4096, 204, 0), (torch.bfloat16, 33, 2048, 102, 0), (torch.bfloat16, 9, 1024, 51, 8),
+    (torch.bfloat16, 17, 512, 25, 0), (torch.bfloat16, 5, 264, 13, 0), (torch.bfloat16, 6, 40, 7, 0),
+    (torch.bfloat16, 4, 8, 8, 0), (torch.bfloat16, 3, 12_000, 600, 0), (torch.bfloat16, 5, 1001, 50, 0),
+    (torch.float32, 33, 1024, 51, 0), (torch.float32, 7, 33, 5, 3), (torch.float32, 2, 5000, 250, 0)])
+def test_mp_bitmask_encoding(dct, dtype, B, D, k, pad):
+    x = si.relu_activations(B, D, DEV, 1300 + D, dtype=dtype, row_stride=D + pad if pad else None)
+    dy = si.normal_matrix(B, D, DEV, 1400 + D, dtype=dtype)
+    words = (D + 31) // 32
+    mask = torch.full((B, words), -1, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=dtype, device=DEV)
+    tau = torch.zeros(B, dtype=dtype, device=DEV)
+    dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, tau)
+    xh = host(x.contiguous()) if not pad else oracle.as_numpy(x.cpu())
+    emask, eval_, etau = oracle.rowtopk_fwd_bitmask(xh, k)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), emask)
+    assert np.array_equal(bits(host(val).reshape(-1)), bits(eval_.reshape(-1)))
+    assert np.array_equal(bits(host(tau)), bits(etau))
+    # the index form of the same call keeps the same set
+    idx = torch.zeros(B, k, dtype=torch.int32, device=DEV)
+    val2 = torch.zeros_like(val)
+    dct.dct_rowtopk_fwd(x, k, idx, val2, None)
+    assert torch.equal(val.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                       val2.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+    # backward and decompression through the bitmap
+    dval = torch.full((B, k), 3.0, device=DEV).to(dtype)
+    dct.dct_rowtopk_bwd_bitmask(dy, mask, dval)
+    assert np.array_equal(bits(host(dval).reshape(-1)), bits(oracle.rowtopk_bwd_bitmask(host(dy), emask, k).reshape(-1)))
+    buf = torch.full((B, D + 5), 3.0, device=DEV).to(dtype)
+    dct.dct_rowtopk_scatter_bitmask(mask, val, buf[:, :D])
+    assert np.array_equal(bits(host(buf[:, :D].contiguous()).reshape(-1)),
+                          bits(oracle.rowscatter_bitmask(emask, eval_, D).reshape(-1)))
+    assert torch.all(buf[:, D:] == 3.0)
+
+
+def test_mp_bitmask_hard_rows_and_short_masks(dct):
+    # ties across the quota boundary, all-equal rows, all-zero rows (the bitmap must pick the lowest columns)
+    B, D, k = 12, 4096, 204
+    x = si.relu_activations(B, D, DEV, 1500, dtype=torch.bfloat16)
+    x[0] = 0.75
+    x[1] = 0.0
+    x[2, ::2] = 1.0
+    x[3] = (torch.arange(D, device=DEV) % 7).to(torch.bfloat16)
+    mask = torch.zeros(B, D // 32, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=torch.bfloat16, device=DEV)
+    dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, None)
+    emask, eval_, _ = oracle.rowtopk_fwd_bitmask(host(x), k)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), emask)
+    assert np.array_equal(host(val), eval_)
+    # a mask with fewer / more set bits than k (not produced by the forward pass): defined behaviour
+    dy = si.normal_matrix(B, D, DEV, 1501, dtype=torch.bfloat16)
+    m2 = mask.clone()
+    m2[0] = 0
+    m2[0, 3] = 0b1011
+    m2[1] = -1
+    dval = torch.full((B, k), 3.0, device=DEV).to(torch.bfloat16)
+    dct.dct_rowtopk_bwd_bitmask(dy, m2, dval)
+    want = oracle.rowtopk_bwd_bitmask(host(dy), m2.cpu().numpy().view(np.uint32), k)
+    assert np.array_equal(host(dval), want)
+    out = torch.full((B, D), 3.0, device=DEV).to(torch.bfloat16)
+    dct.dct_rowtopk_scatter_bitmask(m2, val, out)
+    assert np.array_equal(host(out), oracle.rowscatter_bitmask(m2.cpu().numpy().view(np.uint32), host(val), D))
+
+
+def test_mp_bitmask_c5_block(dct):
+    x, dy, k = si.config_c5(DEV, b=4096)
+    B, D = x.shape
+    mask = torch.zeros(B, D // 32, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=x.dtype, device=DEV)
+    dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, None)
+    emask, eval_, _ = oracle.rowtopk_fwd_bitmask(host(x), k)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), emask) and np.array_equal(host(val), eval_)
+    dval = torch.zeros_like(val)
+    dct.dct_rowtopk_bwd_bitmask(dy, mask, dval)
+    assert np.array_equal(host(dval), oracle.rowtopk_bwd_bitmask(host(dy), emask, k))
