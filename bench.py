@@ -40,7 +40,7 @@ CALL_KERNELS = {
                                  ("dct::select_partition_kernel<0, false> [c4]", 1),
                                  ("dct::select_pass_kernel<0, false>", 3), ("dct::select_finish_kernel", 1)],
     "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false>", 1)],
-    "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_bf16_kernel<8>", 1)],
+    "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_bf16_kernel<8, false>", 1)],
     "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_gather_kernel<unsigned short>", 1)],
     "dct_ef_select_threshold[c4]": [("dct::select_gather_kernel<0, true>", 1), ("dct::select_bounds_kernel<0>", 1),
                                     ("dct::select_partition_kernel<0, true>", 1),
@@ -49,6 +49,9 @@ CALL_KERNELS = {
     "dct_scatter[c4,assign]": [("dct::scatter_assign_kernel<unsigned int>", 1)],
     "dct_scatter[c4,add]": [("dct::scatter_pairs_kernel<unsigned int, true>", 1)],
     "dct_rowtopk_scatter[c5]": [("dct::rowscatter_lds_kernel<unsigned short>", 1)],
+    "dct_rowtopk_fwd_bitmask[c5]": [("dct::fast::rowtopk_fwd_bf16_kernel<8, true>", 1)],
+    "dct_rowtopk_bwd_bitmask[c5]": [("dct::rowtopk_bitmask_lanes_kernel<unsigned short, true>", 1)],
+    "dct_rowtopk_scatter_bitmask[c5]": [("dct::rowtopk_bitmask_lanes_kernel<unsigned short, false>", 1)],
 }
 
 
@@ -238,7 +241,19 @@ def main():
     call_fwd(0)
     us = time_calls(lambda i: dct.dct_rowtopk_scatter(idx5, val5, d5[i & 1]), args.reps)
     rx_calls.append(entry("dct_rowtopk_scatter[c5]", us, B5 * D5 * 2 + B5 * k5 * 6, B5 * D5))
-    del d5
+
+    # ------------------------------------------------------------ the mask as a bitmap (not part of the step)
+    bm_calls = []
+    mask5 = torch.zeros(B5, D5 // 32, dtype=torch.int32, device=dev)
+    us = time_calls(lambda i: dct.dct_rowtopk_fwd_bitmask(x5[i & 1], k5, mask5, val5, None), args.reps)
+    bm_calls.append(entry("dct_rowtopk_fwd_bitmask[c5]", us, B5 * D5 * 2 + B5 * (D5 // 8 + k5 * 2), B5 * D5))
+    us = time_calls(lambda i: dct.dct_rowtopk_bwd_bitmask(dy5[i & 1], mask5, dval5), args.reps)
+    bm_calls.append(entry("dct_rowtopk_bwd_bitmask[c5]", us, int(B5 * lines128) + B5 * (D5 // 8 + k5 * 2), B5 * D5,
+                          extra={"note": "algorithmic_bytes counts the 128-byte lines the gather touches"}))
+    us = time_calls(lambda i: dct.dct_rowtopk_scatter_bitmask(mask5, val5, d5[i & 1]), args.reps)
+    bm_calls.append(entry("dct_rowtopk_scatter_bitmask[c5]", us, B5 * D5 * 2 + B5 * (D5 // 8 + k5 * 2), B5 * D5))
+    del d5, mask5
+    call_fwd(0)
 
     # ------------------------------------------------------------ many small tensors per call (not part of the step)
     # 24 tensors from 64 to 2^20 elements (the largest is c1-sized), 1 % kept: one batched select +
@@ -289,7 +304,7 @@ def main():
     probes = {"read_GBps": round(probe_bytes / (us_read * 1e-6) / 1e9, 1),
               "copy_GBps": round(probe_bytes / (us_copy * 1e-6) / 1e9, 1)}
     del probe_src, probe_dst
-    for c in calls + ef_calls + rx_calls:
+    for c in calls + ef_calls + rx_calls + bm_calls:
         c["frac_of_probe_read"] = round(c["GBps"] / probes["read_GBps"], 4)
         log(f"[bench] {c['call']}: {c['us']} us, {c['GBps']} GB/s = {c['frac_of_hbm_peak']:.1%} of 8 TB/s")
     log(f"[bench] probes: {probes}")
@@ -302,7 +317,7 @@ def main():
                 "launches_per_call": dom["launches"],
                 "note": "achieved = algorithmic bytes of the call / HIP-event time of the call; traffic = scaled "
                         "FETCH_SIZE + WRITE_SIZE of its kernels from profiles/bench_hbm_counters.txt"}
-    for c in calls + ef_calls + rx_calls:
+    for c in calls + ef_calls + rx_calls + bm_calls:
         c["traffic"] = measured_traffic(c["call"])
 
     # ------------------------------------------------------------ c3: select once, reuse on fresh draws
@@ -381,7 +396,7 @@ def main():
         "config": {"workload": "c4 DP select+compact (N=2^28 fp32, keep 0.5%) + c5 MP row top-k fwd+bwd "
                                "(65536x4096 bf16, k=204)" + (" [SHRUNK 16x: not a valid number]" if args.small else ""),
                    "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
-        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls,
+        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls, "bitmask_calls": bm_calls,
         "batched_small_tensors": batched, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -193,6 +193,104 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_kernel(const W* __
   }
 }
 
+// The same two consumers with lane-contiguous columns: lane l of a wavefront owns columns
+// [64 l, 64 l + 64) of a 4096-column pass, i.e. two mask words; one wave scan of the popcounts
+// gives every lane its first slot, and the lanes then walk their own set bits, so all the
+// gathers of a row are in flight together.  The dense row of the decompression is assembled
+// in LDS (zeros + the values at their columns) and written with coalesced stores; it needs
+// D * sizeof(W) <= kBmRowBytes.
+constexpr uint32_t kBmRowBytes = 16384;
+template <typename W, bool GATHER>
+__global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
+    const W* __restrict__ src, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, const uint32_t* __restrict__ mask,
+    W* __restrict__ dst, uint64_t dst_stride, bool vec_ok) {
+  constexpr uint32_t EPV = 16 / sizeof(W);
+  __shared__ uint4 s_rows[GATHER ? 1 : kRtWaves][GATHER ? 1 : kBmRowBytes / 16];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane = lane_id();
+  const uint32_t n_words = (D + 31) / 32;
+  uint4* row4 = s_rows[GATHER ? 0 : wave];
+  W* row_lds = reinterpret_cast<W*>(row4);
+  const uint32_t n_vec = (D + EPV - 1) / EPV;
+  if constexpr (!GATHER) {
+    for (uint32_t q = lane; q < n_vec; q += kWave) row4[q] = make_uint4(0, 0, 0, 0);
+  }
+  for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * kRtWaves + wave; row < B;
+       row += static_cast<uint64_t>(gridDim.x) * kRtWaves) {
+    const uint32_t* mr = mask + row * n_words;
+    if constexpr (!GATHER) wave_lds_sync();  // the row buffer is all zeros again
+    uint32_t base = 0;
+    for (uint32_t c0 = 0; c0 < D; c0 += kWave * 64) {  // passes of 4096 columns
+      const uint32_t col0 = c0 + lane * 64;             // this lane's first column
+      const uint32_t w0 = col0 / 32;
+      uint64_t m = 0;
+      if (w0 < n_words) m = mr[w0];
+      if (w0 + 1 < n_words) m |= static_cast<uint64_t>(mr[w0 + 1]) << 32;
+      if (col0 >= D) m = 0;
+      else if (D - col0 < 64) m &= (1ull << (D - col0)) - 1ull;  // bits past the row's end do not count
+      const uint32_t pc = __popcll(m);
+      const uint32_t incl = fast::wave_incl_scan(pc);
+      uint32_t slot = base + incl - pc;
+      {
+        // the first eight set bits of every lane without a loop: their loads are independent
+        constexpr int kFirst = 8;
+        uint32_t cols[kFirst];
+        bool ok[kFirst];
+        W v[kFirst];
+#pragma unroll
+        for (int j = 0; j < kFirst; ++j) {
+          ok[j] = m != 0 && slot + j < k;
+          cols[j] = col0 + (m != 0 ? __builtin_ctzll(m) : 0);
+          m &= m - 1;  // stays 0 once it is 0
+        }
+#pragma unroll
+        for (int j = 0; j < kFirst; ++j) {
+          if constexpr (GATHER) v[j] = ok[j] ? src[row * stride + cols[j]] : static_cast<W>(0);
+          else v[j] = ok[j] ? src[row * k + slot + j] : static_cast<W>(0);
+        }
+#pragma unroll
+        for (int j = 0; j < kFirst; ++j) {
+          if (ok[j]) {
+            if constexpr (GATHER) dst[row * k + slot + j] = v[j];
+            else row_lds[cols[j]] = v[j];
+          }
+        }
+        slot += min(pc, static_cast<uint32_t>(kFirst));
+      }
+      while (ballot64(m != 0) != 0) {
+        if (m != 0) {
+          const uint32_t c = col0 + __builtin_ctzll(m);
+          m &= m - 1;
+          if (slot < k) {
+            if constexpr (GATHER) dst[row * k + slot] = src[row * stride + c];
+            else row_lds[c] = src[row * k + slot];
+          }
+          ++slot;
+        }
+      }
+      base += __builtin_amdgcn_readlane(incl, kWave - 1);
+    }
+    if constexpr (GATHER) {
+      for (uint32_t j = base + lane; j < k; j += kWave) dst[row * k + j] = 0;
+    } else {
+      wave_lds_sync();
+      W* out = dst + row * dst_stride;
+      if (vec_ok) {
+        uint4* out4 = reinterpret_cast<uint4*>(out);
+        for (uint32_t q = lane; q < n_vec; q += kWave) {
+          const uint4 v = row4[q];
+          st_stream(&out4[q], v.x, v.y, v.z, v.w);
+          row4[q] = make_uint4(0, 0, 0, 0);
+        }
+      } else {
+        for (uint32_t c = lane; c < D; c += kWave) out[c] = row_lds[c];
+        wave_lds_sync();
+        for (uint32_t q = lane; q < n_vec; q += kWave) row4[q] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  }
+}
+
 }  // namespace
 }  // namespace dct
 
@@ -279,13 +377,13 @@ extern "C" int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint3
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
   const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
   if (dt == DCT_F32) {
-    hipLaunchKernelGGL((rowtopk_bitmask_kernel<uint32_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
+    hipLaunchKernelGGL((rowtopk_bitmask_lanes_kernel<uint32_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
                        static_cast<const uint32_t*>(dy), B, D, row_stride_elems, k, d_mask,
-                       static_cast<uint32_t*>(d_dval_out), static_cast<uint64_t>(k));
+                       static_cast<uint32_t*>(d_dval_out), static_cast<uint64_t>(k), false);
   } else {
-    hipLaunchKernelGGL((rowtopk_bitmask_kernel<uint16_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
+    hipLaunchKernelGGL((rowtopk_bitmask_lanes_kernel<uint16_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
                        static_cast<const uint16_t*>(dy), B, D, row_stride_elems, k, d_mask,
-                       static_cast<uint16_t*>(d_dval_out), static_cast<uint64_t>(k));
+                       static_cast<uint16_t*>(d_dval_out), static_cast<uint64_t>(k), false);
   }
   return launch_status();
 }
@@ -301,6 +399,19 @@ extern "C" int dct_rowtopk_scatter_bitmask(const uint32_t* d_mask, const void* d
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
   const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
+  if (static_cast<uint64_t>(D) * es <= kBmRowBytes) {  // the row is assembled on chip
+    const bool vec_ok = is_aligned(d_out, 16) && (out_row_stride_elems * es) % 16 == 0 && (D * es) % 16 == 0;
+    if (dt == DCT_F32) {
+      hipLaunchKernelGGL((rowtopk_bitmask_lanes_kernel<uint32_t, false>), dim3(grid), dim3(kRtThreads), 0, s,
+                         static_cast<const uint32_t*>(d_val), B, D, static_cast<uint64_t>(k), k, d_mask,
+                         static_cast<uint32_t*>(d_out), out_row_stride_elems, vec_ok);
+    } else {
+      hipLaunchKernelGGL((rowtopk_bitmask_lanes_kernel<uint16_t, false>), dim3(grid), dim3(kRtThreads), 0, s,
+                         static_cast<const uint16_t*>(d_val), B, D, static_cast<uint64_t>(k), k, d_mask,
+                         static_cast<uint16_t*>(d_out), out_row_stride_elems, vec_ok);
+    }
+    return launch_status();
+  }
   if (dt == DCT_F32) {
     hipLaunchKernelGGL((rowtopk_bitmask_kernel<uint32_t, false>), dim3(grid), dim3(kRtThreads), 0, s,
                        static_cast<const uint32_t*>(d_val), B, D, static_cast<uint64_t>(k), k, d_mask,
