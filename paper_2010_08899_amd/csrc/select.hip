@@ -140,11 +140,11 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
   __syncthreads();
 
   // sample ranks (1-based from the top) that bracket rank k of the vector with a
-  // margin of six standard deviations of the sample count, plus slack
+  // margin of five standard deviations of the sample count, plus slack
   const uint64_t r = static_cast<uint64_t>(k) * kSampleSize / n;
   uint32_t sq = 0;
   while (static_cast<uint64_t>(sq + 1) * (sq + 1) <= r) ++sq;
-  const uint64_t delta = 6ull * (sq + 1) + 16;
+  const uint64_t delta = 5ull * (sq + 1) + 8;
   const uint64_t rank_hi = r > delta ? r - delta : 0;                     // 0: no upper bound
   const uint64_t rank_lo = r + delta + 1 <= kSampleSize ? r + delta + 1 : 0;  // 0: no lower bound
 

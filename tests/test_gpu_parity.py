@@ -819,3 +819,55 @@ def test_mp_bitmask_c5_block(dct):
     dval = torch.zeros_like(val)
     dct.dct_rowtopk_bwd_bitmask(dy, mask, dval)
     assert np.array_equal(host(dval), oracle.rowtopk_bwd_bitmask(host(dy), emask, k))
+
+
+# ------------------------------------------------------------------ the wider rows at the benchmark's full sizes
+def test_ef_and_decompress_c4_full(dct):
+    """Error feedback and decompression on the full c4 gradient (N = 2^28), the launch shape the
+    benchmark times.  The oracle's threshold comes from its nth_element selection on its own sum."""
+    g, k = si.config_c4(DEV)
+    n = g.numel()
+    e = si.residual_vector(n, DEV, 2100)
+    ef = EF(dct, n, capacity=2 * k)
+    thr = ef.select(g, e, k)
+    gh, eh = host(g), host(e)
+    w = oracle.ef_accumulate(gh, eh)
+    exp = oracle.select_threshold(w, k, method="nth")
+    assert thr == exp
+    e_out = torch.empty_like(e)
+    idx, val, cnt, guard = ef.compact(g, e, e_out, 1)
+    eidx, eval_, ecnt, e_exp = oracle.ef_threshold_compact(gh, eh, exp, 1, capacity=2 * k)
+    assert cnt == ecnt == k and np.array_equal(idx, eidx) and np.array_equal(bits(val), bits(eval_))
+    assert np.all(guard == -7)
+    assert np.array_equal(bits(host(e_out)), bits(e_exp))
+    del e_exp, eh
+    # decompress the message (count stays on the device) and check conservation on the device
+    dense = torch.empty_like(g)
+    dct.dct_scatter(ef.idx, ef.val, ef.count, dense)
+    assert np.array_equal(bits(host(dense)), bits(oracle.scatter(eidx, eval_, n)))
+    assert torch.equal(dense + e_out, torch.from_numpy(w).to(DEV))
+
+
+def test_bitmask_and_decompress_c5_full(dct):
+    x, dy, k = si.config_c5(DEV)
+    B, D = x.shape
+    assert (B, D, k) == (65536, 4096, 204)
+    mask = torch.zeros(B, D // 32, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=x.dtype, device=DEV)
+    dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, None)
+    xh = host(x)
+    emask, eval_, _ = oracle.rowtopk_fwd_bitmask(xh, k)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), emask) and np.array_equal(host(val), eval_)
+    dval = torch.zeros_like(val)
+    dct.dct_rowtopk_bwd_bitmask(dy, mask, dval)
+    assert np.array_equal(host(dval), oracle.rowtopk_bwd_bitmask(host(dy), emask, k))
+    out = torch.empty_like(x)
+    dct.dct_rowtopk_scatter_bitmask(mask, val, out)
+    want = oracle.rowscatter_bitmask(emask, eval_, D)
+    assert np.array_equal(host(out), want)
+    # the index form decompresses to the same dense matrix
+    idx = torch.zeros(B, k, dtype=torch.int32, device=DEV)
+    dct.dct_rowtopk_fwd(x, k, idx, val, None)
+    out2 = torch.empty_like(x)
+    dct.dct_rowtopk_scatter(idx, val, out2)
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
