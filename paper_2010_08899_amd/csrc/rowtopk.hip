@@ -5,6 +5,7 @@
 // which is a gather of dy at the forward indices (no new selection: Sec. 2.2,
 // "the same mask is used").
 #include <algorithm>
+#include <type_traits>
 
 #include "dct_common.hpp"
 #include "rowtopk_fast.hpp"
@@ -313,29 +314,34 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   auto* io = static_cast<int32_t*>(idx_or_mask);
   uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
   if (grid > 65536u * 4) grid = 65536u * 4;
-  // bf16 rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, D <= 4096
-  if (dt == DCT_BF16 && D % 8 == 0 && D <= 4096 && is_aligned(x, 16) && row_stride_elems % 8 == 0) {
+  // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 64 lanes x 8 vectors
+  const uint32_t epv = static_cast<uint32_t>(16 / es);
+  if (D % epv == 0 && D <= 512u * epv && is_aligned(x, 16) && row_stride_elems % epv == 0) {
     uint32_t fgrid = (B + fast::kWaves - 1) / fast::kWaves;
     const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 4u;
     if (fgrid > resident) fgrid = resident;
-    const auto* xp = static_cast<const uint16_t*>(x);
-    auto* vp = static_cast<uint16_t*>(d_val_out);
-    auto* tp = static_cast<uint16_t*>(d_tau_out);
     const dim3 g(fgrid), b(fast::kThreads);
-#define DCT_LAUNCH_FAST(NVV)                                                                                   \
-  do {                                                                                                         \
-    if (mask)                                                                                                  \
-      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<NVV, true>), g, b, 0, s, xp, B, D, row_stride_elems, k, \
-                         io, vp, tp);                                                                          \
-    else                                                                                                       \
-      hipLaunchKernelGGL((fast::rowtopk_fwd_bf16_kernel<NVV, false>), g, b, 0, s, xp, B, D, row_stride_elems,  \
-                         k, io, vp, tp);                                                                       \
+    const uint32_t vecs = D / epv;  // 16-byte vectors per row, spread over 64 lanes
+#define DCT_LAUNCH_ONCHIP(NVV, MK, F32V)                                                                        \
+  do {                                                                                                          \
+    using W = std::conditional_t<F32V, uint32_t, uint16_t>;                                                     \
+    hipLaunchKernelGGL((fast::rowtopk_fwd_onchip_kernel<NVV, MK, F32V>), g, b, 0, s, static_cast<const W*>(x), B, \
+                       D, row_stride_elems, k, io, static_cast<W*>(d_val_out), static_cast<W*>(d_tau_out));     \
   } while (0)
-    if (D <= 512) DCT_LAUNCH_FAST(1);
-    else if (D <= 1024) DCT_LAUNCH_FAST(2);
-    else if (D <= 2048) DCT_LAUNCH_FAST(4);
-    else DCT_LAUNCH_FAST(8);
-#undef DCT_LAUNCH_FAST
+#define DCT_LAUNCH_ONCHIP_NV(MK, F32V)                       \
+  do {                                                       \
+    if (vecs <= 64) DCT_LAUNCH_ONCHIP(1, MK, F32V);          \
+    else if (vecs <= 128) DCT_LAUNCH_ONCHIP(2, MK, F32V);    \
+    else if (vecs <= 256) DCT_LAUNCH_ONCHIP(4, MK, F32V);    \
+    else DCT_LAUNCH_ONCHIP(8, MK, F32V);                     \
+  } while (0)
+    if (dt == DCT_F32) {
+      if (mask) DCT_LAUNCH_ONCHIP_NV(true, true); else DCT_LAUNCH_ONCHIP_NV(false, true);
+    } else {
+      if (mask) DCT_LAUNCH_ONCHIP_NV(true, false); else DCT_LAUNCH_ONCHIP_NV(false, false);
+    }
+#undef DCT_LAUNCH_ONCHIP_NV
+#undef DCT_LAUNCH_ONCHIP
     return launch_status();
   }
 #define DCT_LAUNCH_GENERIC(DTV, MK)                                                                       \

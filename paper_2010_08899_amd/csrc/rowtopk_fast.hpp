@@ -1,5 +1,6 @@
-// Fast forward kernel of dct_rowtopk_fwd for bf16 rows of up to 4096 columns
-// (Algorithm 2, forward loop: per row the k largest |X_act,i|).
+// On-chip forward kernel of dct_rowtopk_fwd (Algorithm 2, forward loop: per row the
+// k largest |X_act,i|) for bf16 rows of up to 4096 columns and fp32 rows of up to
+// 2048 columns.
 //
 // One wavefront owns one row at a time and keeps it on chip:
 //   1. the row is loaded once with coalesced 16-byte loads and written to a
@@ -11,19 +12,26 @@
 //      pairs column i with column 16 + i, so that shifting those two bits into an
 //      accumulator yields a per-lane bitmap in plain column order;
 //   3. tau_i is found exactly.  Rows of one matrix have similar thresholds, so the
-//      previous row's tau predicts a window of 64 key values: two packed compare
+//      previous row's tau predicts a window of 32 key values: two packed compare
 //      sweeps give the per-lane bitmaps of the keys at or above the window's ends,
 //      the few keys inside the window are histogrammed (one LDS bin per lane) and
-//      a wave scan over the bins locates the k-th largest key.  If the window does
-//      not contain it (or there is no previous row) a bisection over the upper key
-//      bits narrows the range to 64 values first;
+//      a wave scan over the bins locates the k-th largest key.  The first row of a
+//      wavefront takes its prediction from a sample of the row (8 keys per lane);
+//      a window that does not contain tau_i is followed by a galloping search from
+//      that window in the direction the counts point to, then by bisection;
 //   4. ties at tau_i are resolved by column order with one wave scan of per-lane
 //      tie counts; the survivors' columns are then listed in order in the padding of
 //      the LDS row buffer (slot = survivors in lower lanes + survivors at lower
 //      columns of the lane) and written out with coalesced stores.
+// fp32 rows run the same search on the UPPER 16 bits of their keys (which have
+// exactly the layout of a bf16 key); the k-th largest key then lies among the
+// few keys whose upper half equals the result, and a second, small selection on
+// their lower halves finishes the job (step 3b in the code).
 // Everything is integer work on the key bits; values are copied from the LDS copy
 // of the row bit for bit.
 #pragma once
+
+#include <type_traits>
 
 #include "dct_common.hpp"
 
@@ -67,31 +75,50 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_wave_barrier();
 }
 
-// NV = 16-byte vectors per lane: the lane owns columns [lane*NV*8, (lane+1)*NV*8).
+// NV = 16-byte vectors per lane: the lane owns NV*8 (bf16) or NV*4 (fp32) contiguous columns.
 // MASK: the row's mask is written as a bitmap (ceil(D/32) words per row, bit c%32 of word c/32 =
 // column c kept) through `idx_out` instead of k column indices; the values are written either way.
-template <int NV, bool MASK>
-__global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
-    const uint16_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k,
-    int32_t* __restrict__ idx_out, uint16_t* __restrict__ val_out, uint16_t* __restrict__ tau_out) {
-  constexpr int REGS = 4 * NV;                      // packed registers per lane (2 columns each)
+// F32: fp32 rows (the packed 16-bit keys are the upper halves of the fp32 keys).
+template <int NV, bool MASK, bool F32>
+__global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
+    const std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride,
+    uint32_t k, int32_t* __restrict__ idx_out, std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ val_out,
+    std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ tau_out) {
+  using word_t = std::conditional_t<F32, uint32_t, uint16_t>;
+  constexpr int ES = F32 ? 4 : 2;                   // bytes per element
+  constexpr int EPV = 16 / ES;                      // elements per 16-byte vector
+  constexpr int COLS = NV * EPV;                    // columns per lane
+  constexpr int REGS = COLS / 2;                    // packed key registers per lane (2 columns each)
   constexpr int RPW = REGS < 16 ? REGS : 16;        // registers per bitmap word
   constexpr int WORDS = (REGS + 15) / 16;
-  constexpr int COLS = NV * 8;                      // columns per lane
   constexpr int CHUNK = (NV + 1) * 16;              // LDS bytes per lane chunk (16 bytes of padding)
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
   __shared__ uint32_t s_hist[kWaves][kWave];
+  __shared__ uint32_t s_fix[F32 ? kWaves : 1][F32 ? kWave * WORDS : 1];  // fp32: decisions handed back to the owner lane
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: row numbers stay scalar
   const uint32_t lane = lane_id();
   char* row_lds = reinterpret_cast<char*>(s_row[wave]);
   uint32_t* hist = s_hist[wave];
-  const uint32_t n_vec = D / 8;                     // the host guarantees D % 8 == 0
+  const uint32_t n_vec = D / EPV;                   // the host guarantees whole 16-byte vectors
+  [[maybe_unused]] uint32_t* fix = s_fix[F32 ? wave : 0];
+  if constexpr (F32) {
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) fix[lane * WORDS + w] = 0;
+  }
 
   // bit q of bitmap word w <-> local column kColsPerWord * w + q of the lane
   constexpr int kColsPerWord = 2 * RPW;
+  // 16-bit key material of local column lc (bf16: the element; fp32: its upper half)
   auto key_at = [&](uint32_t lc) {
-    return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(row_lds + lane * CHUNK + lc * 2));
+    return static_cast<uint32_t>(
+        *reinterpret_cast<const uint16_t*>(row_lds + lane * CHUNK + lc * ES + (F32 ? 2 : 0)));
+  };
+  // the stored element of row column col, bit for bit
+  auto raw_at_col = [&](uint32_t col) -> uint32_t {
+    const char* p = row_lds + (col / COLS) * CHUNK + (col % COLS) * ES;
+    if constexpr (F32) return *reinterpret_cast<const uint32_t*>(p);
+    else return *reinterpret_cast<const uint16_t*>(p);
   };
   // the 16 padding bytes of every lane chunk hold the ordered list of surviving columns
   constexpr uint32_t kStageSlots = kWave * 8;
@@ -129,7 +156,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     }
     wave_lds_fence();
     if (row + row_step < B) load_row(row + row_step);
-    uint32_t R[REGS];  // R[r] = columns (2r, 2r+1) of the lane
+    uint32_t R[4 * NV];  // the lane's columns as loaded: two per word (bf16) or one per word (fp32)
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
       const uint4 v = *reinterpret_cast<const uint4*>(row_lds + lane * CHUNK + m * 16);
@@ -138,15 +165,21 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
       R[4 * m + 2] = v.z;
       R[4 * m + 3] = v.w;
     }
-    // K[RPW*w + i] = keys of columns (2*RPW*w + i, 2*RPW*w + RPW + i), bit 15 of each half set
+    // K[RPW*w + i] = 16-bit keys of columns (2*RPW*w + i, 2*RPW*w + RPW + i), bit 15 of each half set
     uint32_t K[REGS];
 #pragma unroll
     for (int w = 0; w < WORDS; ++w) {
 #pragma unroll
       for (int i = 0; i < RPW; ++i) {
-        const uint32_t a = R[RPW * w + i / 2], b2 = R[RPW * w + RPW / 2 + i / 2];
-        // v_perm_b32 picks bytes from {b2, a}: the two low halves (i even) or the two high halves (i odd)
-        const uint32_t pair = __builtin_amdgcn_perm(b2, a, (i & 1) ? 0x07060302u : 0x05040100u);
+        uint32_t pair;
+        if constexpr (F32) {
+          // the two upper halves: bytes 2,3 of each word
+          pair = __builtin_amdgcn_perm(R[2 * RPW * w + RPW + i], R[2 * RPW * w + i], 0x07060302u);
+        } else {
+          const uint32_t a = R[RPW * w + i / 2], b2 = R[RPW * w + RPW / 2 + i / 2];
+          // v_perm_b32 picks bytes from {b2, a}: the two low halves (i even) or the two high halves (i odd)
+          pair = __builtin_amdgcn_perm(b2, a, (i & 1) ? 0x07060302u : 0x05040100u);
+        }
         K[RPW * w + i] = (pair & 0x7FFF7FFFu) | 0x80008000u;
       }
     }
@@ -355,8 +388,110 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
       }
     }
 
-    // ---- 4. ties: the `quota` lowest columns among the n_eq ties survive
-    if (quota >= n_eq) {
+    uint32_t tie_quota = quota, tie_n = n_eq;  // ties still to be resolved by column order
+    [[maybe_unused]] uint32_t tau_low = 0;
+    if constexpr (F32) {
+      // ---- 3b. fp32: the search ran on the upper halves of the keys.  The k-th largest key is one of
+      // the tie_n keys whose upper half is tau: find t, the tie_quota-th largest LOWER half among them.
+      auto low_at = [&](uint32_t lc) {
+        return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(row_lds + lane * CHUNK + lc * 4));
+      };
+      uint32_t t = 0;
+      if (tie_n <= static_cast<uint32_t>(kWave)) {
+        // few of them: list their columns in order, one per lane, and bisect on registers
+        uint32_t tc = 0;
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
+        uint32_t ts = wave_incl_scan(tc) - tc;
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w) {
+          uint32_t m = tie[w];
+          while (ballot64(m != 0) != 0) {
+            if (m != 0) {
+              const uint32_t q = __builtin_ctz(m);
+              m &= m - 1;
+              *stage_at(ts++) = static_cast<uint16_t>(lane * COLS + kColsPerWord * w + q);
+            }
+          }
+        }
+        wave_lds_fence();
+        const bool valid = lane < tie_n;
+        const uint32_t col = valid ? *stage_at(lane) : 0u;
+        const uint32_t low = valid ? (raw_at_col(col) & 0xFFFFu) : 0u;
+        for (int bit = 15; bit >= 0; --bit) {
+          const uint32_t cand = t | (1u << bit);
+          if (static_cast<uint32_t>(__popcll(ballot64(valid && low >= cand))) >= tie_quota) t = cand;
+        }
+        const bool gt = valid && low > t, eq = valid && low == t;
+        const uint64_t m_eq = ballot64(eq);
+        const uint32_t left = tie_quota - static_cast<uint32_t>(__popcll(ballot64(gt)));  // >= 1 by the choice of t
+        if (gt || (eq && lanes_below(m_eq) < left)) {  // list order is column order
+          const uint32_t lc = col % COLS;
+          atomicOr(&fix[(col / COLS) * WORDS + lc / kColsPerWord], 1u << (lc % kColsPerWord));
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w) {
+          keep[w] |= fix[lane * WORDS + w];
+          fix[lane * WORDS + w] = 0;
+          tie[w] = 0;
+        }
+        tie_quota = 0;
+        tie_n = 0;
+      } else {
+        // many keys share the upper half (constant or coarsely quantised rows): every lane walks its own
+        static_assert(!F32 || WORDS == 1, "an fp32 lane owns at most 32 columns: one bitmap word");
+        auto for_own_ties = [&](auto&& body) {  // body(bit, lower half)
+          uint32_t m = tie[0];
+          while (ballot64(m != 0) != 0) {
+            if (m != 0) {
+              const uint32_t q = __builtin_ctz(m);
+              m &= m - 1;
+              body(q, low_at(q));
+            }
+          }
+        };
+        uint32_t mn = 0xFFFFu, mx = 0;
+        for_own_ties([&](uint32_t, uint32_t low) {
+          mn = min(mn, low);
+          mx = max(mx, low);
+        });
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+          mn = min(mn, static_cast<uint32_t>(__shfl_xor(mn, d, kWave)));
+          mx = max(mx, static_cast<uint32_t>(__shfl_xor(mx, d, kWave)));
+        }
+        t = mn;  // all lower halves equal (the usual case here): column order alone decides, below
+        if (mn != mx) {
+          const int top = 31 - __builtin_clz(mn ^ mx);   // bisect on the bits in which they differ
+          t = mn & ~((2u << top) - 1u);
+          for (int bit = top; bit >= 0; --bit) {
+            const uint32_t cand = t | (1u << bit);
+            uint32_t cnt = 0;
+            for_own_ties([&](uint32_t, uint32_t low) { cnt += low >= cand ? 1u : 0u; });
+            if (wave_total(cnt) >= tie_quota) t = cand;
+          }
+          // greater lower halves survive; equal ones are the ties that column order resolves
+          uint32_t ng = 0, ne = 0, up = 0, rest = 0;
+          for_own_ties([&](uint32_t q, uint32_t low) {
+            const bool greater = low > t, equal = low == t;
+            up |= greater ? (1u << q) : 0u;
+            rest |= equal ? (1u << q) : 0u;
+            ng += greater ? 1u : 0u;
+            ne += equal ? 1u : 0u;
+          });
+          keep[0] |= up;
+          tie[0] = rest;
+          const uint32_t both = wave_total(ng | (ne << 16));
+          tie_quota -= both & 0xFFFFu;
+          tie_n = both >> 16;
+        }
+      }
+      tau_low = t;
+    }
+
+    // ---- 4. ties: the `tie_quota` lowest columns among the tie_n ties survive
+    if (tie_quota >= tie_n) {
 #pragma unroll
       for (int w = 0; w < WORDS; ++w) keep[w] |= tie[w];
     } else {
@@ -364,7 +499,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
 #pragma unroll
       for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
       const uint32_t before = wave_incl_scan(tc) - tc;     // ties in lower lanes
-      const uint32_t allowed = quota > before ? quota - before : 0u;  // ties this lane may keep
+      const uint32_t allowed = tie_quota > before ? tie_quota - before : 0u;  // ties this lane may keep
       // lanes below the boundary keep all their ties, lanes above it none; the one lane on the
       // boundary drops its highest columns until `allowed` ties are left
       uint32_t t[WORDS];
@@ -388,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
     for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
     uint32_t slot = wave_incl_scan(kc) - kc;
     int32_t* io = idx_out + row * k;
-    uint16_t* vo = val_out + row * k;
+    word_t* vo = val_out + row * k;
     if constexpr (MASK) {
       // the per-lane bitmaps ARE the mask: COLS bits per lane, packed into 32-bit words
       const uint32_t n_words = (D + 31) / 32;
@@ -398,7 +533,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         for (int w = 0; w < WORDS; ++w)
           if (lane * WORDS + w < n_words) mo[lane * WORDS + w] = keep[w];
       } else {
-        constexpr uint32_t kLanesPerWord = 32 / COLS;  // 2 or 4 neighbouring lanes share a word
+        constexpr uint32_t kLanesPerWord = 32 / COLS;  // 2, 4 or 8 neighbouring lanes share a word
         uint32_t v = keep[0] << ((lane % kLanesPerWord) * COLS);
 #pragma unroll
         for (uint32_t d = 1; d < kLanesPerWord; d <<= 1) v |= __shfl_xor(v, d, kWave);
@@ -428,21 +563,21 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
         for (int j = 0; j < 4; ++j) col[j] = j * kWave + lane < k ? *stage_at(j * kWave + lane) : 0u;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          raw[j] = *reinterpret_cast<const uint16_t*>(row_lds + (col[j] / COLS) * CHUNK + (col[j] % COLS) * 2);
+          raw[j] = raw_at_col(col[j]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const uint32_t o = j * kWave + lane;
           if (o < k) {
             if constexpr (!MASK) io[o] = static_cast<int32_t>(col[j]);
-            vo[o] = static_cast<uint16_t>(raw[j]);
+            vo[o] = static_cast<word_t>(raw[j]);
           }
         }
       } else {
         for (uint32_t j = lane; j < k; j += kWave) {
           const uint32_t col = *stage_at(j);
-          const uint32_t raw = *reinterpret_cast<const uint16_t*>(row_lds + (col / COLS) * CHUNK + (col % COLS) * 2);
+          const uint32_t raw = raw_at_col(col);
           if constexpr (!MASK) io[j] = static_cast<int32_t>(col);
-          vo[j] = static_cast<uint16_t>(raw);
+          vo[j] = static_cast<word_t>(raw);
         }
       }
     } else {
@@ -456,14 +591,14 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_bf16_kernel(
             const uint32_t lc = kColsPerWord * w + q;
             if (slot < k) {
               if constexpr (!MASK) io[slot] = static_cast<int32_t>(lane * COLS + lc);
-              vo[slot] = static_cast<uint16_t>(key_at(lc));
+              vo[slot] = static_cast<word_t>(raw_at_col(lane * COLS + lc));
             }
             ++slot;
           }
         }
       }
     }
-    if (tau_out && lane == 0) tau_out[row] = static_cast<uint16_t>(tau);
+    if (tau_out && lane == 0) tau_out[row] = static_cast<word_t>(F32 ? ((tau << 16) | tau_low) : tau);
   }
 }
 

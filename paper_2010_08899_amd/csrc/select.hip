@@ -10,10 +10,10 @@
 // from the top bin down to find the bin of the k-th largest key.
 //
 // For large vectors the radix passes do not run over the vector.  A first kernel
-// reads a stratified sample of 16384 keys and takes two of its order statistics
-// as bounds lo <= tau <= hi that hold with overwhelming probability.  One
-// streaming pass over the vector (coalesced 16-byte loads, one contiguous chunk
-// per workgroup) counts the keys above hi and appends the keys in [lo, hi] --
+// gathers a stratified sample of 16384 keys, a second one brackets two of its
+// order statistics to get bounds lo <= tau <= hi that hold with overwhelming
+// probability.  One streaming pass over the vector (coalesced 16-byte loads, tiles
+// dealt round-robin to the workgroups) counts the keys above hi and appends the keys in [lo, hi] --
 // well under 1 % of the vector -- to a candidate buffer through LDS staging.  The
 // radix passes then run over the candidates only, so the vector is read from HBM
 // once.  The counts tell exactly whether the bounds held (n_above < k <= n_above

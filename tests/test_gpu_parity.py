@@ -313,6 +313,38 @@ def test_mp_bf16_on_chip_kernel_hard_rows(dct, D):
         check_mp(dct, x, dy, k)
 
 
+@pytest.mark.parametrize("D", [256, 1024, 2048])
+def test_mp_fp32_on_chip_kernel_hard_rows(dct, D):
+    """fp32 rows for the on-chip kernel: its search runs on the upper halves of the keys, so the hard
+    cases are many keys that share an upper half -- with equal lower halves (constants, zeros), with
+    distinct ones (a narrow band of values), a handful of them, and more than a wavefront of them."""
+    gen = torch.Generator(device=DEV).manual_seed(172)
+    rows = [t for _, t in si.adversarial_vectors(D, DEV, 171)]
+    for s_ in (1e-30, 1e30, 1.0, 1e-3):
+        rows.append(torch.randn(D, device=DEV, generator=gen) * s_)
+    step = torch.arange(D, device=DEV, dtype=torch.float32)
+    perm = torch.randperm(D, device=DEV, generator=gen)
+    rows.append(1.0 + step[perm] * 2.0 ** -20)                     # every key in one upper-half bin, all distinct
+    rows.append(-(1.0 + (step[perm] % 37) * 2.0 ** -18))           # the same with repeats
+    band = torch.randn(D, device=DEV, generator=gen)
+    band[perm[: min(50, D // 4)]] = 3.0 + step[: min(50, D // 4)] * 2.0 ** -21     # a handful sharing the top bin
+    rows.append(band)
+    band2 = torch.randn(D, device=DEV, generator=gen) * 0.1
+    band2[perm[: D // 2]] = 2.0 + step[: D // 2] * 2.0 ** -22                       # more than 64 sharing it
+    rows.append(band2)
+    sparse = torch.zeros(D, device=DEV)
+    sparse[5::97] = 2.0
+    rows.append(sparse)
+    nanrow = torch.randn(D, device=DEV, generator=gen)
+    nanrow[7] = float("nan")
+    rows.append(nanrow)
+    x = torch.stack(rows * 3).contiguous()
+    x = x[torch.randperm(x.shape[0], device=DEV, generator=gen)].contiguous()
+    dy = si.normal_matrix(x.shape[0], D, DEV, 173)
+    for k in (1, 7, D // 20, D // 2, D):
+        check_mp(dct, x, dy, k)
+
+
 def test_mp_c2_full(dct):
     x, dy, k = si.config_c2(DEV)
     idx, val, dval = check_mp(dct, x, dy, k)
