@@ -314,11 +314,12 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   auto* io = static_cast<int32_t*>(idx_or_mask);
   uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
   if (grid > 65536u * 4) grid = 65536u * 4;
-  // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 64 lanes x 8 vectors
+  // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 4096 columns
   const uint32_t epv = static_cast<uint32_t>(16 / es);
-  if (D % epv == 0 && D <= 512u * epv && is_aligned(x, 16) && row_stride_elems % epv == 0) {
+  if (D % epv == 0 && D <= 4096u && is_aligned(x, 16) && row_stride_elems % epv == 0) {
     uint32_t fgrid = (B + fast::kWaves - 1) / fast::kWaves;
-    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 4u;
+    // workgroups per CU that the LDS row buffers allow: 4, or 2 for 16 KiB rows
+    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * (D * es > 8192u ? 2u : 4u);
     if (fgrid > resident) fgrid = resident;
     const dim3 g(fgrid), b(fast::kThreads);
     const uint32_t vecs = D / epv;  // 16-byte vectors per row, spread over 64 lanes
@@ -333,7 +334,8 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     if (vecs <= 64) DCT_LAUNCH_ONCHIP(1, MK, F32V);          \
     else if (vecs <= 128) DCT_LAUNCH_ONCHIP(2, MK, F32V);    \
     else if (vecs <= 256) DCT_LAUNCH_ONCHIP(4, MK, F32V);    \
-    else DCT_LAUNCH_ONCHIP(8, MK, F32V);                     \
+    else if (vecs <= 512) DCT_LAUNCH_ONCHIP(8, MK, F32V);    \
+    else if constexpr (F32V) DCT_LAUNCH_ONCHIP(16, MK, F32V); \
   } while (0)
     if (dt == DCT_F32) {
       if (mask) DCT_LAUNCH_ONCHIP_NV(true, true); else DCT_LAUNCH_ONCHIP_NV(false, true);

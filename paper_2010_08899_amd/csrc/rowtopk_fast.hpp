@@ -1,6 +1,5 @@
 // On-chip forward kernel of dct_rowtopk_fwd (Algorithm 2, forward loop: per row the
-// k largest |X_act,i|) for bf16 rows of up to 4096 columns and fp32 rows of up to
-// 2048 columns.
+// k largest |X_act,i|) for rows of up to 4096 columns, bf16 or fp32.
 //
 // One wavefront owns one row at a time and keeps it on chip:
 //   1. the row is loaded once with coalesced 16-byte loads and written to a
@@ -91,6 +90,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
   constexpr int REGS = COLS / 2;                    // packed key registers per lane (2 columns each)
   constexpr int RPW = REGS < 16 ? REGS : 16;        // registers per bitmap word
   constexpr int WORDS = (REGS + 15) / 16;
+  static_assert(WORDS <= 2, "a lane owns at most 64 columns");
   constexpr int CHUNK = (NV + 1) * 16;              // LDS bytes per lane chunk (16 bytes of padding)
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
   __shared__ uint32_t s_hist[kWaves][kWave];
@@ -440,22 +440,24 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
         tie_n = 0;
       } else {
         // many keys share the upper half (constant or coarsely quantised rows): every lane walks its own
-        static_assert(!F32 || WORDS == 1, "an fp32 lane owns at most 32 columns: one bitmap word");
-        auto for_own_ties = [&](auto&& body) {  // body(bit, lower half)
-          uint32_t m = tie[0];
+        // body(bit, lower half) for every set bit of m, a bitmap of local columns col0 ...
+        auto walk = [&](uint32_t m, uint32_t col0, auto&& body) {
           while (ballot64(m != 0) != 0) {
             if (m != 0) {
               const uint32_t q = __builtin_ctz(m);
               m &= m - 1;
-              body(q, low_at(q));
+              body(q, low_at(col0 + q));
             }
           }
         };
         uint32_t mn = 0xFFFFu, mx = 0;
-        for_own_ties([&](uint32_t, uint32_t low) {
-          mn = min(mn, low);
-          mx = max(mx, low);
-        });
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w) {
+          walk(tie[w], kColsPerWord * w, [&](uint32_t, uint32_t low) {
+            mn = min(mn, low);
+            mx = max(mx, low);
+          });
+        }
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
           mn = min(mn, static_cast<uint32_t>(__shfl_xor(mn, d, kWave)));
@@ -468,20 +470,26 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
           for (int bit = top; bit >= 0; --bit) {
             const uint32_t cand = t | (1u << bit);
             uint32_t cnt = 0;
-            for_own_ties([&](uint32_t, uint32_t low) { cnt += low >= cand ? 1u : 0u; });
+#pragma unroll
+            for (int w = 0; w < WORDS; ++w)
+              walk(tie[w], kColsPerWord * w, [&](uint32_t, uint32_t low) { cnt += low >= cand ? 1u : 0u; });
             if (wave_total(cnt) >= tie_quota) t = cand;
           }
           // greater lower halves survive; equal ones are the ties that column order resolves
-          uint32_t ng = 0, ne = 0, up = 0, rest = 0;
-          for_own_ties([&](uint32_t q, uint32_t low) {
-            const bool greater = low > t, equal = low == t;
-            up |= greater ? (1u << q) : 0u;
-            rest |= equal ? (1u << q) : 0u;
-            ng += greater ? 1u : 0u;
-            ne += equal ? 1u : 0u;
-          });
-          keep[0] |= up;
-          tie[0] = rest;
+          uint32_t ng = 0, ne = 0;
+#pragma unroll
+          for (int w = 0; w < WORDS; ++w) {
+            uint32_t up = 0, rest = 0;
+            walk(tie[w], kColsPerWord * w, [&](uint32_t q, uint32_t low) {
+              const bool greater = low > t, equal = low == t;
+              up |= greater ? (1u << q) : 0u;
+              rest |= equal ? (1u << q) : 0u;
+              ng += greater ? 1u : 0u;
+              ne += equal ? 1u : 0u;
+            });
+            keep[w] |= up;
+            tie[w] = rest;
+          }
           const uint32_t both = wave_total(ng | (ne << 16));
           tie_quota -= both & 0xFFFFu;
           tie_n = both >> 16;

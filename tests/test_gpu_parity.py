@@ -313,7 +313,7 @@ def test_mp_bf16_on_chip_kernel_hard_rows(dct, D):
         check_mp(dct, x, dy, k)
 
 
-@pytest.mark.parametrize("D", [256, 1024, 2048])
+@pytest.mark.parametrize("D", [256, 1024, 2048, 4096])
 def test_mp_fp32_on_chip_kernel_hard_rows(dct, D):
     """fp32 rows for the on-chip kernel: its search runs on the upper halves of the keys, so the hard
     cases are many keys that share an upper half -- with equal lower halves (constants, zeros), with
