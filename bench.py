@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--reps", type=int, default=30, help="launches per kernel for the per-call timings")
     ap.add_argument("--c3-draws", type=int, default=1000, help="distinct resident draws for the c3 reuse loop")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-batched", action="store_true",
+                    help="skip the small-tensor comparison (its per-tensor calls launch the same kernels as the "
+                         "large configurations, which blurs per-kernel profiles)")
     ap.add_argument("--small", action="store_true", help="shrink c4/c5 by 16x (debugging only, not a valid number)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -258,40 +261,42 @@ def main():
     # ------------------------------------------------------------ many small tensors per call (not part of the step)
     # 24 tensors from 64 to 2^20 elements (the largest is c1-sized), 1 % kept: one batched select +
     # one batched compaction against one pair of calls per tensor.
-    bt_sizes = [1 << 20, 512 * 1024, 512 * 256, 256 * 64, 1024, 512, 256, 64] * 3
-    bt_segs, off_b, out_b = [], 0, 0
-    for n_b in bt_sizes:
-        k_b = max(1, n_b // 100)
-        bt_segs.append((off_b, n_b, k_b, out_b, 2 * k_b))
-        off_b += n_b
-        out_b += 2 * k_b
-    gb = si.gaussian_gradient(off_b, dev, si.BASE_SEED + 70)
-    bt_table = dct.segment_table(bt_segs)
-    bt_ws = dct.new_batched_workspace(gb, bt_table)
-    bt_thr = torch.zeros(len(bt_segs), 4, dtype=torch.int32, device=dev)
-    bt_idx = torch.zeros(out_b, dtype=torch.int32, device=dev)
-    bt_val = torch.zeros(out_b, dtype=torch.float32, device=dev)
-    bt_cnt = torch.zeros(len(bt_segs), dtype=torch.int64, device=dev)
-    one_sws = dct.new_select_workspace(gb[: bt_sizes[0]])
-    one_cws = dct.new_compact_workspace(gb[: bt_sizes[0]])
-    one_cnt = torch.zeros(1, dtype=torch.int64, device=dev)
+    batched = None
+    bt_sizes = [] if args.no_batched else [1 << 20, 512 * 1024, 512 * 256, 256 * 64, 1024, 512, 256, 64] * 3
+    if bt_sizes:
+        bt_segs, off_b, out_b = [], 0, 0
+        for n_b in bt_sizes:
+            k_b = max(1, n_b // 100)
+            bt_segs.append((off_b, n_b, k_b, out_b, 2 * k_b))
+            off_b += n_b
+            out_b += 2 * k_b
+        gb = si.gaussian_gradient(off_b, dev, si.BASE_SEED + 70)
+        bt_table = dct.segment_table(bt_segs)
+        bt_ws = dct.new_batched_workspace(gb, bt_table)
+        bt_thr = torch.zeros(len(bt_segs), 4, dtype=torch.int32, device=dev)
+        bt_idx = torch.zeros(out_b, dtype=torch.int32, device=dev)
+        bt_val = torch.zeros(out_b, dtype=torch.float32, device=dev)
+        bt_cnt = torch.zeros(len(bt_segs), dtype=torch.int64, device=dev)
+        one_sws = dct.new_select_workspace(gb[: bt_sizes[0]])
+        one_cws = dct.new_compact_workspace(gb[: bt_sizes[0]])
+        one_cnt = torch.zeros(1, dtype=torch.int64, device=dev)
 
-    def batched_pair(i):
-        dct.dct_select_threshold_batched(gb, bt_table, bt_thr, bt_ws)
-        dct.dct_threshold_compact_batched(gb, bt_table, bt_thr, dct.DCT_GE_TAU, bt_idx, bt_val, bt_cnt, bt_ws)
+        def batched_pair(i):
+            dct.dct_select_threshold_batched(gb, bt_table, bt_thr, bt_ws)
+            dct.dct_threshold_compact_batched(gb, bt_table, bt_thr, dct.DCT_GE_TAU, bt_idx, bt_val, bt_cnt, bt_ws)
 
-    def per_tensor_pairs(i):
-        for (o, n_b, k_b, oo, cap_b) in bt_segs:
-            dct.dct_select_threshold(gb[o:o + n_b], k_b, thr, one_sws)
-            dct.dct_threshold_compact(gb[o:o + n_b], thr, dct.DCT_GE_TAU, bt_idx[oo:oo + cap_b],
-                                      bt_val[oo:oo + cap_b], one_cnt, one_cws)
+        def per_tensor_pairs(i):
+            for (o, n_b, k_b, oo, cap_b) in bt_segs:
+                dct.dct_select_threshold(gb[o:o + n_b], k_b, thr, one_sws)
+                dct.dct_threshold_compact(gb[o:o + n_b], thr, dct.DCT_GE_TAU, bt_idx[oo:oo + cap_b],
+                                          bt_val[oo:oo + cap_b], one_cnt, one_cws)
 
-    us_bt = time_calls(batched_pair, 10)
-    us_pt = time_calls(per_tensor_pairs, 10)
-    batched = {"tensors": len(bt_segs), "elements": off_b, "kept_fraction": 0.01,
-               "batched_select_plus_compact_us": round(us_bt, 1), "one_call_pair_per_tensor_us": round(us_pt, 1),
-               "elements_per_s_batched": off_b / (us_bt * 1e-6)}
-    log(f"[bench] batched: {batched}")
+        us_bt = time_calls(batched_pair, 10)
+        us_pt = time_calls(per_tensor_pairs, 10)
+        batched = {"tensors": len(bt_segs), "elements": off_b, "kept_fraction": 0.01,
+                   "batched_select_plus_compact_us": round(us_bt, 1), "one_call_pair_per_tensor_us": round(us_pt, 1),
+                   "elements_per_s_batched": off_b / (us_bt * 1e-6)}
+        log(f"[bench] batched: {batched}")
     call_select(0)
 
     # plain streaming kernels: the achievable HBM rate measured in the same run
