@@ -318,8 +318,10 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   const uint32_t epv = static_cast<uint32_t>(16 / es);
   if (D % epv == 0 && D <= 4096u && is_aligned(x, 16) && row_stride_elems % epv == 0) {
     uint32_t fgrid = (B + fast::kWaves - 1) / fast::kWaves;
-    // workgroups per CU that the LDS row buffers allow: 4, or 2 for 16 KiB rows
-    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * (D * es > 8192u ? 2u : 4u);
+    // workgroups per CU that registers and the LDS row buffers allow (rows of up to 2 / 4 / 8 / 16 KiB)
+    const uint32_t row_bytes = D * static_cast<uint32_t>(es);
+    const uint32_t per_cu = row_bytes <= 2048u ? 8u : row_bytes <= 4096u ? 6u : row_bytes <= 8192u ? 4u : 2u;
+    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * per_cu;
     if (fgrid > resident) fgrid = resident;
     const dim3 g(fgrid), b(fast::kThreads);
     const uint32_t vecs = D / epv;  // 16-byte vectors per row, spread over 64 lanes
