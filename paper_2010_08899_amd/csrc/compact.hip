@@ -209,39 +209,66 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     auto emit = [&](const uint32_t* raw, bool in, uint32_t index0, auto nelem_tag) {
       constexpr int NE = decltype(nelem_tag)::value;
       // Cheap common case first: one compare per element against tau (keys >= tau are the
-      // survivors and, in exactly-k mode, the ties); most groups of rows have none.
-      bool ge[NE];
-      uint64_t any = 0;
+      // survivors and, in exactly-k mode, the ties), collected in a per-lane bitmap; most groups
+      // of rows have none.
+      uint32_t ge_bits = 0;
 #pragma unroll
-      for (int e = 0; e < NE; ++e) {
-        ge[e] = in && (raw[e] & E::kKeyMask) >= tau;
-        any |= ballot64(ge[e]);
-      }
-      if (any == 0) return;
-      bool fa[NE], fe[NE];
-      uint32_t row_a = 0, row_e = 0;
+      for (int e = 0; e < NE; ++e) ge_bits |= (raw[e] & E::kKeyMask) >= tau ? (1u << e) : 0u;
+      if (!in) ge_bits = 0;
+      const uint64_t m_any = ballot64(ge_bits != 0);
+      if (m_any == 0) return;
+      uint32_t e_bits = 0;
+      if constexpr (EXACT) {
 #pragma unroll
-      for (int e = 0; e < NE; ++e) {
-        fe[e] = EXACT && ge[e] && (raw[e] & E::kKeyMask) == tau;
-        fa[e] = ge[e] && !fe[e];
-        row_a += __popcll(ballot64(fa[e]));
-        if constexpr (EXACT) row_e += __popcll(ballot64(fe[e]));
+        for (int e = 0; e < NE; ++e) e_bits |= (raw[e] & E::kKeyMask) == tau ? (1u << e) : 0u;
+        e_bits &= ge_bits;
       }
+      const uint32_t a_bits = ge_bits & ~e_bits;
+      uint32_t row_a, row_e;
       {
         if constexpr (!DIRECT) {
-          uint32_t slot = staged;
+          // Index order inside the row is (lane, element), so one wave scan of the per-lane counts
+          // (both packed into one word: a lane holds at most 8 elements) places every lane's pairs.
+          // When no lane holds two survivors (the usual case) a ballot ranks them.
+          uint32_t before;  // pairs of this row in lower lanes
+          if (ballot64((ge_bits & (ge_bits - 1)) != 0) == 0) {
+            row_e = EXACT ? static_cast<uint32_t>(__popcll(ballot64(e_bits != 0))) : 0u;
+            row_a = static_cast<uint32_t>(__popcll(m_any)) - row_e;
+            before = lanes_below(m_any);
+          } else {
+            const uint32_t mine = __popc(a_bits) | (__popc(e_bits) << 16);
+            const uint32_t incl = wave_prefix_sum(mine);
+            const uint32_t excl = incl - mine;
+            const uint32_t total = __builtin_amdgcn_readlane(incl, kWave - 1);
+            row_a = total & 0xFFFFu;
+            row_e = total >> 16;
+            before = (excl & 0xFFFFu) + (excl >> 16);
+          }
+          if (ge_bits != 0) {
+            uint32_t slot = staged + before;
 #pragma unroll
-          for (int e = 0; e < NE; ++e) slot += lanes_below(ballot64(fa[e] || fe[e]));
-#pragma unroll
-          for (int e = 0; e < NE; ++e) {
-            if ((fa[e] || fe[e]) && slot < kCtStageCap) {
-              s_idx[wave][slot] = (index0 + e) | (fe[e] ? kTieFlag : 0u);
-              s_val[wave][slot] = static_cast<word_t>(raw[e]);
+            for (int e = 0; e < NE; ++e) {
+              if ((ge_bits >> e) & 1u) {
+                if (slot < kCtStageCap) {
+                  s_idx[wave][slot] = (index0 + e) | (((e_bits >> e) & 1u) ? kTieFlag : 0u);
+                  s_val[wave][slot] = static_cast<word_t>(raw[e]);
+                }
+                ++slot;
+              }
             }
-            slot += (fa[e] || fe[e]) ? 1u : 0u;
           }
           staged += row_a + row_e;
         } else {
+          bool fa[NE], fe[NE];
+          row_a = 0;
+          row_e = 0;
+#pragma unroll
+          for (int e = 0; e < NE; ++e) {
+            fa[e] = (a_bits >> e) & 1u;
+            fe[e] = (e_bits >> e) & 1u;
+            row_a += __popcll(ballot64(fa[e]));
+            if constexpr (EXACT) row_e += __popcll(ballot64(fe[e]));
+          }
           // ties of this group that survive: those with global tie rank < quota
           uint32_t tie_rank = e_before + ne;
           const bool some_ties = EXACT && row_e != 0 && tie_rank < quota;
