@@ -230,33 +230,42 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
   // NE keys per lane
   auto take = [&](const uint32_t* raw, bool in, auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
-    // one compare per element in the common case: keys >= lo are rare
-    bool ge[NE];
-    uint64_t any = 0;
+    // one compare per element in the common case: keys >= lo are rare (per-lane bitmap)
+    uint32_t ge_bits = 0;
 #pragma unroll
-    for (int e = 0; e < NE; ++e) {
-      ge[e] = in && (raw[e] & E::kKeyMask) >= lo;
-      any |= ballot64(ge[e]);
-    }
-    if (any == 0) return;
-    bool c[NE];
-    uint32_t n_c = 0;
+    for (int e = 0; e < NE; ++e) ge_bits |= (raw[e] & E::kKeyMask) >= lo ? (1u << e) : 0u;
+    if (!in) ge_bits = 0;
+    const uint64_t m_any = ballot64(ge_bits != 0);
+    if (m_any == 0) return;
+    uint32_t hi_bits = 0;
 #pragma unroll
-    for (int e = 0; e < NE; ++e) {
-      const uint32_t key = raw[e] & E::kKeyMask;
-      above += __popcll(ballot64(ge[e] && key > hi));
-      c[e] = ge[e] && key <= hi;
-      n_c += __popcll(ballot64(c[e]));
+    for (int e = 0; e < NE; ++e) hi_bits |= (raw[e] & E::kKeyMask) > hi ? (1u << e) : 0u;
+    hi_bits &= ge_bits;
+    const uint32_t c_bits = ge_bits & ~hi_bits;  // candidates: lo <= key <= hi
+    // counts of the row and the candidates in lower lanes: a ballot when no lane holds two
+    // keys >= lo (the usual case), else one wave scan of the packed per-lane counts
+    uint32_t n_c, before;
+    if (ballot64((ge_bits & (ge_bits - 1)) != 0) == 0) {
+      const uint64_t m_c = ballot64(c_bits != 0);
+      n_c = static_cast<uint32_t>(__popcll(m_c));
+      above += static_cast<uint32_t>(__popcll(m_any)) - n_c;
+      before = lanes_below(m_c);
+    } else {
+      const uint32_t mine = __popc(hi_bits) | (__popc(c_bits) << 16);
+      const uint32_t incl = wave_prefix_sum(mine);
+      const uint32_t total = __builtin_amdgcn_readlane(incl, kWave - 1);
+      above += total & 0xFFFFu;
+      n_c = total >> 16;
+      before = (incl - mine) >> 16;
     }
     if (n_c != 0) {
       if (staged + n_c > kPartStage) flush();  // n_c <= 64 * NE <= 512 <= kPartStage
-      uint32_t slot = staged;
+      if (c_bits != 0) {
+        uint32_t slot = staged + before;
 #pragma unroll
-      for (int e = 0; e < NE; ++e) slot += lanes_below(ballot64(c[e]));
-#pragma unroll
-      for (int e = 0; e < NE; ++e) {
-        if (c[e]) stage[slot] = raw[e] & E::kKeyMask;
-        slot += c[e] ? 1u : 0u;
+        for (int e = 0; e < NE; ++e) {
+          if ((c_bits >> e) & 1u) stage[slot++] = raw[e] & E::kKeyMask;
+        }
       }
       staged += n_c;
     }
