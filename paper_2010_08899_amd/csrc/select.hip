@@ -35,6 +35,7 @@ constexpr int kSelMaxPasses = 3;
 constexpr int kSelUnroll = 4;                   // 16-byte loads in flight per lane in the radix passes
 constexpr uint32_t kSelMaxGrid = 4096;
 constexpr uint32_t kCandGrid = 256;
+constexpr uint32_t kFallbackGrid = 1024;
 
 constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes run over the vector itself
 constexpr int kSampleThreads = 1024;
@@ -140,10 +141,11 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
   __syncthreads();
 
   // sample ranks (1-based from the top) that bracket rank k of the vector with a
-  // margin of five standard deviations of the sample count, plus slack
+  // margin of five standard deviations of the sample count (binomial: r (S - r) / S), plus slack
   const uint64_t r = static_cast<uint64_t>(k) * kSampleSize / n;
+  const uint64_t var = r * (kSampleSize - r) / kSampleSize;
   uint32_t sq = 0;
-  while (static_cast<uint64_t>(sq + 1) * (sq + 1) <= r) ++sq;
+  while (static_cast<uint64_t>(sq + 1) * (sq + 1) <= var) ++sq;
   const uint64_t delta = 5ull * (sq + 1) + 8;
   const uint64_t rank_hi = r > delta ? r - delta : 0;                     // 0: no upper bound
   const uint64_t rank_lo = r + delta + 1 <= kSampleSize ? r + delta + 1 : 0;  // 0: no lower bound
@@ -402,9 +404,9 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     st = ws->state[pass - 1];
   }
   // vectors of the source; a workgroup with nothing to read leaves at once
-  // (the candidate passes use at most kCandGrid workgroups: fewer histogram merges)
+  // (the candidate passes use few workgroups -- fewer histogram merges -- unless there are many candidates)
   const uint32_t src_vecs = st.from_cand ? (st.n_src + 3) / 4 : n_virt / V + 1;
-  const uint32_t n_wg = st.from_cand ? min(gridDim.x, kCandGrid) : gridDim.x;
+  const uint32_t n_wg = st.from_cand ? min(gridDim.x, max(kCandGrid, src_vecs / (span * 8))) : gridDim.x;
   if (blockIdx.x != 0 && (blockIdx.x >= n_wg || blockIdx.x * span >= src_vecs)) return;
   if (pass != 0) st = advance_state(st, ws->hist[pass - 1], s_tmp);
   if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[pass] = st;
@@ -502,7 +504,9 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(SelWs* ws, i
   }
 }
 
-uint32_t cand_capacity(uint64_t n) { return n >= kSampleMinN ? static_cast<uint32_t>(n / 64 + 65536) : 0u; }
+// Room for the keys between the sample bounds: about 10 sqrt(p (1 - p) / 16384) of the vector when a
+// fraction p is kept, i.e. at most 4 % (p = 1/2).
+uint32_t cand_capacity(uint64_t n) { return n >= kSampleMinN ? static_cast<uint32_t>(n / 16 + 65536) : 0u; }
 
 }  // namespace
 }  // namespace dct
@@ -581,9 +585,10 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
   const uint32_t span = kSelThreads * kSelUnroll;
   uint32_t grid = (n_vec_all + span - 1) / span;
   if (grid > kSelMaxGrid) grid = kSelMaxGrid;
-  // After a partition pass the radix passes normally see the candidates only: a small grid
-  // (it still covers the whole vector, more slowly, should the bounds have failed).
-  if (cand_cap != 0 && grid > kCandGrid) grid = kCandGrid;
+  // After a partition pass the radix passes normally see the candidates only and most of these
+  // workgroups leave at once; the grid is sized for the case that the bounds failed and the passes
+  // run over the whole vector.
+  if (cand_cap != 0 && grid > kFallbackGrid) grid = kFallbackGrid;
   const PassDigits dg = pass_digits(dt);
   for (int p = 0; p < dg.n_pass; ++p) {
     if (ef) {

@@ -112,6 +112,17 @@ def test_dp_bf16(dct):
     check_dp(dct, g[1:], 100)  # 2-byte-aligned base
 
 
+@pytest.mark.parametrize("frac", [0.02, 0.05, 0.10, 0.25, 0.50, 0.90, 0.999])
+def test_dp_low_sparsity_levels(dct, frac):
+    """The paper's lower compression levels (a quarter of the vector kept, and beyond): sampled
+    selection with many candidates, compaction with more survivors than fit on chip."""
+    n = 5_000_011
+    g = si.gaussian_gradient(n, DEV, 2200)
+    check_dp(dct, g, int(n * frac), select_method="nth")
+    t3 = si.student_t3_gradient(n, DEV, 2201)
+    check_dp(dct, t3, int(n * frac), modes=(0,), select_method="nth")
+
+
 def test_dp_c1_full(dct):
     g, k = si.config_c1(DEV)
     dp, thr = check_dp(dct, g, k)
