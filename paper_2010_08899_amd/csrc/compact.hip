@@ -20,9 +20,16 @@
 //   4. With its exclusive prefix known, the workgroup copies its staged pairs to
 //      their final slots; in exactly-k mode a tie is written while fewer than
 //      tie_quota ties precede it (ties are staged with a flag bit).
-// If a wavefront's LDS region overflows (dense survivors, or a tie value that
-// covers much of the vector) the workgroup still counts everything, and after the
-// scan streams its chunk a second time, writing straight to the final slots.
+// The survivors of a chunk wait on chip, so the grid as a whole can hold about
+// four million of them.  A vector that keeps more (the paper's lower sparsity
+// levels) is cut into up to a dozen contiguous slices ("rounds") that are processed
+// one after the other by the same workgroups; the (round, workgroup) pairs form one
+// sequence for the prefix exchange.  The number of rounds comes from the counts in
+// the threshold record.  If a wavefront's LDS region overflows all the same (more
+// survivors than the record promised, a tie value that covers much of the vector,
+// or more rounds needed than are worth their cost) the workgroup still counts
+// everything, and after the scan streams its chunk a second time, writing straight
+// to the final slots.
 //
 // Error feedback (Algorithm 1, "W_grad = W_grad + E_grad" before the mask and
 // "E_grad = W_grad - W_hat_grad" after it) rides on the same pass: the EF variant
@@ -51,11 +58,12 @@ constexpr int kCtRows = 8;                              // 16-byte loads per lan
 constexpr uint32_t kCtTileVecs = kCtThreads * kCtRows;  // granule of the chunking: 32 KiB
 constexpr int kCtWgPerCu = 4;
 constexpr uint32_t kCtMaxGrid = 2048;
-constexpr uint32_t kCtGroup = 64;                       // workgroups per descriptor group
-constexpr uint32_t kCtMaxGroups = kCtMaxGrid / kCtGroup;
-static_assert(kCtMaxGroups <= kWave, "the group-level look-back is a single poll");
+constexpr uint32_t kCtGroup = 64;                       // (virtual) workgroups per descriptor group
+constexpr uint32_t kCtMaxRounds = 12;                   // slices a dense vector is cut into (at most)
+constexpr uint32_t kCtMaxVirtual = kCtMaxGrid * kCtMaxRounds;
+constexpr uint32_t kCtMaxGroups = kCtMaxVirtual / kCtGroup;
 constexpr uint32_t kCtStageCap = 1152;                  // staged pairs per wavefront (36 KiB of LDS per workgroup)
-constexpr uint32_t kCtMagic = 0x44435433u;              // "DCT3"
+constexpr uint32_t kCtMagic = 0x44435434u;              // "DCT4"
 constexpr uint32_t kCtHeaderBytes = 256;
 constexpr uint32_t kCtSpinLimit = 1u << 20;
 constexpr uint32_t kTieFlag = 0x80000000u;
@@ -69,13 +77,14 @@ struct CompactHeader {
   uint32_t magic;
   uint32_t epoch;
   uint32_t error;
-  uint32_t pad[61];
+  uint32_t used[2];  // descriptors of each set that the last call using it wrote (they must be cleared)
+  uint32_t pad[59];
 };
 static_assert(sizeof(CompactHeader) == kCtHeaderBytes, "header size");
 
 struct DescSet {
-  uint64_t wg[kCtMaxGrid];
-  uint64_t group[kCtGroup];
+  uint64_t wg[kCtMaxVirtual];
+  uint64_t group[kCtMaxGroups];
 };
 constexpr size_t kCtWsBytes = kCtHeaderBytes + 2 * sizeof(DescSet);
 
@@ -113,25 +122,33 @@ __device__ uint64_t sum_members(const uint64_t* first, uint32_t m, const uint32_
   }
 }
 
-// Sum over all groups before group g (g <= 63): nearest groups first, up to and
+// Sum over all groups before group g: nearest groups first, 64 at a time, up to and
 // including the first one that carries an inclusive prefix.
 __device__ uint64_t group_prefix(const uint64_t* gdesc, uint32_t g, const uint32_t* error_flag, bool& failed) {
-  if (g == 0) return 0;
   const int lane = lane_id();
+  uint64_t sum = 0;
   uint32_t spins = 0;
-  for (;;) {
-    const int i = static_cast<int>(g) - 1 - lane;
-    const uint64_t d = i >= 0 ? ld_agent(gdesc + i) : kStInclusive;
+  int pos = static_cast<int>(g);  // groups [0, pos) are still to be accounted for
+  while (pos > 0) {
+    const int i = pos - 1 - lane;
+    const uint64_t d = i >= 0 ? ld_agent(gdesc + i) : kStInclusive;  // the virtual group -1: inclusive 0
     const uint32_t st = static_cast<uint32_t>(d >> 62);
     const uint64_t invalid = ballot64(st == 0);
-    const int f = __builtin_ctzll(ballot64(st == 2));  // exists: lane g reads the virtual group -1
+    const uint64_t incl = ballot64(st == 2);
+    const int f = incl ? __builtin_ctzll(incl) : 63;  // nearest group with an inclusive prefix, if any
     const uint64_t need = (f == 63) ? ~0ull : ((2ull << f) - 1);
-    if ((invalid & need) == 0) return wave_sum_u64(lane <= f ? (d & kPayload) : 0ull);
-    if (!keep_waiting(spins, error_flag)) {
-      failed = true;
-      return 0;
+    if ((invalid & need) != 0) {
+      if (!keep_waiting(spins, error_flag)) {
+        failed = true;
+        return 0;
+      }
+      continue;
     }
+    sum += wave_sum_u64(lane <= f ? (d & kPayload) : 0ull);
+    if (incl) break;
+    pos -= kWave;
   }
+  return sum;
 }
 
 // Work description shared by all workgroups (computed on the host).
@@ -140,7 +157,7 @@ struct CompactGeom {
   uint32_t n_vec;        // full 16-byte vectors after the head
   uint32_t tail;         // elements after the last full vector (< kVec)
   uint32_t grid;         // workgroups
-  uint32_t vecs_per_wg;  // chunk length in vectors (multiple of kCtTileVecs)
+  uint32_t tiles;        // granules of kCtTileVecs vectors that cover the full vectors (>= 1)
 };
 
 // EF: g is W_grad, e_in the residual E_grad (may be the same buffer as e_out), e_out the new residual.
@@ -163,37 +180,55 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
   const uint32_t wg = blockIdx.x;
   const uint32_t lane = lane_id();
   const int wave = threadIdx.x / kWave;
-  const bool first_wg = wg == 0, last_wg = wg == geo.grid - 1;
 
-  // ---- workspace: this call's descriptor set; the other one is cleared for the next call
+  // ---- workspace: this call's descriptor set; what the previous call wrote into the other set
+  // is cleared for the next call
   const uint32_t magic = hdr->magic;
   const uint32_t epoch = hdr->epoch;
   if (magic != kCtMagic) {  // never initialised (uniform over the grid)
-    if (first_wg && threadIdx.x == 0) *count_out = DCT_COUNT_WORKSPACE_ERROR;
+    if (wg == 0 && threadIdx.x == 0) *count_out = DCT_COUNT_WORKSPACE_ERROR;
     return;
   }
   DescSet* sets = reinterpret_cast<DescSet*>(reinterpret_cast<char*>(hdr) + kCtHeaderBytes);
   DescSet* mine_set = sets + (epoch & 1u);
   {
-    uint64_t* other = reinterpret_cast<uint64_t*>(sets + ((epoch & 1u) ^ 1u));
-    constexpr uint32_t kWords = sizeof(DescSet) / 8;
-    for (uint32_t i = wg * kCtThreads + threadIdx.x; i < kWords; i += geo.grid * kCtThreads) st_agent(other + i, 0ull);
+    DescSet* other = sets + ((epoch & 1u) ^ 1u);
+    const uint32_t used = min(hdr->used[(epoch & 1u) ^ 1u], kCtMaxVirtual);
+    for (uint32_t i = wg * kCtThreads + threadIdx.x; i < used; i += geo.grid * kCtThreads) st_agent(&other->wg[i], 0ull);
+    const uint32_t used_groups = (used + kCtGroup - 1) / kCtGroup;
+    for (uint32_t i = wg * kCtThreads + threadIdx.x; i < used_groups; i += geo.grid * kCtThreads)
+      st_agent(&other->group[i], 0ull);
   }
 
   const uint32_t tau = thr->tau_key;
   const uint32_t quota = thr->tie_quota;
 
-  // ---- this wavefront's share: rows of 64 vectors [row_lo, row_hi) of the chunk [wg_lo, wg_hi)
-  const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
-  const uint32_t wg_lo = wg * geo.vecs_per_wg;
-  const uint32_t wg_hi = min(wg_lo + geo.vecs_per_wg, geo.n_vec);
-  const uint32_t rows_total = (wg_hi - wg_lo + kWave - 1) / kWave;
-  const uint32_t rows_per_wave = ((rows_total + kCtWaves - 1) / kCtWaves + kCtRows - 1) / kCtRows * kCtRows;
-  const uint32_t row_lo = min(static_cast<uint32_t>(wave) * rows_per_wave, rows_total);
-  const uint32_t row_hi = min(row_lo + rows_per_wave, rows_total);
+  // ---- rounds.  All survivors of a workgroup's chunk wait in LDS until the chunk's place in the
+  // output is known, so a chunk may hold only about 4600 of them.  A vector with more survivors
+  // than the whole grid can hold at once is cut into `rounds` contiguous slices that are processed
+  // one after the other; the (round, workgroup) pairs form one long sequence of virtual workgroups
+  // for the prefix exchange.  The number of rounds is derived from the counts in the threshold
+  // record (the same in every workgroup); if it turns out too low, the second-pass fallback of the
+  // chunks that overflow keeps the result exact.
+  uint32_t rounds;
+  {
+    const uint64_t expected = static_cast<uint64_t>(thr->n_gt) + thr->n_eq;  // ties are staged too
+    const uint64_t room = static_cast<uint64_t>(geo.grid) * kCtWaves * kCtStageCap * 7 / 8;
+    const uint64_t want = (expected + room - 1) / room;
+    // Every round costs a pipeline drain and refill (about 15 us on MI355X); beyond a dozen rounds
+    // reading the vector twice (the second-pass fallback) is cheaper.
+    rounds = want < 1 ? 1u : (want > kCtMaxRounds ? 1u : static_cast<uint32_t>(want));
+    rounds = min(rounds, geo.tiles);
+  }
+  const uint32_t n_virtual = rounds * geo.grid;
+  const uint32_t tiles_per_round = (geo.tiles + rounds - 1) / rounds;
+  const uint32_t vecs_per_wg = (tiles_per_round + geo.grid - 1) / geo.grid * kCtTileVecs;
 
-  const bool do_head = first_wg && wave == 0 && geo.head != 0;
-  const bool do_tail = last_wg && wave == kCtWaves - 1 && geo.tail != 0;
+  // ---- this wavefront's share of the current round: rows of 64 vectors [row_lo, row_hi) of the
+  // workgroup's chunk [wg_lo, wg_hi)
+  const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
+  uint32_t wg_lo = 0, wg_hi = 0, row_lo = 0, row_hi = 0;
+  bool do_head = false, do_tail = false;
   const uint32_t tail_base = geo.head + geo.n_vec * V;
 
   // One pass over the wavefront's share.  DIRECT = false: stage survivors (ties
@@ -259,39 +294,31 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
           }
           staged += row_a + row_e;
         } else {
-          bool fa[NE], fe[NE];
-          row_a = 0;
-          row_e = 0;
+          // the exclusive counts are known: one wave scan of the per-lane counts places the row
+          const uint32_t mine = __popc(a_bits) | (__popc(e_bits) << 16);
+          const uint32_t incl = wave_prefix_sum(mine);
+          const uint32_t excl = incl - mine;
+          const uint32_t total = __builtin_amdgcn_readlane(incl, kWave - 1);
+          row_a = total & 0xFFFFu;
+          row_e = total >> 16;
+          if (ge_bits != 0) {
+            uint32_t a_run = a_before + na + (excl & 0xFFFFu);  // keys above the cut before this lane's
+            uint32_t t_run = e_before + ne + (excl >> 16);      // ties before them (both in the whole vector)
 #pragma unroll
-          for (int e = 0; e < NE; ++e) {
-            fa[e] = (a_bits >> e) & 1u;
-            fe[e] = (e_bits >> e) & 1u;
-            row_a += __popcll(ballot64(fa[e]));
-            if constexpr (EXACT) row_e += __popcll(ballot64(fe[e]));
-          }
-          // ties of this group that survive: those with global tie rank < quota
-          uint32_t tie_rank = e_before + ne;
-          const bool some_ties = EXACT && row_e != 0 && tie_rank < quota;
-          if (some_ties) {
-#pragma unroll
-            for (int e = 0; e < NE; ++e) tie_rank += lanes_below(ballot64(fe[e]));
-          }
-          uint32_t slot = a_before + na + (EXACT ? min(e_before + ne, quota) : 0u);
-          bool keep[NE];
-#pragma unroll
-          for (int e = 0; e < NE; ++e) {
-            keep[e] = fa[e] || (some_ties && fe[e] && tie_rank < quota);
-            tie_rank += fe[e] ? 1u : 0u;
-            slot += lanes_below(ballot64(keep[e]));
-          }
-#pragma unroll
-          for (int e = 0; e < NE; ++e) {
-            if (keep[e] && slot < capacity) {
-              idx_out[slot] = static_cast<int32_t>(index0 + e);
-              val_out[slot] = static_cast<word_t>(raw[e]);
-              if constexpr (EF) e_out[index0 + e] = 0;  // delivered: nothing is left behind
+            for (int e = 0; e < NE; ++e) {
+              if ((ge_bits >> e) & 1u) {
+                const bool tie = (e_bits >> e) & 1u;
+                // a tie survives while fewer than `quota` ties precede it; kept ties before: min(t_run, quota)
+                const uint32_t slot = a_run + (EXACT ? min(t_run, quota) : 0u);
+                if ((!tie || t_run < quota) && slot < capacity) {
+                  idx_out[slot] = static_cast<int32_t>(index0 + e);
+                  val_out[slot] = static_cast<word_t>(raw[e]);
+                  if constexpr (EF) e_out[index0 + e] = 0;  // delivered: nothing is left behind
+                }
+                a_run += tie ? 0u : 1u;
+                t_run += tie ? 1u : 0u;
+              }
             }
-            slot += keep[e] ? 1u : 0u;
           }
         }
       }
@@ -388,99 +415,117 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     return staged;
   };
 
-  // ---- 1+2: stream the chunk, stage survivors in LDS
-  const uint32_t staged = pass(std::false_type{}, 0u, 0u);
-  // the residual stores of this pass have landed before anything (the +0 of a delivered pair, the
-  // second pass's loads) touches the same addresses again
-  if constexpr (EF) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  if (lane == 0) {
-    s_wave_a[wave] = wa;
-    s_wave_e[wave] = we | (staged > kCtStageCap ? kTieFlag : 0u);  // top bit: this wavefront's region overflowed
-  }
-  __syncthreads();
-
-  // ---- 3: wavefront 0 publishes the counts and obtains the exclusive prefix
-  if (wave == 0) {
-    uint32_t ta = 0, te = 0;
-#pragma unroll
-    for (int w = 0; w < kCtWaves; ++w) {
-      ta += s_wave_a[w];
-      te += s_wave_e[w] & ~kTieFlag;
+  for (uint32_t round = 0; round < rounds; ++round) {
+    const uint32_t vwg = round * geo.grid + wg;  // this workgroup's place in the sequence of chunks
+    {
+      const uint32_t slice_lo = min(round * tiles_per_round * kCtTileVecs, geo.n_vec);
+      const uint32_t slice_hi = min(slice_lo + tiles_per_round * kCtTileVecs, geo.n_vec);
+      wg_lo = min(slice_lo + wg * vecs_per_wg, slice_hi);
+      wg_hi = min(wg_lo + vecs_per_wg, slice_hi);
+      const uint32_t rows_total = (wg_hi - wg_lo + kWave - 1) / kWave;
+      const uint32_t rows_per_wave = ((rows_total + kCtWaves - 1) / kCtWaves + kCtRows - 1) / kCtRows * kCtRows;
+      row_lo = min(static_cast<uint32_t>(wave) * rows_per_wave, rows_total);
+      row_hi = min(row_lo + rows_per_wave, rows_total);
+      do_head = vwg == 0 && wave == 0 && geo.head != 0;
+      do_tail = vwg == n_virtual - 1 && wave == kCtWaves - 1 && geo.tail != 0;
     }
-    const uint64_t mine = pack(ta, te);
-    const uint32_t grp = wg / kCtGroup, member = wg % kCtGroup;
-    const bool leader = member == kCtGroup - 1;
-    bool failed = false;
-    if (lane == 0) st_agent(&mine_set->wg[wg], kStAggregate | mine);
-    const uint64_t before_in_group = sum_members(&mine_set->wg[grp * kCtGroup], member, &hdr->error, failed);
-    if (leader && grp != 0 && lane == 0)
-      st_agent(&mine_set->group[grp], kStAggregate | ((before_in_group + mine) & kPayload));
-    const uint64_t before_groups = group_prefix(mine_set->group, grp, &hdr->error, failed);
-    const uint64_t excl = (before_groups + before_in_group) & kPayload;
+    __syncthreads();  // the previous round's pairs have left the staging area
+
+    // ---- 1+2: stream the chunk, stage survivors in LDS
+    const uint32_t staged = pass(std::false_type{}, 0u, 0u);
+    // the residual stores of this pass have landed before anything (the +0 of a delivered pair, the
+    // second pass's loads) touches the same addresses again
+    if constexpr (EF) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (lane == 0) {
-      if (failed) {  // a predecessor never published: report it (the result of this call is void)
-        atomicOr(&hdr->error, 1u);
-        *count_out = DCT_COUNT_WORKSPACE_ERROR;
-        st_agent(&hdr->magic, 0u);
+      s_wave_a[wave] = wa;
+      s_wave_e[wave] = we | (staged > kCtStageCap ? kTieFlag : 0u);  // top bit: this wavefront's region overflowed
+    }
+    __syncthreads();
+
+    // ---- 3: wavefront 0 publishes the counts and obtains the exclusive prefix
+    if (wave == 0) {
+      uint32_t ta = 0, te = 0;
+#pragma unroll
+      for (int w = 0; w < kCtWaves; ++w) {
+        ta += s_wave_a[w];
+        te += s_wave_e[w] & ~kTieFlag;
       }
-      if (leader) st_agent(&mine_set->group[grp], kStInclusive | ((excl + mine) & kPayload));
-      s_excl = excl;
-      if (last_wg) {  // every other workgroup has read the epoch and published: finish the call
-        const uint64_t total = (excl + mine) & kPayload;
-        uint64_t c = cnt_a(total);
-        if (EXACT) c += min(cnt_e(total), quota);
-        const uint32_t err = __builtin_amdgcn_readfirstlane(ld_agent(&hdr->error));
-        if (failed || err != 0) {
+      const uint64_t mine = pack(ta, te);
+      const uint32_t grp = vwg / kCtGroup, member = vwg % kCtGroup;
+      const bool leader = member == kCtGroup - 1;
+      bool failed = false;
+      if (lane == 0) st_agent(&mine_set->wg[vwg], kStAggregate | mine);
+      const uint64_t before_in_group = sum_members(&mine_set->wg[grp * kCtGroup], member, &hdr->error, failed);
+      if (leader && grp != 0 && lane == 0)
+        st_agent(&mine_set->group[grp], kStAggregate | ((before_in_group + mine) & kPayload));
+      const uint64_t before_groups = group_prefix(mine_set->group, grp, &hdr->error, failed);
+      const uint64_t excl = (before_groups + before_in_group) & kPayload;
+      if (lane == 0) {
+        if (failed) {  // a predecessor never published: report it (the result of this call is void)
+          atomicOr(&hdr->error, 1u);
           *count_out = DCT_COUNT_WORKSPACE_ERROR;
-          st_agent(&hdr->magic, 0u);  // force a re-initialisation
-        } else {
-          *count_out = c;
-          st_agent(&hdr->epoch, epoch + 1u);
+          st_agent(&hdr->magic, 0u);
+        }
+        if (leader) st_agent(&mine_set->group[grp], kStInclusive | ((excl + mine) & kPayload));
+        s_excl = excl;
+        if (vwg == n_virtual - 1) {  // every other workgroup has read the epoch and published: finish the call
+          const uint64_t total = (excl + mine) & kPayload;
+          uint64_t c = cnt_a(total);
+          if (EXACT) c += min(cnt_e(total), quota);
+          const uint32_t err = __builtin_amdgcn_readfirstlane(ld_agent(&hdr->error));
+          if (failed || err != 0) {
+            *count_out = DCT_COUNT_WORKSPACE_ERROR;
+            st_agent(&hdr->magic, 0u);  // force a re-initialisation
+          } else {
+            *count_out = c;
+            st_agent(&hdr->used[epoch & 1u], n_virtual);
+            st_agent(&hdr->epoch, epoch + 1u);
+          }
         }
       }
     }
-  }
-  __syncthreads();
+    __syncthreads();
 
-  // ---- 4: final slots
-  const uint64_t excl = s_excl;
-  uint32_t a_before = cnt_a(excl), e_before = cnt_e(excl);
-  bool overflow = false;
-  for (int w = 0; w < kCtWaves; ++w) {
-    const uint32_t ew = s_wave_e[w];
-    overflow = overflow || (ew & kTieFlag) != 0;
-    if (w < wave) {
-      a_before += s_wave_a[w];
-      e_before += ew & ~kTieFlag;
+    // ---- 4: final slots
+    const uint64_t excl = s_excl;
+    uint32_t a_before = cnt_a(excl), e_before = cnt_e(excl);
+    bool overflow = false;
+    for (int w = 0; w < kCtWaves; ++w) {
+      const uint32_t ew = s_wave_e[w];
+      overflow = overflow || (ew & kTieFlag) != 0;
+      if (w < wave) {
+        a_before += s_wave_a[w];
+        e_before += ew & ~kTieFlag;
+      }
     }
-  }
-  if (overflow) {  // uniform over the workgroup: second pass over the chunk, straight to the outputs
-    // With error feedback the second pass reads back what the first one stored (the barriers
-    // above have waited for those stores): drop this CU's cached copies of the old lines first.
-    if constexpr (EF) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    pass(std::true_type{}, a_before, e_before);
-    return;
-  }
-  const uint32_t n_staged = wa + we;
-  const uint32_t ties_left = EXACT ? (quota > e_before ? quota - e_before : 0u) : 0u;
-  uint32_t out = a_before + (EXACT ? min(e_before, quota) : 0u);
-  uint32_t ties_seen = 0;
-  for (uint32_t j0 = 0; j0 < n_staged; j0 += kWave) {
-    const uint32_t j = j0 + lane;
-    const bool valid = j < n_staged;
-    const uint32_t ent = valid ? s_idx[wave][j] : 0u;
-    const bool is_tie = EXACT && (ent & kTieFlag) != 0;
-    const uint64_t m_tie = ballot64(is_tie);
-    const bool keep = valid && (!is_tie || ties_seen + lanes_below(m_tie) < ties_left);
-    const uint64_t m_keep = ballot64(keep);
-    const uint32_t slot = out + lanes_below(m_keep);
-    if (keep && slot < capacity) {
-      idx_out[slot] = static_cast<int32_t>(ent & ~kTieFlag);
-      val_out[slot] = s_val[wave][j];
-      if constexpr (EF) e_out[ent & ~kTieFlag] = 0;  // delivered: nothing is left behind
+    if (overflow) {  // uniform over the workgroup: second pass over the chunk, straight to the outputs
+      // With error feedback the second pass reads back what the first one stored (the barriers
+      // above have waited for those stores): drop this CU's cached copies of the old lines first.
+      if constexpr (EF) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      pass(std::true_type{}, a_before, e_before);
+      continue;
     }
-    out += __popcll(m_keep);
-    ties_seen += __popcll(m_tie);
+    const uint32_t n_staged = wa + we;
+    const uint32_t ties_left = EXACT ? (quota > e_before ? quota - e_before : 0u) : 0u;
+    uint32_t out = a_before + (EXACT ? min(e_before, quota) : 0u);
+    uint32_t ties_seen = 0;
+    for (uint32_t j0 = 0; j0 < n_staged; j0 += kWave) {
+      const uint32_t j = j0 + lane;
+      const bool valid = j < n_staged;
+      const uint32_t ent = valid ? s_idx[wave][j] : 0u;
+      const bool is_tie = EXACT && (ent & kTieFlag) != 0;
+      const uint64_t m_tie = ballot64(is_tie);
+      const bool keep = valid && (!is_tie || ties_seen + lanes_below(m_tie) < ties_left);
+      const uint64_t m_keep = ballot64(keep);
+      const uint32_t slot = out + lanes_below(m_keep);
+      if (keep && slot < capacity) {
+        idx_out[slot] = static_cast<int32_t>(ent & ~kTieFlag);
+        val_out[slot] = s_val[wave][j];
+        if constexpr (EF) e_out[ent & ~kTieFlag] = 0;  // delivered: nothing is left behind
+      }
+      out += __popcll(m_keep);
+      ties_seen += __popcll(m_tie);
+    }
   }
 }
 
@@ -500,7 +545,7 @@ CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt) {
   if (max_grid > kCtMaxGrid) max_grid = kCtMaxGrid;
   const uint32_t tiles_per_wg = (tiles + max_grid - 1) / max_grid;
   geo.grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;
-  geo.vecs_per_wg = tiles_per_wg * kCtTileVecs;
+  geo.tiles = tiles;
   return geo;
 }
 
