@@ -183,8 +183,13 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
 
   // ---- workspace: this call's descriptor set; what the previous call wrote into the other set
   // is cleared for the next call
+  // (everything the prologue needs from memory is requested before the first wait)
   const uint32_t magic = hdr->magic;
   const uint32_t epoch = hdr->epoch;
+  const uint32_t used0 = hdr->used[0], used1 = hdr->used[1];
+  const uint32_t tau = thr->tau_key;
+  const uint32_t quota = thr->tie_quota;
+  const uint32_t thr_gt = thr->n_gt, thr_eq = thr->n_eq;
   if (magic != kCtMagic) {  // never initialised (uniform over the grid)
     if (wg == 0 && threadIdx.x == 0) *count_out = DCT_COUNT_WORKSPACE_ERROR;
     return;
@@ -193,15 +198,12 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
   DescSet* mine_set = sets + (epoch & 1u);
   {
     DescSet* other = sets + ((epoch & 1u) ^ 1u);
-    const uint32_t used = min(hdr->used[(epoch & 1u) ^ 1u], kCtMaxVirtual);
+    const uint32_t used = min((epoch & 1u) ? used0 : used1, kCtMaxVirtual);
     for (uint32_t i = wg * kCtThreads + threadIdx.x; i < used; i += geo.grid * kCtThreads) st_agent(&other->wg[i], 0ull);
     const uint32_t used_groups = (used + kCtGroup - 1) / kCtGroup;
     for (uint32_t i = wg * kCtThreads + threadIdx.x; i < used_groups; i += geo.grid * kCtThreads)
       st_agent(&other->group[i], 0ull);
   }
-
-  const uint32_t tau = thr->tau_key;
-  const uint32_t quota = thr->tie_quota;
 
   // ---- rounds.  All survivors of a workgroup's chunk wait in LDS until the chunk's place in the
   // output is known, so a chunk may hold only about 4600 of them.  A vector with more survivors
@@ -212,12 +214,15 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
   // chunks that overflow keeps the result exact.
   uint32_t rounds;
   {
-    const uint64_t expected = static_cast<uint64_t>(thr->n_gt) + thr->n_eq;  // ties are staged too
-    const uint64_t room = static_cast<uint64_t>(geo.grid) * kCtWaves * kCtStageCap * 7 / 8;
-    const uint64_t want = (expected + room - 1) / room;
+    // ties are staged too; the record is the same for every lane: keep the arithmetic scalar
+    const uint64_t expected = static_cast<uint64_t>(__builtin_amdgcn_readfirstlane(thr_gt)) +
+                              __builtin_amdgcn_readfirstlane(thr_eq);
+    const uint64_t room = static_cast<uint64_t>(geo.grid) * (kCtWaves * kCtStageCap * 7 / 8);
     // Every round costs a pipeline drain and refill (about 15 us on MI355X); beyond a dozen rounds
     // reading the vector twice (the second-pass fallback) is cheaper.
-    rounds = want < 1 ? 1u : (want > kCtMaxRounds ? 1u : static_cast<uint32_t>(want));
+    rounds = 1;
+    while (rounds <= kCtMaxRounds && expected > room * rounds) ++rounds;  // ceil(expected / room), no division
+    if (rounds > kCtMaxRounds) rounds = 1;
     rounds = min(rounds, geo.tiles);
   }
   const uint32_t n_virtual = rounds * geo.grid;
@@ -429,7 +434,9 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
       do_head = vwg == 0 && wave == 0 && geo.head != 0;
       do_tail = vwg == n_virtual - 1 && wave == kCtWaves - 1 && geo.tail != 0;
     }
-    __syncthreads();  // the previous round's pairs have left the staging area
+    // the previous round's pairs have left the staging area (not in round 0: the barrier would also
+    // wait for the descriptor-clearing stores above, a memory round trip before streaming starts)
+    if (round != 0) __syncthreads();
 
     // ---- 1+2: stream the chunk, stage survivors in LDS
     const uint32_t staged = pass(std::false_type{}, 0u, 0u);
