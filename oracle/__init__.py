@@ -57,6 +57,11 @@ def _load():
         lib.oracle_rowscatter_bitmask.argtypes = [vp, vp, i32, u32, u32, u32, vp, u64]
         for f in (lib.oracle_rowtopk_fwd_bitmask, lib.oracle_rowtopk_bwd_bitmask, lib.oracle_rowscatter_bitmask):
             f.restype = ctypes.c_int
+        lib.oracle_rowtopk_fwd_idx16.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp, vp]
+        lib.oracle_rowtopk_bwd_idx16.argtypes = [vp, i32, u32, u32, u64, u32, vp, vp]
+        lib.oracle_rowscatter_idx16.argtypes = [vp, vp, i32, u32, u32, u32, vp, u64]
+        for f in (lib.oracle_rowtopk_fwd_idx16, lib.oracle_rowtopk_bwd_idx16, lib.oracle_rowscatter_idx16):
+            f.restype = ctypes.c_int
         for f in (lib.oracle_ef_accumulate, lib.oracle_ef_select_threshold, lib.oracle_ef_threshold_compact):
             f.restype = ctypes.c_int
         for f in (lib.oracle_select_threshold, lib.oracle_select_threshold_nth, lib.oracle_threshold_compact,
@@ -269,4 +274,42 @@ def rowscatter_bitmask(mask: np.ndarray, val: np.ndarray, D: int):
     rc = _load().oracle_rowscatter_bitmask(_ptr(mask), _ptr(val), _dtype_code(val), B, D, k, _ptr(out), D)
     if rc != 0:
         raise ValueError("oracle_rowscatter_bitmask: invalid arguments")
+    return out
+
+
+# ---- Algorithm 2 with the mask as 16-bit column indices -------------------------
+def rowtopk_fwd_idx16(x: np.ndarray, k: int):
+    """Returns (idx uint16[B,k], val[B,k], tau[B]); rows of at most 65536 columns."""
+    B, D = x.shape
+    idx = np.zeros((B, k), dtype=np.uint16)
+    val = np.zeros((B, k), dtype=x.dtype)
+    tau = np.zeros(B, dtype=x.dtype)
+    rc = _load().oracle_rowtopk_fwd_idx16(_ptr(x), _dtype_code(x), B, D, _row_stride(x), int(k),
+                                          _ptr(idx), _ptr(val), _ptr(tau))
+    if rc != 0:
+        raise ValueError(f"oracle_rowtopk_fwd_idx16: error {rc}")
+    return idx, val, tau
+
+
+def rowtopk_bwd_idx16(dy: np.ndarray, idx: np.ndarray):
+    B, D = dy.shape
+    idx = np.ascontiguousarray(idx)
+    assert idx.dtype == np.uint16 and idx.shape[0] == B
+    k = idx.shape[1]
+    dval = np.zeros((B, k), dtype=dy.dtype)
+    rc = _load().oracle_rowtopk_bwd_idx16(_ptr(dy), _dtype_code(dy), B, D, _row_stride(dy), k, _ptr(idx), _ptr(dval))
+    if rc != 0:
+        raise ValueError(f"oracle_rowtopk_bwd_idx16: error {rc}")
+    return dval
+
+
+def rowscatter_idx16(idx: np.ndarray, val: np.ndarray, D: int):
+    idx = np.ascontiguousarray(idx)
+    val = np.ascontiguousarray(val)
+    assert idx.dtype == np.uint16 and val.shape == idx.shape
+    B, k = idx.shape
+    out = np.full((B, D), 7, dtype=val.dtype)
+    rc = _load().oracle_rowscatter_idx16(_ptr(idx), _ptr(val), _dtype_code(val), B, D, k, _ptr(out), D)
+    if rc != 0:
+        raise ValueError("oracle_rowscatter_idx16: invalid arguments")
     return out

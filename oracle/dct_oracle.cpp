@@ -414,4 +414,58 @@ int oracle_rowscatter_bitmask(const uint32_t* mask, const void* val, int dtype, 
     return 0;
 }
 
+// ---- Algorithm 2 with the mask sent as 16-bit column indices -------------------
+// The kept set, its order and the values are those of oracle_rowtopk_fwd; a column
+// index is stored in 16 bits, which every column of a row of D <= 65536 fits.
+int oracle_rowtopk_fwd_idx16(const void* x, int dtype, uint32_t B, uint32_t D, uint64_t row_stride, uint32_t k,
+                             uint16_t* idx_out, void* val_out, void* tau_out) {
+    if (!idx_out || D > 65536u) return 1;
+    std::vector<int32_t> idx(static_cast<size_t>(B) * k);
+    const int rc = oracle_rowtopk_fwd(x, dtype, B, D, row_stride, k, idx.data(), val_out, tau_out);
+    if (rc != 0) return rc;
+    for (size_t o = 0; o < idx.size(); ++o) {
+        if (idx[o] < 0 || idx[o] > 65535) return 3;
+        idx_out[o] = static_cast<uint16_t>(idx[o]);
+    }
+    return 0;
+}
+
+// Backward through 16-bit indices: dval[b, j] = dy[b, idx[b, j]].
+int oracle_rowtopk_bwd_idx16(const void* dy, int dtype, uint32_t B, uint32_t D, uint64_t row_stride, uint32_t k,
+                             const uint16_t* idx, void* dval_out) {
+    if (!dy || !idx || !dval_out || B == 0 || D == 0 || D > 65536u || k == 0 || k > D || row_stride < D) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    const size_t es = elem_size(dtype);
+    for (uint32_t b = 0; b < B; ++b) {
+        const unsigned char* row = static_cast<const unsigned char*>(dy) + es * row_stride * b;
+        for (uint32_t j = 0; j < k; ++j) {
+            const uint64_t o = static_cast<uint64_t>(b) * k + j;
+            const uint32_t c = idx[o];
+            if (c >= D) return 2;
+            std::memcpy(static_cast<unsigned char*>(dval_out) + es * o, row + es * c, es);
+        }
+    }
+    return 0;
+}
+
+// Receiver side for 16-bit indices: dense row = zeros with val[b, j] at column idx[b, j];
+// a column >= D is skipped.
+int oracle_rowscatter_idx16(const uint16_t* idx, const void* val, int dtype, uint32_t B, uint32_t D, uint32_t k,
+                            void* out, uint64_t out_stride) {
+    if (!idx || !val || !out || B == 0 || D == 0 || D > 65536u || k == 0 || out_stride < D) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    const size_t es = elem_size(dtype);
+    for (uint32_t b = 0; b < B; ++b) {
+        unsigned char* row = static_cast<unsigned char*>(out) + es * out_stride * b;
+        std::memset(row, 0, es * D);
+        for (uint32_t j = 0; j < k; ++j) {
+            const uint64_t o = static_cast<uint64_t>(b) * k + j;
+            const uint32_t c = idx[o];
+            if (c >= D) continue;
+            std::memcpy(row + es * c, static_cast<const unsigned char*>(val) + es * o, es);
+        }
+    }
+    return 0;
+}
+
 }  // extern "C"

@@ -708,3 +708,54 @@ def test_bitmask_against_numpy_packbits_and_index_form(bf16):
     m = np.array([[0b1010]], dtype=np.uint32)
     d = oracle.rowtopk_bwd_bitmask(f32("1 2 3 4 5".split()).reshape(1, 5), m, 3)
     assert d.tolist() == [[2.0, 4.0, 0.0]]
+
+
+# ------------------------------------------------------------------ Algorithm 2 with 16-bit column indices
+def test_idx16_hand_worked_and_limits():
+    """The fixture's kept columns, stored in 16 bits; the widest row whose last column still fits."""
+    gd = read_golden("alg2_worked.txt")
+    k = int(gd["k"][0])
+    x = np.stack([f32(gd[f"x{b}"]) for b in range(3)])
+    idx, val, tau = oracle.rowtopk_fwd_idx16(x, k)
+    assert idx.dtype == np.uint16
+    for b in range(3):
+        assert idx[b].tolist() == [int(c) for c in gd[f"idx{b}"]], b
+        assert np.array_equal(bits(val[b]), bits(f32(gd[f"val{b}"])))
+    # D = 65536: column 65535 is the largest magnitude and must come back as 0xFFFF
+    x = np.zeros((1, 65536), dtype=np.float32)
+    x[0, 65535] = -9.0
+    x[0, 32768] = 5.0
+    x[0, 7] = 1.0
+    idx, val, tau = oracle.rowtopk_fwd_idx16(x, 3)
+    assert idx[0].tolist() == [7, 32768, 65535] and val[0].tolist() == [1.0, 5.0, -9.0] and tau[0] == 1.0
+    with pytest.raises(ValueError):
+        oracle.rowtopk_fwd_idx16(np.zeros((1, 65537), dtype=np.float32), 3)
+    with pytest.raises(ValueError):   # an index past the row's end is an error of the backward pass
+        oracle.rowtopk_bwd_idx16(np.zeros((1, 8), dtype=np.float32), np.array([[8]], dtype=np.uint16))
+    # decompression skips such an index
+    out = oracle.rowscatter_idx16(np.array([[1, 9]], dtype=np.uint16), f32(["2", "3"]).reshape(1, 2), 8)
+    assert out.tolist() == [[0, 2.0, 0, 0, 0, 0, 0, 0]]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_idx16_against_numpy_stable_sort_gather_and_put(bf16):
+    rng = np.random.default_rng(23)
+    for B, D, k in [(5, 33, 7), (4, 64, 64), (6, 1000, 50), (2, 40000, 123)]:
+        x = np.maximum(rng.standard_normal((B, D)), 0).astype(np.float32)
+        dy = rng.standard_normal((B, D)).astype(np.float32)
+        if bf16:
+            x = to_bf16_bits(x.reshape(-1)).reshape(B, D)
+            dy = to_bf16_bits(dy.reshape(-1)).reshape(B, D)
+            keys = (x & 0x7FFF).astype(np.int64)
+        else:
+            keys = (x.view(np.uint32) & 0x7FFFFFFF).astype(np.int64)
+        # library routines: a stable sort by descending key keeps the lower column first among equals
+        order = np.argsort(-keys, axis=1, kind="stable")[:, :k]
+        want_idx = np.sort(order, axis=1)
+        idx, val, tau = oracle.rowtopk_fwd_idx16(x, k)
+        assert np.array_equal(idx.astype(np.int64), want_idx)
+        assert np.array_equal(val, np.take_along_axis(x, want_idx, axis=1))
+        assert np.array_equal(oracle.rowtopk_bwd_idx16(dy, idx), np.take_along_axis(dy, want_idx, axis=1))
+        dense = np.zeros((B, D), dtype=val.dtype)
+        np.put_along_axis(dense, want_idx, val, axis=1)
+        assert np.array_equal(oracle.rowscatter_idx16(idx, val, D), dense)
