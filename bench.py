@@ -40,18 +40,21 @@ CALL_KERNELS = {
                                  ("dct::select_partition_kernel<0, false> [c4]", 1),
                                  ("dct::select_pass_kernel<0, false>", 3), ("dct::select_finish_kernel", 1)],
     "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false>", 1)],
-    "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, false, false>", 1)],
-    "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_gather_kernel<unsigned short>", 1)],
+    "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 0, false>", 1)],
+    "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_gather_kernel<unsigned short, int>", 1)],
     "dct_ef_select_threshold[c4]": [("dct::select_gather_kernel<0, true>", 1), ("dct::select_bounds_kernel<0>", 1),
                                     ("dct::select_partition_kernel<0, true>", 1),
                                     ("dct::select_pass_kernel<0, true>", 3), ("dct::select_finish_kernel", 1)],
     "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true>", 1)],
     "dct_scatter[c4,assign]": [("dct::scatter_assign_kernel<unsigned int>", 1)],
     "dct_scatter[c4,add]": [("dct::scatter_pairs_kernel<unsigned int, true>", 1)],
-    "dct_rowtopk_scatter[c5]": [("dct::rowscatter_lds_kernel<unsigned short>", 1)],
-    "dct_rowtopk_fwd_bitmask[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, true, false>", 1)],
+    "dct_rowtopk_scatter[c5]": [("dct::rowscatter_lds_kernel<unsigned short, int>", 1)],
+    "dct_rowtopk_fwd_bitmask[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 1, false>", 1)],
     "dct_rowtopk_bwd_bitmask[c5]": [("dct::rowtopk_bitmask_lanes_kernel<unsigned short, true>", 1)],
     "dct_rowtopk_scatter_bitmask[c5]": [("dct::rowtopk_bitmask_lanes_kernel<unsigned short, false>", 1)],
+    "dct_rowtopk_fwd_idx16[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 2, false>", 1)],
+    "dct_rowtopk_bwd_idx16[c5]": [("dct::rowtopk_bwd_gather_kernel<unsigned short, unsigned short>", 1)],
+    "dct_rowtopk_scatter_idx16[c5]": [("dct::rowscatter_lds_kernel<unsigned short, unsigned short>", 1)],
 }
 
 
@@ -255,7 +258,19 @@ def main():
                           extra={"note": "algorithmic_bytes counts the 128-byte lines the gather touches"}))
     us = time_calls(lambda i: dct.dct_rowtopk_scatter_bitmask(mask5, val5, d5[i & 1]), args.reps)
     bm_calls.append(entry("dct_rowtopk_scatter_bitmask[c5]", us, B5 * D5 * 2 + B5 * (D5 // 8 + k5 * 2), B5 * D5))
-    del d5, mask5
+    del mask5
+
+    # ------------------------------------------------------------ the mask as 16-bit indices (not part of the step)
+    i16_calls = []
+    idx16 = torch.zeros(B5, k5, dtype=torch.int16, device=dev)
+    us = time_calls(lambda i: dct.dct_rowtopk_fwd_idx16(x5[i & 1], k5, idx16, val5, None), args.reps)
+    i16_calls.append(entry("dct_rowtopk_fwd_idx16[c5]", us, B5 * D5 * 2 + B5 * k5 * 4, B5 * D5))
+    us = time_calls(lambda i: dct.dct_rowtopk_bwd_idx16(dy5[i & 1], idx16, dval5), args.reps)
+    i16_calls.append(entry("dct_rowtopk_bwd_idx16[c5]", us, int(B5 * lines128) + B5 * k5 * 4, B5 * D5,
+                           extra={"note": "algorithmic_bytes counts the 128-byte lines the gather touches"}))
+    us = time_calls(lambda i: dct.dct_rowtopk_scatter_idx16(idx16, val5, d5[i & 1]), args.reps)
+    i16_calls.append(entry("dct_rowtopk_scatter_idx16[c5]", us, B5 * D5 * 2 + B5 * k5 * 4, B5 * D5))
+    del d5, idx16
     call_fwd(0)
 
     # ------------------------------------------------------------ many small tensors per call (not part of the step)
@@ -406,7 +421,7 @@ def main():
         "config": {"workload": "c4 DP select+compact (N=2^28 fp32, keep 0.5%) + c5 MP row top-k fwd+bwd "
                                "(65536x4096 bf16, k=204)" + (" [SHRUNK 16x: not a valid number]" if args.small else ""),
                    "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
-        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls, "bitmask_calls": bm_calls,
+        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls, "bitmask_calls": bm_calls, "idx16_calls": i16_calls,
         "batched_small_tensors": batched, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -187,6 +187,22 @@ int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint32_t D, uint
 int dct_rowtopk_scatter_bitmask(const uint32_t* d_mask, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k,
                                 void* d_out, uint64_t out_row_stride_elems, void* hip_stream);
 
+/* --------------------------------------- DCT-MP, the mask as 16-bit indices ---
+ * The same three operations with the mask of Algorithm 2 carried as uint16 column
+ * indices (D <= 65536; a wider row returns DCT_ERR_INVALID): 4 bytes per kept bf16
+ * entry on the wire instead of 6, and unlike the bitmap the cost does not grow as
+ * the rows get sparser.  Kept set, order, values and tau are those of
+ * dct_rowtopk_fwd; arguments as there except
+ *   d_idx_out / d_idx   device uint16[B*k], 2-byte aligned
+ * An index >= D is handled as in dct_rowtopk_bwd / dct_rowtopk_scatter.
+ */
+int dct_rowtopk_fwd_idx16(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
+                          uint16_t* d_idx_out, void* d_val_out, void* d_tau_out, void* hip_stream);
+int dct_rowtopk_bwd_idx16(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
+                          const uint16_t* d_idx, void* d_dval_out, void* hip_stream);
+int dct_rowtopk_scatter_idx16(const uint16_t* d_idx, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k,
+                              void* d_out, uint64_t out_row_stride_elems, void* hip_stream);
+
 /* ------------------------------------------------------ DCT-DP, many tensors ---
  * Layer-wise compression (Sec. 2.1: every layer's gradient is compressed on its
  * own, with its own threshold) for many tensors with a fixed number of launches:

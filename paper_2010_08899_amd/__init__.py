@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     dct_threshold_compact_workspace_init, lib, new_compact_workspace, new_select_workspace, read_count,
     read_threshold, Segment, segment_table, dct_batched_workspace_bytes, new_batched_workspace,
     dct_select_threshold_batched, dct_threshold_compact_batched, dct_rowtopk_fwd_bitmask,
-    dct_rowtopk_bwd_bitmask, dct_rowtopk_scatter_bitmask,
+    dct_rowtopk_bwd_bitmask, dct_rowtopk_scatter_bitmask, dct_rowtopk_fwd_idx16, dct_rowtopk_bwd_idx16,
+    dct_rowtopk_scatter_idx16,
 )

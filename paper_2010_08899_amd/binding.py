@@ -52,6 +52,15 @@ _EXPORTS = {
     "dct_rowtopk_scatter_bitmask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32,
                                                    ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
                                                    ctypes.c_void_p]),
+    "dct_rowtopk_fwd_idx16": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
+                                             ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_void_p]),
+    "dct_rowtopk_bwd_idx16": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32,
+                                             ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_void_p]),
+    "dct_rowtopk_scatter_idx16": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32,
+                                                 ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
+                                                 ctypes.c_void_p]),
     "dct_batched_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32]),
     "dct_select_threshold_batched": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_uint32,
                                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -384,6 +393,45 @@ def dct_rowtopk_scatter(idx: torch.Tensor, val: torch.Tensor, out: torch.Tensor)
         raise ValueError("val must be a contiguous [B, k] tensor of out.dtype")
     _check(lib().dct_rowtopk_scatter(_dev(idx, "idx"), _dev(val, "val"), _dt(out), B, D, idx.shape[1], ptr, stride,
                                      _stream()), "dct_rowtopk_scatter")
+
+
+# ------------------------------------------------------------------ DCT-MP, the mask as 16-bit indices
+_IDX16 = (torch.uint16, torch.int16)  # both hold the same 16 bits; the library reads them unsigned
+
+
+def dct_rowtopk_fwd_idx16(x: torch.Tensor, k: int, idx_out: torch.Tensor, val_out: torch.Tensor,
+                          tau_out: torch.Tensor | None = None) -> None:
+    ptr, B, D, stride = _rows(x, "x")
+    if idx_out.dtype not in _IDX16 or val_out.dtype != x.dtype or not idx_out.is_contiguous() \
+            or not val_out.is_contiguous() or idx_out.numel() != B * k or val_out.numel() != B * k:
+        raise ValueError("idx_out / val_out must be contiguous [B, k] uint16 / x.dtype tensors")
+    if tau_out is not None and (tau_out.dtype != x.dtype or tau_out.numel() != B or not tau_out.is_contiguous()):
+        raise ValueError("tau_out must be a contiguous [B] tensor of x.dtype")
+    _check(lib().dct_rowtopk_fwd_idx16(ptr, _dt(x), B, D, stride, int(k), _dev(idx_out, "idx_out"),
+                                       _dev(val_out, "val_out"),
+                                       _dev(tau_out, "tau_out") if tau_out is not None else None, _stream()),
+           "dct_rowtopk_fwd_idx16")
+
+
+def dct_rowtopk_bwd_idx16(dy: torch.Tensor, idx: torch.Tensor, dval_out: torch.Tensor) -> None:
+    ptr, B, D, stride = _rows(dy, "dy")
+    if idx.dtype not in _IDX16 or idx.dim() != 2 or idx.shape[0] != B or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous uint16 [B, k] tensor")
+    k = idx.shape[1]
+    if dval_out.dtype != dy.dtype or dval_out.numel() != B * k or not dval_out.is_contiguous():
+        raise ValueError("dval_out must be a contiguous [B, k] tensor of dy.dtype")
+    _check(lib().dct_rowtopk_bwd_idx16(ptr, _dt(dy), B, D, stride, k, _dev(idx, "idx"), _dev(dval_out, "dval_out"),
+                                       _stream()), "dct_rowtopk_bwd_idx16")
+
+
+def dct_rowtopk_scatter_idx16(idx: torch.Tensor, val: torch.Tensor, out: torch.Tensor) -> None:
+    ptr, B, D, stride = _rows(out, "out")
+    if idx.dtype not in _IDX16 or idx.dim() != 2 or idx.shape[0] != B or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous uint16 [B, k] tensor")
+    if val.dtype != out.dtype or val.shape != idx.shape or not val.is_contiguous():
+        raise ValueError("val must be a contiguous [B, k] tensor of out.dtype")
+    _check(lib().dct_rowtopk_scatter_idx16(_dev(idx, "idx"), _dev(val, "val"), _dt(out), B, D, idx.shape[1], ptr,
+                                           stride, _stream()), "dct_rowtopk_scatter_idx16")
 
 
 # ------------------------------------------------------------------ measurement helpers

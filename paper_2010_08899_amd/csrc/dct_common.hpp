@@ -99,6 +99,15 @@ __device__ __forceinline__ void st_stream(uint4* p, uint32_t x, uint32_t y, uint
   __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p));
 }
 
+// How a row's mask leaves the row top-k forward kernels: k column indices of 32 or 16 bits, or a
+// bitmap of ceil(D/32) words.  `put_col` stores column `col` as entry `pos` of an index list.
+enum RowEnc : int { kEncIdx32 = 0, kEncBitmap = 1, kEncIdx16 = 2 };
+template <int ENC>
+__device__ __forceinline__ void put_col(void* idx_base, uint64_t pos, uint32_t col) {
+  if constexpr (ENC == kEncIdx32) static_cast<int32_t*>(idx_base)[pos] = static_cast<int32_t>(col);
+  if constexpr (ENC == kEncIdx16) static_cast<uint16_t*>(idx_base)[pos] = static_cast<uint16_t>(col);
+}
+
 inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // Compute units of the current device (cached per device).

@@ -38,12 +38,12 @@ __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digi
   if (active && !same) atomicAdd(&h[digit], 1u);
 }
 
-// MASK: the row's mask goes out as a bitmap (through `idx_out`, ceil(D/32) words per row)
-// instead of column indices.
-template <int DT, bool MASK>
+// ENC (RowEnc): the row's mask goes out through `idx_out` as 32- or 16-bit column indices or as a
+// bitmap of ceil(D/32) words per row.
+template <int DT, int ENC>
 __global__ __launch_bounds__(kRtThreads) void rowtopk_fwd_generic_kernel(
     const typename Elem<DT>::word_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k,
-    int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out,
+    void* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out,
     typename Elem<DT>::word_t* __restrict__ tau_out) {
   using E = Elem<DT>;
   __shared__ uint32_t s_hist[kRtWaves][kRtBins];
@@ -109,7 +109,6 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_fwd_generic_kernel(
 
     // ordered emit
     uint32_t out = 0, ties_seen = 0;
-    int32_t* io = idx_out + row * k;
     typename E::word_t* vo = val_out + row * k;
     for (uint32_t c0 = 0; c0 < D; c0 += kWave) {
       const uint32_t c = c0 + lane;
@@ -123,12 +122,12 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_fwd_generic_kernel(
       const uint64_t m_keep = ballot64(keep);
       const uint32_t slot = out + lanes_below(m_keep);
       if (keep && slot < k) {
-        if constexpr (!MASK) io[slot] = static_cast<int32_t>(c);
+        put_col<ENC>(idx_out, row * k + slot, c);
         vo[slot] = static_cast<typename E::word_t>(raw);
       }
-      if constexpr (MASK) {  // the ballot is the mask of these 64 columns
+      if constexpr (ENC == kEncBitmap) {  // the ballot is the mask of these 64 columns
         const uint32_t n_words = (D + 31) / 32;
-        uint32_t* mo = reinterpret_cast<uint32_t*>(idx_out) + row * n_words;
+        uint32_t* mo = static_cast<uint32_t*>(idx_out) + row * n_words;
         const uint32_t w = c0 / 32 + lane;
         if (lane < 2 && w < n_words) mo[w] = static_cast<uint32_t>(m_keep >> (32 * lane));
       }
@@ -142,10 +141,10 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_fwd_generic_kernel(
 // ---------------------------------------------------------------------------
 // Backward: gather through the forward indices.
 // ---------------------------------------------------------------------------
-template <typename W>
+template <typename W, typename I>
 __global__ __launch_bounds__(256) void rowtopk_bwd_gather_kernel(const W* __restrict__ dy, uint32_t B, uint32_t D,
                                                                 uint64_t stride, uint32_t k,
-                                                                const int32_t* __restrict__ idx,
+                                                                const I* __restrict__ idx,
                                                                 W* __restrict__ dval) {
   const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= k) return;
@@ -299,19 +298,19 @@ using namespace dct;
 
 namespace {
 
-// idx_or_mask: int32[B*k] column indices, or (mask = true) uint32[B*ceil(D/32)] bitmap words.
+// idx_or_mask: int32[B*k] or uint16[B*k] column indices, or uint32[B*ceil(D/32)] bitmap words (enc: RowEnc).
 int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
-               void* idx_or_mask, void* d_val_out, void* d_tau_out, bool mask, void* hip_stream) {
+               void* idx_or_mask, void* d_val_out, void* d_tau_out, int enc, void* hip_stream) {
   if (!x || !idx_or_mask || !d_val_out || B == 0 || D == 0 || k == 0 || k > D || row_stride_elems < D)
     return DCT_ERR_INVALID;
   if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
-  if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
+  if (D > (enc == kEncIdx16 ? 65536u : 0x7FFFFFFFu)) return DCT_ERR_INVALID;
   const size_t es = dt == DCT_F32 ? 4 : 2;
-  if (!is_aligned(x, es) || !is_aligned(idx_or_mask, 4) || !is_aligned(d_val_out, es) ||
+  if (!is_aligned(x, es) || !is_aligned(idx_or_mask, enc == kEncIdx16 ? 2 : 4) || !is_aligned(d_val_out, es) ||
       (d_tau_out && !is_aligned(d_tau_out, es)))
     return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  auto* io = static_cast<int32_t*>(idx_or_mask);
+  void* io = idx_or_mask;
   uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
   if (grid > 65536u * 4) grid = 65536u * 4;
   // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 4096 columns
@@ -339,11 +338,15 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     else if (vecs <= 512) DCT_LAUNCH_ONCHIP(8, MK, F32V);    \
     else if constexpr (F32V) DCT_LAUNCH_ONCHIP(16, MK, F32V); \
   } while (0)
-    if (dt == DCT_F32) {
-      if (mask) DCT_LAUNCH_ONCHIP_NV(true, true); else DCT_LAUNCH_ONCHIP_NV(false, true);
-    } else {
-      if (mask) DCT_LAUNCH_ONCHIP_NV(true, false); else DCT_LAUNCH_ONCHIP_NV(false, false);
-    }
+#define DCT_LAUNCH_ONCHIP_ENC(F32V)                                        \
+  do {                                                                    \
+    if (enc == kEncBitmap) DCT_LAUNCH_ONCHIP_NV(kEncBitmap, F32V);        \
+    else if (enc == kEncIdx16) DCT_LAUNCH_ONCHIP_NV(kEncIdx16, F32V);     \
+    else DCT_LAUNCH_ONCHIP_NV(kEncIdx32, F32V);                           \
+  } while (0)
+    if (dt == DCT_F32) DCT_LAUNCH_ONCHIP_ENC(true);
+    else DCT_LAUNCH_ONCHIP_ENC(false);
+#undef DCT_LAUNCH_ONCHIP_ENC
 #undef DCT_LAUNCH_ONCHIP_NV
 #undef DCT_LAUNCH_ONCHIP
     return launch_status();
@@ -352,11 +355,15 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   hipLaunchKernelGGL((rowtopk_fwd_generic_kernel<DTV, MK>), dim3(grid), dim3(kRtThreads), 0, s,            \
                      static_cast<const Elem<DTV>::word_t*>(x), B, D, row_stride_elems, k, io,              \
                      static_cast<Elem<DTV>::word_t*>(d_val_out), static_cast<Elem<DTV>::word_t*>(d_tau_out))
-  if (dt == DCT_F32) {
-    if (mask) DCT_LAUNCH_GENERIC(DCT_F32, true); else DCT_LAUNCH_GENERIC(DCT_F32, false);
-  } else {
-    if (mask) DCT_LAUNCH_GENERIC(DCT_BF16, true); else DCT_LAUNCH_GENERIC(DCT_BF16, false);
-  }
+#define DCT_LAUNCH_GENERIC_ENC(DTV)                                  \
+  do {                                                              \
+    if (enc == kEncBitmap) DCT_LAUNCH_GENERIC(DTV, kEncBitmap);     \
+    else if (enc == kEncIdx16) DCT_LAUNCH_GENERIC(DTV, kEncIdx16);  \
+    else DCT_LAUNCH_GENERIC(DTV, kEncIdx32);                        \
+  } while (0)
+  if (dt == DCT_F32) DCT_LAUNCH_GENERIC_ENC(DCT_F32);
+  else DCT_LAUNCH_GENERIC_ENC(DCT_BF16);
+#undef DCT_LAUNCH_GENERIC_ENC
 #undef DCT_LAUNCH_GENERIC
   return launch_status();
 }
@@ -366,13 +373,13 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
 extern "C" int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
                                uint32_t k, int32_t* d_idx_out, void* d_val_out, void* d_tau_out,
                                void* hip_stream) {
-  return launch_fwd(x, dt, B, D, row_stride_elems, k, d_idx_out, d_val_out, d_tau_out, false, hip_stream);
+  return launch_fwd(x, dt, B, D, row_stride_elems, k, d_idx_out, d_val_out, d_tau_out, kEncIdx32, hip_stream);
 }
 
 extern "C" int dct_rowtopk_fwd_bitmask(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
                                        uint32_t k, uint32_t* d_mask_out, void* d_val_out, void* d_tau_out,
                                        void* hip_stream) {
-  return launch_fwd(x, dt, B, D, row_stride_elems, k, d_mask_out, d_val_out, d_tau_out, true, hip_stream);
+  return launch_fwd(x, dt, B, D, row_stride_elems, k, d_mask_out, d_val_out, d_tau_out, kEncBitmap, hip_stream);
 }
 
 extern "C" int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
@@ -434,24 +441,45 @@ extern "C" int dct_rowtopk_scatter_bitmask(const uint32_t* d_mask, const void* d
   return launch_status();
 }
 
-extern "C" int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
-                               uint32_t k, const int32_t* d_idx, void* d_dval_out, void* hip_stream) {
+namespace {
+
+template <typename I>
+int launch_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k, const I* d_idx,
+               void* d_dval_out, void* hip_stream) {
   if (!dy || !d_idx || !d_dval_out || B == 0 || D == 0 || k == 0 || k > D || row_stride_elems < D)
     return DCT_ERR_INVALID;
   if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
-  if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
+  if (D > (sizeof(I) == 2 ? 65536u : 0x7FFFFFFFu)) return DCT_ERR_INVALID;
   const size_t es = dt == DCT_F32 ? 4 : 2;
-  if (!is_aligned(dy, es) || !is_aligned(d_idx, 4) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
+  if (!is_aligned(dy, es) || !is_aligned(d_idx, sizeof(I)) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const dim3 grid((k + 255) / 256, B < 65535u ? B : 65535u);
   if (dt == DCT_F32) {
-    hipLaunchKernelGGL((rowtopk_bwd_gather_kernel<uint32_t>), grid, dim3(256), 0, s,
+    hipLaunchKernelGGL((rowtopk_bwd_gather_kernel<uint32_t, I>), grid, dim3(256), 0, s,
                        static_cast<const uint32_t*>(dy), B, D, row_stride_elems, k, d_idx,
                        static_cast<uint32_t*>(d_dval_out));
   } else {
-    hipLaunchKernelGGL((rowtopk_bwd_gather_kernel<uint16_t>), grid, dim3(256), 0, s,
+    hipLaunchKernelGGL((rowtopk_bwd_gather_kernel<uint16_t, I>), grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(dy), B, D, row_stride_elems, k, d_idx,
                        static_cast<uint16_t*>(d_dval_out));
   }
   return launch_status();
+}
+
+}  // namespace
+
+extern "C" int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                               uint32_t k, const int32_t* d_idx, void* d_dval_out, void* hip_stream) {
+  return launch_bwd(dy, dt, B, D, row_stride_elems, k, d_idx, d_dval_out, hip_stream);
+}
+
+extern "C" int dct_rowtopk_fwd_idx16(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                                     uint32_t k, uint16_t* d_idx_out, void* d_val_out, void* d_tau_out,
+                                     void* hip_stream) {
+  return launch_fwd(x, dt, B, D, row_stride_elems, k, d_idx_out, d_val_out, d_tau_out, kEncIdx16, hip_stream);
+}
+
+extern "C" int dct_rowtopk_bwd_idx16(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems,
+                                     uint32_t k, const uint16_t* d_idx, void* d_dval_out, void* hip_stream) {
+  return launch_bwd(dy, dt, B, D, row_stride_elems, k, d_idx, d_dval_out, hip_stream);
 }

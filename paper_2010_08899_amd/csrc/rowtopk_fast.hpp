@@ -75,13 +75,14 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // NV = 16-byte vectors per lane: the lane owns NV*8 (bf16) or NV*4 (fp32) contiguous columns.
-// MASK: the row's mask is written as a bitmap (ceil(D/32) words per row, bit c%32 of word c/32 =
-// column c kept) through `idx_out` instead of k column indices; the values are written either way.
+// ENC (RowEnc): the row's mask is written through `idx_out` as k ascending column indices of 32 or
+// 16 bits, or as a bitmap (ceil(D/32) words per row, bit c%32 of word c/32 = column c kept); the
+// values are written either way.
 // F32: fp32 rows (the packed 16-bit keys are the upper halves of the fp32 keys).
-template <int NV, bool MASK, bool F32>
+template <int NV, int ENC, bool F32>
 __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     const std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride,
-    uint32_t k, int32_t* __restrict__ idx_out, std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ val_out,
+    uint32_t k, void* __restrict__ idx_out, std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ val_out,
     std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ tau_out) {
   using word_t = std::conditional_t<F32, uint32_t, uint16_t>;
   constexpr int ES = F32 ? 4 : 2;                   // bytes per element
@@ -530,12 +531,12 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
 #pragma unroll
     for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
     uint32_t slot = wave_incl_scan(kc) - kc;
-    int32_t* io = idx_out + row * k;
-    word_t* vo = val_out + row * k;
-    if constexpr (MASK) {
+    const uint64_t o0 = row * k;  // first output slot of the row
+    word_t* vo = val_out + o0;
+    if constexpr (ENC == kEncBitmap) {
       // the per-lane bitmaps ARE the mask: COLS bits per lane, packed into 32-bit words
       const uint32_t n_words = (D + 31) / 32;
-      uint32_t* mo = reinterpret_cast<uint32_t*>(idx_out) + row * n_words;
+      uint32_t* mo = static_cast<uint32_t*>(idx_out) + row * n_words;
       if constexpr (COLS >= 32) {
 #pragma unroll
         for (int w = 0; w < WORDS; ++w)
@@ -576,7 +577,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
         for (int j = 0; j < 4; ++j) {
           const uint32_t o = j * kWave + lane;
           if (o < k) {
-            if constexpr (!MASK) io[o] = static_cast<int32_t>(col[j]);
+            put_col<ENC>(idx_out, o0 + o, col[j]);
             vo[o] = static_cast<word_t>(raw[j]);
           }
         }
@@ -584,7 +585,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
         for (uint32_t j = lane; j < k; j += kWave) {
           const uint32_t col = *stage_at(j);
           const uint32_t raw = raw_at_col(col);
-          if constexpr (!MASK) io[j] = static_cast<int32_t>(col);
+          put_col<ENC>(idx_out, o0 + j, col);
           vo[j] = static_cast<word_t>(raw);
         }
       }
@@ -598,7 +599,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
             m &= m - 1;
             const uint32_t lc = kColsPerWord * w + q;
             if (slot < k) {
-              if constexpr (!MASK) io[slot] = static_cast<int32_t>(lane * COLS + lc);
+              put_col<ENC>(idx_out, o0 + slot, lane * COLS + lc);
               vo[slot] = static_cast<word_t>(raw_at_col(lane * COLS + lc));
             }
             ++slot;

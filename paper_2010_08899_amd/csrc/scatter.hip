@@ -142,9 +142,9 @@ __global__ void scatter_pairs_kernel(const int32_t* __restrict__ idx, const W* _
 }
 
 // Dense rows, one wavefront per row, the row assembled in LDS (D * sizeof(W) <= kRowLdsBytes).
-template <typename W>
+template <typename W, typename I>
 __global__ __launch_bounds__(kScThreads) void rowscatter_lds_kernel(
-    const int32_t* __restrict__ idx, const W* __restrict__ val, uint32_t B, uint32_t D, uint32_t k,
+    const I* __restrict__ idx, const W* __restrict__ val, uint32_t B, uint32_t D, uint32_t k,
     W* __restrict__ out, uint64_t out_stride, bool vec_ok) {
   constexpr int kWaves = kScThreads / kWave;
   constexpr uint32_t EPV = 16 / sizeof(W);
@@ -184,9 +184,9 @@ __global__ __launch_bounds__(kScThreads) void rowscatter_lds_kernel(
 
 // Dense rows of any width: a workgroup zeroes the row in global memory, waits for those stores, then
 // drops the values in.
-template <typename W>
+template <typename W, typename I>
 __global__ __launch_bounds__(kScThreads) void rowscatter_global_kernel(
-    const int32_t* __restrict__ idx, const W* __restrict__ val, uint32_t B, uint32_t D, uint32_t k, W* out,
+    const I* __restrict__ idx, const W* __restrict__ val, uint32_t B, uint32_t D, uint32_t k, W* out,
     uint64_t out_stride) {
   for (uint64_t b = blockIdx.x; b < B; b += gridDim.x) {
     W* dst = out + b * out_stride;
@@ -259,39 +259,54 @@ extern "C" int dct_scatter(const int32_t* d_idx, const void* d_val, const uint64
   return launch_status();
 }
 
-extern "C" int dct_rowtopk_scatter(const int32_t* d_idx, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k,
-                                   void* d_out, uint64_t out_row_stride_elems, void* hip_stream) {
+namespace {
+
+template <typename I>
+int launch_rowscatter(const I* d_idx, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k, void* d_out,
+                      uint64_t out_row_stride_elems, void* hip_stream) {
   if (!d_idx || !d_val || !d_out || B == 0 || D == 0 || k == 0 || k > D || out_row_stride_elems < D)
     return DCT_ERR_INVALID;
   if (dt != DCT_F32 && dt != DCT_BF16) return DCT_ERR_INVALID;
-  if (D > 0x7FFFFFFFu) return DCT_ERR_INVALID;
+  if (D > (sizeof(I) == 2 ? 65536u : 0x7FFFFFFFu)) return DCT_ERR_INVALID;
   const size_t es = dt == DCT_F32 ? 4 : 2;
-  if (!is_aligned(d_idx, 4) || !is_aligned(d_val, es) || !is_aligned(d_out, es)) return DCT_ERR_INVALID;
+  if (!is_aligned(d_idx, sizeof(I)) || !is_aligned(d_val, es) || !is_aligned(d_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
   if (static_cast<uint64_t>(D) * es <= kRowLdsBytes) {
     const bool vec_ok = is_aligned(d_out, 16) && (out_row_stride_elems * es) % 16 == 0 && (D * es) % 16 == 0;
     const uint32_t grid = std::min<uint32_t>((B + 3) / 4, resident);
     if (dt == DCT_F32) {
-      hipLaunchKernelGGL((rowscatter_lds_kernel<uint32_t>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
+      hipLaunchKernelGGL((rowscatter_lds_kernel<uint32_t, I>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
                          static_cast<const uint32_t*>(d_val), B, D, k, static_cast<uint32_t*>(d_out),
                          out_row_stride_elems, vec_ok);
     } else {
-      hipLaunchKernelGGL((rowscatter_lds_kernel<uint16_t>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
+      hipLaunchKernelGGL((rowscatter_lds_kernel<uint16_t, I>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
                          static_cast<const uint16_t*>(d_val), B, D, k, static_cast<uint16_t*>(d_out),
                          out_row_stride_elems, vec_ok);
     }
   } else {
     const uint32_t grid = std::min<uint32_t>(B, resident * 4u);
     if (dt == DCT_F32) {
-      hipLaunchKernelGGL((rowscatter_global_kernel<uint32_t>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
+      hipLaunchKernelGGL((rowscatter_global_kernel<uint32_t, I>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
                          static_cast<const uint32_t*>(d_val), B, D, k, static_cast<uint32_t*>(d_out),
                          out_row_stride_elems);
     } else {
-      hipLaunchKernelGGL((rowscatter_global_kernel<uint16_t>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
+      hipLaunchKernelGGL((rowscatter_global_kernel<uint16_t, I>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
                          static_cast<const uint16_t*>(d_val), B, D, k, static_cast<uint16_t*>(d_out),
                          out_row_stride_elems);
     }
   }
   return launch_status();
+}
+
+}  // namespace
+
+extern "C" int dct_rowtopk_scatter(const int32_t* d_idx, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k,
+                                   void* d_out, uint64_t out_row_stride_elems, void* hip_stream) {
+  return launch_rowscatter(d_idx, d_val, dt, B, D, k, d_out, out_row_stride_elems, hip_stream);
+}
+
+extern "C" int dct_rowtopk_scatter_idx16(const uint16_t* d_idx, const void* d_val, int dt, uint32_t B, uint32_t D,
+                                         uint32_t k, void* d_out, uint64_t out_row_stride_elems, void* hip_stream) {
+  return launch_rowscatter(d_idx, d_val, dt, B, D, k, d_out, out_row_stride_elems, hip_stream);
 }

@@ -864,6 +864,94 @@ def test_mp_bitmask_c5_block(dct):
     assert np.array_equal(host(dval), oracle.rowtopk_bwd_bitmask(host(dy), emask, k))
 
 
+# ------------------------------------------------------------------ Algorithm 2, the mask as 16-bit indices
+def _u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("dtype,B,D,k,pad", [
+    (torch.bfloat16, 17, 512, 25, 0), (torch.bfloat16, 5, 264, 13, 0), (torch.bfloat16, 6, 40, 7, 0),
+    (torch.bfloat16, 4, 8, 8, 0), (torch.bfloat16, 3, 12_000, 600, 0), (torch.bfloat16, 5, 1001, 50, 0),
+    (torch.bfloat16, 9, 4096, 300, 8), (torch.bfloat16, 70, 2048, 102, 0),
+    (torch.float32, 33, 1024, 51, 0), (torch.float32, 7, 33, 5, 3), (torch.float32, 2, 5000, 250, 0),
+    (torch.float32, 6, 4096, 204, 0)])
+def test_mp_idx16_encoding(dct, dtype, B, D, k, pad):
+    x = si.relu_activations(B, D, DEV, 1600 + D, dtype=dtype, row_stride=D + pad if pad else None)
+    dy = si.normal_matrix(B, D, DEV, 1700 + D, dtype=dtype)
+    idx = torch.full((B, k), -1, dtype=torch.int16, device=DEV)
+    val = torch.zeros(B, k, dtype=dtype, device=DEV)
+    tau = torch.zeros(B, dtype=dtype, device=DEV)
+    dct.dct_rowtopk_fwd_idx16(x, k, idx, val, tau)
+    xh = host(x.contiguous()) if not pad else oracle.as_numpy(x.cpu())
+    eidx, eval_, etau = oracle.rowtopk_fwd_idx16(xh, k)
+    assert np.array_equal(_u16(idx), eidx)
+    assert np.array_equal(bits(host(val).reshape(-1)), bits(eval_.reshape(-1)))
+    assert np.array_equal(bits(host(tau)), bits(etau))
+    dval = torch.full((B, k), 3.0, device=DEV).to(dtype)
+    dct.dct_rowtopk_bwd_idx16(dy, idx, dval)
+    assert np.array_equal(bits(host(dval).reshape(-1)), bits(oracle.rowtopk_bwd_idx16(host(dy), eidx).reshape(-1)))
+    buf = torch.full((B, D + 5), 3.0, device=DEV).to(dtype)
+    dct.dct_rowtopk_scatter_idx16(idx, val, buf[:, :D])
+    assert np.array_equal(bits(host(buf[:, :D].contiguous()).reshape(-1)),
+                          bits(oracle.rowscatter_idx16(eidx, eval_, D).reshape(-1)))
+    assert torch.all(buf[:, D:] == 3.0)
+
+
+def test_mp_idx16_widest_row_hard_rows_and_bad_indices(dct):
+    # D = 65536: the last column (0xFFFF) is kept in row 0; D = 65537 does not fit 16 bits
+    B, D, k = 3, 65536, 300
+    x = si.relu_activations(B, D, DEV, 1800, dtype=torch.bfloat16)
+    x[0, D - 1] = -100.0
+    x[1] = 0.5          # all equal: the k lowest columns
+    idx = torch.zeros(B, k, dtype=torch.int16, device=DEV)
+    val = torch.zeros(B, k, dtype=torch.bfloat16, device=DEV)
+    dct.dct_rowtopk_fwd_idx16(x, k, idx, val, None)
+    eidx, eval_, _ = oracle.rowtopk_fwd_idx16(host(x), k)
+    assert np.array_equal(_u16(idx), eidx) and np.array_equal(host(val), eval_)
+    assert int(eidx[0, -1]) == 0xFFFF and eidx[1].tolist() == list(range(k))
+    dy = si.normal_matrix(B, D, DEV, 1801, dtype=torch.bfloat16)
+    dval = torch.zeros_like(val)
+    dct.dct_rowtopk_bwd_idx16(dy, idx, dval)
+    assert np.array_equal(host(dval), oracle.rowtopk_bwd_idx16(host(dy), eidx))
+    out = torch.full((B, D), 3.0, device=DEV).to(torch.bfloat16)
+    dct.dct_rowtopk_scatter_idx16(idx, val, out)
+    assert np.array_equal(host(out), oracle.rowscatter_idx16(eidx, eval_, D))
+    wide = torch.zeros(1, 65537, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(dct.DctError):
+        dct.dct_rowtopk_fwd_idx16(wide, 4, torch.zeros(1, 4, dtype=torch.int16, device=DEV),
+                                  torch.zeros(1, 4, dtype=torch.bfloat16, device=DEV), None)
+    # an index past the row's end: zero in the backward pass, skipped by the decompression
+    D2, k2 = 1000, 4
+    dy2 = si.normal_matrix(2, D2, DEV, 1802, dtype=torch.float32)
+    bad = torch.tensor([[1, 5, 1000, 65535], [0, 2, 3, 999]], dtype=torch.int32).to(torch.uint16).to(DEV)
+    dv = torch.full((2, k2), 3.0, device=DEV)
+    dct.dct_rowtopk_bwd_idx16(dy2, bad, dv)
+    want = torch.stack([torch.stack([dy2[0, 1], dy2[0, 5], dy2.new_zeros(()), dy2.new_zeros(())]),
+                        dy2[1, [0, 2, 3, 999]]])
+    assert torch.equal(dv, want)
+    v2 = torch.arange(1, 9, dtype=torch.float32, device=DEV).reshape(2, 4)
+    o2 = torch.full((2, D2), 3.0, device=DEV)
+    dct.dct_rowtopk_scatter_idx16(bad, v2, o2)
+    assert np.array_equal(host(o2), oracle.rowscatter_idx16(_u16(bad), host(v2), D2))
+
+
+def test_mp_idx16_c5_block_matches_the_int32_form(dct):
+    x, dy, k = si.config_c5(DEV, b=4096)
+    B, D = x.shape
+    idx = torch.zeros(B, k, dtype=torch.int16, device=DEV)
+    val = torch.zeros(B, k, dtype=x.dtype, device=DEV)
+    dct.dct_rowtopk_fwd_idx16(x, k, idx, val, None)
+    eidx, eval_, _ = oracle.rowtopk_fwd_idx16(host(x), k)
+    assert np.array_equal(_u16(idx), eidx) and np.array_equal(host(val), eval_)
+    idx32 = torch.zeros(B, k, dtype=torch.int32, device=DEV)
+    val32 = torch.zeros_like(val)
+    dct.dct_rowtopk_fwd(x, k, idx32, val32, None)
+    assert np.array_equal(idx32.cpu().numpy(), eidx.astype(np.int32))
+    dval = torch.zeros_like(val)
+    dct.dct_rowtopk_bwd_idx16(dy, idx, dval)
+    assert np.array_equal(host(dval), oracle.rowtopk_bwd_idx16(host(dy), eidx))
+
+
 # ------------------------------------------------------------------ the wider rows at the benchmark's full sizes
 def test_ef_and_decompress_c4_full(dct):
     """Error feedback and decompression on the full c4 gradient (N = 2^28), the launch shape the
