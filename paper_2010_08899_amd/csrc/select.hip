@@ -14,7 +14,8 @@
 // order statistics to get bounds lo <= tau <= hi that hold with overwhelming
 // probability.  One streaming pass over the vector (coalesced 16-byte loads, tiles
 // dealt round-robin to the workgroups) counts the keys above hi and appends the keys in [lo, hi] --
-// well under 1 % of the vector -- to a candidate buffer through LDS staging.  The
+// well under 1 % of the vector -- to a candidate buffer (64 regions, each with its own
+// counter) through LDS staging.  The
 // radix passes then run over the candidates only, so the vector is read from HBM
 // once.  The counts tell exactly whether the bounds held (n_above < k <= n_above
 // + n_candidates, no buffer overflow); if they did not, the same radix passes run
@@ -45,17 +46,27 @@ constexpr int kPartRows = 4;                    // 16-byte loads per lane per st
 constexpr uint32_t kPartStage = 1024;           // staged candidate keys per wavefront
 constexpr uint32_t kPartTileVecs = kSelThreads * kPartRows;
 
+// The candidate buffer is cut into kCandRegions regions with a counter each: workgroup w of the
+// partition pass appends to region w % kCandRegions.  (All workgroups finish together; their end-of-chunk
+// reservations on ONE counter serialised and cost the pass a tenth of its time.)
+constexpr uint32_t kCandRegions = 64;
+struct alignas(128) RegionCount {
+  unsigned long long c;  // keys > hi seen by the region's workgroups (high word), keys in [lo, hi] they appended
+                         // (low word; may exceed the region)
+  uint32_t pad[30];      // a 128-byte line of its own
+};
 struct SelWs {
-  unsigned long long counts;  // partition pass: keys > hi (high word), keys in [lo, hi] (low word; may exceed the buffer)
+  RegionCount counts[kCandRegions];
   uint32_t lo, hi;     // bounds from the sample
   uint32_t sampled;    // 1 when the sample / partition kernels ran
-  uint32_t cand_cap;
-  uint32_t pad[2];
+  uint32_t cand_cap;   // capacity of the whole candidate buffer, a multiple of 4 * kCandRegions keys
+  uint32_t pad[4];
   SelState state[kSelMaxPasses + 1];  // state[p]: search state at the start of pass p
   uint32_t hist[kSelMaxPasses][kSelBins];
   uint32_t sample[kSampleSize];       // keys of the stratified sample
-  uint32_t cand[4];    // candidate keys follow (cand_cap of them)
+  uint32_t cand[4];    // candidate keys follow (cand_cap of them, region r at r * cand_cap / kCandRegions)
 };
+static_assert(offsetof(SelWs, cand) % 16 == 0, "candidate regions are read as 16-byte vectors");
 
 struct PassDigits {
   int n_pass;
@@ -214,7 +225,10 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
   const uint32_t lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const uint32_t wg = blockIdx.x;
-  const uint32_t lo = ws->lo, hi = ws->hi, cand_cap = ws->cand_cap;
+  const uint32_t lo = ws->lo, hi = ws->hi;
+  const uint32_t region_cap = ws->cand_cap / kCandRegions;
+  unsigned long long* region_count = &ws->counts[wg % kCandRegions].c;
+  uint32_t* region_keys = ws->cand + static_cast<size_t>(wg % kCandRegions) * region_cap;
   uint32_t* stage = s_stage[wave];
   uint32_t staged = 0, above = 0;
   __shared__ uint32_t s_cnt[kSelWaves], s_abv[kSelWaves], s_base;
@@ -223,10 +237,10 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
   auto flush = [&]() {
     if (staged == 0) return;
     uint32_t base = 0;
-    if (lane == 0) base = static_cast<uint32_t>(atomicAdd(&ws->counts, static_cast<unsigned long long>(staged)));
+    if (lane == 0) base = static_cast<uint32_t>(atomicAdd(region_count, static_cast<unsigned long long>(staged)));
     base = __builtin_amdgcn_readfirstlane(base);
     for (uint32_t i = lane; i < staged; i += kWave)
-      if (base + i < cand_cap) ws->cand[base + i] = stage[i];
+      if (base + i < region_cap) region_keys[base + i] = stage[i];
     staged = 0;
   };
   // NE keys per lane
@@ -359,14 +373,14 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
     }
     uint32_t base = 0;
     if (c != 0 || a != 0)
-      base = static_cast<uint32_t>(atomicAdd(&ws->counts, (static_cast<unsigned long long>(a) << 32) | c));
+      base = static_cast<uint32_t>(atomicAdd(region_count, (static_cast<unsigned long long>(a) << 32) | c));
     s_base = base;
   }
   __syncthreads();
   uint32_t base = s_base;
   for (int w = 0; w < wave; ++w) base += s_cnt[w];
   for (uint32_t i = lane; i < staged; i += kWave)
-    if (base + i < cand_cap) ws->cand[base + i] = stage[i];
+    if (base + i < region_cap) region_keys[base + i] = stage[i];
 }
 
 // ------------------------------------------------------------------ kernel 3
@@ -382,14 +396,29 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
   constexpr int V = E::kVec;
   __shared__ uint32_t h[kSelBins];
   __shared__ uint32_t s_tmp[kSelWaves + 4];
+  __shared__ uint32_t s_tot[3];
   const uint32_t span = kSelThreads * kSelUnroll;  // vectors per workgroup per iteration
+  const uint32_t region_cap = ws->cand_cap / kCandRegions;
 
   // ---- search state at the start of this pass
   SelState st;
   if (pass == 0) {
-    const unsigned long long counts = ws->counts;
-    const uint32_t n_above = static_cast<uint32_t>(counts >> 32), n_cand = static_cast<uint32_t>(counts);
-    const bool ok = ws->sampled != 0 && n_cand <= ws->cand_cap && n_above < k && k <= n_above + n_cand;
+    // totals of the partition pass over the regions (one counter per lane of the first wavefront)
+    if (threadIdx.x < kWave) {
+      static_assert(kCandRegions == kWave, "one region counter per lane");
+      const unsigned long long c = ws->counts[threadIdx.x].c;
+      const uint32_t a_sum = wave_sum_u32(static_cast<uint32_t>(c >> 32));
+      const uint32_t c_sum = wave_sum_u32(static_cast<uint32_t>(c));  // < 2^31: every key is counted at most once
+      const bool over = ballot64(static_cast<uint32_t>(c) > region_cap) != 0;
+      if (threadIdx.x == 0) {
+        s_tot[0] = a_sum;
+        s_tot[1] = c_sum;
+        s_tot[2] = over ? 1u : 0u;
+      }
+    }
+    __syncthreads();
+    const uint32_t n_above = s_tot[0], n_cand = s_tot[1];
+    const bool ok = ws->sampled != 0 && s_tot[2] == 0 && n_above < k && k <= n_above + n_cand;
     st.k_rem = ok ? k - n_above : k;
     st.n_gt = ok ? n_above : 0u;
     st.from_cand = ok ? 1u : 0u;
@@ -406,8 +435,9 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
   // vectors of the source; a workgroup with nothing to read leaves at once
   // (the candidate passes use few workgroups -- fewer histogram merges -- unless there are many candidates)
   const uint32_t src_vecs = st.from_cand ? (st.n_src + 3) / 4 : n_virt / V + 1;
-  const uint32_t n_wg = st.from_cand ? min(gridDim.x, max(kCandGrid, src_vecs / (span * 8))) : gridDim.x;
-  if (blockIdx.x != 0 && (blockIdx.x >= n_wg || blockIdx.x * span >= src_vecs)) return;
+  // candidate passes: workgroup b reads part b / kCandRegions of region b % kCandRegions
+  const uint32_t parts = max(1u, min(gridDim.x, max(kCandGrid, src_vecs / (span * 8))) / kCandRegions);
+  if (blockIdx.x != 0 && (st.from_cand ? blockIdx.x / kCandRegions >= parts : blockIdx.x * span >= src_vecs)) return;
   if (pass != 0) st = advance_state(st, ws->hist[pass - 1], s_tmp);
   if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[pass] = st;
   if (st.width == 0) return;  // every digit is fixed already
@@ -420,15 +450,17 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
   __syncthreads();
 
   if (st.from_cand) {
-    // candidate keys: u32, 16-byte-aligned buffer, n_src of them
-    const uint4* cv = reinterpret_cast<const uint4*>(ws->cand);
-    const uint32_t n_src = st.n_src;
-    for (uint32_t base = blockIdx.x * span; base < src_vecs; base += n_wg * span) {
+    // candidate keys of one region: u32, 16-byte-aligned, as many as its counter says
+    const uint32_t region = blockIdx.x % kCandRegions, part = blockIdx.x / kCandRegions;
+    const uint4* cv = reinterpret_cast<const uint4*>(ws->cand + static_cast<size_t>(region) * region_cap);
+    const uint32_t n_src = part < parts ? static_cast<uint32_t>(ws->counts[region].c) : 0u;  // <= region_cap here
+    const uint32_t reg_vecs = (n_src + 3) / 4;
+    for (uint32_t base = part * span; base < reg_vecs; base += parts * span) {
       uint4 v[kSelUnroll];
 #pragma unroll
       for (int u = 0; u < kSelUnroll; ++u) {
         const uint32_t vi = base + u * kSelThreads + threadIdx.x;
-        v[u] = vi < src_vecs ? cv[vi] : make_uint4(0, 0, 0, 0);  // the buffer is padded to whole vectors
+        v[u] = vi < reg_vecs ? cv[vi] : make_uint4(0, 0, 0, 0);  // a region holds whole vectors
       }
 #pragma unroll
       for (int u = 0; u < kSelUnroll; ++u) {
@@ -506,7 +538,9 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(SelWs* ws, i
 
 // Room for the keys between the sample bounds: about 10 sqrt(p (1 - p) / 16384) of the vector when a
 // fraction p is kept, i.e. at most 4 % (p = 1/2).
-uint32_t cand_capacity(uint64_t n) { return n >= kSampleMinN ? static_cast<uint32_t>(n / 16 + 65536) : 0u; }
+uint32_t cand_capacity(uint64_t n) {
+  return n >= kSampleMinN ? static_cast<uint32_t>(n / 16 + 65536) & ~(4u * kCandRegions - 1u) : 0u;
+}
 
 }  // namespace
 }  // namespace dct
