@@ -952,6 +952,68 @@ def test_mp_idx16_c5_block_matches_the_int32_form(dct):
     assert np.array_equal(host(dval), oracle.rowtopk_bwd_idx16(host(dy), eidx))
 
 
+# ------------------------------------------------------------------ side stream, HIP graph
+def test_calls_on_a_side_stream_and_in_a_captured_graph(dct):
+    """The calls launch on the stream they are given and allocate nothing, so a training loop can
+    capture them: one DP step (select + exactly-k compaction, 5 M elements: the sampled selection
+    with its seven launches) and one MP step (forward + backward) are captured once and replayed on
+    fresh data, with eager work and synchronisations in between; every replay is checked against the oracle."""
+    n, k = 5_000_003, 25_000
+    B, D, kk = 300, 1024, 51
+    g = torch.empty(n, device=DEV)
+    x = torch.empty(B, D, dtype=torch.bfloat16, device=DEV)
+    dy = torch.empty(B, D, dtype=torch.bfloat16, device=DEV)
+    thr = torch.zeros(4, dtype=torch.int32, device=DEV)
+    sws, cws = dct.new_select_workspace(g), dct.new_compact_workspace(g)
+    idx = torch.zeros(k, dtype=torch.int32, device=DEV)
+    val = torch.zeros(k, device=DEV)
+    cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ridx = torch.zeros(B, kk, dtype=torch.int32, device=DEV)
+    rval = torch.zeros(B, kk, dtype=torch.bfloat16, device=DEV)
+    dval = torch.zeros_like(rval)
+
+    def step():
+        dct.dct_select_threshold(g, k, thr, sws)
+        dct.dct_threshold_compact(g, thr, dct.DCT_EXACT_K, idx, val, cnt, cws)
+        dct.dct_rowtopk_fwd(x, kk, ridx, rval, None)
+        dct.dct_rowtopk_bwd(dy, ridx, dval)
+
+    def fill(seed):
+        g.copy_(si.gaussian_gradient(n, DEV, seed))
+        x.copy_(si.relu_activations(B, D, DEV, seed + 1, dtype=torch.bfloat16))
+        dy.copy_(si.normal_matrix(B, D, DEV, seed + 2, dtype=torch.bfloat16))
+
+    def check():
+        torch.cuda.synchronize()
+        gh = host(g)
+        exp = oracle.select_threshold(gh, k, method="nth")
+        assert dct.read_threshold(thr) == exp
+        eidx, eval_, ecnt = oracle.threshold_compact(gh, exp, oracle.EXACT_K)
+        assert cnt.item() == ecnt == k
+        assert np.array_equal(idx.cpu().numpy(), eidx) and np.array_equal(bits(host(val)), bits(eval_))
+        ei, ev, _ = oracle.rowtopk_fwd(host(x), kk)
+        assert np.array_equal(ridx.cpu().numpy(), ei) and np.array_equal(host(rval), ev)
+        assert np.array_equal(host(dval), oracle.rowtopk_bwd(host(dy), ei))
+
+    side = torch.cuda.Stream()
+    fill(3000)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # eager, not the default stream
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    check()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for r in range(3):
+        fill(3100 + 10 * r)         # eager work between the replays
+        idx.fill_(-1)
+        val.zero_()
+        graph.replay()
+        check()
+
+
 # ------------------------------------------------------------------ the wider rows at the benchmark's full sizes
 def test_ef_and_decompress_c4_full(dct):
     """Error feedback and decompression on the full c4 gradient (N = 2^28), the launch shape the
