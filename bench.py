@@ -78,19 +78,29 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_calls(fn, reps, warmup=2):
-    """Median duration in microseconds of fn(i) over `reps` back-to-back calls, each bracketed by HIP
-    events on the stream the kernels are launched on (torch's current stream)."""
+def time_calls(fn, reps, warmup=2, per_call=False):
+    """Average duration in microseconds of fn(i) over `reps` back-to-back calls: two HIP events around the
+    whole region, on the stream the kernels are launched on (torch's current stream).  per_call=True brackets
+    every call with events instead and returns the median interval (each event adds about 2.5 us)."""
     for i in range(warmup):
         fn(i)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    if per_call:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for i in range(reps):
+            fn(i)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)])) * 1e3
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
-    ev[0].record()
+    e0.record()
     for i in range(reps):
         fn(i)
-        ev[i + 1].record()
+    e1.record()
     torch.cuda.synchronize()
-    return float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)])) * 1e3
+    return e0.elapsed_time(e1) * 1e3 / reps
 
 
 def main():
@@ -338,7 +348,7 @@ def main():
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom["call"]),
                 "algorithmic_bytes": dom["algorithmic_bytes"], "launch_us": dom["us"],
-                "note": "achieved = algorithmic bytes of one launch / median HIP-event time of one launch; traffic = "
+                "note": "achieved = algorithmic bytes of one launch / average time of one launch (HIP events around the region of back-to-back launches); traffic = "
                         "scaled FETCH_SIZE + WRITE_SIZE of the kernel from profiles/bench_hbm_counters.txt",
                 "longest_call": {k_: v for k_, v in max(calls, key=lambda c: c["us"]).items()
                                  if k_ in ("call", "us", "GBps", "frac_of_hbm_peak", "launches", "algorithmic_bytes")}}
@@ -369,20 +379,11 @@ def main():
         us_sel3 = time_calls(lambda i: dct.dct_select_threshold(g0, k3, thr3, ws3s), 10)
         iters = si.C3_DRAWS
         # the loop as a training run issues it: iterations back to back, two events around all of them
-        # (an event after every call adds about 2.5 us to a 25 us kernel)
-        for i in range(5):
-            dct.dct_threshold_compact(bank[i % draws], thr3, dct.DCT_GE_TAU, idx3, val3, cnt3, ws3)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(iters):
-            dct.dct_threshold_compact(bank[i % draws], thr3, dct.DCT_GE_TAU, idx3, val3, cnt3, ws3)
-        e1.record()
-        torch.cuda.synchronize()
-        us_c3 = e0.elapsed_time(e1) * 1e3 / iters
+        us_c3 = time_calls(lambda i: dct.dct_threshold_compact(bank[i % draws], thr3, dct.DCT_GE_TAU, idx3, val3,
+                                                               cnt3, ws3), iters, warmup=5)
         last = dct.read_count(cnt3, capacity=cap3)
         us_c3_events = time_calls(lambda i: dct.dct_threshold_compact(bank[i % draws], thr3, dct.DCT_GE_TAU, idx3,
-                                                                      val3, cnt3, ws3), min(iters, 200), warmup=5)
+                                                                      val3, cnt3, ws3), min(iters, 200), warmup=5, per_call=True)
         alg3 = n3 * 4 + k3 * 8 + 8
         c3 = {"n": n3, "k": k3, "distinct_draws": draws, "iterations": iters, "select_us": round(us_sel3, 2),
               "compact_us_per_iteration": round(us_c3, 2),
