@@ -45,6 +45,7 @@
 // through the count.  The workspace holds two descriptor sets used by alternate
 // calls (an epoch word picks the set): every call clears the other set for its
 // successor and the last workgroup advances the epoch, so a call is one launch.
+#include <algorithm>
 #include <type_traits>
 
 #include "dct_common.hpp"
@@ -162,7 +163,7 @@ struct CompactGeom {
 
 // EF: g is W_grad, e_in the residual E_grad (may be the same buffer as e_out), e_out the new residual.
 template <int DT, bool EXACT, bool EF>
-__global__ __launch_bounds__(kCtThreads) void compact_kernel(
+__global__ __launch_bounds__(kCtThreads, kCtWgPerCu) void compact_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* e_in,
     typename Elem<DT>::word_t* e_out, CompactGeom geo, const dct_threshold* __restrict__ thr,
     int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out, uint32_t capacity,
@@ -223,16 +224,28 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     rounds = 1;
     while (rounds <= kCtMaxRounds && expected > room * rounds) ++rounds;  // ceil(expected / room), no division
     if (rounds > kCtMaxRounds) rounds = 1;
+    if constexpr (EF) {
+      // With error feedback the kernel writes as much as a third of what it reads.  The memory system
+      // sustains such a mix better when the grid works within a narrow window of the vector, and the
+      // slices do just that: 8 slices of >= 128 KiB per workgroup took c4 from 661 to 603 us, their
+      // seven drains included (4 slices: 621 us, 16: 649 us).
+      uint32_t window_rounds = 1;
+      while (window_rounds < 8u && geo.tiles >= 8u * window_rounds * geo.grid) window_rounds *= 2u;
+      rounds = max(rounds, window_rounds);
+    }
     rounds = min(rounds, geo.tiles);
   }
   const uint32_t n_virtual = rounds * geo.grid;
   const uint32_t tiles_per_round = (geo.tiles + rounds - 1) / rounds;
-  const uint32_t vecs_per_wg = (tiles_per_round + geo.grid - 1) / geo.grid * kCtTileVecs;
+  // a slice is dealt to the workgroups, and a workgroup's chunk to its wavefronts, in whole rows of 64 vectors
+  const uint32_t vecs_per_wg =
+      ((tiles_per_round * kCtTileVecs + geo.grid - 1) / geo.grid + kWave - 1) / kWave * kWave;
 
   // ---- this wavefront's share of the current round: rows of 64 vectors [row_lo, row_hi) of the
   // workgroup's chunk [wg_lo, wg_hi)
   const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
   uint32_t wg_lo = 0, wg_hi = 0, row_lo = 0, row_hi = 0;
+  uint32_t wave_hi = 0;  // first vector past this wavefront's rows
   bool do_head = false, do_tail = false;
   const uint32_t tail_base = geo.head + geo.n_vec * V;
 
@@ -362,7 +375,7 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     constexpr bool kAdd = EF && !DIRECT;
     auto load_rows = [&](Rows& buf, uint32_t row) {
       const uint32_t vec0 = wg_lo + row * kWave + lane;
-      if (wg_lo + (row + ROWS) * kWave <= wg_hi) {  // uniform: all rows inside the chunk
+      if (wg_lo + (row + ROWS) * kWave <= wave_hi) {  // uniform: all rows inside the wavefront's share
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
           buf.a[r] = ld_stream(&av[vec0 + r * kWave]);
@@ -372,18 +385,18 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
           const uint32_t vi = vec0 + r * kWave;
-          buf.a[r] = vi < wg_hi ? av[vi] : make_uint4(0, 0, 0, 0);
-          if constexpr (kAdd) buf.b[r] = vi < wg_hi ? bv[vi] : make_uint4(0, 0, 0, 0);
+          buf.a[r] = vi < wave_hi ? av[vi] : make_uint4(0, 0, 0, 0);
+          if constexpr (kAdd) buf.b[r] = vi < wave_hi ? bv[vi] : make_uint4(0, 0, 0, 0);
         }
       }
     };
     auto process_rows = [&](const Rows& buf, uint32_t row) {
       const uint32_t vec0 = wg_lo + row * kWave + lane;
-      const bool full = wg_lo + (row + ROWS) * kWave <= wg_hi;
+      const bool full = wg_lo + (row + ROWS) * kWave <= wave_hi;
 #pragma unroll
       for (int r = 0; r < ROWS; ++r) {
         const uint32_t vi = vec0 + r * kWave;
-        const bool in = full || vi < wg_hi;
+        const bool in = full || vi < wave_hi;
         uint32_t raw[V];
 #pragma unroll
         for (int e = 0; e < V; ++e) raw[e] = E::raw(buf.a[r], e);
@@ -428,9 +441,10 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
       wg_lo = min(slice_lo + wg * vecs_per_wg, slice_hi);
       wg_hi = min(wg_lo + vecs_per_wg, slice_hi);
       const uint32_t rows_total = (wg_hi - wg_lo + kWave - 1) / kWave;
-      const uint32_t rows_per_wave = ((rows_total + kCtWaves - 1) / kCtWaves + kCtRows - 1) / kCtRows * kCtRows;
+      const uint32_t rows_per_wave = (rows_total + kCtWaves - 1) / kCtWaves;
       row_lo = min(static_cast<uint32_t>(wave) * rows_per_wave, rows_total);
       row_hi = min(row_lo + rows_per_wave, rows_total);
+      wave_hi = min(wg_lo + row_hi * kWave, wg_hi);
       do_head = vwg == 0 && wave == 0 && geo.head != 0;
       do_tail = vwg == n_virtual - 1 && wave == kCtWaves - 1 && geo.tail != 0;
     }
@@ -537,7 +551,7 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
 }
 
 // Head / full vectors / tail split of n elements starting at address `addr`, and the chunking.
-CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt) {
+CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt, uint32_t wg_per_cu) {
   const uint32_t es = dt == DCT_F32 ? 4 : 2;
   const uint32_t vec = 16 / es;
   CompactGeom geo;
@@ -548,12 +562,26 @@ CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt) {
   geo.tail = static_cast<uint32_t>((n - head) % vec);
   uint32_t tiles = (geo.n_vec + kCtTileVecs - 1) / kCtTileVecs;
   if (tiles == 0) tiles = 1;
-  uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * kCtWgPerCu;
+  uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * wg_per_cu;
   if (max_grid > kCtMaxGrid) max_grid = kCtMaxGrid;
   const uint32_t tiles_per_wg = (tiles + max_grid - 1) / max_grid;
   geo.grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;
   geo.tiles = tiles;
   return geo;
+}
+
+// Workgroups of one instantiation that a CU holds at once, at most kCtWgPerCu (asked of the runtime once).
+// The kernel's waits are on lower-numbered workgroups of the same launch, and with several rounds a
+// workgroup also waits on every workgroup's earlier rounds: the whole grid has to be resident.
+template <int DT, bool EXACT, bool EF>
+uint32_t resident_per_cu() {
+  static const uint32_t cached = [] {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, compact_kernel<DT, EXACT, EF>, kCtThreads, 0) != hipSuccess)
+      nb = 0;
+    return static_cast<uint32_t>(std::min(std::max(nb, 0), static_cast<int>(kCtWgPerCu)));
+  }();
+  return cached;
 }
 
 }  // namespace
@@ -599,7 +627,13 @@ int launch_compact(const void* g, const void* e_in, void* e_out, int dt, uint64_
   }
   if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < kCtWsBytes) return DCT_ERR_WORKSPACE;
 
-  const CompactGeom geo = make_geom(reinterpret_cast<uintptr_t>(g), n, dt);
+  const bool exact = mode == DCT_EXACT_K;
+  const uint32_t per_cu = ef ? (exact ? resident_per_cu<DCT_F32, true, true>() : resident_per_cu<DCT_F32, false, true>())
+                          : dt == DCT_F32
+                              ? (exact ? resident_per_cu<DCT_F32, true, false>() : resident_per_cu<DCT_F32, false, false>())
+                              : (exact ? resident_per_cu<DCT_BF16, true, false>() : resident_per_cu<DCT_BF16, false, false>());
+  if (per_cu == 0) return DCT_ERR_HIP;
+  const CompactGeom geo = make_geom(reinterpret_cast<uintptr_t>(g), n, dt, per_cu);
   const uint32_t cap = capacity > 0xFFFFFFFFull ? 0xFFFFFFFFu : static_cast<uint32_t>(capacity);
   auto* hdr = static_cast<CompactHeader*>(d_ws);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);

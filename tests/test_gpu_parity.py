@@ -952,6 +952,16 @@ def test_mp_idx16_c5_block_matches_the_int32_form(dct):
     assert np.array_equal(host(dval), oracle.rowtopk_bwd_idx16(host(dy), eidx))
 
 
+@pytest.mark.parametrize("frac", [0.05, 0.25])
+def test_dp_ef_low_sparsity_levels(dct, frac):
+    """Error feedback with more survivors than the grid holds on chip: the compaction runs in several
+    rounds, in which every workgroup waits on all workgroups of the earlier rounds (both modes)."""
+    n = 5_000_011
+    g = si.gaussian_gradient(n, DEV, 2300)
+    e = si.residual_vector(n, DEV, 2301)
+    check_ef(dct, g, e, int(n * frac), in_place=False)
+
+
 # ------------------------------------------------------------------ side stream, HIP graph
 def test_calls_on_a_side_stream_and_in_a_captured_graph(dct):
     """The calls launch on the stream they are given and allocate nothing, so a training loop can
