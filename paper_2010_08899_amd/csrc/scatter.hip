@@ -25,6 +25,8 @@ namespace {
 constexpr int kScThreads = 256;
 constexpr uint32_t kScTileBytes = 16384;
 constexpr uint32_t kScMaxGrid = 2048;
+constexpr uint32_t kScAssignMaxGrid = 8192;
+constexpr uint32_t kScWgPerCu = 16;  // workgroups per CU of the assign kernel: two rounds of the resident ones
 constexpr uint32_t kRowLdsBytes = 16384;  // per wavefront in the on-chip row kernel
 
 // Pairs to apply: the survivor count clipped to what the buffers hold; the
@@ -66,42 +68,68 @@ __global__ __launch_bounds__(kScThreads) void scatter_assign_kernel(
   constexpr uint32_t TILE = kScTileBytes / sizeof(W);
   constexpr uint32_t VPT = kScTileBytes / 16 / kScThreads;  // 16-byte vectors per thread per tile
   constexpr uint32_t EPV = 16 / sizeof(W);
-  __shared__ uint4 s_tile4[kScTileBytes / 16];
-  W* s_tile = reinterpret_cast<W*>(s_tile4);
+  // two tile buffers, used in turn: a buffer is written into while the barrier since its last clearing
+  // is the one of the tile in between, so a tile costs one barrier
+  __shared__ uint4 s_tiles[2][kScTileBytes / 16];
+  __shared__ uint32_t s_batch_last;
 
   const uint32_t m = valid_pairs(count, capacity);
   const uint32_t n_tiles = (n + TILE - 1) / TILE;
   const uint32_t tile_lo = blockIdx.x * tiles_per_wg;
   const uint32_t tile_hi = min(tile_lo + tiles_per_wg, n_tiles);
   if (tile_lo >= tile_hi) return;
-  uint32_t p = lower_bound_wg(idx, m, tile_lo * TILE);
+  uint64_t p = lower_bound_wg(idx, m, tile_lo * TILE);
 
-  for (uint32_t v = 0; v < VPT; ++v) s_tile4[v * kScThreads + threadIdx.x] = make_uint4(0, 0, 0, 0);
+  // The pairs are taken from the list a batch at a time, one pair per thread, and the batch after it is
+  // already on its way: the tiles wait for no load (at c4's density a batch lasts a dozen tiles).
+  constexpr uint32_t kNone = 0xFFFFFFFFu;  // never inside a tile: n < 2^31
+  auto load_pair = [&](uint64_t first, uint32_t& pi, W& pv) {
+    const uint64_t j = first + threadIdx.x;
+    pi = j < m ? static_cast<uint32_t>(idx[j]) : kNone;
+    pv = j < m ? val[j] : static_cast<W>(0);
+  };
+  uint32_t bi, ni;
+  W bv, nv;
+  load_pair(p, bi, bv);
+  load_pair(p + kScThreads, ni, nv);
+  // index of the batch's last pair (kNone when the list ends inside the batch): once a tile reaches
+  // past it, the batch is used up
+  if (threadIdx.x == kScThreads - 1) s_batch_last = bi;
+  for (uint32_t v = 0; v < VPT; ++v) {
+    s_tiles[0][v * kScThreads + threadIdx.x] = make_uint4(0, 0, 0, 0);
+    s_tiles[1][v * kScThreads + threadIdx.x] = make_uint4(0, 0, 0, 0);
+  }
+  __syncthreads();
+
   for (uint32_t tile = tile_lo; tile < tile_hi; ++tile) {
     const uint32_t t0 = tile * TILE;
     const uint32_t len = min(TILE, n - t0);
-    __syncthreads();  // the tile buffer is all zeros again
+    uint4* tile4 = s_tiles[(tile - tile_lo) & 1u];
+    W* s_tile = reinterpret_cast<W*>(tile4);
     for (;;) {
-      const uint64_t j = static_cast<uint64_t>(p) + threadIdx.x;
-      bool in = false;
-      if (j < m) {
-        const uint32_t rel = static_cast<uint32_t>(idx[j]) - t0;
-        in = rel < len;
-        if (in) s_tile[rel] = val[j];
-      }
-      const uint32_t cnt = __syncthreads_count(in);  // also orders the LDS writes before the reads below
-      p += cnt;
-      if (cnt < kScThreads) break;
+      const uint32_t rel = bi - t0;
+      if (bi != kNone && rel < len) s_tile[rel] = bv;
+      const uint32_t last = s_batch_last;
+      if (last == kNone || last - t0 >= len) break;  // uniform; an index below t0 wraps to a huge value:
+                                                     // ascending lists never get there, others just stop here
+      // the whole batch lies at or before this tile: the prefetched one takes its place
+      __syncthreads();  // everybody has read s_batch_last
+      p += kScThreads;
+      bi = ni;
+      bv = nv;
+      load_pair(p + kScThreads, ni, nv);
+      if (threadIdx.x == kScThreads - 1) s_batch_last = bi;
+      __syncthreads();
     }
+    __syncthreads();  // the tile's values are in place
     // write the tile and clear what was read (each thread its own vectors)
     uint4* dst = reinterpret_cast<uint4*>(out + t0);
     if (len == TILE) {
 #pragma unroll
       for (uint32_t v = 0; v < VPT; ++v) {
         const uint32_t q = v * kScThreads + threadIdx.x;
-        const uint4 x = s_tile4[q];
-        st_stream(&dst[q], x.x, x.y, x.z, x.w);
-        s_tile4[q] = make_uint4(0, 0, 0, 0);
+        dst[q] = tile4[q];
+        tile4[q] = make_uint4(0, 0, 0, 0);
       }
     } else {
       for (uint32_t v = 0; v < VPT; ++v) {
@@ -110,7 +138,7 @@ __global__ __launch_bounds__(kScThreads) void scatter_assign_kernel(
           const uint32_t i = q * EPV + e;
           if (i < len) out[t0 + i] = s_tile[i];
         }
-        s_tile4[q] = make_uint4(0, 0, 0, 0);
+        tile4[q] = make_uint4(0, 0, 0, 0);
       }
     }
   }
@@ -228,8 +256,8 @@ extern "C" int dct_scatter(const int32_t* d_idx, const void* d_val, const uint64
   if (is_aligned(d_out, 16)) {
     const uint32_t tile = kScTileBytes / static_cast<uint32_t>(es);
     const uint32_t n_tiles = (n32 + tile - 1) / tile;
-    uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * 8u;
-    if (max_grid > kScMaxGrid) max_grid = kScMaxGrid;
+    uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * kScWgPerCu;
+    if (max_grid > kScAssignMaxGrid) max_grid = kScAssignMaxGrid;
     const uint32_t tiles_per_wg = (n_tiles + max_grid - 1) / max_grid;
     const uint32_t grid = (n_tiles + tiles_per_wg - 1) / tiles_per_wg;
     if (dt == DCT_F32) {
