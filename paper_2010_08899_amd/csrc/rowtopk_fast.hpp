@@ -314,6 +314,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     // six per stream, so that the second walk below needs no LDS reads.
     uint32_t listA = 0, listB = 0;
     bool list_full = false;
+    uint32_t n_pops = 0;  // pops of the longest stream (uniform)
     {
       uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
       uint32_t sh = 0;
@@ -331,6 +332,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
           list_full = true;
         }
         sh += 5u;
+        ++n_pops;
       }
     }
     wave_lds_fence();
@@ -354,10 +356,9 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     }
     const uint32_t bs = static_cast<uint32_t>(bstar);
     if (!list_full) {
-      // every stream popped at most six keys: replay the pops from the remembered bins, straight-line
+      // every stream popped at most six keys: replay the pops from the remembered bins (no LDS reads)
       uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
-#pragma unroll
-      for (int j = 0; j < 6; ++j) {
+      for (uint32_t j = 0; j < n_pops; ++j) {
         const uint32_t bitA = mA & (0u - mA);  // 0 once the stream is exhausted: contributes nothing
         mA ^= bitA;
         uint32_t bitB;
@@ -368,7 +369,9 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
           bitB = mA != 0 ? 0x80000000u >> __builtin_clz(mA) : 0u;
           mA ^= bitB;
         }
-        const uint32_t bA = (listA >> (5 * j)) & 31u, bB = (listB >> (5 * j)) & 31u;
+        const uint32_t bA = listA & 31u, bB = listB & 31u;
+        listA >>= 5;
+        listB >>= 5;
         keep[0] |= bA > bs ? bitA : 0u;
         tie[0] |= bA == bs ? bitA : 0u;
         keep[wB] |= bB > bs ? bitB : 0u;
@@ -565,22 +568,30 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
         }
       }
       wave_lds_fence();
-      if (k <= 4 * kWave) {
-        // up to four outputs per lane: all list reads first, then all value reads, then the stores
-        uint32_t col[4], raw[4];
+      // up to G outputs per lane: all list reads first, then all value reads, then the stores
+      auto write_groups = [&](auto g_tag) {
+        constexpr int G = decltype(g_tag)::value;
+        uint32_t col[G], raw[G];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) col[j] = j * kWave + lane < k ? *stage_at(j * kWave + lane) : 0u;
+        for (int j = 0; j < G; ++j) col[j] = j * kWave + lane < k ? *stage_at(j * kWave + lane) : 0u;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < G; ++j)
           raw[j] = raw_at_col(col[j]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < G; ++j) {
           const uint32_t o = j * kWave + lane;
           if (o < k) {
             put_col<ENC>(idx_out, o0 + o, col[j]);
             vo[o] = static_cast<word_t>(raw[j]);
           }
         }
+      };
+      if (k <= kWave) {
+        write_groups(std::integral_constant<int, 1>{});
+      } else if (k <= 2 * kWave) {
+        write_groups(std::integral_constant<int, 2>{});
+      } else if (k <= 4 * kWave) {
+        write_groups(std::integral_constant<int, 4>{});
       } else {
         for (uint32_t j = lane; j < k; j += kWave) {
           const uint32_t col = *stage_at(j);
