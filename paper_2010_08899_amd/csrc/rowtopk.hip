@@ -155,6 +155,20 @@ __global__ __launch_bounds__(256) void rowtopk_bwd_gather_kernel(const W* __rest
   }
 }
 
+// The same gather with one thread per output element over all rows: for k well below a workgroup's
+// 256 threads (narrow rows) the row-per-workgroup grid above leaves most threads idle.
+template <typename W, typename I>
+__global__ __launch_bounds__(256) void rowtopk_bwd_gather_flat_kernel(const W* __restrict__ dy, uint64_t n_out,
+                                                                     uint32_t D, uint64_t stride, uint32_t k,
+                                                                     const I* __restrict__ idx,
+                                                                     W* __restrict__ dval) {
+  const uint64_t o = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (o >= n_out) return;
+  const uint32_t b = static_cast<uint32_t>(o / k);  // B < 2^32
+  const uint32_t c = static_cast<uint32_t>(idx[o]);
+  dval[o] = c < D ? dy[static_cast<uint64_t>(b) * stride + c] : static_cast<W>(0);
+}
+
 // ---------------------------------------------------------------------------
 // Consumers of the bitmap form, one wavefront per row: column c of a 64-column
 // group belongs to lane c % 64; a ballot of the mask bits ranks the kept columns.
@@ -453,6 +467,20 @@ int launch_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stri
   const size_t es = dt == DCT_F32 ? 4 : 2;
   if (!is_aligned(dy, es) || !is_aligned(d_idx, sizeof(I)) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint64_t n_out = static_cast<uint64_t>(B) * k;
+  if (k < 192u && (n_out + 255) / 256 <= 0x7FFFFFFFull) {  // few outputs per row: one thread per output over all rows
+    const dim3 fgrid(static_cast<uint32_t>((n_out + 255) / 256));
+    if (dt == DCT_F32) {
+      hipLaunchKernelGGL((rowtopk_bwd_gather_flat_kernel<uint32_t, I>), fgrid, dim3(256), 0, s,
+                         static_cast<const uint32_t*>(dy), n_out, D, row_stride_elems, k, d_idx,
+                         static_cast<uint32_t*>(d_dval_out));
+    } else {
+      hipLaunchKernelGGL((rowtopk_bwd_gather_flat_kernel<uint16_t, I>), fgrid, dim3(256), 0, s,
+                         static_cast<const uint16_t*>(dy), n_out, D, row_stride_elems, k, d_idx,
+                         static_cast<uint16_t*>(d_dval_out));
+    }
+    return launch_status();
+  }
   const dim3 grid((k + 255) / 256, B < 65535u ? B : 65535u);
   if (dt == DCT_F32) {
     hipLaunchKernelGGL((rowtopk_bwd_gather_kernel<uint32_t, I>), grid, dim3(256), 0, s,
