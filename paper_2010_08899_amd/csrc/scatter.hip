@@ -210,6 +210,46 @@ __global__ __launch_bounds__(kScThreads) void rowscatter_lds_kernel(
   }
 }
 
+// Narrow dense rows (output row stride = D, whole 16-byte vectors): a wavefront assembles R consecutive
+// rows at once, R * D * sizeof(W) <= kRowLdsBytes, so that the fixed work per step covers 16 KiB of
+// output whatever the row width (one row per step left 512-byte rows at a quarter of the rate).
+template <typename W, typename I>
+__global__ __launch_bounds__(kScThreads) void rowscatter_block_kernel(
+    const I* __restrict__ idx, const W* __restrict__ val, uint32_t B, uint32_t D, uint32_t k,
+    W* __restrict__ out, uint32_t R) {
+  constexpr int kWaves = kScThreads / kWave;
+  constexpr uint32_t EPV = 16 / sizeof(W);
+  __shared__ uint4 s_rows[kWaves][kRowLdsBytes / 16];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane = lane_id();
+  uint4* blk4 = s_rows[wave];
+  W* blk = reinterpret_cast<W*>(blk4);
+  const uint32_t vpr = D / EPV;  // vectors per row
+  for (uint32_t q = lane; q < R * vpr; q += kWave) blk4[q] = make_uint4(0, 0, 0, 0);
+  for (uint64_t b0 = (static_cast<uint64_t>(blockIdx.x) * kWaves + wave) * R; b0 < B;
+       b0 += static_cast<uint64_t>(gridDim.x) * kWaves * R) {
+    const uint32_t rows = static_cast<uint32_t>(min(static_cast<uint64_t>(R), B - b0));
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t n_pairs = rows * k;  // the block's pairs are contiguous in idx / val
+    const I* bi = idx + b0 * k;
+    const W* bv = val + b0 * k;
+    for (uint32_t j = lane; j < n_pairs; j += kWave) {
+      const uint32_t r = j / k;
+      const uint32_t c = static_cast<uint32_t>(bi[j]);
+      if (c < D) blk[r * D + c] = bv[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    uint4* dst4 = reinterpret_cast<uint4*>(out + b0 * D);
+    for (uint32_t q = lane; q < rows * vpr; q += kWave) {
+      const uint4 x = blk4[q];
+      st_stream(&dst4[q], x.x, x.y, x.z, x.w);
+      blk4[q] = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
 // Dense rows of any width: a workgroup zeroes the row in global memory, waits for those stores, then
 // drops the values in.
 template <typename W, typename I>
@@ -302,6 +342,19 @@ int launch_rowscatter(const I* d_idx, const void* d_val, int dt, uint32_t B, uin
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
   if (static_cast<uint64_t>(D) * es <= kRowLdsBytes) {
     const bool vec_ok = is_aligned(d_out, 16) && (out_row_stride_elems * es) % 16 == 0 && (D * es) % 16 == 0;
+    const uint32_t rows_per_step = static_cast<uint32_t>(kRowLdsBytes / (D * es));
+    if (vec_ok && out_row_stride_elems == D && rows_per_step >= 2) {  // narrow dense rows: several per step
+      const uint32_t steps = (B + rows_per_step - 1) / rows_per_step;
+      const uint32_t bgrid = std::min<uint32_t>((steps + 3) / 4, resident);
+      if (dt == DCT_F32) {
+        hipLaunchKernelGGL((rowscatter_block_kernel<uint32_t, I>), dim3(bgrid), dim3(kScThreads), 0, s, d_idx,
+                           static_cast<const uint32_t*>(d_val), B, D, k, static_cast<uint32_t*>(d_out), rows_per_step);
+      } else {
+        hipLaunchKernelGGL((rowscatter_block_kernel<uint16_t, I>), dim3(bgrid), dim3(kScThreads), 0, s, d_idx,
+                           static_cast<const uint16_t*>(d_val), B, D, k, static_cast<uint16_t*>(d_out), rows_per_step);
+      }
+      return launch_status();
+    }
     const uint32_t grid = std::min<uint32_t>((B + 3) / 4, resident);
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((rowscatter_lds_kernel<uint32_t, I>), dim3(grid), dim3(kScThreads), 0, s, d_idx,

@@ -650,7 +650,10 @@ def test_scatter_after_error_feedback_conserves_the_gradient(dct):
 @pytest.mark.parametrize("dtype,B,D,k,pad", [
     (torch.float32, 33, 1024, 51, 0), (torch.float32, 5, 40, 6, 0), (torch.float32, 9, 1000, 50, 24),
     (torch.bfloat16, 64, 4096, 204, 0), (torch.bfloat16, 7, 520, 26, 8), (torch.bfloat16, 3, 12_000, 600, 0),
-    (torch.float32, 3, 5000, 250, 0), (torch.bfloat16, 10, 33, 33, 1)])
+    (torch.float32, 3, 5000, 250, 0), (torch.bfloat16, 10, 33, 33, 1),
+    # narrow dense rows: several rows per step, ragged last block, k = D
+    (torch.bfloat16, 1000, 256, 12, 0), (torch.bfloat16, 2077, 512, 25, 0), (torch.float32, 300, 128, 128, 0),
+    (torch.float32, 4097, 256, 13, 0), (torch.bfloat16, 129, 8, 3, 0)])
 def test_rowtopk_scatter(dct, dtype, B, D, k, pad):
     x = si.relu_activations(B, D, DEV, 900 + D, dtype=dtype)
     idx = torch.zeros(B, k, dtype=torch.int32, device=DEV)
