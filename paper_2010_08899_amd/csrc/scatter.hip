@@ -343,7 +343,7 @@ int launch_rowscatter(const I* d_idx, const void* d_val, int dt, uint32_t B, uin
   if (static_cast<uint64_t>(D) * es <= kRowLdsBytes) {
     const bool vec_ok = is_aligned(d_out, 16) && (out_row_stride_elems * es) % 16 == 0 && (D * es) % 16 == 0;
     const uint32_t rows_per_step = static_cast<uint32_t>(kRowLdsBytes / (D * es));
-    if (vec_ok && out_row_stride_elems == D && rows_per_step >= 2) {  // narrow dense rows: several per step
+    if (vec_ok && out_row_stride_elems == D && rows_per_step >= 8) {  // dense rows of up to 2 KiB: several per step
       const uint32_t steps = (B + rows_per_step - 1) / rows_per_step;
       const uint32_t bgrid = std::min<uint32_t>((steps + 3) / 4, resident);
       if (dt == DCT_F32) {
