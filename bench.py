@@ -142,6 +142,15 @@ def main():
     x5[1] = si.relu_activations(c5_b, si.C5_D, dev, si.BASE_SEED + 50, dtype=torch.bfloat16)
     dy5[1] = si.normal_matrix(c5_b, si.C5_D, dev, si.BASE_SEED + 51, dtype=torch.bfloat16)
     B5, D5 = x5[0].shape
+    def checksum(t):
+        """64-bit sum of the tensor's words (wraps): identifies the generated bytes."""
+        w = t.reshape(-1).view(torch.int32 if t.element_size() == 4 else torch.int16)
+        return int(w.sum(dtype=torch.int64).item()) & ((1 << 64) - 1)
+
+    inputs = {"torch": torch.__version__, "base_seed": si.BASE_SEED,
+              "checksums": {"c4_g": [checksum(g4[0]), checksum(g4[1])], "c5_x": [checksum(x5[0]), checksum(x5[1])],
+                            "c5_dy": [checksum(dy5[0]), checksum(dy5[1])]},
+              "c4_nonzero_rows": (c4_rows * 5) // 100}
     torch.cuda.synchronize()
     log(f"[bench] inputs resident in {time.time() - t0:.1f}s: c4 N={n4} k={k4}; c5 {B5}x{D5} bf16 k={k5}")
 
@@ -438,6 +447,7 @@ def main():
                    "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
         "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls, "bitmask_calls": bm_calls, "idx16_calls": i16_calls,
         "batched_small_tensors": batched, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
+        "inputs": inputs,
     }
     print(json.dumps(out), flush=True)
 

@@ -40,9 +40,16 @@
 // the outputs keeps its value in the residual.  The second-pass fallback re-reads
 // w from the new residual, which also makes updating the residual in place safe.
 //
-// A workgroup only ever waits for workgroups with a lower index, which start
-// earlier; the waits are bounded all the same and a wait that runs out is reported
-// through the count.  The workspace holds two descriptor sets used by alternate
+// With error feedback the vector is also cut into up to 8 slices when it would not
+// have to be: the drains between slices keep the workgroups in step, and a kernel
+// that writes a third of what it reads runs faster when its accesses stay within a
+// narrow window of the vector (c4: 603 us in 8 slices against 661 us in one).
+//
+// A workgroup only ever waits for workgroups with a lower index (and, from the
+// second round on, for every workgroup's earlier rounds), so the whole grid has to
+// be resident: the kernel is compiled for four wavefronts per SIMD and the grid is
+// sized from the occupancy the runtime reports.  The waits are bounded all the
+// same and a wait that runs out is reported through the count.  The workspace holds two descriptor sets used by alternate
 // calls (an epoch word picks the set): every call clears the other set for its
 // successor and the last workgroup advances the epoch, so a call is one launch.
 #include <algorithm>
