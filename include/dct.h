@@ -103,6 +103,16 @@ int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_thre
  *                dct_threshold_compact_workspace_init.  Each call leaves it
  *                initialised again, so it can be reused call after call on the same
  *                stream.  Two calls that share a workspace must not overlap.
+ *
+ * Concurrency.  The kernel's workgroups exchange their counts while they run, so its
+ * whole grid (at most four workgroups per CU) has to be on the chip together.  Run
+ * alone on the device that is always so.  When other kernels hold CUs at the same
+ * time (another stream), a call that needs several rounds -- more than about four
+ * million survivors, or any dct_ef_threshold_compact on a large vector -- may find
+ * part of its grid waiting for room; its waits are bounded, and if one runs out the
+ * call ends with *d_count_out = DCT_COUNT_WORKSPACE_ERROR (no output is valid, the
+ * workspace has to be initialised again), it does not hang.  Keep such calls from
+ * overlapping with other work, e.g. by issuing them on one stream.
  */
 size_t dct_threshold_compact_workspace_bytes(int dt, uint64_t n);
 int dct_threshold_compact_workspace_init(void* d_ws, size_t ws_bytes, void* hip_stream);
