@@ -9,6 +9,7 @@
 
 #include "dct_common.hpp"
 #include "rowtopk_fast.hpp"
+#include "rowtopk_quad.hpp"
 
 namespace dct {
 namespace {
@@ -16,6 +17,7 @@ namespace {
 constexpr int kRtThreads = 256;
 constexpr int kRtWaves = kRtThreads / kWave;
 constexpr int kRtBins = 2048;
+constexpr uint32_t kQuadMinRows = 8192;  // below this the one-row-per-wavefront kernel has more wavefronts to offer
 
 // ---------------------------------------------------------------------------
 // Generic forward kernel: one wavefront per row, any D, any row stride, rows
@@ -329,6 +331,35 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   if (grid > 65536u * 4) grid = 65536u * 4;
   // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 4096 columns
   const uint32_t epv = static_cast<uint32_t>(16 / es);
+  // narrow bf16 rows, many of them: four rows per wavefront (index encodings; the four lists share 512 staging slots)
+  if (dt == DCT_BF16 && enc != kEncBitmap && D % 8 == 0 && D <= quad::kMaxD && 4 * k <= quad::kStageSlots &&
+      B >= kQuadMinRows && is_aligned(x, 16) && row_stride_elems % 8 == 0) {
+    const uint32_t vecs = D / 8;
+    const uint32_t nv = vecs <= 16 ? 1u : vecs <= 32 ? 2u : vecs <= 64 ? 4u : 8u;
+    const uint32_t groups = (B + quad::kRows - 1) / quad::kRows;
+    uint32_t qgrid = (groups + quad::kWaves - 1) / quad::kWaves;
+    // workgroups per CU that registers and the LDS row buffers allow
+    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * (nv == 8 ? 4u : nv == 4 ? 6u : 8u);
+    if (qgrid > resident) qgrid = resident;
+    const auto* xq = static_cast<const uint16_t*>(x);
+    auto* vq = static_cast<uint16_t*>(d_val_out);
+    auto* tq = static_cast<uint16_t*>(d_tau_out);
+#define DCT_LAUNCH_QUAD(NVV, ENCV)                                                                              \
+  hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV>), dim3(qgrid), dim3(quad::kThreads), 0, s, xq, B, \
+                     D, row_stride_elems, k, io, vq, tq)
+#define DCT_LAUNCH_QUAD_NV(ENCV)                  \
+  do {                                            \
+    if (nv == 1) DCT_LAUNCH_QUAD(1, ENCV);        \
+    else if (nv == 2) DCT_LAUNCH_QUAD(2, ENCV);   \
+    else if (nv == 4) DCT_LAUNCH_QUAD(4, ENCV);   \
+    else DCT_LAUNCH_QUAD(8, ENCV);                \
+  } while (0)
+    if (enc == kEncIdx16) DCT_LAUNCH_QUAD_NV(kEncIdx16);
+    else DCT_LAUNCH_QUAD_NV(kEncIdx32);
+#undef DCT_LAUNCH_QUAD_NV
+#undef DCT_LAUNCH_QUAD
+    return launch_status();
+  }
   if (D % epv == 0 && D <= 4096u && is_aligned(x, 16) && row_stride_elems % epv == 0) {
     uint32_t fgrid = (B + fast::kWaves - 1) / fast::kWaves;
     // workgroups per CU that registers and the LDS row buffers allow (rows of up to 2 / 4 / 8 / 16 KiB)

@@ -1,0 +1,448 @@
+// Forward kernel of dct_rowtopk_fwd (Algorithm 2, forward loop: per row the k largest
+// |X_act,i|) for NARROW bf16 rows: up to 1024 columns, four rows per wavefront.
+//
+// The one-row-per-wavefront kernel (rowtopk_fast.hpp) spends about 250 vector instructions
+// per row on work that does not depend on the row's width (wave scans, the walks over the
+// window keys and the survivors, the output code), which is what limits it below 2048
+// columns.  Here every row of a group of four consecutive rows lives on one DPP row of 16
+// lanes: the per-lane work (packed 16-bit compares, bitmaps, bit walks) is the same code, the
+// per-row reductions and scans are DPP operations inside the 16 lanes, and the fixed work is
+// paid once per four rows.  What is uniform per row (the threshold, the counts, the window)
+// is held per lane, equal within a row.
+//
+// The search for tau_i is the windowed one of the wide kernel: the row four rows earlier (the
+// same slot of the previous group) predicts a window of 32 key values; two compare sweeps give
+// the bitmaps at its ends, the keys inside it are histogrammed (32 LDS bins per row).  The
+// prediction is a running mean of the slot's thresholds (narrow rows vary more from one to
+// the next than wide ones); a wavefront's first group predicts from a sample of each row.
+// Rows whose window misses gallop away from it and are then bracketed by bisection over the
+// window positions, in lock step for the four rows.
+#pragma once
+
+#include "dct_common.hpp"
+#include "rowtopk_fast.hpp"
+
+namespace dct {
+namespace quad {
+
+using fast::kSampleRegs;
+using fast::kWindow;
+using fast::pk_add_u16;
+using fast::pk_lshr15_u16;
+using fast::pk_sub_u16;
+using fast::wave_lds_fence;
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kRows = 4;               // rows per wavefront
+constexpr int kLanes = kWave / kRows;  // lanes per row: one DPP row
+constexpr uint32_t kMaxD = 1024;
+constexpr uint32_t kStageSlots = kWave * 8;  // survivor columns of the four rows: 4 k <= kStageSlots
+
+// Sum over the 16 lanes of a DPP row, delivered to every lane of the row.
+__device__ __forceinline__ uint32_t row_sum(uint32_t x) {
+  uint32_t v = x;
+  v += __builtin_amdgcn_update_dpp(0u, v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x141, 0xf, 0xf, false);  // row_half_mirror
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x140, 0xf, 0xf, false);  // row_mirror
+  return v;
+}
+// Inclusive prefix sum over the lanes of a DPP row (lower lanes first).
+__device__ __forceinline__ uint32_t row_incl_scan(uint32_t x) {
+  uint32_t v = x;
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  return v;
+}
+// Inclusive suffix sum over the lanes of a DPP row (this lane and the higher ones).
+__device__ __forceinline__ uint32_t row_suffix_scan(uint32_t x) {
+  uint32_t v = x;
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x101, 0xf, 0xf, false);  // row_shl:1
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x102, 0xf, 0xf, false);  // row_shl:2
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x104, 0xf, 0xf, false);  // row_shl:4
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x108, 0xf, 0xf, false);  // row_shl:8
+  return v;
+}
+// The 16 ballot bits of this lane's row.
+__device__ __forceinline__ uint32_t row_ballot(bool p, uint32_t lane) {
+  return static_cast<uint32_t>(ballot64(p) >> (lane & 48u)) & 0xFFFFu;
+}
+
+// NV = 16-byte vectors per lane: a lane owns NV * 8 contiguous columns, a row 16 * NV * 8.
+// ENC (RowEnc): kEncIdx32 or kEncIdx16.
+template <int NV, int ENC>
+__global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
+    const uint16_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, void* __restrict__ idx_out,
+    uint16_t* __restrict__ val_out, uint16_t* __restrict__ tau_out) {
+  static_assert(ENC == kEncIdx32 || ENC == kEncIdx16, "index encodings only");
+  constexpr int COLS = NV * 8;                  // columns per lane
+  constexpr int REGS = COLS / 2;                // packed key registers per lane (2 columns each)
+  constexpr int RPW = REGS < 16 ? REGS : 16;    // registers per bitmap word
+  constexpr int WORDS = (REGS + 15) / 16;
+  static_assert(WORDS <= 2, "a lane owns at most 64 columns");
+  constexpr int CHUNK = (NV + 1) * 16;          // LDS bytes per lane chunk (16 bytes of padding)
+  constexpr int kColsPerWord = 2 * RPW;
+  constexpr int wB = WORDS - 1;
+  __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
+  __shared__ uint32_t s_hist[kWaves][kRows][kWindow];
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane = lane_id();
+  const uint32_t g = lane / kLanes, s = lane % kLanes;  // row of the group, lane of the row
+  char* row_lds = reinterpret_cast<char*>(s_row[wave]);
+  uint32_t* hist = s_hist[wave][g];
+  const uint32_t n_vec = D / 8;  // the host guarantees whole 16-byte vectors, n_vec <= 16 * NV
+
+  // 16-bit key material of local column lc of this lane
+  auto key_at = [&](uint32_t lc) {
+    return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(row_lds + lane * CHUNK + lc * 2));
+  };
+  // the stored element of column col of row rg of the group, bit for bit
+  auto raw_at = [&](uint32_t rg, uint32_t col) -> uint32_t {
+    return *reinterpret_cast<const uint16_t*>(row_lds + (rg * kLanes + col / COLS) * CHUNK + (col % COLS) * 2);
+  };
+  // the 16 padding bytes of every lane chunk hold the ordered lists of surviving columns (row rg at rg * k)
+  auto stage_at = [&](uint32_t slot) {
+    return reinterpret_cast<uint16_t*>(row_lds + (slot >> 3) * CHUNK + NV * 16 + (slot & 7u) * 2);
+  };
+
+  constexpr uint32_t kNone = 0xFFFFFFFFu;
+  uint32_t guess = kNone;  // tau of this lane's row slot in the previous group; none yet
+
+  const uint64_t n_groups = (static_cast<uint64_t>(B) + kRows - 1) / kRows;
+  const uint64_t group_step = static_cast<uint64_t>(gridDim.x) * kWaves;
+  uint64_t grp = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
+  uint4 nxt[NV];
+  auto load_group = [&](uint64_t gi) {
+    const uint64_t row = gi * kRows + g;
+    const uint4* xr = reinterpret_cast<const uint4*>(x + row * stride);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const uint32_t q = j * kLanes + s;
+      nxt[j] = (row < B && q < n_vec) ? ld_stream(&xr[q]) : make_uint4(0, 0, 0, 0);
+    }
+  };
+  if (grp < n_groups) load_group(grp);
+
+  for (; grp < n_groups; grp += group_step) {
+    const uint64_t my_row = grp * kRows + g;
+    // ---- 1. rows -> LDS (padded) -> registers, lane-contiguous within each row
+    wave_lds_fence();  // the previous group's readers are done with the buffer
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const uint32_t q = j * kLanes + s;
+      *reinterpret_cast<uint4*>(row_lds + (g * kLanes + q / NV) * CHUNK + (q % NV) * 16) = nxt[j];
+    }
+    wave_lds_fence();
+    if (grp + group_step < n_groups) load_group(grp + group_step);
+    uint32_t R[4 * NV];
+#pragma unroll
+    for (int m = 0; m < NV; ++m) {
+      const uint4 v = *reinterpret_cast<const uint4*>(row_lds + lane * CHUNK + m * 16);
+      R[4 * m + 0] = v.x;
+      R[4 * m + 1] = v.y;
+      R[4 * m + 2] = v.z;
+      R[4 * m + 3] = v.w;
+    }
+    // K[RPW*w + i] = 16-bit keys of columns (2*RPW*w + i, 2*RPW*w + RPW + i), bit 15 of each half set
+    uint32_t K[REGS];
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) {
+#pragma unroll
+      for (int i = 0; i < RPW; ++i) {
+        const uint32_t a = R[RPW * w + i / 2], b2 = R[RPW * w + RPW / 2 + i / 2];
+        const uint32_t pair = __builtin_amdgcn_perm(b2, a, (i & 1) ? 0x07060302u : 0x05040100u);
+        K[RPW * w + i] = (pair & 0x7FFF7FFFu) | 0x80008000u;
+      }
+    }
+
+    // per-lane bitmap of the keys >= t (t <= 0x8000; t may differ from row to row)
+    auto ge_bitmap = [&](uint32_t t, uint32_t* out) {
+      const uint32_t t2 = t | (t << 16);
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) {
+        uint32_t a = 0;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i)
+          a = ((a >> 1) & ~0x80008000u) | (pk_sub_u16(K[RPW * w + i], t2) & 0x80008000u);
+        out[w] = RPW == 16 ? a : (((a & 0xFFFFu) >> (16 - RPW)) | ((a >> (32 - 2 * RPW)) & ~((1u << RPW) - 1u)));
+      }
+    };
+    // number of keys >= t in this lane's row
+    auto count_ge = [&](uint32_t t) {
+      const uint32_t t2 = t | (t << 16);
+      uint32_t acc = 0;
+#pragma unroll
+      for (int i = 0; i < REGS; ++i) acc = pk_add_u16(acc, pk_lshr15_u16(pk_sub_u16(K[i], t2)));
+      return row_sum((acc & 0xFFFFu) + (acc >> 16));
+    };
+    // two independent bit streams per step (see the wide kernel)
+    auto pop2 = [&](uint32_t& mA, uint32_t& mB, bool& vA, uint32_t& cA, bool& vB, uint32_t& cB) {
+      vA = mA != 0;
+      cA = vA ? __builtin_ctz(mA) : 0u;
+      mA &= mA - 1;
+      if constexpr (WORDS == 2) {
+        vB = mB != 0;
+        cB = kColsPerWord + (vB ? __builtin_ctz(mB) : 0u);
+        mB &= mB - 1;
+      } else {
+        vB = mA != 0;
+        cB = vB ? 31u - __builtin_clz(mA) : 0u;
+        mA &= ~(vB ? (1u << cB) : 0u);
+      }
+    };
+
+    // ---- 2. locate tau of every row
+    uint32_t above[WORDS], inwin[WORDS];
+    uint32_t wlo = 0, n_above = 0, n_win = 0;
+    auto window_at = [&](uint32_t lo_end) {
+      wlo = lo_end;
+      uint32_t lo_bits[WORDS];
+      ge_bitmap(wlo, lo_bits);
+      ge_bitmap(wlo + kWindow, above);
+      uint32_t ca = 0, cw = 0;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) {
+        inwin[w] = lo_bits[w] & ~above[w];
+        ca += __popc(above[w]);
+        cw += __popc(inwin[w]);
+      }
+      const uint32_t both = row_sum(ca | (cw << 16));  // each count is at most 1024
+      n_above = both & 0xFFFFu;
+      n_win = both >> 16;
+    };
+    if (guess == kNone && REGS > kSampleRegs) {
+      // no previous group (uniform): estimate tau as the matching order statistic of a sample of the row
+      // (kSampleRegs registers of every lane), by bisection over all 15 key bits
+      const uint32_t ks = max(1u, (k * kSampleRegs + REGS - 1) / REGS);
+      uint32_t t = 0;
+      for (int bit = 14; bit >= 0; --bit) {
+        const uint32_t cand = t | (1u << bit);
+        const uint32_t t2 = cand | (cand << 16);
+        uint32_t acc = 0;
+#pragma unroll
+        for (int i = 0; i < kSampleRegs; ++i) acc = pk_add_u16(acc, pk_lshr15_u16(pk_sub_u16(K[i], t2)));
+        if (row_sum((acc & 0xFFFFu) + (acc >> 16)) >= ks) t = cand;
+      }
+      guess = t;
+    }
+    const bool have = guess != kNone;
+    {
+      uint32_t lo_end = have ? (guess >= kWindow / 2 ? guess - kWindow / 2 : 0u) : 0u;
+      lo_end = min(lo_end, 0x8000u - kWindow);
+      window_at(lo_end);
+    }
+    bool hit = have && n_above < k && k <= n_above + n_win;
+    if (ballot64(!hit) != 0) {
+      // Brackets in units of the window width, per row: count_ge(lo_u * width) >= k > count_ge(hi_u * width).
+      // Rows that hit take no part (their bracket is closed from the start).  Every count is taken by all
+      // four rows together; a row that does not need it probes a harmless position and ignores the result.
+      uint32_t lo_u = 0, hi_u = 0x8000u / kWindow;
+      const bool up = n_above >= k;  // tau is at or above the failed window's upper end
+      bool gallop = have && !hit;
+      if (gallop) {
+        if (up) lo_u = (wlo + kWindow) / kWindow;   // rounded down: still has >= k keys at or above it
+        else hi_u = (wlo + kWindow - 1) / kWindow;  // rounded up: still has < k keys at or above it
+      }
+      if (hit) hi_u = lo_u + 1;
+      // gallop away from the failed window in the direction the counts point to: most misses are near misses
+      for (uint32_t step = 1; ballot64(gallop) != 0; step *= 2) {
+        const uint32_t probe = up ? min(lo_u + step, hi_u) : (hi_u > step ? hi_u - step : 0u);
+        const uint32_t c = count_ge(probe * kWindow);
+        if (gallop) {
+          if (up) {
+            if (probe == hi_u) gallop = false;
+            else if (c >= k) lo_u = probe;
+            else { hi_u = probe; gallop = false; }
+          } else {
+            if (probe == 0u) gallop = false;
+            else if (c < k) hi_u = probe;
+            else { lo_u = probe; gallop = false; }
+          }
+        }
+      }
+      while (ballot64(hi_u - lo_u > 1) != 0) {
+        const uint32_t mid = (lo_u + hi_u) / 2;
+        const uint32_t c = count_ge(mid * kWindow);  // every lane of the row agrees
+        if (hi_u - lo_u > 1) {
+          if (c >= k) lo_u = mid; else hi_u = mid;
+        }
+      }
+      window_at(hit ? wlo : lo_u * kWindow);  // a row that had hit gets its window again
+    }
+
+    // histogram of the keys inside the window: bin = key - wlo, 32 bins per row
+    s_hist[wave][lane / 32][lane % 32] = 0;
+    s_hist[wave][2 + lane / 32][lane % 32] = 0;
+    wave_lds_fence();
+    uint32_t listA = 0, listB = 0;
+    bool list_full = false;
+    uint32_t n_pops = 0;
+    {
+      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+      uint32_t sh = 0;
+      while (ballot64((mA | mB) != 0) != 0) {
+        bool vA, vB;
+        uint32_t cA, cB;
+        pop2(mA, mB, vA, cA, vB, cB);
+        const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
+        if (vA) atomicAdd(&hist[bA], 1u);
+        if (vB) atomicAdd(&hist[bB], 1u);
+        if (sh < 30u) {
+          listA |= (vA ? bA : 0u) << sh;
+          listB |= (vB ? bB : 0u) << sh;
+        } else {
+          list_full = true;
+        }
+        sh += 5u;
+        ++n_pops;
+      }
+    }
+    wave_lds_fence();
+    // lane s of a row holds bins s and 16 + s; suffix sums over the 32 bins of the row
+    const uint32_t c_lo = hist[s], c_hi = hist[kLanes + s];
+    const uint32_t suf_hi = row_suffix_scan(c_hi);
+    const uint32_t suf_lo = row_sum(c_hi) + row_suffix_scan(c_lo);
+    const uint32_t m_hi = row_ballot(n_above + suf_hi >= k, lane);
+    const uint32_t m_lo = row_ballot(n_above + suf_lo >= k, lane);  // non-empty: bin 0 reaches n_above + n_win >= k
+    const bool upper = m_hi != 0;
+    const uint32_t bstar = upper ? kLanes + (31u - __builtin_clz(m_hi)) : 31u - __builtin_clz(m_lo | 1u);
+    const int src = static_cast<int>((lane & 48u) | (bstar & 15u));
+    const uint32_t n_eq = __shfl(upper ? c_hi : c_lo, src, kWave);
+    const uint32_t sfx = __shfl(upper ? suf_hi : suf_lo, src, kWave);
+    const uint32_t tau = wlo + bstar;
+    const uint32_t n_gt = n_above + sfx - n_eq;
+    const uint32_t quota = k - n_gt;  // ties at tau to keep, lowest columns first
+    // the prediction for the next group's row in this slot: a running mean, which varies less than single rows do
+    guess = have ? (3u * guess + tau + 2u) / 4u : tau;
+
+    // ---- keep / tie bitmaps: above the window, plus the window keys compared with tau
+    uint32_t keep[WORDS], tie[WORDS];
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) {
+      keep[w] = above[w];
+      tie[w] = 0;
+    }
+    const uint32_t bs = bstar;
+    if (ballot64(list_full) == 0) {
+      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+      for (uint32_t j = 0; j < n_pops; ++j) {
+        const uint32_t bitA = mA & (0u - mA);  // 0 once the stream is exhausted: contributes nothing
+        mA ^= bitA;
+        uint32_t bitB;
+        if constexpr (WORDS == 2) {
+          bitB = mB & (0u - mB);
+          mB ^= bitB;
+        } else {
+          bitB = mA != 0 ? 0x80000000u >> __builtin_clz(mA) : 0u;
+          mA ^= bitB;
+        }
+        const uint32_t bA = listA & 31u, bB = listB & 31u;
+        listA >>= 5;
+        listB >>= 5;
+        keep[0] |= bA > bs ? bitA : 0u;
+        tie[0] |= bA == bs ? bitA : 0u;
+        keep[wB] |= bB > bs ? bitB : 0u;
+        tie[wB] |= bB == bs ? bitB : 0u;
+      }
+    } else {
+      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+      while (ballot64((mA | mB) != 0) != 0) {
+        bool vA, vB;
+        uint32_t cA, cB;
+        pop2(mA, mB, vA, cA, vB, cB);
+        const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
+        const uint32_t mkA = 1u << cA, mkB = 1u << (cB & 31u);
+        keep[0] |= (vA && bA > bs) ? mkA : 0u;
+        tie[0] |= (vA && bA == bs) ? mkA : 0u;
+        keep[wB] |= (vB && bB > bs) ? mkB : 0u;
+        tie[wB] |= (vB && bB == bs) ? mkB : 0u;
+      }
+    }
+
+    // ---- 3. ties: the `quota` lowest columns among the n_eq ties of a row survive
+    {
+      uint32_t tc = 0;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
+      const bool trim = quota < n_eq;  // per row
+      if (ballot64(trim) != 0) {
+        const uint32_t before = row_incl_scan(tc) - tc;               // ties in lower lanes of the row
+        const uint32_t allowed = quota > before ? quota - before : 0u;  // ties this lane may keep
+        if (trim) {
+          // lanes below the boundary keep all their ties, lanes above it none; the one lane on the
+          // boundary drops its highest columns until `allowed` ties are left
+#pragma unroll
+          for (int w = 0; w < WORDS; ++w) tie[w] = allowed != 0 ? tie[w] : 0u;
+          if (allowed != 0 && allowed < tc) {
+            for (uint32_t drop = tc - allowed; drop != 0; --drop) {
+              if (WORDS == 2 && tie[wB] != 0)
+                tie[wB] ^= 0x80000000u >> __builtin_clz(tie[wB]);
+              else
+                tie[0] ^= 0x80000000u >> __builtin_clz(tie[0]);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) keep[w] |= tie[w];
+    }
+
+    // ---- 4. write the survivors: slot = survivors in lower lanes of the row + at lower columns of this lane
+    uint32_t kc = 0;
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
+    const uint32_t slot = row_incl_scan(kc) - kc;
+    {
+      const uint32_t base = g * k;  // this row's list
+      uint32_t mA = keep[0], mB = WORDS == 2 ? keep[wB] : 0u;
+      uint32_t slotA = slot, slotB = WORDS == 2 ? slot + __popc(keep[0]) : slot + kc - 1u;
+      while (ballot64((mA | mB) != 0) != 0) {
+        bool vA, vB;
+        uint32_t cA, cB;
+        pop2(mA, mB, vA, cA, vB, cB);
+        if (vA && slotA < k) *stage_at(base + slotA) = static_cast<uint16_t>(s * COLS + cA);
+        if (vB && slotB < k) *stage_at(base + slotB) = static_cast<uint16_t>(s * COLS + cB);
+        ++slotA;
+        slotB += WORDS == 2 ? 1u : 0xFFFFFFFFu;
+      }
+    }
+    wave_lds_fence();
+    // the four rows are consecutive, so their k outputs each form one block of 4 k entries
+    {
+      const uint64_t row0 = grp * kRows;
+      const uint32_t rows_here = static_cast<uint32_t>(min(static_cast<uint64_t>(kRows), B - row0));
+      if (k <= kWave) {
+        uint32_t col[kRows], raw[kRows];
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) col[r] = lane < k ? *stage_at(r * k + lane) : 0u;
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) raw[r] = raw_at(r, col[r]);
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+          if (static_cast<uint32_t>(r) < rows_here && lane < k) {
+            const uint64_t o = (row0 + r) * k + lane;
+            put_col<ENC>(idx_out, o, col[r]);
+            val_out[o] = static_cast<uint16_t>(raw[r]);
+          }
+        }
+      } else {
+        for (uint32_t r = 0; r < rows_here; ++r) {
+          for (uint32_t j = lane; j < k; j += kWave) {
+            const uint32_t col = *stage_at(r * k + j);
+            const uint64_t o = (row0 + r) * k + j;
+            put_col<ENC>(idx_out, o, col);
+            val_out[o] = static_cast<uint16_t>(raw_at(r, col));
+          }
+        }
+      }
+    }
+    if (tau_out && s == 0 && my_row < B) tau_out[my_row] = static_cast<uint16_t>(tau);
+  }
+}
+
+}  // namespace quad
+}  // namespace dct

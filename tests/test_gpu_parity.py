@@ -867,6 +867,40 @@ def test_mp_bitmask_c5_block(dct):
     assert np.array_equal(host(dval), oracle.rowtopk_bwd_bitmask(host(dy), emask, k))
 
 
+# ------------------------------------------------------------------ MP: many narrow bf16 rows (four rows per wavefront)
+@pytest.mark.parametrize("B,D,k,pad,idx16", [
+    (8192, 256, 12, 0, False), (8193, 512, 25, 0, False), (10_000, 1024, 51, 0, False), (8200, 128, 6, 0, True),
+    (9001, 264, 13, 8, False), (8192, 1000, 128, 0, False), (8195, 64, 64, 0, True), (8190 + 9, 8, 3, 0, False),
+    (8192, 1024, 1, 0, False), (8194, 520, 100, 16, True)])
+def test_mp_many_narrow_rows(dct, B, D, k, pad, idx16):
+    x = si.relu_activations(B, D, DEV, 1900 + D + k, dtype=torch.bfloat16, row_stride=D + pad if pad else None)
+    # hard rows among the ordinary ones, spread over the slots of a group of four: all equal, all zero, two
+    # values alternating, few distinct values, NaN, signed, ties straddling the quota
+    gen = torch.Generator(device=DEV).manual_seed(77)
+    cols = torch.arange(D, device=DEV)
+    x[0] = 0.75
+    x[5] = 0.0
+    x[10] = torch.where(cols % 2 == 0, 1.0, 2.0).to(torch.bfloat16)
+    x[15] = (cols % 7).to(torch.bfloat16)
+    x[16] = torch.randn(D, device=DEV, generator=gen).to(torch.bfloat16)
+    x[17, D // 2] = float("nan")
+    x[22] = -x[23].clone()
+    x[B - 1] = 3.0
+    x[B - 2] = (cols % 3).to(torch.bfloat16)
+    idx = torch.full((B, k), -1, dtype=torch.int16 if idx16 else torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=torch.bfloat16, device=DEV)
+    tau = torch.zeros(B, dtype=torch.bfloat16, device=DEV)
+    (dct.dct_rowtopk_fwd_idx16 if idx16 else dct.dct_rowtopk_fwd)(x, k, idx, val, tau)
+    xh = host(x.contiguous()) if not pad else oracle.as_numpy(x.cpu())
+    eidx, eval_, etau = oracle.rowtopk_fwd(xh, k)
+    got = idx.cpu().numpy()
+    got = got.view(np.uint16).astype(np.int32) if idx16 else got
+    bad = np.nonzero((got != eidx).any(axis=1))[0]
+    assert bad.size == 0, (bad[:10], got[bad[0]], eidx[bad[0]])
+    assert np.array_equal(bits(host(val).reshape(-1)), bits(eval_.reshape(-1)))
+    assert np.array_equal(bits(host(tau)), bits(etau))
+
+
 # ------------------------------------------------------------------ Algorithm 2, the mask as 16-bit indices
 def _u16(t):
     return t.cpu().numpy().view(np.uint16)
