@@ -248,6 +248,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     };
     // Brackets in units of the window width: count_ge(lo_u * width) >= k > count_ge(hi_u * width).
     uint32_t lo_u = 0, hi_u = 0x8000u / kWindow;
+    const bool had_guess = guess != 0xFFFFFFFFu;  // a previous row of this wavefront (not the sample estimate)
     if (guess == 0xFFFFFFFFu && REGS > kSampleRegs) {
       // no previous row: estimate tau as the matching order statistic of a sample of the row
       // (kSampleRegs registers of every lane), by bisection over all 15 key bits
@@ -345,7 +346,9 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     const uint32_t n_eq = __builtin_amdgcn_readlane(c, bstar);
     const uint32_t n_gt = n_above + __builtin_amdgcn_readlane(suffix, bstar) - n_eq;
     const uint32_t quota = k - n_gt;  // ties at tau to keep, lowest columns first
-    guess = tau;
+    // the next row's prediction: a running mean of the thresholds seen, which misses less often than the
+    // last row's alone (narrow rows vary a lot from one to the next)
+    guess = had_guess ? (3u * guess + tau + 2u) / 4u : tau;
 
     // ---- keep / tie bitmaps: above the window, plus the window keys compared with tau
     uint32_t keep[WORDS], tie[WORDS];
