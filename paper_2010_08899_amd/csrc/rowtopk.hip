@@ -331,8 +331,8 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   if (grid > 65536u * 4) grid = 65536u * 4;
   // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 4096 columns
   const uint32_t epv = static_cast<uint32_t>(16 / es);
-  // narrow bf16 rows, many of them: four rows per wavefront (index encodings; the four lists share 512 staging slots)
-  if (dt == DCT_BF16 && enc != kEncBitmap && D % 8 == 0 && D <= quad::kMaxD && 4 * k <= quad::kStageSlots &&
+  // narrow bf16 rows, many of them: four rows per wavefront (the four lists of survivors share 512 staging slots)
+  if (dt == DCT_BF16 && D % 8 == 0 && D <= quad::kMaxD && 4 * k <= quad::kStageSlots &&
       B >= kQuadMinRows && is_aligned(x, 16) && row_stride_elems % 8 == 0) {
     const uint32_t vecs = D / 8;
     const uint32_t nv = vecs <= 16 ? 1u : vecs <= 32 ? 2u : vecs <= 64 ? 4u : 8u;
@@ -355,6 +355,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     else DCT_LAUNCH_QUAD(8, ENCV);                \
   } while (0)
     if (enc == kEncIdx16) DCT_LAUNCH_QUAD_NV(kEncIdx16);
+    else if (enc == kEncBitmap) DCT_LAUNCH_QUAD_NV(kEncBitmap);
     else DCT_LAUNCH_QUAD_NV(kEncIdx32);
 #undef DCT_LAUNCH_QUAD_NV
 #undef DCT_LAUNCH_QUAD

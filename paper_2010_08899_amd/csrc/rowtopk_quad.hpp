@@ -72,12 +72,11 @@ __device__ __forceinline__ uint32_t row_ballot(bool p, uint32_t lane) {
 }
 
 // NV = 16-byte vectors per lane: a lane owns NV * 8 contiguous columns, a row 16 * NV * 8.
-// ENC (RowEnc): kEncIdx32 or kEncIdx16.
+// ENC (RowEnc): how the mask is written (32- or 16-bit column indices, or a bitmap of ceil(D/32) words per row).
 template <int NV, int ENC>
 __global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
     const uint16_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, void* __restrict__ idx_out,
     uint16_t* __restrict__ val_out, uint16_t* __restrict__ tau_out) {
-  static_assert(ENC == kEncIdx32 || ENC == kEncIdx16, "index encodings only");
   constexpr int COLS = NV * 8;                  // columns per lane
   constexpr int REGS = COLS / 2;                // packed key registers per lane (2 columns each)
   constexpr int RPW = REGS < 16 ? REGS : 16;    // registers per bitmap word
@@ -396,6 +395,22 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
 #pragma unroll
     for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
     const uint32_t slot = row_incl_scan(kc) - kc;
+    if constexpr (ENC == kEncBitmap) {
+      // the per-lane bitmaps ARE the mask: COLS bits per lane, packed into the row's 32-bit words
+      const uint32_t n_words = (D + 31) / 32;
+      uint32_t* mo = static_cast<uint32_t*>(idx_out) + my_row * n_words;
+      if constexpr (COLS >= 32) {
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w)
+          if (my_row < B && s * WORDS + w < n_words) mo[s * WORDS + w] = keep[w];
+      } else {
+        constexpr uint32_t kLanesPerWord = 32 / COLS;  // 2 or 4 neighbouring lanes of the row share a word
+        uint32_t v = keep[0] << ((s % kLanesPerWord) * COLS);
+#pragma unroll
+        for (uint32_t d = 1; d < kLanesPerWord; d <<= 1) v |= __shfl_xor(v, d, kWave);
+        if (my_row < B && s % kLanesPerWord == 0 && s / kLanesPerWord < n_words) mo[s / kLanesPerWord] = v;
+      }
+    }
     {
       const uint32_t base = g * k;  // this row's list
       uint32_t mA = keep[0], mB = WORDS == 2 ? keep[wB] : 0u;

@@ -901,6 +901,19 @@ def test_mp_many_narrow_rows(dct, B, D, k, pad, idx16):
     assert np.array_equal(bits(host(tau)), bits(etau))
 
 
+@pytest.mark.parametrize("B,D,k", [(8192, 256, 12), (8199, 64, 5), (8193, 128, 9), (9000, 1024, 51), (8192, 520, 26)])
+def test_mp_many_narrow_rows_bitmask(dct, B, D, k):
+    x = si.relu_activations(B, D, DEV, 1950 + D, dtype=torch.bfloat16)
+    x[3] = 0.5
+    x[B - 1] = 0.0
+    mask = torch.full((B, (D + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=torch.bfloat16, device=DEV)
+    dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, None)
+    emask, eval_, _ = oracle.rowtopk_fwd_bitmask(host(x), k)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), emask)
+    assert np.array_equal(host(val), eval_)
+
+
 # ------------------------------------------------------------------ Algorithm 2, the mask as 16-bit indices
 def _u16(t):
     return t.cpu().numpy().view(np.uint16)
