@@ -307,6 +307,73 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
   }
 }
 
+// The two consumers for NARROW rows whose mask is a power of two of words, at most 32 (D = 32 ... 1024 in
+// powers of two): one lane per mask word, so a wavefront covers 64 / WPR rows at once.  One wave scan of the
+// popcounts, less its value at the row's first lane, ranks every word's kept columns within its row.
+// GATHER: dval[b, j] = dy[b, column of the j-th set bit]; otherwise the rows are assembled in LDS (2 or 4 KiB of
+// dense output per step) and written with coalesced 16-byte stores; that needs dst_stride == D and 16-byte
+// aligned output.
+template <typename W, bool GATHER>
+__global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_words_kernel(
+    const W* __restrict__ src, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, const uint32_t* __restrict__ mask,
+    W* __restrict__ dst, uint32_t wpr) {
+  constexpr uint32_t EPV = 16 / sizeof(W);
+  __shared__ uint4 s_blk[GATHER ? 1 : kRtWaves][GATHER ? 1 : kWave * 32 * sizeof(W) / 16];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane = lane_id();
+  const uint32_t rows_per_step = kWave / wpr;
+  const uint32_t r_loc = lane / wpr, w = lane % wpr;  // row of the step, word of the row
+  uint4* blk4 = s_blk[GATHER ? 0 : wave];
+  W* blk = reinterpret_cast<W*>(blk4);
+  const uint32_t blk_vecs = kWave * 32 / EPV;  // the step's dense output in 16-byte vectors
+  if constexpr (!GATHER) {
+    for (uint32_t q = lane; q < blk_vecs; q += kWave) blk4[q] = make_uint4(0, 0, 0, 0);
+  }
+  const uint64_t n_steps = (static_cast<uint64_t>(B) + rows_per_step - 1) / rows_per_step;
+  for (uint64_t step = static_cast<uint64_t>(blockIdx.x) * kRtWaves + wave; step < n_steps;
+       step += static_cast<uint64_t>(gridDim.x) * kRtWaves) {
+    const uint64_t row = step * rows_per_step + r_loc;
+    const bool live = row < B;
+    if constexpr (!GATHER) wave_lds_sync();  // the block buffer is all zeros again
+    uint32_t m = live ? mask[row * wpr + w] : 0u;  // D = 32 * wpr: every bit of a word is a column
+    const uint32_t pc = __popc(m);
+    const uint32_t incl = fast::wave_incl_scan(pc);
+    const int first = static_cast<int>(lane - w);  // the row's first lane
+    const uint32_t prev = __shfl(incl, first > 0 ? first - 1 : 0, kWave);  // taken by all lanes together
+    const uint32_t before_row = first > 0 ? prev : 0u;                      // set bits of the rows in lower lanes
+    uint32_t slot = incl - pc - before_row;
+    const uint32_t row_bits = __shfl(incl, first + static_cast<int>(wpr) - 1, kWave) - before_row;
+    while (ballot64(m != 0) != 0) {
+      if (m != 0) {
+        const uint32_t c = 32 * w + __builtin_ctz(m);
+        m &= m - 1;
+        if (slot < k) {
+          if constexpr (GATHER) dst[row * k + slot] = src[row * stride + c];
+          else blk[r_loc * D + c] = src[row * k + slot];
+        }
+        ++slot;
+      }
+    }
+    if constexpr (GATHER) {
+      if (live)
+        for (uint32_t j = row_bits + w; j < k; j += wpr) dst[row * k + j] = 0;  // fewer set bits than k
+    } else {
+      wave_lds_sync();
+      const uint64_t row0 = step * rows_per_step;
+      const uint32_t rows_here = static_cast<uint32_t>(min(static_cast<uint64_t>(rows_per_step), B - row0));
+      uint4* out4 = reinterpret_cast<uint4*>(dst + row0 * D);
+      const uint32_t n_q = rows_here * (D / EPV);
+      for (uint32_t q = lane; q < blk_vecs; q += kWave) {
+        if (q < n_q) {
+          const uint4 v = blk4[q];
+          st_stream(&out4[q], v.x, v.y, v.z, v.w);
+        }
+        blk4[q] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  }
+}
+
 }  // namespace
 }  // namespace dct
 
@@ -438,6 +505,21 @@ extern "C" int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint3
   if (!is_aligned(dy, es) || !is_aligned(d_mask, 4) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
+  const uint32_t wpr = D / 32;
+  if (D % 32 == 0 && wpr <= 32 && (wpr & (wpr - 1)) == 0) {  // narrow rows: several per wavefront, one lane per word
+    const uint32_t steps = (B + kWave / wpr - 1) / (kWave / wpr);
+    const uint32_t wgrid = std::min<uint32_t>((steps + kRtWaves - 1) / kRtWaves, resident);
+    if (dt == DCT_F32) {
+      hipLaunchKernelGGL((rowtopk_bitmask_words_kernel<uint32_t, true>), dim3(wgrid), dim3(kRtThreads), 0, s,
+                         static_cast<const uint32_t*>(dy), B, D, row_stride_elems, k, d_mask,
+                         static_cast<uint32_t*>(d_dval_out), wpr);
+    } else {
+      hipLaunchKernelGGL((rowtopk_bitmask_words_kernel<uint16_t, true>), dim3(wgrid), dim3(kRtThreads), 0, s,
+                         static_cast<const uint16_t*>(dy), B, D, row_stride_elems, k, d_mask,
+                         static_cast<uint16_t*>(d_dval_out), wpr);
+    }
+    return launch_status();
+  }
   const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
   if (dt == DCT_F32) {
     hipLaunchKernelGGL((rowtopk_bitmask_lanes_kernel<uint32_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
@@ -462,6 +544,22 @@ extern "C" int dct_rowtopk_scatter_bitmask(const uint32_t* d_mask, const void* d
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
   const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
+  const uint32_t wpr = D / 32;
+  if (D % 32 == 0 && wpr <= 32 && (wpr & (wpr - 1)) == 0 && out_row_stride_elems == D && is_aligned(d_out, 16)) {
+    // narrow dense rows: several per wavefront, one lane per mask word
+    const uint32_t steps = (B + kWave / wpr - 1) / (kWave / wpr);
+    const uint32_t wgrid = std::min<uint32_t>((steps + kRtWaves - 1) / kRtWaves, resident);
+    if (dt == DCT_F32) {
+      hipLaunchKernelGGL((rowtopk_bitmask_words_kernel<uint32_t, false>), dim3(wgrid), dim3(kRtThreads), 0, s,
+                         static_cast<const uint32_t*>(d_val), B, D, static_cast<uint64_t>(k), k, d_mask,
+                         static_cast<uint32_t*>(d_out), wpr);
+    } else {
+      hipLaunchKernelGGL((rowtopk_bitmask_words_kernel<uint16_t, false>), dim3(wgrid), dim3(kRtThreads), 0, s,
+                         static_cast<const uint16_t*>(d_val), B, D, static_cast<uint64_t>(k), k, d_mask,
+                         static_cast<uint16_t*>(d_out), wpr);
+    }
+    return launch_status();
+  }
   if (static_cast<uint64_t>(D) * es <= kBmRowBytes) {  // the row is assembled on chip
     const bool vec_ok = is_aligned(d_out, 16) && (out_row_stride_elems * es) % 16 == 0 && (D * es) % 16 == 0;
     if (dt == DCT_F32) {

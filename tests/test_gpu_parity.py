@@ -914,6 +914,34 @@ def test_mp_many_narrow_rows_bitmask(dct, B, D, k):
     assert np.array_equal(host(val), eval_)
 
 
+@pytest.mark.parametrize("dtype,B,D,k", [
+    (torch.bfloat16, 1000, 256, 12), (torch.bfloat16, 77, 32, 5), (torch.bfloat16, 513, 1024, 51),
+    (torch.float32, 300, 64, 64), (torch.float32, 1025, 512, 25), (torch.bfloat16, 9, 128, 1)])
+def test_mp_bitmask_consumers_narrow_rows(dct, dtype, B, D, k):
+    """Masks of 1 ... 32 words per row (a power of two): several rows per wavefront, one lane per word."""
+    x = si.relu_activations(B, D, DEV, 1960 + D, dtype=dtype)
+    dy = si.normal_matrix(B, D, DEV, 1961 + D, dtype=dtype)
+    mask = torch.zeros(B, D // 32, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=dtype, device=DEV)
+    dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, None)
+    emask, eval_, _ = oracle.rowtopk_fwd_bitmask(host(x), k)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), emask)
+    # masks the forward pass would not produce: fewer set bits than k, more than k, none
+    m2 = mask.clone()
+    m2[0] = 0
+    m2[1] = -1
+    if B > 5:
+        m2[5] = 0
+        m2[5, 0] = 0b101
+    m2h = m2.cpu().numpy().view(np.uint32)
+    dval = torch.full((B, k), 3.0, device=DEV).to(dtype)
+    dct.dct_rowtopk_bwd_bitmask(dy, m2, dval)
+    assert np.array_equal(bits(host(dval).reshape(-1)), bits(oracle.rowtopk_bwd_bitmask(host(dy), m2h, k).reshape(-1)))
+    out = torch.full((B, D), 3.0, device=DEV).to(dtype)
+    dct.dct_rowtopk_scatter_bitmask(m2, val, out)
+    assert np.array_equal(bits(host(out).reshape(-1)), bits(oracle.rowscatter_bitmask(m2h, host(val), D).reshape(-1)))
+
+
 # ------------------------------------------------------------------ Algorithm 2, the mask as 16-bit indices
 def _u16(t):
     return t.cpu().numpy().view(np.uint16)
