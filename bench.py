@@ -292,6 +292,29 @@ def main():
     del d5, idx16
     call_fwd(0)
 
+    # ------------------------------------------------------------ the paper's own MP widths (not part of the step)
+    # Sec. 3.1 / 3.2: DLRM MLP layers of 512 and 256 units, Transformer FFN of 1024: 512 MiB of bf16 rows each
+    narrow = []
+    if not args.no_batched:
+        for Dn in (256, 512, 1024):
+            Bn = max(1, ((512 << 20) // shrink) // (Dn * 2))
+            kn = Dn // 20
+            xn = [si.relu_activations(Bn, Dn, dev, si.BASE_SEED + 60 + j, dtype=torch.bfloat16) for j in range(2)]
+            idxn = torch.zeros(Bn, kn, dtype=torch.int32, device=dev)
+            valn = torch.zeros(Bn, kn, dtype=torch.bfloat16, device=dev)
+            dvaln = torch.zeros_like(valn)
+            outn = torch.empty_like(xn[0])
+            uf = time_calls(lambda i: dct.dct_rowtopk_fwd(xn[i & 1], kn, idxn, valn, None), 10)
+            ub = time_calls(lambda i: dct.dct_rowtopk_bwd(xn[i & 1], idxn, dvaln), 10)
+            us_ = time_calls(lambda i: dct.dct_rowtopk_scatter(idxn, valn, outn), 10)
+            fb = Bn * Dn * 2 + Bn * kn * 6
+            narrow.append({"B": Bn, "D": Dn, "k": kn, "dtype": "bf16", "fwd_us": round(uf, 1),
+                           "fwd_frac_of_hbm_peak": round(fb / (uf * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                           "bwd_us": round(ub, 1), "scatter_us": round(us_, 1)})
+            log(f"[bench] MP {Bn}x{Dn} bf16 k={kn}: fwd {uf:.1f} us ({narrow[-1]['fwd_frac_of_hbm_peak'] * 100:.1f}% of peak), "
+                f"bwd {ub:.1f} us, scatter {us_:.1f} us")
+            del xn, idxn, valn, dvaln, outn
+
     # ------------------------------------------------------------ many small tensors per call (not part of the step)
     # 24 tensors from 64 to 2^20 elements (the largest is c1-sized), 1 % kept: one batched select +
     # one batched compaction against one pair of calls per tensor.
@@ -446,7 +469,7 @@ def main():
                                "(65536x4096 bf16, k=204)" + (" [SHRUNK 16x: not a valid number]" if args.small else ""),
                    "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
         "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls, "bitmask_calls": bm_calls, "idx16_calls": i16_calls,
-        "batched_small_tensors": batched, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
+        "paper_mp_widths": narrow, "batched_small_tensors": batched, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
         "inputs": inputs,
     }
     print(json.dumps(out), flush=True)
