@@ -424,10 +424,11 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     st.from_cand = ok ? 1u : 0u;
     st.n_src = ok ? n_cand : n_virt - off;
     st.last_count = st.n_src;
-    // candidates share the leading bits on which lo and hi agree
-    const uint32_t diff = ok ? (ws->lo ^ ws->hi) : E::kKeyMask;
+    // The candidate passes select on key - lo, which lies in [0, hi - lo]: only the bits of that range
+    // are left to resolve (the bits in which lo and hi differ can be many more, when a carry separates them).
+    const uint32_t diff = ok ? (ws->hi - ws->lo) : E::kKeyMask;
     st.rem_bits = diff ? 32u - __builtin_clz(diff) : 0u;
-    st.prefix = ok ? (ws->lo & ~((st.rem_bits >= 32u ? 0u : (1u << st.rem_bits)) - 1u)) : 0u;
+    st.prefix = 0u;
     st.width = min(kDigitBits, st.rem_bits);
   } else {
     st = ws->state[pass - 1];
@@ -454,6 +455,7 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     const uint32_t region = blockIdx.x % kCandRegions, part = blockIdx.x / kCandRegions;
     const uint4* cv = reinterpret_cast<const uint4*>(ws->cand + static_cast<size_t>(region) * region_cap);
     const uint32_t n_src = part < parts ? static_cast<uint32_t>(ws->counts[region].c) : 0u;  // <= region_cap here
+    const uint32_t base_key = ws->lo;
     const uint32_t reg_vecs = (n_src + 3) / 4;
     for (uint32_t base = part * span; base < reg_vecs; base += parts * span) {
       uint4 v[kSelUnroll];
@@ -467,7 +469,7 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
         const uint32_t e0 = (base + u * kSelThreads + threadIdx.x) * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t key = Elem<DCT_F32>::raw(v[u], e);
+          const uint32_t key = Elem<DCT_F32>::raw(v[u], e) - base_key;
           hist_add(h, e0 + e < n_src && (key & fixed_mask) == prefix, (key >> shift) & dmask);
         }
       }
@@ -529,7 +531,7 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_kernel(SelWs* ws, i
   __shared__ uint32_t s_tmp[kSelWaves + 4];
   const SelState st = advance_state(ws->state[last], ws->hist[last], s_tmp);
   if (threadIdx.x == 0) {
-    out->tau_key = st.prefix;
+    out->tau_key = st.prefix + (st.from_cand ? ws->lo : 0u);  // the candidate passes work on key - lo
     out->n_gt = st.n_gt;
     out->n_eq = st.last_count;
     out->tie_quota = st.k_rem;
