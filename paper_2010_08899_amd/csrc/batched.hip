@@ -205,7 +205,7 @@ __global__ __launch_bounds__(kBtThreads) void bt_count_kernel(const typename Ele
 // One workgroup per segment: exclusive prefix of its tiles' counts (both halves of the packed word
 // stay below 2^31, so one 64-bit add sums both), and the segment's survivor count.
 template <bool EXACT>
-__global__ __launch_bounds__(kBtThreads) void bt_scan_kernel(const BtSeg* __restrict__ segs, uint32_t n_seg,
+__global__ __launch_bounds__(kBtThreads) void bt_scan_kernel(const BtSeg* __restrict__ segs,
                                                              const dct_threshold* __restrict__ thr,
                                                              const uint64_t* __restrict__ counts,
                                                              uint64_t* __restrict__ offsets,
@@ -415,7 +415,7 @@ extern "C" int dct_threshold_compact_batched(const void* g, int dt, const dct_se
     using W = Elem<DTV>::word_t;                                                                                 \
     hipLaunchKernelGGL((bt_count_kernel<DTV, EX>), tgrid, block, 0, s, static_cast<const W*>(g), d_segs, n_seg,  \
                        d_thr, d_counts);                                                                         \
-    hipLaunchKernelGGL((bt_scan_kernel<EX>), dim3(n_seg), block, 0, s, d_segs, n_seg, d_thr, d_counts,           \
+    hipLaunchKernelGGL((bt_scan_kernel<EX>), dim3(n_seg), block, 0, s, d_segs, d_thr, d_counts,                  \
                        d_offsets, d_count_out);                                                                  \
     hipLaunchKernelGGL((bt_write_kernel<DTV, EX>), tgrid, block, 0, s, static_cast<const W*>(g), d_segs, n_seg,  \
                        d_thr, d_offsets, d_idx_out, static_cast<W*>(d_val_out));                                 \

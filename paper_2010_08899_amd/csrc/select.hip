@@ -107,7 +107,7 @@ __device__ __forceinline__ uint4 add4(const uint4& a, const uint4& b) {
 
 // ------------------------------------------------------------------ kernel 1a
 // Clears the workspace for the direct (no sample) path.
-__global__ void select_init_kernel(SelWs* ws, uint32_t k, uint32_t n) {
+__global__ void select_init_kernel(SelWs* ws) {
   uint32_t* w = reinterpret_cast<uint32_t*>(ws);
   const uint32_t n_words = offsetof(SelWs, sample) / 4;
   for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) w[i] = 0;
@@ -608,7 +608,7 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
       hipLaunchKernelGGL((select_partition_kernel<DCT_BF16, false>), pgrid, pblock, 0, s, g16, nullptr, geo, ws);
     }
   } else {
-    hipLaunchKernelGGL(select_init_kernel, dim3(32), dim3(256), 0, s, ws, k32, n32);
+    hipLaunchKernelGGL(select_init_kernel, dim3(32), dim3(256), 0, s, ws);
   }
   if (hipGetLastError() != hipSuccess) return DCT_ERR_HIP;
 
