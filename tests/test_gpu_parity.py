@@ -1102,6 +1102,113 @@ def test_calls_on_a_side_stream_and_in_a_captured_graph(dct):
         check()
 
 
+# ------------------------------------------------------------------ seeded random configurations
+def test_random_mp_configurations(dct):
+    """Forty seeded draws of (dtype, B, D, k, encoding, value structure): every forward kernel and every
+    consumer against the oracle.  Value structures: post-ReLU, signed, four distinct values (ties everywhere),
+    rows whose scale varies by orders of magnitude (the window prediction keeps missing), mostly zero rows,
+    constant rows among ordinary ones."""
+    rng = np.random.default_rng(20100889)
+    for case in range(40):
+        dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+        D = int(rng.choice([8, 16, 24, 64, 72, 128, 200, 256, 264, 512, 520, 1000, 1024, 1032, 2048, 4096]))
+        B = int(rng.integers(8192, 10000)) if rng.random() < 0.5 else int(rng.integers(1, 400))
+        B = min(B, max(1, 12_000_000 // D))
+        k = min(D, [1, max(1, D // 20), max(1, D // 3), D][int(rng.integers(0, 4))])
+        kind, enc = int(rng.integers(0, 6)), int(rng.integers(0, 3))
+        gen = torch.Generator(device=DEV).manual_seed(int(rng.integers(1 << 30)))
+        x = torch.randn(B, D, device=DEV, generator=gen)
+        if kind == 0:
+            x = torch.relu(x)
+        elif kind == 2:
+            x = torch.randint(0, 4, (B, D), device=DEV, generator=gen).float() * 0.5
+        elif kind == 3:
+            x = torch.relu(x) * torch.exp(4 * torch.randn(B, 1, device=DEV, generator=gen))
+        elif kind == 4:
+            x = torch.relu(x - 1.5)
+        elif kind == 5:
+            x[::3] = 0.25
+        x = x.to(dtype).contiguous()
+        dy = torch.randn(B, D, device=DEV, generator=gen).to(dtype)
+        val = torch.zeros(B, k, dtype=dtype, device=DEV)
+        tau = torch.zeros(B, dtype=dtype, device=DEV)
+        dval = torch.full((B, k), 3.0, device=DEV).to(dtype)
+        out = torch.full((B, D), 3.0, device=DEV).to(dtype)
+        xh, dyh = host(x), host(dy)
+        ei, ev, et = oracle.rowtopk_fwd(xh, k)
+        what = dict(case=case, dtype=dtype, B=B, D=D, k=k, kind=kind, enc=enc)
+        if enc == 2:
+            mask = torch.full((B, (D + 31) // 32), -1, dtype=torch.int32, device=DEV)
+            dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, tau)
+            em, _, _ = oracle.rowtopk_fwd_bitmask(xh, k)
+            assert np.array_equal(mask.cpu().numpy().view(np.uint32), em), what
+            dct.dct_rowtopk_bwd_bitmask(dy, mask, dval)
+            dct.dct_rowtopk_scatter_bitmask(mask, val, out)
+        else:
+            idx = torch.full((B, k), -1, dtype=torch.int16 if enc == 1 else torch.int32, device=DEV)
+            (dct.dct_rowtopk_fwd_idx16 if enc == 1 else dct.dct_rowtopk_fwd)(x, k, idx, val, tau)
+            got = idx.cpu().numpy()
+            got = got.view(np.uint16).astype(np.int32) if enc == 1 else got
+            assert np.array_equal(got, ei), what
+            (dct.dct_rowtopk_bwd_idx16 if enc == 1 else dct.dct_rowtopk_bwd)(dy, idx, dval)
+            (dct.dct_rowtopk_scatter_idx16 if enc == 1 else dct.dct_rowtopk_scatter)(idx, val, out)
+        assert np.array_equal(bits(host(val).reshape(-1)), bits(ev.reshape(-1))), what
+        assert np.array_equal(bits(host(tau)), bits(et)), what
+        assert np.array_equal(bits(host(dval).reshape(-1)), bits(oracle.rowtopk_bwd(dyh, ei).reshape(-1))), what
+        assert np.array_equal(bits(host(out).reshape(-1)), bits(oracle.rowscatter(ei, ev, D).reshape(-1))), what
+
+
+def test_random_dp_configurations(dct):
+    """Thirty seeded draws of (size, kept fraction, dtype, error feedback, mode, capacity, base offset, value
+    structure: Gaussian, 95 % zeros, seven distinct values, log-normal magnitudes, sorted)."""
+    rng = np.random.default_rng(889)
+    for case in range(30):
+        n = int(rng.integers(4_200_000, 7_000_000)) if rng.random() < 0.4 else int(rng.integers(1, 300_000))
+        bf16 = rng.random() < 0.25
+        ef = (not bf16) and rng.random() < 0.4
+        k = min(n, max(1, int(n * float(rng.choice([1e-4, 1e-3, 5e-3, 0.02, 0.1, 0.3, 0.6, 1.0])))))
+        kind, mode = int(rng.integers(0, 5)), int(rng.integers(0, 2))
+        gen = torch.Generator(device=DEV).manual_seed(int(rng.integers(1 << 30)))
+        g = torch.randn(n, device=DEV, generator=gen)
+        if kind == 0:
+            g = g * 1e-3
+        elif kind == 1:
+            g = g * (torch.rand(n, device=DEV, generator=gen) < 0.05)
+        elif kind == 2:
+            g = torch.randint(-3, 4, (n,), device=DEV, generator=gen).float()
+        elif kind == 3:
+            g = torch.exp(6 * g) * torch.sign(torch.randn(n, device=DEV, generator=gen))
+        else:
+            g = torch.sort(g)[0]
+        off = 0 if ef else int(rng.integers(0, 4))
+        buf = torch.zeros(n + 8, device=DEV, dtype=torch.bfloat16 if bf16 else torch.float32)
+        buf[off:off + n] = g.to(buf.dtype)
+        g = buf[off:off + n]
+        gh = host(g)
+        cap = int(min(n, max(16, k * float(rng.choice([0.5, 1.0, 2.0])))))
+        what = dict(case=case, n=n, k=k, bf16=bf16, ef=ef, kind=kind, off=off, cap=cap, mode=mode)
+        if ef:
+            e = torch.randn(n, device=DEV, generator=gen) * 1e-3
+            eh = host(e)
+            efb = EF(dct, n, capacity=cap)
+            thr = efb.select(g, e, k)
+            exp = oracle.ef_select_threshold(gh, eh, k)
+            assert thr == exp, what
+            e_out = torch.empty_like(e)
+            idx, val, cnt, guard = efb.compact(g, e, e_out, mode)
+            ei, ev, ec, ee = oracle.ef_threshold_compact(gh, eh, exp, mode, capacity=cap)
+            assert np.array_equal(bits(host(e_out)), bits(ee)), what
+        else:
+            dp = DP(dct, g, capacity=cap)
+            thr = dp.select(k)
+            exp = oracle.select_threshold(gh, k, method="nth")
+            assert thr == exp, what
+            idx, val, cnt, guard = dp.compact(mode)
+            ei, ev, ec = oracle.threshold_compact(gh, exp, mode, capacity=cap)
+        assert cnt == ec and np.array_equal(idx, ei) and np.array_equal(bits(val), bits(ev)), what
+        assert np.all(guard == -7), what
+
+
 # ------------------------------------------------------------------ the wider rows at the benchmark's full sizes
 def test_ef_and_decompress_c4_full(dct):
     """Error feedback and decompression on the full c4 gradient (N = 2^28), the launch shape the
