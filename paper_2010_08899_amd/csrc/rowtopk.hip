@@ -396,7 +396,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   void* io = idx_or_mask;
   uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
   if (grid > 65536u * 4) grid = 65536u * 4;
-  // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 4096 columns
+  // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 16 KiB
   const uint32_t epv = static_cast<uint32_t>(16 / es);
   // narrow bf16 rows, many of them: four rows per wavefront (the four lists of survivors share 512 staging slots)
   if (dt == DCT_BF16 && D % 8 == 0 && D <= quad::kMaxD && 4 * k <= quad::kStageSlots &&
@@ -428,7 +428,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
 #undef DCT_LAUNCH_QUAD
     return launch_status();
   }
-  if (D % epv == 0 && D <= 4096u && is_aligned(x, 16) && row_stride_elems % epv == 0) {
+  if (D % epv == 0 && D * es <= 16384u && is_aligned(x, 16) && row_stride_elems % epv == 0) {
     uint32_t fgrid = (B + fast::kWaves - 1) / fast::kWaves;
     // workgroups per CU that registers and the LDS row buffers allow (rows of up to 2 / 4 / 8 / 16 KiB)
     const uint32_t row_bytes = D * static_cast<uint32_t>(es);
@@ -449,7 +449,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     else if (vecs <= 128) DCT_LAUNCH_ONCHIP(2, MK, F32V);    \
     else if (vecs <= 256) DCT_LAUNCH_ONCHIP(4, MK, F32V);    \
     else if (vecs <= 512) DCT_LAUNCH_ONCHIP(8, MK, F32V);    \
-    else if constexpr (F32V) DCT_LAUNCH_ONCHIP(16, MK, F32V); \
+    else DCT_LAUNCH_ONCHIP(16, MK, F32V);                    \
   } while (0)
 #define DCT_LAUNCH_ONCHIP_ENC(F32V)                                        \
   do {                                                                    \

@@ -1,5 +1,5 @@
 // On-chip forward kernel of dct_rowtopk_fwd (Algorithm 2, forward loop: per row the
-// k largest |X_act,i|) for rows of up to 4096 columns, bf16 or fp32.
+// k largest |X_act,i|) for rows of up to 16 KiB: 8192 bf16 or 4096 fp32 columns.
 //
 // One wavefront owns one row at a time and keeps it on chip:
 //   1. the row is loaded once with coalesced 16-byte loads and written to a
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
   constexpr int REGS = COLS / 2;                    // packed key registers per lane (2 columns each)
   constexpr int RPW = REGS < 16 ? REGS : 16;        // registers per bitmap word
   constexpr int WORDS = (REGS + 15) / 16;
-  static_assert(WORDS <= 2, "a lane owns at most 64 columns");
+  static_assert(WORDS <= 2 || (WORDS == 4 && !F32), "a lane owns at most 64 columns (bf16: 128)");
   constexpr int CHUNK = (NV + 1) * 16;              // LDS bytes per lane chunk (16 bytes of padding)
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
   __shared__ uint32_t s_hist[kWaves][kWave];
@@ -210,14 +210,18 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     // Bit loops run two independent streams per step so that their LDS round trips overlap:
     // with two bitmap words, stream A walks word 0 and stream B word 1 (both upwards); with one
     // word, A takes the lowest and B the highest remaining bit.  c = local column of the bit.
-    constexpr int wB = WORDS - 1;
-    auto pop2 = [&](uint32_t& mA, uint32_t& mB, bool& vA, uint32_t& cA, bool& vB, uint32_t& cB) {
+    // The bitmap words of a lane are walked in pairs: stream A takes word 2p, stream B word 2p + 1 (with
+    // one word per lane, A takes its lowest and B its highest remaining bit).
+    constexpr int PAIRS = (WORDS + 1) / 2;
+    auto word_a = [](int p) { return 2 * p; };
+    auto word_b = [](int p) { return WORDS == 1 ? 0 : 2 * p + 1; };
+    auto pop2 = [&](uint32_t& mA, uint32_t& mB, bool& vA, uint32_t& cA, bool& vB, uint32_t& cB, int p) {
       vA = mA != 0;
-      cA = vA ? __builtin_ctz(mA) : 0u;
+      cA = kColsPerWord * word_a(p) + (vA ? __builtin_ctz(mA) : 0u);
       mA &= mA - 1;
-      if constexpr (WORDS == 2) {
+      if constexpr (WORDS >= 2) {
         vB = mB != 0;
-        cB = kColsPerWord + (vB ? __builtin_ctz(mB) : 0u);
+        cB = kColsPerWord * word_b(p) + (vB ? __builtin_ctz(mB) : 0u);
         mB &= mB - 1;
       } else {
         vB = mA != 0;
@@ -313,27 +317,28 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     wave_lds_fence();
     // The bins (key - wlo, 5 bits) of the window keys are also remembered per stream in pop order,
     // six per stream, so that the second walk below needs no LDS reads.
-    uint32_t listA = 0, listB = 0;
+    uint32_t listA[PAIRS], listB[PAIRS], n_pops[PAIRS];  // n_pops: pops of the longest stream (uniform)
     bool list_full = false;
-    uint32_t n_pops = 0;  // pops of the longest stream (uniform)
-    {
-      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p) {
+      listA[p] = listB[p] = n_pops[p] = 0;
+      uint32_t mA = inwin[word_a(p)], mB = WORDS >= 2 ? inwin[word_b(p)] : 0u;
       uint32_t sh = 0;
       while (ballot64((mA | mB) != 0) != 0) {
         bool vA, vB;
         uint32_t cA, cB;
-        pop2(mA, mB, vA, cA, vB, cB);
+        pop2(mA, mB, vA, cA, vB, cB, p);
         const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
         if (vA) atomicAdd(&hist[bA], 1u);
         if (vB) atomicAdd(&hist[bB], 1u);
         if (sh < 30u) {
-          listA |= (vA ? bA : 0u) << sh;
-          listB |= (vB ? bB : 0u) << sh;
+          listA[p] |= (vA ? bA : 0u) << sh;
+          listB[p] |= (vB ? bB : 0u) << sh;
         } else {
           list_full = true;
         }
         sh += 5u;
-        ++n_pops;
+        ++n_pops[p];
       }
     }
     wave_lds_fence();
@@ -360,38 +365,45 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     const uint32_t bs = static_cast<uint32_t>(bstar);
     if (!list_full) {
       // every stream popped at most six keys: replay the pops from the remembered bins (no LDS reads)
-      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
-      for (uint32_t j = 0; j < n_pops; ++j) {
-        const uint32_t bitA = mA & (0u - mA);  // 0 once the stream is exhausted: contributes nothing
-        mA ^= bitA;
-        uint32_t bitB;
-        if constexpr (WORDS == 2) {
-          bitB = mB & (0u - mB);
-          mB ^= bitB;
-        } else {
-          bitB = mA != 0 ? 0x80000000u >> __builtin_clz(mA) : 0u;
-          mA ^= bitB;
+#pragma unroll
+      for (int p = 0; p < PAIRS; ++p) {
+        uint32_t mA = inwin[word_a(p)], mB = WORDS >= 2 ? inwin[word_b(p)] : 0u;
+        uint32_t la = listA[p], lb = listB[p];
+        for (uint32_t j = 0; j < n_pops[p]; ++j) {
+          const uint32_t bitA = mA & (0u - mA);  // 0 once the stream is exhausted: contributes nothing
+          mA ^= bitA;
+          uint32_t bitB;
+          if constexpr (WORDS >= 2) {
+            bitB = mB & (0u - mB);
+            mB ^= bitB;
+          } else {
+            bitB = mA != 0 ? 0x80000000u >> __builtin_clz(mA) : 0u;
+            mA ^= bitB;
+          }
+          const uint32_t bA = la & 31u, bB = lb & 31u;
+          la >>= 5;
+          lb >>= 5;
+          keep[word_a(p)] |= bA > bs ? bitA : 0u;
+          tie[word_a(p)] |= bA == bs ? bitA : 0u;
+          keep[word_b(p)] |= bB > bs ? bitB : 0u;
+          tie[word_b(p)] |= bB == bs ? bitB : 0u;
         }
-        const uint32_t bA = listA & 31u, bB = listB & 31u;
-        listA >>= 5;
-        listB >>= 5;
-        keep[0] |= bA > bs ? bitA : 0u;
-        tie[0] |= bA == bs ? bitA : 0u;
-        keep[wB] |= bB > bs ? bitB : 0u;
-        tie[wB] |= bB == bs ? bitB : 0u;
       }
     } else {
-      uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
-      while (ballot64((mA | mB) != 0) != 0) {
-        bool vA, vB;
-        uint32_t cA, cB;
-        pop2(mA, mB, vA, cA, vB, cB);
-        const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
-        const uint32_t mkA = 1u << cA, mkB = 1u << (cB & 31u);
-        keep[0] |= (vA && bA > bs) ? mkA : 0u;
-        tie[0] |= (vA && bA == bs) ? mkA : 0u;
-        keep[wB] |= (vB && bB > bs) ? mkB : 0u;
-        tie[wB] |= (vB && bB == bs) ? mkB : 0u;
+#pragma unroll
+      for (int p = 0; p < PAIRS; ++p) {
+        uint32_t mA = inwin[word_a(p)], mB = WORDS >= 2 ? inwin[word_b(p)] : 0u;
+        while (ballot64((mA | mB) != 0) != 0) {
+          bool vA, vB;
+          uint32_t cA, cB;
+          pop2(mA, mB, vA, cA, vB, cB, p);
+          const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
+          const uint32_t mkA = 1u << (cA & 31u), mkB = 1u << (cB & 31u);
+          keep[word_a(p)] |= (vA && bA > bs) ? mkA : 0u;
+          tie[word_a(p)] |= (vA && bA == bs) ? mkA : 0u;
+          keep[word_b(p)] |= (vB && bB > bs) ? mkB : 0u;
+          tie[word_b(p)] |= (vB && bB == bs) ? mkB : 0u;
+        }
       }
     }
 
@@ -522,10 +534,14 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
       for (int w = 0; w < WORDS; ++w) t[w] = allowed != 0 ? tie[w] : 0u;
       if (allowed != 0 && allowed < tc) {
         for (uint32_t drop = tc - allowed; drop != 0; --drop) {
-          if (WORDS == 2 && t[wB] != 0)
-            t[wB] ^= 0x80000000u >> __builtin_clz(t[wB]);
-          else
-            t[0] ^= 0x80000000u >> __builtin_clz(t[0]);
+          bool done = false;  // clear the highest remaining tie of the lane
+#pragma unroll
+          for (int w = WORDS - 1; w >= 0; --w) {
+            if (!done && t[w] != 0) {
+              t[w] ^= 0x80000000u >> __builtin_clz(t[w]);
+              done = true;
+            }
+          }
         }
       }
 #pragma unroll
@@ -558,16 +574,21 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
     if (k <= kStageSlots) {
       // list the surviving columns in order in LDS, then write idx / val with coalesced stores
       {
-        uint32_t mA = keep[0], mB = WORDS == 2 ? keep[wB] : 0u;
-        uint32_t slotA = slot, slotB = WORDS == 2 ? slot + __popc(keep[0]) : slot + kc - 1u;
-        while (ballot64((mA | mB) != 0) != 0) {
-          bool vA, vB;
-          uint32_t cA, cB;
-          pop2(mA, mB, vA, cA, vB, cB);
-          if (vA && slotA < k) *stage_at(slotA) = static_cast<uint16_t>(lane * COLS + cA);
-          if (vB && slotB < k) *stage_at(slotB) = static_cast<uint16_t>(lane * COLS + cB);
-          ++slotA;
-          slotB += WORDS == 2 ? 1u : 0xFFFFFFFFu;
+        uint32_t first = slot;  // slot of the pair's first survivor
+#pragma unroll
+        for (int p = 0; p < PAIRS; ++p) {
+          uint32_t mA = keep[word_a(p)], mB = WORDS >= 2 ? keep[word_b(p)] : 0u;
+          uint32_t slotA = first, slotB = WORDS >= 2 ? first + __popc(mA) : first + kc - 1u;
+          first += __popc(mA) + __popc(mB);
+          while (ballot64((mA | mB) != 0) != 0) {
+            bool vA, vB;
+            uint32_t cA, cB;
+            pop2(mA, mB, vA, cA, vB, cB, p);
+            if (vA && slotA < k) *stage_at(slotA) = static_cast<uint16_t>(lane * COLS + cA);
+            if (vB && slotB < k) *stage_at(slotB) = static_cast<uint16_t>(lane * COLS + cB);
+            ++slotA;
+            slotB += WORDS >= 2 ? 1u : 0xFFFFFFFFu;
+          }
         }
       }
       wave_lds_fence();

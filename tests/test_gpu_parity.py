@@ -867,6 +867,35 @@ def test_mp_bitmask_c5_block(dct):
     assert np.array_equal(host(dval), oracle.rowtopk_bwd_bitmask(host(dy), emask, k))
 
 
+# ------------------------------------------------------------------ MP: bf16 rows of 4096 ... 8192 columns (four bitmap words per lane)
+@pytest.mark.parametrize("B,D,k,enc", [(37, 8192, 409, 0), (20, 5120, 256, 1), (9, 6144, 300, 2), (5, 8192, 512, 0),
+                                       (6, 4104, 1, 0), (4, 8192, 8192, 0), (11, 7168, 1000, 2)])
+def test_mp_bf16_wide_rows(dct, B, D, k, enc):
+    x = si.relu_activations(B, D, DEV, 1980 + D + k, dtype=torch.bfloat16)
+    cols = torch.arange(D, device=DEV)
+    x[0] = 0.75                                    # all equal: the k lowest columns
+    x[1] = 0.0
+    x[2] = torch.where(cols % 2 == 0, 1.0, 2.0).to(torch.bfloat16)
+    x[3] = (cols % 5).to(torch.bfloat16)           # ties across the quota boundary in every word of a lane
+    val = torch.zeros(B, k, dtype=torch.bfloat16, device=DEV)
+    tau = torch.zeros(B, dtype=torch.bfloat16, device=DEV)
+    xh = host(x)
+    ei, ev, et = oracle.rowtopk_fwd(xh, k)
+    if enc == 2:
+        mask = torch.full((B, (D + 31) // 32), -1, dtype=torch.int32, device=DEV)
+        dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, tau)
+        em, _, _ = oracle.rowtopk_fwd_bitmask(xh, k)
+        assert np.array_equal(mask.cpu().numpy().view(np.uint32), em)
+    else:
+        idx = torch.full((B, k), -1, dtype=torch.int16 if enc == 1 else torch.int32, device=DEV)
+        (dct.dct_rowtopk_fwd_idx16 if enc == 1 else dct.dct_rowtopk_fwd)(x, k, idx, val, tau)
+        got = idx.cpu().numpy()
+        got = got.view(np.uint16).astype(np.int32) if enc == 1 else got
+        bad = np.nonzero((got != ei).any(axis=1))[0]
+        assert bad.size == 0, (bad[:10], got[bad[0]][:20], ei[bad[0]][:20])
+    assert np.array_equal(host(val), ev) and np.array_equal(host(tau), et)
+
+
 # ------------------------------------------------------------------ MP: many narrow bf16 rows (four rows per wavefront)
 @pytest.mark.parametrize("B,D,k,pad,idx16", [
     (8192, 256, 12, 0, False), (8193, 512, 25, 0, False), (10_000, 1024, 51, 0, False), (8200, 128, 6, 0, True),
