@@ -1140,7 +1140,7 @@ def test_random_mp_configurations(dct):
     rng = np.random.default_rng(20100889)
     for case in range(40):
         dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
-        D = int(rng.choice([8, 16, 24, 64, 72, 128, 200, 256, 264, 512, 520, 1000, 1024, 1032, 2048, 4096]))
+        D = int(rng.choice([8, 16, 24, 64, 72, 128, 200, 256, 264, 512, 520, 1000, 1024, 1032, 2048, 4096, 5120, 8192]))
         B = int(rng.integers(8192, 10000)) if rng.random() < 0.5 else int(rng.integers(1, 400))
         B = min(B, max(1, 12_000_000 // D))
         k = min(D, [1, max(1, D // 20), max(1, D // 3), D][int(rng.integers(0, 4))])
