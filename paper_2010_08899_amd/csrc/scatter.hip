@@ -25,8 +25,11 @@ namespace {
 constexpr int kScThreads = 256;
 constexpr uint32_t kScTileBytes = 16384;
 constexpr uint32_t kScMaxGrid = 2048;
-constexpr uint32_t kScAssignMaxGrid = 8192;
-constexpr uint32_t kScWgPerCu = 16;  // workgroups per CU of the assign kernel: two rounds of the resident ones
+// Tiles per workgroup of the assign kernel.  Many short workgroups, started by the hardware in address order,
+// keep the stores in flight within a narrow window of the output, which is what writes want on this chip
+// (c4: 4 tiles 187 us, 8 tiles 202 us, 16 tiles 214 us); with 2 tiles the search at the start of every
+// workgroup costs more than that wins (254 us).
+constexpr uint32_t kScTilesPerWg = 4;
 constexpr uint32_t kRowLdsBytes = 16384;  // per wavefront in the on-chip row kernel
 
 // Pairs to apply: the survivor count clipped to what the buffers hold; the
@@ -296,9 +299,7 @@ extern "C" int dct_scatter(const int32_t* d_idx, const void* d_val, const uint64
   if (is_aligned(d_out, 16)) {
     const uint32_t tile = kScTileBytes / static_cast<uint32_t>(es);
     const uint32_t n_tiles = (n32 + tile - 1) / tile;
-    uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * kScWgPerCu;
-    if (max_grid > kScAssignMaxGrid) max_grid = kScAssignMaxGrid;
-    const uint32_t tiles_per_wg = (n_tiles + max_grid - 1) / max_grid;
+    const uint32_t tiles_per_wg = kScTilesPerWg;
     const uint32_t grid = (n_tiles + tiles_per_wg - 1) / tiles_per_wg;
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((scatter_assign_kernel<uint32_t>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
