@@ -110,6 +110,9 @@ __device__ __forceinline__ void put_col(void* idx_base, uint64_t pos, uint32_t c
 
 inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// ceil(a / b) for any a: a + b - 1 would wrap for a close to 2^32.
+inline uint32_t ceil_div(uint32_t a, uint32_t b) { return a / b + (a % b != 0 ? 1u : 0u); }
+
 // Compute units of the current device (cached per device).
 inline int device_cu_count() {
   static int cached[64] = {0};

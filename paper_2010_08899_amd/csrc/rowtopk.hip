@@ -394,7 +394,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   void* io = idx_or_mask;
-  uint32_t grid = (B + kRtWaves - 1) / kRtWaves;
+  uint32_t grid = ceil_div(B, kRtWaves);
   if (grid > 65536u * 4) grid = 65536u * 4;
   // rows that fit the on-chip kernel: whole 16-byte vectors, 16-byte-aligned rows, at most 16 KiB
   const uint32_t epv = static_cast<uint32_t>(16 / es);
@@ -403,7 +403,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
       B >= kQuadMinRows && is_aligned(x, 16) && row_stride_elems % 8 == 0) {
     const uint32_t vecs = D / 8;
     const uint32_t nv = vecs <= 16 ? 1u : vecs <= 32 ? 2u : vecs <= 64 ? 4u : 8u;
-    const uint32_t groups = (B + quad::kRows - 1) / quad::kRows;
+    const uint32_t groups = ceil_div(B, quad::kRows);
     uint32_t qgrid = (groups + quad::kWaves - 1) / quad::kWaves;
     // workgroups per CU that registers and the LDS row buffers allow
     const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * (nv == 8 ? 4u : nv == 4 ? 6u : 8u);
@@ -429,7 +429,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     return launch_status();
   }
   if (D % epv == 0 && D * es <= 16384u && is_aligned(x, 16) && row_stride_elems % epv == 0) {
-    uint32_t fgrid = (B + fast::kWaves - 1) / fast::kWaves;
+    uint32_t fgrid = ceil_div(B, fast::kWaves);
     // workgroups per CU that registers and the LDS row buffers allow (rows of up to 2 / 4 / 8 / 16 KiB)
     const uint32_t row_bytes = D * static_cast<uint32_t>(es);
     const uint32_t per_cu = row_bytes <= 2048u ? 8u : row_bytes <= 4096u ? 6u : row_bytes <= 8192u ? 4u : 2u;
@@ -507,7 +507,7 @@ extern "C" int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint3
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
   const uint32_t wpr = D / 32;
   if (D % 32 == 0 && wpr <= 32 && (wpr & (wpr - 1)) == 0) {  // narrow rows: several per wavefront, one lane per word
-    const uint32_t steps = (B + kWave / wpr - 1) / (kWave / wpr);
+    const uint32_t steps = ceil_div(B, kWave / wpr);
     const uint32_t wgrid = std::min<uint32_t>((steps + kRtWaves - 1) / kRtWaves, resident);
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((rowtopk_bitmask_words_kernel<uint32_t, true>), dim3(wgrid), dim3(kRtThreads), 0, s,
@@ -520,7 +520,7 @@ extern "C" int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint3
     }
     return launch_status();
   }
-  const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
+  const uint32_t grid = std::min<uint32_t>(ceil_div(B, kRtWaves), resident);
   if (dt == DCT_F32) {
     hipLaunchKernelGGL((rowtopk_bitmask_lanes_kernel<uint32_t, true>), dim3(grid), dim3(kRtThreads), 0, s,
                        static_cast<const uint32_t*>(dy), B, D, row_stride_elems, k, d_mask,
@@ -543,11 +543,11 @@ extern "C" int dct_rowtopk_scatter_bitmask(const uint32_t* d_mask, const void* d
   if (!is_aligned(d_mask, 4) || !is_aligned(d_val, es) || !is_aligned(d_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
-  const uint32_t grid = std::min<uint32_t>((B + kRtWaves - 1) / kRtWaves, resident);
+  const uint32_t grid = std::min<uint32_t>(ceil_div(B, kRtWaves), resident);
   const uint32_t wpr = D / 32;
   if (D % 32 == 0 && wpr <= 32 && (wpr & (wpr - 1)) == 0 && out_row_stride_elems == D && is_aligned(d_out, 16)) {
     // narrow dense rows: several per wavefront, one lane per mask word
-    const uint32_t steps = (B + kWave / wpr - 1) / (kWave / wpr);
+    const uint32_t steps = ceil_div(B, kWave / wpr);
     const uint32_t wgrid = std::min<uint32_t>((steps + kRtWaves - 1) / kRtWaves, resident);
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((rowtopk_bitmask_words_kernel<uint32_t, false>), dim3(wgrid), dim3(kRtThreads), 0, s,
@@ -598,7 +598,8 @@ int launch_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stri
   if (!is_aligned(dy, es) || !is_aligned(d_idx, sizeof(I)) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint64_t n_out = static_cast<uint64_t>(B) * k;
-  if (k < 192u && (n_out + 255) / 256 <= 0x7FFFFFFFull) {  // few outputs per row: one thread per output over all rows
+  // few outputs per row: one thread per output over all rows (a grid holds fewer than 2^32 threads)
+  if (k < 192u && n_out + 255 <= 0xFFFFFFFFull) {
     const dim3 fgrid(static_cast<uint32_t>((n_out + 255) / 256));
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((rowtopk_bwd_gather_flat_kernel<uint32_t, I>), fgrid, dim3(256), 0, s,

@@ -345,7 +345,7 @@ int launch_rowscatter(const I* d_idx, const void* d_val, int dt, uint32_t B, uin
     const bool vec_ok = is_aligned(d_out, 16) && (out_row_stride_elems * es) % 16 == 0 && (D * es) % 16 == 0;
     const uint32_t rows_per_step = static_cast<uint32_t>(kRowLdsBytes / (D * es));
     if (vec_ok && out_row_stride_elems == D && rows_per_step >= 8) {  // dense rows of up to 2 KiB: several per step
-      const uint32_t steps = (B + rows_per_step - 1) / rows_per_step;
+      const uint32_t steps = ceil_div(B, rows_per_step);
       const uint32_t bgrid = std::min<uint32_t>((steps + 3) / 4, resident);
       if (dt == DCT_F32) {
         hipLaunchKernelGGL((rowscatter_block_kernel<uint32_t, I>), dim3(bgrid), dim3(kScThreads), 0, s, d_idx,
@@ -356,7 +356,7 @@ int launch_rowscatter(const I* d_idx, const void* d_val, int dt, uint32_t B, uin
       }
       return launch_status();
     }
-    const uint32_t grid = std::min<uint32_t>((B + 3) / 4, resident);
+    const uint32_t grid = std::min<uint32_t>(ceil_div(B, 4u), resident);
     if (dt == DCT_F32) {
       hipLaunchKernelGGL((rowscatter_lds_kernel<uint32_t, I>), dim3(grid), dim3(kScThreads), 0, s, d_idx,
                          static_cast<const uint32_t*>(d_val), B, D, k, static_cast<uint32_t*>(d_out),

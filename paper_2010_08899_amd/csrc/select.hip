@@ -205,9 +205,11 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
 
 // ------------------------------------------------------------------ kernel 2
 // Streaming partition pass: count keys > hi, append keys in [lo, hi] to the
-// candidate buffer.  One contiguous chunk per workgroup, a contiguous quarter per
-// wavefront; candidates are staged in LDS and flushed with one slot reservation
-// per flush (their order is irrelevant: only the multiset of keys matters).
+// candidate buffer.  Tiles of 16 KiB go round-robin to the workgroups, a quarter of
+// each tile to a wavefront; candidates are staged in LDS per wavefront and written
+// to the workgroup's region of the buffer with one slot reservation per workgroup
+// at the end (and one per wavefront whenever its staging area fills up before that).
+// Their order is irrelevant: only the multiset of keys matters.
 struct PartGeom {
   uint32_t head, n_vec, tail, grid, vecs_per_wg;
 };
