@@ -41,6 +41,8 @@ def bits(a):
 
 
 def keys_of(v):
+    if v.dtype == torch.bfloat16:
+        return v.view(torch.int16).to(torch.int32) & 0x7FFF
     return v.view(torch.int32) & 0x7FFFFFFF
 
 
@@ -73,26 +75,30 @@ def check_threshold_record(keys, k, thr):
     assert (thr.n_gt, thr.n_eq, thr.tie_quota) == (n_gt, n_eq, k - n_gt)
 
 
-def test_dp_longest_vector(dct):
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_dp_longest_vector(dct, dtype):
     n = (1 << 31) - 1
     k = n // 200
     g = si.gaussian_gradient(n, DEV, 3100)
-    # a planted value near the 0.5 % quantile (2.807 sigma): tau lands on it, with a million ties to ration
-    tie_value = 2.82e-3
+    # a planted value near the 0.5 % quantile (2.807 sigma): tau lands on it, with two million ties to ration
+    # (bf16 has ties by the million without any planting: 2^31 elements share 2^15 keys)
+    tie_value = float(torch.tensor(2.82e-3).to(dtype))
     g[::1000] = tie_value
     g[n - 1] = -tie_value
+    g = g.to(dtype)
     keys = keys_of(g)
+    it = torch.int32 if dtype == torch.float32 else torch.int16
 
     thr_t = torch.zeros(4, dtype=torch.int32, device=DEV)
     dct.dct_select_threshold(g, k, thr_t, dct.new_select_workspace(g))
     thr = oracle.Threshold(*dct.read_threshold(thr_t))
     check_threshold_record(keys, k, thr)
-    assert thr.tau_key == int(np.array([tie_value], dtype=np.float32).view(np.uint32)[0])
+    assert thr.tau_key == int(keys[0])
     assert 1 < thr.tie_quota < thr.n_eq
 
     cap = thr.n_gt + thr.n_eq + 16
     idx = torch.full((cap,), -7, dtype=torch.int32, device=DEV)
-    val = torch.zeros(cap, dtype=torch.float32, device=DEV)
+    val = torch.zeros(cap, dtype=dtype, device=DEV)
     cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
     ws = dct.new_compact_workspace(g)
 
@@ -102,7 +108,7 @@ def test_dp_longest_vector(dct):
     want = torch.cat([indices_where(keys, thr.tau_key, "gt"),
                       indices_where(keys, thr.tau_key, "eq", limit=thr.tie_quota)]).sort().values
     assert want.numel() == k and torch.equal(idx[:k].long(), want)
-    assert torch.equal(val[:k].view(torch.int32), g[want].view(torch.int32))
+    assert torch.equal(val[:k].view(it), g[want].view(it))
     assert bool((idx[k:] == -7).all())
 
     # GE_TAU: the paper's mask
@@ -112,7 +118,7 @@ def test_dp_longest_vector(dct):
     assert c == thr.n_gt + thr.n_eq
     want = indices_where(keys, thr.tau_key, "ge")
     assert torch.equal(idx[:c].long(), want)
-    assert torch.equal(val[:c].view(torch.int32), g[want].view(torch.int32))
+    assert torch.equal(val[:c].view(it), g[want].view(it))
     assert int(idx[c - 1]) == n - 1 and bool((idx[c:] == -7).all())  # the very last element is a tie
 
     # the oracle on the last 2^20 elements
@@ -124,11 +130,11 @@ def test_dp_longest_vector(dct):
     assert np.array_equal(bits(host(val[first:c])), bits(eval_))
 
     # decompression: a dense vector with the survivors in place
-    dense = torch.full((n,), 5.0, device=DEV)
+    dense = torch.full((n,), 5.0, dtype=dtype, device=DEV)
     dct.dct_scatter(idx, val, cnt, dense)
-    expect = torch.zeros(n, device=DEV)
+    expect = torch.zeros(n, dtype=dtype, device=DEV)
     expect[want] = g[want]
-    assert torch.equal(dense.view(torch.int32), expect.view(torch.int32))
+    assert torch.equal(dense.view(it), expect.view(it))
 
 
 def test_dp_ef_longest_vector(dct):
