@@ -70,6 +70,11 @@ typedef struct {
  * workspace uninitialised or corrupted (no survivor is written in that case). */
 #define DCT_COUNT_WORKSPACE_ERROR UINT64_MAX
 
+/* tau_key of a threshold record whose selection gave up (see "Concurrency" at
+ * dct_select_threshold); the other three words are 0.  No key has bit 31 set, so
+ * a compaction with such a record keeps nothing. */
+#define DCT_TAU_KEY_ERROR 0xFFFFFFFFu
+
 /* ---------------------------------------------------------------- DCT-DP ---
  * Algorithm 1, threshold selection ("sort |W_grad|; tau = w_floor(N*eta)"),
  * computed exactly without sorting or copying the gradient: a radix select over
@@ -81,6 +86,14 @@ typedef struct {
  *   d_thr_out  device, receives the dct_threshold
  *   d_ws       device workspace of at least dct_select_threshold_workspace_bytes,
  *              256-byte aligned; contents on entry are irrelevant, it is scratch
+ *
+ * Concurrency: the last kernel of the call runs all radix passes in one launch, its
+ * workgroups (at most one per compute unit) meeting at grid barriers between the
+ * passes.  They are resident together when the device has room for them, which a
+ * stream that runs alone always has.  If other work keeps part of the grid off the
+ * device for about a second, the waiting workgroups give up, every kernel still ends,
+ * and the record reads {DCT_TAU_KEY_ERROR, 0, 0, 0}: select again.  The same holds
+ * for dct_ef_select_threshold.
  */
 size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n);
 int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,

@@ -17,6 +17,7 @@ from . import build as _build
 DCT_OK, DCT_ERR_INVALID, DCT_ERR_WORKSPACE, DCT_ERR_OVERFLOW, DCT_ERR_HIP = range(5)
 DCT_F32, DCT_BF16 = 0, 1
 DCT_GE_TAU, DCT_EXACT_K = 0, 1
+DCT_TAU_KEY_ERROR = 0xFFFFFFFF
 DCT_SCATTER_ASSIGN, DCT_SCATTER_ADD = 0, 1
 COUNT_WORKSPACE_ERROR = (1 << 64) - 1
 
@@ -232,9 +233,12 @@ def dct_ef_threshold_compact(g: torch.Tensor, e_in: torch.Tensor, e_out: torch.T
 
 
 def read_threshold(thr: torch.Tensor) -> Threshold:
-    """Synchronising host copy of a device dct_threshold."""
-    v = thr.cpu().tolist()
-    return Threshold(*(x & 0xFFFFFFFF for x in v))
+    """Synchronising host copy of a device dct_threshold; raises if the selection gave up."""
+    v = [x & 0xFFFFFFFF for x in thr.cpu().tolist()]
+    if v[0] == DCT_TAU_KEY_ERROR:
+        raise DctError(DCT_ERR_HIP, "dct_select_threshold (its workgroups did not become resident together: "
+                                    "select again)")
+    return Threshold(*v)
 
 
 def read_count(count_out: torch.Tensor, capacity: int | None = None) -> int:

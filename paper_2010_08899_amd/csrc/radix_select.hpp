@@ -102,11 +102,13 @@ __device__ BinHit find_bin(LoadBin load_bin, uint32_t k_rem, uint32_t* s_tmp) {
   return r;
 }
 
-// Search state after the pass whose state was `prev` and whose histogram is `hist`.
-__device__ SelState advance_state(const SelState& prev, const uint32_t* hist, uint32_t* s_tmp) {
+// Search state after the pass whose state was `prev` and whose histogram load_bin reads (called by all
+// THREADS threads of a workgroup, see find_bin).
+template <int THREADS, typename LoadBin>
+__device__ SelState advance_state_with(const SelState& prev, LoadBin load_bin, uint32_t* s_tmp) {
   SelState st = prev;
   if (prev.width != 0) {  // uniform
-    const BinHit hit = find_bin<kSelThreads>([&](uint32_t b) { return hist[b]; }, prev.k_rem, s_tmp);
+    const BinHit hit = find_bin<THREADS>(load_bin, prev.k_rem, s_tmp);
     st.rem_bits = prev.rem_bits - prev.width;
     st.prefix = prev.prefix | (hit.bin << st.rem_bits);
     st.k_rem = prev.k_rem - hit.above;
@@ -115,6 +117,10 @@ __device__ SelState advance_state(const SelState& prev, const uint32_t* hist, ui
   }
   st.width = min(kDigitBits, st.rem_bits);
   return st;
+}
+// The same for a histogram that an earlier kernel completed, by a workgroup of kSelThreads threads.
+__device__ SelState advance_state(const SelState& prev, const uint32_t* hist, uint32_t* s_tmp) {
+  return advance_state_with<kSelThreads>(prev, [&](uint32_t b) { return hist[b]; }, s_tmp);
 }
 
 

@@ -6,8 +6,9 @@
 // The exact part is a radix select over the key bits, most significant digit
 // first (11 + 11 + 9 bits for fp32, 8 + 7 for bf16): each pass histograms one
 // digit of the keys that match the digits fixed so far (LDS histogram per
-// workgroup, merged into a global one), and the next kernel walks the histogram
-// from the top bin down to find the bin of the k-th largest key.
+// workgroup, merged into one in the workspace), and after a grid barrier every
+// workgroup walks the merged histogram from the top bin down to find the bin of the
+// k-th largest key.  All passes run in one launch.
 //
 // For large vectors the radix passes do not run over the vector.  A first kernel
 // gathers a stratified sample of 16384 keys, a second one brackets two of its
@@ -26,6 +27,8 @@
 // sort) the EF variants of the kernels that read the vector read g and the
 // residual e together and select on w = g + e, one fp32 addition per element,
 // without storing w: dct_ef_threshold_compact forms the same sums again.
+#include <algorithm>
+
 #include "dct_common.hpp"
 #include "radix_select.hpp"
 
@@ -34,9 +37,11 @@ namespace {
 
 constexpr int kSelMaxPasses = 3;
 constexpr int kSelUnroll = 4;                   // 16-byte loads in flight per lane in the radix passes
-constexpr uint32_t kSelMaxGrid = 4096;
-constexpr uint32_t kCandGrid = 256;
-constexpr uint32_t kFallbackGrid = 1024;
+constexpr uint32_t kSelMaxGrid = 4096;            // workgroups of the partition pass (at most)
+constexpr int kTailThreads = 1024;                // the kernel of the radix passes: few, large workgroups
+constexpr uint32_t kTailMaxGrid = 256;
+constexpr int kTailKeep = 8;                      // 16-byte vectors of candidates per thread kept in registers
+constexpr uint32_t kTailSpinLimit = 1u << 20;     // polls of a grid barrier (about a second) before giving up
 
 constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes run over the vector itself
 constexpr int kSampleThreads = 1024;
@@ -60,8 +65,8 @@ struct SelWs {
   uint32_t lo, hi;     // bounds from the sample
   uint32_t sampled;    // 1 when the sample / partition kernels ran
   uint32_t cand_cap;   // capacity of the whole candidate buffer, a multiple of 4 * kCandRegions keys
-  uint32_t pad[4];
-  SelState state[kSelMaxPasses + 1];  // state[p]: search state at the start of pass p
+  uint32_t bar[kSelMaxPasses];  // workgroups that have merged their histogram of pass p
+  uint32_t pad;
   uint32_t hist[kSelMaxPasses][kSelBins];
   uint32_t sample[kSampleSize];       // keys of the stratified sample
   uint32_t cand[4];    // candidate keys follow (cand_cap of them, region r at r * cand_cap / kCandRegions)
@@ -386,26 +391,77 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
 }
 
 // ------------------------------------------------------------------ kernel 3
-// One radix pass.  Every workgroup first derives the search state of this pass
-// (from the partition counts for pass 0, from the previous pass's histogram
-// otherwise), then histograms its part of the source.
+// Vector vi of a candidate region that holds n_src keys, as the candidate passes use it: key - lo for
+// the keys (below 2^31), all ones for the slots past the region's end (they match no prefix).
+__device__ __forceinline__ uint4 offset_keys(const uint4& v, uint32_t vi, uint32_t n_src, uint32_t lo_key) {
+  const uint32_t n_valid = n_src > vi * 4u ? n_src - vi * 4u : 0u;
+  return make_uint4(n_valid > 0u ? v.x - lo_key : 0xFFFFFFFFu, n_valid > 1u ? v.y - lo_key : 0xFFFFFFFFu,
+                    n_valid > 2u ? v.z - lo_key : 0xFFFFFFFFu, n_valid > 3u ? v.w - lo_key : 0xFFFFFFFFu);
+}
+
+__device__ __forceinline__ uint32_t add_agent(uint32_t* p, uint32_t v) {
+  return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The radix passes and the result, in one launch.  Every workgroup derives the search state
+// (from the partition counts at first, from the merged histogram after each pass), histograms
+// its part of the source in LDS and adds the non-empty bins to the pass's histogram in the
+// workspace; a grid barrier (an arrival counter polled with agent-scope loads) separates a pass
+// from the search in its histogram, which every workgroup repeats for itself.  The grid is
+// small enough to be resident as a whole; a workgroup that waits longer than about a second
+// gives up (spin_limit polls), and workgroup 0 then stores DCT_TAU_KEY_ERROR in the result.
+//
+// Merging costs more than reading here: after the subtraction of lo the candidates fill most of
+// the 2048 bins of the first digit, every workgroup adds most of its bins, and the device
+// sustains some 40 G such adds a second (256 workgroups x 2048 bins: 13 us).  The candidate
+// passes are therefore left to one workgroup per region (64 of them, 1024 threads each; the
+// others leave at once), and what then limits them is one CU's instruction rate: about 27
+// keys per thread on c4, held in registers from the first pass on and tested with two
+// instructions per key and pass.  A pass over the vector itself (small vectors, or bounds
+// that failed) uses the whole grid.  On c4 the kernel takes 25 us, against 26 us for the
+// three pass kernels and the finishing kernel it replaced, and 43 us less on c3, whose
+// larger grids spent their time merging.
 template <int DT, bool EF>
-__global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
+__global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
     const typename Elem<DT>::word_t* __restrict__ g_al, const typename Elem<DT>::word_t* __restrict__ e_al,
-    uint32_t off, uint32_t n_virt, uint32_t k, SelWs* ws, int pass) {
+    uint32_t off, uint32_t n_virt, uint32_t k, SelWs* ws, int n_pass, uint32_t spin_limit,
+    dct_threshold* __restrict__ out) {
   static_assert(!EF || DT == DCT_F32, "error feedback is an fp32 addition");
   using E = Elem<DT>;
   constexpr int V = E::kVec;
   __shared__ uint32_t h[kSelBins];
-  __shared__ uint32_t s_tmp[kSelWaves + 4];
+  __shared__ uint32_t s_tmp[kTailThreads / kWave + 4];
   __shared__ uint32_t s_tot[3];
-  const uint32_t span = kSelThreads * kSelUnroll;  // vectors per workgroup per iteration
+  __shared__ uint32_t s_arrived;
+  const uint32_t span = kTailThreads * kSelUnroll;  // vectors per workgroup per iteration
   const uint32_t region_cap = ws->cand_cap / kCandRegions;
 
-  // ---- search state at the start of this pass
+  // The head of the candidate region this workgroup will read (if it reads candidates at all) is
+  // requested before anything else and stays in registers for all passes: kTailKeep vectors per
+  // thread, which is the whole region unless the bounds were wide.  (No partition pass: the
+  // counters are zero and nothing is loaded.)
+  const uint32_t lo_key = ws->lo;
+  uint32_t cnt0 = 0;
+  uint4 keep[kTailKeep];
+  {
+    const uint32_t region0 = blockIdx.x % kCandRegions;
+    if (blockIdx.x < kCandRegions) cnt0 = min(static_cast<uint32_t>(ws->counts[region0].c), region_cap);
+    const uint4* cv = reinterpret_cast<const uint4*>(ws->cand + static_cast<size_t>(region0) * region_cap);
+    const uint32_t vecs0 = (cnt0 + 3) / 4;
+#pragma unroll
+    for (int u = 0; u < kTailKeep; ++u) {
+      const uint32_t vi = u * kTailThreads + threadIdx.x;
+      keep[u] = vi < vecs0 ? cv[vi] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < kTailKeep; ++u) keep[u] = offset_keys(keep[u], u * kTailThreads + threadIdx.x, cnt0, lo_key);
+  }
+
+  // ---- search state before the first pass
   SelState st;
-  if (pass == 0) {
-    // totals of the partition pass over the regions (one counter per lane of the first wavefront)
+  {
+    // totals of the partition pass over the regions (one counter per lane of the first wavefront;
+    // all zero when no partition pass ran)
     if (threadIdx.x < kWave) {
       static_assert(kCandRegions == kWave, "one region counter per lane");
       const unsigned long long c = ws->counts[threadIdx.x].c;
@@ -432,112 +488,182 @@ __global__ __launch_bounds__(kSelThreads) void select_pass_kernel(
     st.rem_bits = diff ? 32u - __builtin_clz(diff) : 0u;
     st.prefix = 0u;
     st.width = min(kDigitBits, st.rem_bits);
-  } else {
-    st = ws->state[pass - 1];
   }
-  // vectors of the source; a workgroup with nothing to read leaves at once
-  // (the candidate passes use few workgroups -- fewer histogram merges -- unless there are many candidates)
-  const uint32_t src_vecs = st.from_cand ? (st.n_src + 3) / 4 : n_virt / V + 1;
-  // candidate passes: workgroup b reads part b / kCandRegions of region b % kCandRegions
-  const uint32_t parts = max(1u, min(gridDim.x, max(kCandGrid, src_vecs / (span * 8))) / kCandRegions);
-  if (blockIdx.x != 0 && (st.from_cand ? blockIdx.x / kCandRegions >= parts : blockIdx.x * span >= src_vecs)) return;
-  if (pass != 0) st = advance_state(st, ws->hist[pass - 1], s_tmp);
-  if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[pass] = st;
-  if (st.width == 0) return;  // every digit is fixed already
+  // workgroups that take part (the same number in every workgroup's view: it decides the barriers)
+  const uint32_t src_vecs = n_virt / V + 1;
+  const uint32_t n_active =
+      st.from_cand ? min(gridDim.x, kCandRegions) : min(gridDim.x, (src_vecs + span - 1) / span);
+  if (blockIdx.x >= n_active) return;
 
-  const uint32_t shift = st.rem_bits - st.width;
-  const uint32_t dmask = (1u << st.width) - 1u;
-  const uint32_t fixed_mask = E::kKeyMask & ~((1u << st.rem_bits) - 1u);
-  const uint32_t prefix = st.prefix;
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) h[i] = 0;
-  __syncthreads();
+  for (int pass = 0; pass < n_pass && st.width != 0; ++pass) {  // uniform over the grid
+    const uint32_t shift = st.rem_bits - st.width;
+    const uint32_t dmask = (1u << st.width) - 1u;
+    const uint32_t fixed_mask = E::kKeyMask & ~((1u << st.rem_bits) - 1u);
+    const uint32_t prefix = st.prefix;
+    for (int i = threadIdx.x; i < kSelBins; i += kTailThreads) h[i] = 0;
+    __syncthreads();
 
-  if (st.from_cand) {
-    // candidate keys of one region: u32, 16-byte-aligned, as many as its counter says
-    const uint32_t region = blockIdx.x % kCandRegions, part = blockIdx.x / kCandRegions;
-    const uint4* cv = reinterpret_cast<const uint4*>(ws->cand + static_cast<size_t>(region) * region_cap);
-    const uint32_t n_src = part < parts ? static_cast<uint32_t>(ws->counts[region].c) : 0u;  // <= region_cap here
-    const uint32_t base_key = ws->lo;
-    const uint32_t reg_vecs = (n_src + 3) / 4;
-    for (uint32_t base = part * span; base < reg_vecs; base += parts * span) {
-      uint4 v[kSelUnroll];
-#pragma unroll
-      for (int u = 0; u < kSelUnroll; ++u) {
-        const uint32_t vi = base + u * kSelThreads + threadIdx.x;
-        v[u] = vi < reg_vecs ? cv[vi] : make_uint4(0, 0, 0, 0);  // a region holds whole vectors
-      }
-#pragma unroll
-      for (int u = 0; u < kSelUnroll; ++u) {
-        const uint32_t e0 = (base + u * kSelThreads + threadIdx.x) * 4;
+    if (st.from_cand) {
+      // candidate keys, a region at a time: u32, 16-byte-aligned, as many as the region's counter says
+      // One vector of four offset keys per lane (offset_keys() below).  The digits of candidates differ
+      // from lane to lane as a rule (plain LDS adds, after one test whether the wavefront has anything
+      // to add at all: in the later passes it rarely has); when every key the wavefront adds falls into
+      // ONE bin -- ties -- a single add replaces up to 256 that would serialise.
+      const uint32_t fixed_all = ~((1u << st.rem_bits) - 1u);  // with bit 31: set in no prefix, in all fillers
+      auto add_vec = [&](const uint4& v) {
+        const uint32_t key[4] = {v.x, v.y, v.z, v.w};
+        bool act[4];
+        bool any = false;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t key = Elem<DCT_F32>::raw(v[u], e) - base_key;
-          hist_add(h, e0 + e < n_src && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+          act[e] = (key[e] & fixed_all) == prefix;
+          any |= act[e];
+        }
+        const uint64_t m_any = ballot64(any);
+        if (m_any == 0) return;
+        // (the empty asm keeps the compiler from computing the digits ahead of the test above, for all the
+        // vectors a thread holds: most of a later pass's time went there)
+        uint32_t k0 = key[0], k1 = key[1], k2 = key[2], k3 = key[3];
+        asm volatile("" : "+v"(k0), "+v"(k1), "+v"(k2), "+v"(k3));
+        const uint32_t digit[4] = {(k0 >> shift) & dmask, (k1 >> shift) & dmask, (k2 >> shift) & dmask,
+                                   (k3 >> shift) & dmask};
+        const uint32_t mine = act[0] ? digit[0] : act[1] ? digit[1] : act[2] ? digit[2] : digit[3];
+        const int leader = __builtin_ctzll(m_any);
+        const uint32_t d0 = __shfl(mine, leader, kWave);  // a digit that some lane adds
+        bool differs = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) differs |= act[e] && digit[e] != d0;
+        if (ballot64(differs) == 0) {
+          uint32_t total = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) total += static_cast<uint32_t>(__popcll(ballot64(act[e])));
+          if (static_cast<int>(lane_id()) == leader) atomicAdd(&h[d0], total);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (act[e]) atomicAdd(&h[digit[e]], 1u);
+        }
+      };
+      for (uint32_t region = blockIdx.x; region < kCandRegions; region += n_active) {
+        const uint4* cv = reinterpret_cast<const uint4*>(ws->cand + static_cast<size_t>(region) * region_cap);
+        const bool first = region == blockIdx.x;  // its head is in registers
+        const uint32_t n_src = first ? cnt0 : static_cast<uint32_t>(ws->counts[region].c);  // <= region_cap here
+        const uint32_t reg_vecs = (n_src + 3) / 4;
+        if (first) {
+#pragma unroll
+          for (int u = 0; u < kTailKeep; ++u) add_vec(keep[u]);
+        }
+        for (uint32_t base = first ? kTailKeep * kTailThreads : 0u; base < reg_vecs; base += span) {
+          uint4 v[kSelUnroll];
+#pragma unroll
+          for (int u = 0; u < kSelUnroll; ++u) {
+            const uint32_t vi = base + u * kTailThreads + threadIdx.x;
+            v[u] = vi < reg_vecs ? cv[vi] : make_uint4(0, 0, 0, 0);  // a region holds whole vectors
+          }
+#pragma unroll
+          for (int u = 0; u < kSelUnroll; ++u)
+            add_vec(offset_keys(v[u], base + u * kTailThreads + threadIdx.x, n_src, lo_key));
         }
       }
-    }
-  } else {
-    // the vector itself.  Vectors [v_lo, v_hi) are entirely inside the data; at most one
-    // vector on each side straddles an end and is read element by element by workgroup 0.
-    const uint32_t v_lo = off ? 1u : 0u;
-    const uint32_t v_hi = n_virt / V;
-    const uint4* gv = reinterpret_cast<const uint4*>(g_al);
-    const uint4* ev = reinterpret_cast<const uint4*>(e_al);
-    for (uint32_t base = v_lo + blockIdx.x * span; base < v_hi; base += gridDim.x * span) {
-      uint4 v[kSelUnroll], ve4[EF ? kSelUnroll : 1];
-      bool in[kSelUnroll];
+    } else {
+      // the vector itself.  Vectors [v_lo, v_hi) are entirely inside the data; at most one
+      // vector on each side straddles an end and is read element by element by workgroup 0.
+      const uint32_t v_lo = off ? 1u : 0u;
+      const uint32_t v_hi = n_virt / V;
+      const uint4* gv = reinterpret_cast<const uint4*>(g_al);
+      const uint4* ev = reinterpret_cast<const uint4*>(e_al);
+      for (uint32_t base = v_lo + blockIdx.x * span; base < v_hi; base += n_active * span) {
+        uint4 v[kSelUnroll], ve4[EF ? kSelUnroll : 1];
+        bool in[kSelUnroll];
 #pragma unroll
-      for (int u = 0; u < kSelUnroll; ++u) {
-        const uint32_t vi = base + u * kSelThreads + threadIdx.x;
-        in[u] = vi < v_hi;
-        v[u] = in[u] ? gv[vi] : make_uint4(0, 0, 0, 0);
-        if constexpr (EF) ve4[u] = in[u] ? ev[vi] : make_uint4(0, 0, 0, 0);
-      }
+        for (int u = 0; u < kSelUnroll; ++u) {
+          const uint32_t vi = base + u * kTailThreads + threadIdx.x;
+          in[u] = vi < v_hi;
+          v[u] = in[u] ? gv[vi] : make_uint4(0, 0, 0, 0);
+          if constexpr (EF) ve4[u] = in[u] ? ev[vi] : make_uint4(0, 0, 0, 0);
+        }
 #pragma unroll
-      for (int u = 0; u < kSelUnroll; ++u) {
-        if constexpr (EF) v[u] = add4(v[u], ve4[u]);
+        for (int u = 0; u < kSelUnroll; ++u) {
+          if constexpr (EF) v[u] = add4(v[u], ve4[u]);
 #pragma unroll
-        for (int e = 0; e < V; ++e) {
-          const uint32_t key = E::raw(v[u], e) & E::kKeyMask;
-          hist_add(h, in[u] && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+          for (int e = 0; e < V; ++e) {
+            const uint32_t key = E::raw(v[u], e) & E::kKeyMask;
+            hist_add(h, in[u] && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+          }
         }
       }
-    }
-    if (blockIdx.x == 0 && threadIdx.x < kWave) {
-      // head elements [off, min(V, n_virt)) of a misaligned base, tail elements [v_hi*V, n_virt)
-      const uint32_t t = threadIdx.x;
-      uint32_t ve = 0xFFFFFFFFu;
-      if (t < static_cast<uint32_t>(V)) {
-        if (off && t >= off && t < n_virt) ve = t;
-      } else if (t < 2u * V) {
-        const uint32_t c = v_hi * V + (t - V);
-        if (c < n_virt && (c >= static_cast<uint32_t>(V) || !off)) ve = c;
+      if (blockIdx.x == 0 && threadIdx.x < kWave) {
+        // head elements [off, min(V, n_virt)) of a misaligned base, tail elements [v_hi*V, n_virt)
+        const uint32_t t = threadIdx.x;
+        uint32_t ve = 0xFFFFFFFFu;
+        if (t < static_cast<uint32_t>(V)) {
+          if (off && t >= off && t < n_virt) ve = t;
+        } else if (t < 2u * V) {
+          const uint32_t c = v_hi * V + (t - V);
+          if (c < n_virt && (c >= static_cast<uint32_t>(V) || !off)) ve = c;
+        }
+        const bool act = ve != 0xFFFFFFFFu;
+        const uint32_t key = act ? (elem_raw<DT, EF>(g_al, e_al, ve) & E::kKeyMask) : 0u;
+        hist_add(h, act && (key & fixed_mask) == prefix, (key >> shift) & dmask);
       }
-      const bool act = ve != 0xFFFFFFFFu;
-      const uint32_t key = act ? (elem_raw<DT, EF>(g_al, e_al, ve) & E::kKeyMask) : 0u;
-      hist_add(h, act && (key & fixed_mask) == prefix, (key >> shift) & dmask);
     }
-  }
-  __syncthreads();
-  uint32_t* gh = ws->hist[pass];
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) {
-    const uint32_t c = h[i];
-    if (c) atomicAdd(&gh[i], c);
-  }
-}
+    __syncthreads();
 
-// ------------------------------------------------------------------ kernel 4
-// One workgroup: the last histogram fixes the remaining digits; write the result.
-__global__ __launch_bounds__(kSelThreads) void select_finish_kernel(SelWs* ws, int last,
-                                                                    dct_threshold* __restrict__ out) {
-  __shared__ uint32_t s_tmp[kSelWaves + 4];
-  const SelState st = advance_state(ws->state[last], ws->hist[last], s_tmp);
-  if (threadIdx.x == 0) {
+    // merge, then wait until every workgroup has merged
+    uint32_t* gh = ws->hist[pass];
+    if (n_active > 1) {
+      uint32_t seen = 0;
+      for (int i = threadIdx.x; i < kSelBins; i += kTailThreads) {
+        const uint32_t c = h[i];
+        if (c) seen += add_agent(&gh[i], c);  // the value returned: the addition has been performed
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::"v"(seen) : "memory");
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        uint32_t arrived = add_agent(&ws->bar[pass], 1u) + 1u;
+        for (uint32_t spins = 0; arrived < n_active && spins < spin_limit; ++spins) {
+          __builtin_amdgcn_s_sleep(2);
+          arrived = ld_agent(&ws->bar[pass]);
+        }
+        s_arrived = arrived;
+      }
+      __syncthreads();
+      if (s_arrived < n_active) {  // uniform: somebody never came; no result
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+          out->tau_key = DCT_TAU_KEY_ERROR;
+          out->n_gt = 0;
+          out->n_eq = 0;
+          out->tie_quota = 0;
+        }
+        return;
+      }
+      st = advance_state_with<kTailThreads>(st, [&](uint32_t b) { return ld_agent(&gh[b]); }, s_tmp);
+    } else {
+      st = advance_state_with<kTailThreads>(st, [&](uint32_t b) { return h[b]; }, s_tmp);
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     out->tau_key = st.prefix + (st.from_cand ? ws->lo : 0u);  // the candidate passes work on key - lo
     out->n_gt = st.n_gt;
     out->n_eq = st.last_count;
     out->tie_quota = st.k_rem;
   }
+}
+
+// Workgroups of the tail kernel: as many as are resident together (its grid barriers need that), a
+// multiple of the region count when there are that many.
+template <int DT, bool EF>
+uint32_t tail_grid() {
+  static const uint32_t per_cu = [] {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, select_tail_kernel<DT, EF>, kTailThreads, 0) != hipSuccess)
+      nb = 0;
+    return static_cast<uint32_t>(nb > 0 ? nb : 0);
+  }();
+  const uint64_t resident = static_cast<uint64_t>(per_cu) * static_cast<uint32_t>(device_cu_count());
+  uint32_t grid = static_cast<uint32_t>(std::min<uint64_t>(resident, kTailMaxGrid));
+  if (grid > kCandRegions) grid -= grid % kCandRegions;
+  return grid;
 }
 
 // Room for the keys between the sample bounds: about 10 sqrt(p (1 - p) / 16384) of the vector when a
@@ -614,33 +740,28 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
   }
   if (hipGetLastError() != hipSuccess) return DCT_ERR_HIP;
 
-  // radix passes (over the candidates, or over the vector: decided on the device)
+  // radix passes (over the candidates, or over the vector: decided on the device) and the result
   const uint32_t off = static_cast<uint32_t>((addr & 15) / es);
   const uint32_t n_virt = n32 + off;
   const void* g_al = reinterpret_cast<const void*>(addr & ~static_cast<uintptr_t>(15));
   const void* e_al = reinterpret_cast<const void*>(eaddr & ~static_cast<uintptr_t>(15));
-  const uint32_t n_vec_all = n_virt / vec + 1;
-  const uint32_t span = kSelThreads * kSelUnroll;
-  uint32_t grid = (n_vec_all + span - 1) / span;
-  if (grid > kSelMaxGrid) grid = kSelMaxGrid;
-  // After a partition pass the radix passes normally see the candidates only and most of these
-  // workgroups leave at once; the grid is sized for the case that the bounds failed and the passes
-  // run over the whole vector.
-  if (cand_cap != 0 && grid > kFallbackGrid) grid = kFallbackGrid;
   const PassDigits dg = pass_digits(dt);
-  for (int p = 0; p < dg.n_pass; ++p) {
-    if (ef) {
-      hipLaunchKernelGGL((select_pass_kernel<DCT_F32, true>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint32_t*>(g_al), static_cast<const uint32_t*>(e_al), off, n_virt, k32, ws, p);
-    } else if (dt == DCT_F32) {
-      hipLaunchKernelGGL((select_pass_kernel<DCT_F32, false>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint32_t*>(g_al), nullptr, off, n_virt, k32, ws, p);
-    } else {
-      hipLaunchKernelGGL((select_pass_kernel<DCT_BF16, false>), dim3(grid), dim3(kSelThreads), 0, s,
-                         static_cast<const uint16_t*>(g_al), nullptr, off, n_virt, k32, ws, p);
-    }
+  const uint32_t tgrid = ef ? tail_grid<DCT_F32, true>()
+                            : dt == DCT_F32 ? tail_grid<DCT_F32, false>() : tail_grid<DCT_BF16, false>();
+  if (tgrid == 0) return DCT_ERR_HIP;
+  if (ef) {
+    hipLaunchKernelGGL((select_tail_kernel<DCT_F32, true>), dim3(tgrid), dim3(kTailThreads), 0, s,
+                       static_cast<const uint32_t*>(g_al), static_cast<const uint32_t*>(e_al), off, n_virt, k32, ws,
+                       dg.n_pass, kTailSpinLimit, d_thr_out);
+  } else if (dt == DCT_F32) {
+    hipLaunchKernelGGL((select_tail_kernel<DCT_F32, false>), dim3(tgrid), dim3(kTailThreads), 0, s,
+                       static_cast<const uint32_t*>(g_al), nullptr, off, n_virt, k32, ws, dg.n_pass, kTailSpinLimit,
+                       d_thr_out);
+  } else {
+    hipLaunchKernelGGL((select_tail_kernel<DCT_BF16, false>), dim3(tgrid), dim3(kTailThreads), 0, s,
+                       static_cast<const uint16_t*>(g_al), nullptr, off, n_virt, k32, ws, dg.n_pass, kTailSpinLimit,
+                       d_thr_out);
   }
-  hipLaunchKernelGGL(select_finish_kernel, dim3(1), dim3(kSelThreads), 0, s, ws, dg.n_pass - 1, d_thr_out);
   return launch_status();
 }
 

@@ -59,3 +59,18 @@ def test_binding_refuses_cpu_tensors():
     g = torch.zeros(16)
     with pytest.raises(ValueError):
         m.dct_select_threshold(g, 1, torch.zeros(4, dtype=torch.int32), torch.zeros(1024, dtype=torch.uint8))
+
+
+def test_binding_reports_the_error_sentinels():
+    """A selection that gave up leaves DCT_TAU_KEY_ERROR in the record, a compaction with a broken
+    workspace DCT_COUNT_WORKSPACE_ERROR in the count: the host readers raise on both."""
+    import torch
+    import paper_2010_08899_amd as m
+    header = open(os.path.join(ROOT, "include", "dct.h")).read()
+    assert re.search(r"#define\s+DCT_TAU_KEY_ERROR\s+0xFFFFFFFFu", header)
+    ok = torch.tensor([0x3F800000, 7, 2, 1], dtype=torch.int32)
+    assert tuple(m.read_threshold(ok)) == (0x3F800000, 7, 2, 1)
+    with pytest.raises(m.DctError):
+        m.read_threshold(torch.tensor([-1, 0, 0, 0], dtype=torch.int32))
+    with pytest.raises(m.DctError):
+        m.read_count(torch.tensor([-1], dtype=torch.int64))
