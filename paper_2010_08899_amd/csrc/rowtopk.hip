@@ -216,34 +216,52 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_kernel(const W* __
 // in LDS (zeros + the values at their columns) and written with coalesced stores; it needs
 // D * sizeof(W) <= kBmRowBytes.
 constexpr uint32_t kBmRowBytes = 16384;
+constexpr uint32_t kBmStageElems = 1024;  // columns of a row that are listed in LDS before the gather
+constexpr uint32_t kBmWordsList = 512;    // the same for the narrow-row kernel: outputs of one step of a wavefront
 template <typename W, bool GATHER>
 __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
     const W* __restrict__ src, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, const uint32_t* __restrict__ mask,
     W* __restrict__ dst, uint64_t dst_stride, bool vec_ok) {
   constexpr uint32_t EPV = 16 / sizeof(W);
   __shared__ uint4 s_rows[GATHER ? 1 : kRtWaves][GATHER ? 1 : kBmRowBytes / 16];
+  __shared__ uint32_t s_cols[GATHER ? kRtWaves : 1][GATHER ? kBmStageElems : 1];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const uint32_t lane = lane_id();
   const uint32_t n_words = (D + 31) / 32;
   uint4* row4 = s_rows[GATHER ? 0 : wave];
   W* row_lds = reinterpret_cast<W*>(row4);
+  uint32_t* list = s_cols[GATHER ? wave : 0];
+  // GATHER: the lanes list their columns in LDS at their slots, and lane j then fetches the value of slot
+  // j, j + 64, ...: neighbouring lanes ask for neighbouring columns, so one load instruction touches a
+  // third as many cache lines as when every lane fetches its own columns (each from a line of its own),
+  // and the stores are coalesced.
+  const bool staged = GATHER && k <= kBmStageElems;
   const uint32_t n_vec = (D + EPV - 1) / EPV;
   if constexpr (!GATHER) {
     for (uint32_t q = lane; q < n_vec; q += kWave) row4[q] = make_uint4(0, 0, 0, 0);
   }
-  for (uint64_t row = static_cast<uint64_t>(blockIdx.x) * kRtWaves + wave; row < B;
-       row += static_cast<uint64_t>(gridDim.x) * kRtWaves) {
+  // the two mask words of this lane in the pass of 4096 columns that starts at column c0
+  auto load_words = [&](uint64_t row, uint32_t c0) -> uint64_t {
     const uint32_t* mr = mask + row * n_words;
+    const uint32_t col0 = c0 + lane * 64;
+    const uint32_t w0 = col0 / 32;
+    uint64_t m = 0;
+    if (w0 < n_words) m = mr[w0];
+    if (w0 + 1 < n_words) m |= static_cast<uint64_t>(mr[w0 + 1]) << 32;
+    if (col0 >= D) m = 0;
+    else if (D - col0 < 64) m &= (1ull << (D - col0)) - 1ull;  // bits past the row's end do not count
+    return m;
+  };
+  const uint64_t row_step = static_cast<uint64_t>(gridDim.x) * kRtWaves;
+  uint64_t row = static_cast<uint64_t>(blockIdx.x) * kRtWaves + wave;
+  uint64_t m_next = row < B ? load_words(row, 0) : 0ull;
+  for (; row < B; row += row_step) {
     if constexpr (!GATHER) wave_lds_sync();  // the row buffer is all zeros again
     uint32_t base = 0;
     for (uint32_t c0 = 0; c0 < D; c0 += kWave * 64) {  // passes of 4096 columns
       const uint32_t col0 = c0 + lane * 64;             // this lane's first column
-      const uint32_t w0 = col0 / 32;
-      uint64_t m = 0;
-      if (w0 < n_words) m = mr[w0];
-      if (w0 + 1 < n_words) m |= static_cast<uint64_t>(mr[w0 + 1]) << 32;
-      if (col0 >= D) m = 0;
-      else if (D - col0 < 64) m &= (1ull << (D - col0)) - 1ull;  // bits past the row's end do not count
+      uint64_t m = c0 == 0 ? m_next : load_words(row, c0);
+      if (c0 == 0 && row + row_step < B) m_next = load_words(row + row_step, 0);  // on its way during this row
       const uint32_t pc = __popcll(m);
       const uint32_t incl = fast::wave_incl_scan(pc);
       uint32_t slot = base + incl - pc;
@@ -259,16 +277,22 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
           cols[j] = col0 + (m != 0 ? __builtin_ctzll(m) : 0);
           m &= m - 1;  // stays 0 once it is 0
         }
+        if (GATHER && staged) {
 #pragma unroll
-        for (int j = 0; j < kFirst; ++j) {
-          if constexpr (GATHER) v[j] = ok[j] ? src[row * stride + cols[j]] : static_cast<W>(0);
-          else v[j] = ok[j] ? src[row * k + slot + j] : static_cast<W>(0);
-        }
+          for (int j = 0; j < kFirst; ++j)
+            if (ok[j]) list[slot + j] = cols[j];
+        } else {
 #pragma unroll
-        for (int j = 0; j < kFirst; ++j) {
-          if (ok[j]) {
-            if constexpr (GATHER) dst[row * k + slot + j] = v[j];
-            else row_lds[cols[j]] = v[j];
+          for (int j = 0; j < kFirst; ++j) {
+            if constexpr (GATHER) v[j] = ok[j] ? src[row * stride + cols[j]] : static_cast<W>(0);
+            else v[j] = ok[j] ? src[row * k + slot + j] : static_cast<W>(0);
+          }
+#pragma unroll
+          for (int j = 0; j < kFirst; ++j) {
+            if (ok[j]) {
+              if constexpr (GATHER) dst[row * k + slot + j] = v[j];
+              else row_lds[cols[j]] = v[j];
+            }
           }
         }
         slot += min(pc, static_cast<uint32_t>(kFirst));
@@ -278,8 +302,12 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
           const uint32_t c = col0 + __builtin_ctzll(m);
           m &= m - 1;
           if (slot < k) {
-            if constexpr (GATHER) dst[row * k + slot] = src[row * stride + c];
-            else row_lds[c] = src[row * k + slot];
+            if constexpr (GATHER) {
+              if (staged) list[slot] = c;
+              else dst[row * k + slot] = src[row * stride + c];
+            } else {
+              row_lds[c] = src[row * k + slot];
+            }
           }
           ++slot;
         }
@@ -287,7 +315,14 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
       base += __builtin_amdgcn_readlane(incl, kWave - 1);
     }
     if constexpr (GATHER) {
-      for (uint32_t j = base + lane; j < k; j += kWave) dst[row * k + j] = 0;
+      if (staged) {
+        wave_lds_sync();  // the list is complete
+        for (uint32_t j = lane; j < k; j += kWave)
+          dst[row * k + j] = j < base ? src[row * stride + list[j]] : static_cast<W>(0);
+        wave_lds_sync();  // ... and read, before the next row's columns arrive
+      } else {
+        for (uint32_t j = base + lane; j < k; j += kWave) dst[row * k + j] = 0;
+      }
     } else {
       wave_lds_sync();
       W* out = dst + row * dst_stride;
@@ -319,12 +354,19 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_words_kernel(
     W* __restrict__ dst, uint32_t wpr) {
   constexpr uint32_t EPV = 16 / sizeof(W);
   __shared__ uint4 s_blk[GATHER ? 1 : kRtWaves][GATHER ? 1 : kWave * 32 * sizeof(W) / 16];
+  __shared__ uint32_t s_list[GATHER ? kRtWaves : 1][GATHER ? kBmWordsList : 1];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const uint32_t lane = lane_id();
   const uint32_t rows_per_step = kWave / wpr;
   const uint32_t r_loc = lane / wpr, w = lane % wpr;  // row of the step, word of the row
   uint4* blk4 = s_blk[GATHER ? 0 : wave];
   W* blk = reinterpret_cast<W*>(blk4);
+  uint32_t* list = s_list[GATHER ? wave : 0];
+  // GATHER: the step's outputs are rows_per_step * k consecutive elements of dval.  The lanes list
+  // (row of the step, column) per output in LDS, and lane j then fetches outputs j, j + 64, ...:
+  // neighbouring lanes read neighbouring columns and the stores are coalesced.
+  const bool staged = GATHER && rows_per_step * k <= kBmWordsList;
+  constexpr uint32_t kNoSource = 0xFFFFFFFFu;  // an output beyond the row's set bits: zero
   const uint32_t blk_vecs = kWave * 32 / EPV;  // the step's dense output in 16-byte vectors
   if constexpr (!GATHER) {
     for (uint32_t q = lane; q < blk_vecs; q += kWave) blk4[q] = make_uint4(0, 0, 0, 0);
@@ -348,15 +390,30 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_words_kernel(
         const uint32_t c = 32 * w + __builtin_ctz(m);
         m &= m - 1;
         if (slot < k) {
-          if constexpr (GATHER) dst[row * k + slot] = src[row * stride + c];
-          else blk[r_loc * D + c] = src[row * k + slot];
+          if constexpr (GATHER) {
+            if (staged) list[r_loc * k + slot] = (r_loc << 16) | c;  // c < 1024
+            else dst[row * k + slot] = src[row * stride + c];
+          } else {
+            blk[r_loc * D + c] = src[row * k + slot];
+          }
         }
         ++slot;
       }
     }
     if constexpr (GATHER) {
-      if (live)
+      if (staged) {
+        for (uint32_t j = row_bits + w; j < k; j += wpr) list[r_loc * k + j] = kNoSource;  // fewer set bits than k
+        wave_lds_sync();  // the list is complete
+        const uint64_t row0 = step * rows_per_step;
+        const uint32_t rows_here = static_cast<uint32_t>(min(static_cast<uint64_t>(rows_per_step), B - row0));
+        for (uint32_t j = lane; j < rows_here * k; j += kWave) {
+          const uint32_t e = list[j];
+          dst[row0 * k + j] = e != kNoSource ? src[(row0 + (e >> 16)) * stride + (e & 0xFFFFu)] : static_cast<W>(0);
+        }
+        wave_lds_sync();  // ... and read, before the next step's entries arrive
+      } else if (live) {
         for (uint32_t j = row_bits + w; j < k; j += wpr) dst[row * k + j] = 0;  // fewer set bits than k
+      }
     } else {
       wave_lds_sync();
       const uint64_t row0 = step * rows_per_step;

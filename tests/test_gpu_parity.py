@@ -794,7 +794,9 @@ def test_batched_argument_errors(dct):
     (torch.bfloat16, 70, 4096, 204, 0), (torch.bfloat16, 33, 2048, 102, 0), (torch.bfloat16, 9, 1024, 51, 8),
     (torch.bfloat16, 17, 512, 25, 0), (torch.bfloat16, 5, 264, 13, 0), (torch.bfloat16, 6, 40, 7, 0),
     (torch.bfloat16, 4, 8, 8, 0), (torch.bfloat16, 3, 12_000, 600, 0), (torch.bfloat16, 5, 1001, 50, 0),
-    (torch.float32, 33, 1024, 51, 0), (torch.float32, 7, 33, 5, 3), (torch.float32, 2, 5000, 250, 0)])
+    (torch.float32, 33, 1024, 51, 0), (torch.float32, 7, 33, 5, 3), (torch.float32, 2, 5000, 250, 0),
+    # more survivors than the backward kernel lists on chip (1024 per row): its direct path
+    (torch.bfloat16, 5, 4096, 2000, 0), (torch.float32, 3, 2304, 1500, 0), (torch.bfloat16, 3, 9000, 1025, 0)])
 def test_mp_bitmask_encoding(dct, dtype, B, D, k, pad):
     x = si.relu_activations(B, D, DEV, 1300 + D, dtype=dtype, row_stride=D + pad if pad else None)
     dy = si.normal_matrix(B, D, DEV, 1400 + D, dtype=dtype)
