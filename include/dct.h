@@ -87,13 +87,14 @@ typedef struct {
  *   d_ws       device workspace of at least dct_select_threshold_workspace_bytes,
  *              256-byte aligned; contents on entry are irrelevant, it is scratch
  *
- * Concurrency: the last kernel of the call runs all radix passes in one launch, its
- * workgroups (at most one per compute unit) meeting at grid barriers between the
- * passes.  They are resident together when the device has room for them, which a
- * stream that runs alone always has.  If other work keeps part of the grid off the
- * device for about a second, the waiting workgroups give up, every kernel still ends,
- * and the record reads {DCT_TAU_KEY_ERROR, 0, 0, 0}: select again.  The same holds
- * for dct_ef_select_threshold.
+ * Concurrency: the last kernel of the call runs all radix passes in one launch.
+ * Between two passes up to 64 of its workgroups (one per compute unit, the first
+ * of its grid) wait for each other at a grid barrier; after the last pass nobody
+ * waits.  A device has room for the waiting workgroups of several selections at a
+ * time (four streams at once are tested).  If other work keeps some of them off the
+ * device for about a second, the waiting ones give up, every kernel still ends, and
+ * the record reads {DCT_TAU_KEY_ERROR, 0, 0, 0}: select again.  The same holds for
+ * dct_ef_select_threshold.
  */
 size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n);
 int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,

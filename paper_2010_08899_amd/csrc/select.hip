@@ -19,9 +19,12 @@
 // counter) through LDS staging.  The
 // radix passes then run over the candidates only, so the vector is read from HBM
 // once.  The counts tell exactly whether the bounds held (n_above < k <= n_above
-// + n_candidates, no buffer overflow); if they did not, the same radix passes run
-// over the whole vector instead, decided on the device, so the result is always
-// the exact order statistic.  All arithmetic is on integers.
+// + n_candidates) and whether the buffer had room.  If it overflowed (ties by the
+// million at tau) the radix passes run over the keys of the VECTOR that lie in
+// [lo, hi], few distinct values that one pass usually resolves; if the bounds did
+// not hold they run over the whole vector.  Either way this is decided on the
+// device and the result is always the exact order statistic.  All arithmetic is
+// on integers.
 //
 // With error feedback (Algorithm 1, "W_grad = W_grad + E_grad" precedes the
 // sort) the EF variants of the kernels that read the vector read g and the
@@ -40,6 +43,7 @@ constexpr int kSelUnroll = 4;                   // 16-byte loads in flight per l
 constexpr uint32_t kSelMaxGrid = 4096;            // workgroups of the partition pass (at most)
 constexpr int kTailThreads = 1024;                // the kernel of the radix passes: few, large workgroups
 constexpr uint32_t kTailMaxGrid = 256;
+constexpr uint32_t kTailWaiters = 64;              // workgroups of a launch that may wait at a grid barrier
 constexpr int kTailKeep = 8;                      // 16-byte vectors of candidates per thread kept in registers
 constexpr uint32_t kTailSpinLimit = 1u << 20;     // polls of a grid barrier (about a second) before giving up
 
@@ -459,6 +463,7 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
 
   // ---- search state before the first pass
   SelState st;
+  uint32_t range_lo, range_span;  // the keys that take part: range_lo <= key <= range_lo + range_span
   {
     // totals of the partition pass over the regions (one counter per lane of the first wavefront;
     // all zero when no partition pass ran)
@@ -475,30 +480,41 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
       }
     }
     __syncthreads();
-    const uint32_t n_above = s_tot[0], n_cand = s_tot[1];
-    const bool ok = ws->sampled != 0 && s_tot[2] == 0 && n_above < k && k <= n_above + n_cand;
-    st.k_rem = ok ? k - n_above : k;
-    st.n_gt = ok ? n_above : 0u;
-    st.from_cand = ok ? 1u : 0u;
-    st.n_src = ok ? n_cand : n_virt - off;
+    const uint32_t n_above = s_tot[0], n_cand = s_tot[1];  // keys > hi, keys in [lo, hi] (also those that found no room)
+    // Three cases.  The bounds held and the candidate buffer has all keys in [lo, hi]: select among the
+    // candidates.  The bounds held but the buffer overflowed (ties by the million at tau, as in a mostly
+    // zero gradient with k beyond its non-zeros): select among the keys of the VECTOR that lie in
+    // [lo, hi], which are few distinct values -- usually one pass.  The bounds failed: select among all keys.
+    const bool held = ws->sampled != 0 && n_above < k && k <= n_above + n_cand;
+    st.k_rem = held ? k - n_above : k;
+    st.n_gt = held ? n_above : 0u;
+    st.from_cand = held && s_tot[2] == 0 ? 1u : 0u;
+    st.n_src = held ? n_cand : n_virt - off;
     st.last_count = st.n_src;
-    // The candidate passes select on key - lo, which lies in [0, hi - lo]: only the bits of that range
-    // are left to resolve (the bits in which lo and hi differ can be many more, when a carry separates them).
-    const uint32_t diff = ok ? (ws->hi - ws->lo) : E::kKeyMask;
-    st.rem_bits = diff ? 32u - __builtin_clz(diff) : 0u;
+    // In the first two cases the passes select on key - lo, which lies in [0, hi - lo]: only the bits of that
+    // range are left to resolve (the bits in which lo and hi differ can be many more, when a carry separates them).
+    range_lo = held ? lo_key : 0u;
+    range_span = held ? ws->hi - lo_key : E::kKeyMask;
+    st.rem_bits = range_span ? 32u - __builtin_clz(range_span) : 0u;
     st.prefix = 0u;
     st.width = min(kDigitBits, st.rem_bits);
   }
-  // workgroups that take part (the same number in every workgroup's view: it decides the barriers)
+  // Workgroups that take part (the same number in every workgroup's view: it decides the barriers).
+  // Only a pass that another pass follows ends in a barrier where workgroups WAIT; at most kTailWaiters
+  // workgroups, the first of the grid, ever do, so that several selections at a time (one per hardware
+  // queue) still find room for all their waiters.  After the last pass nobody waits: the workgroup that
+  // arrives last finishes the job alone.  A single pass over the vector may therefore use the whole grid.
   const uint32_t src_vecs = n_virt / V + 1;
   const uint32_t n_active =
-      st.from_cand ? min(gridDim.x, kCandRegions) : min(gridDim.x, (src_vecs + span - 1) / span);
+      st.from_cand ? min(gridDim.x, kCandRegions)
+                   : min(st.rem_bits <= kDigitBits ? gridDim.x : min(gridDim.x, kTailWaiters), (src_vecs + span - 1) / span);
   if (blockIdx.x >= n_active) return;
+  bool finisher = blockIdx.x == 0;  // writes the result
 
   for (int pass = 0; pass < n_pass && st.width != 0; ++pass) {  // uniform over the grid
     const uint32_t shift = st.rem_bits - st.width;
     const uint32_t dmask = (1u << st.width) - 1u;
-    const uint32_t fixed_mask = E::kKeyMask & ~((1u << st.rem_bits) - 1u);
+    const uint32_t fixed_all = ~((1u << st.rem_bits) - 1u);  // with bit 31: set in no prefix
     const uint32_t prefix = st.prefix;
     for (int i = threadIdx.x; i < kSelBins; i += kTailThreads) h[i] = 0;
     __syncthreads();
@@ -509,7 +525,7 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
       // from lane to lane as a rule (plain LDS adds, after one test whether the wavefront has anything
       // to add at all: in the later passes it rarely has); when every key the wavefront adds falls into
       // ONE bin -- ties -- a single add replaces up to 256 that would serialise.
-      const uint32_t fixed_all = ~((1u << st.rem_bits) - 1u);  // with bit 31: set in no prefix, in all fillers
+      // (fixed_all has bit 31, which the fillers past a region's end have set)
       auto add_vec = [&](const uint4& v) {
         const uint32_t key[4] = {v.x, v.y, v.z, v.w};
         bool act[4];
@@ -587,8 +603,8 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
           if constexpr (EF) v[u] = add4(v[u], ve4[u]);
 #pragma unroll
           for (int e = 0; e < V; ++e) {
-            const uint32_t key = E::raw(v[u], e) & E::kKeyMask;
-            hist_add(h, in[u] && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+            const uint32_t key = (E::raw(v[u], e) & E::kKeyMask) - range_lo;  // below range_lo: wraps past the span
+            hist_add(h, in[u] && key <= range_span && (key & fixed_all) == prefix, (key >> shift) & dmask);
           }
         }
       }
@@ -603,8 +619,8 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
           if (c < n_virt && (c >= static_cast<uint32_t>(V) || !off)) ve = c;
         }
         const bool act = ve != 0xFFFFFFFFu;
-        const uint32_t key = act ? (elem_raw<DT, EF>(g_al, e_al, ve) & E::kKeyMask) : 0u;
-        hist_add(h, act && (key & fixed_mask) == prefix, (key >> shift) & dmask);
+        const uint32_t key = (act ? (elem_raw<DT, EF>(g_al, e_al, ve) & E::kKeyMask) : 0u) - range_lo;
+        hist_add(h, act && key <= range_span && (key & fixed_all) == prefix, (key >> shift) & dmask);
       }
     }
     __syncthreads();
@@ -619,17 +635,21 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
       }
       asm volatile("s_waitcnt vmcnt(0)" ::"v"(seen) : "memory");
       __syncthreads();
+      const bool last_pass = st.rem_bits <= st.width;  // uniform over the grid
       if (threadIdx.x == 0) {
         uint32_t arrived = add_agent(&ws->bar[pass], 1u) + 1u;
-        for (uint32_t spins = 0; arrived < n_active && spins < spin_limit; ++spins) {
-          __builtin_amdgcn_s_sleep(2);
-          arrived = ld_agent(&ws->bar[pass]);
+        if (!last_pass) {
+          for (uint32_t spins = 0; arrived < n_active && spins < spin_limit; ++spins) {
+            __builtin_amdgcn_s_sleep(2);
+            arrived = ld_agent(&ws->bar[pass]);
+          }
         }
         s_arrived = arrived;
       }
       __syncthreads();
-      if (s_arrived < n_active) {  // uniform: somebody never came; no result
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
+      if (s_arrived < n_active) {  // uniform
+        if (last_pass) return;     // another workgroup arrives last and finishes
+        if (blockIdx.x == 0 && threadIdx.x == 0) {  // somebody never came; no result
           out->tau_key = DCT_TAU_KEY_ERROR;
           out->n_gt = 0;
           out->n_eq = 0;
@@ -637,13 +657,14 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
         }
         return;
       }
+      if (last_pass) finisher = true;
       st = advance_state_with<kTailThreads>(st, [&](uint32_t b) { return ld_agent(&gh[b]); }, s_tmp);
     } else {
       st = advance_state_with<kTailThreads>(st, [&](uint32_t b) { return h[b]; }, s_tmp);
     }
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    out->tau_key = st.prefix + (st.from_cand ? ws->lo : 0u);  // the candidate passes work on key - lo
+  if (finisher && threadIdx.x == 0) {
+    out->tau_key = st.prefix + range_lo;  // the passes work on key - range_lo
     out->n_gt = st.n_gt;
     out->n_eq = st.last_count;
     out->tie_quota = st.k_rem;

@@ -1075,7 +1075,7 @@ def test_dp_ef_low_sparsity_levels(dct, frac):
 def test_calls_on_a_side_stream_and_in_a_captured_graph(dct):
     """The calls launch on the stream they are given and allocate nothing, so a training loop can
     capture them: one DP step (select + exactly-k compaction, 5 M elements: the sampled selection
-    with its seven launches) and one MP step (forward + backward) are captured once and replayed on
+    with its four launches) and one MP step (forward + backward) are captured once and replayed on
     fresh data, with eager work and synchronisations in between; every replay is checked against the oracle."""
     n, k = 5_000_003, 25_000
     B, D, kk = 300, 1024, 51
@@ -1134,6 +1134,33 @@ def test_calls_on_a_side_stream_and_in_a_captured_graph(dct):
 
 
 # ------------------------------------------------------------------ seeded random configurations
+def test_dp_selections_on_four_streams_at_once(dct):
+    """Selections that run at the same time on different streams: the last kernel of each waits at grid
+    barriers, and every waiting workgroup has to find room next to those of the other selections.
+    Inputs of all kinds (radix passes over the vector, over the candidates, over the keys inside the
+    bounds after a candidate overflow), 20 rounds, every record checked against the oracle."""
+    inputs = [(si.gaussian_gradient(1 << 20, DEV, 2600), 10_486),
+              (si.gaussian_gradient(3_000_001, DEV, 2601), 30_000),
+              (si.student_t3_gradient(5_000_003, DEV, 2602), 5_000)]
+    z = si.gaussian_gradient(4_500_000, DEV, 2603)
+    z[torch.rand(z.numel(), device=DEV) < 0.9] = 0.0
+    inputs.append((z, z.numel() // 5))  # k beyond the non-zeros: tau = 0 with four million ties
+    expected = [oracle.select_threshold(host(g), k, method="nth") for g, k in inputs]
+    assert expected[3].tau_key == 0
+    streams = [torch.cuda.Stream() for _ in inputs]
+    thr = [torch.zeros(4, dtype=torch.int32, device=DEV) for _ in inputs]
+    ws = [dct.new_select_workspace(g) for g, _ in inputs]
+    for rnd in range(20):
+        torch.cuda.synchronize()  # the inputs, and the cleared records of the previous round, are in place
+        for i, (g, k) in enumerate(inputs):
+            with torch.cuda.stream(streams[i]):
+                dct.dct_select_threshold(g, k, thr[i], ws[i])
+        torch.cuda.synchronize()
+        for i in range(len(inputs)):
+            assert oracle.Threshold(*dct.read_threshold(thr[i])) == expected[i], (rnd, i)
+            thr[i].zero_()
+
+
 def test_random_mp_configurations(dct):
     """Forty seeded draws of (dtype, B, D, k, encoding, value structure): every forward kernel and every
     consumer against the oracle.  Value structures: post-ReLU, signed, four distinct values (ties everywhere),
