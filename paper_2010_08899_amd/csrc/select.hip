@@ -414,6 +414,7 @@ __device__ __forceinline__ uint32_t add_agent(uint32_t* p, uint32_t v) {
 // from the search in its histogram, which every workgroup repeats for itself.  The grid is
 // small enough to be resident as a whole; a workgroup that waits longer than about a second
 // gives up (spin_limit polls), and workgroup 0 then stores DCT_TAU_KEY_ERROR in the result.
+// After the last pass there is no barrier: the workgroup that arrives last finishes alone.
 //
 // Merging costs more than reading here: after the subtraction of lo the candidates fill most of
 // the 2048 bins of the first digit, every workgroup adds most of its bins, and the device
@@ -421,8 +422,7 @@ __device__ __forceinline__ uint32_t add_agent(uint32_t* p, uint32_t v) {
 // passes are therefore left to one workgroup per region (64 of them, 1024 threads each; the
 // others leave at once), and what then limits them is one CU's instruction rate: about 27
 // keys per thread on c4, held in registers from the first pass on and tested with two
-// instructions per key and pass.  A pass over the vector itself (small vectors, or bounds
-// that failed) uses the whole grid.  On c4 the kernel takes 25 us, against 26 us for the
+// instructions per key and pass.  On c4 the kernel takes 25 us, against 26 us for the
 // three pass kernels and the finishing kernel it replaced, and 43 us less on c3, whose
 // larger grids spent their time merging.
 template <int DT, bool EF>
