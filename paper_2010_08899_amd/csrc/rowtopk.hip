@@ -486,17 +486,17 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     return launch_status();
   }
   if (D % epv == 0 && D * es <= 16384u && is_aligned(x, 16) && row_stride_elems % epv == 0) {
-    uint32_t fgrid = ceil_div(B, fast::kWaves);
-    // workgroups per CU that registers and the LDS row buffers allow (rows of up to 2 / 4 / 8 / 16 KiB)
+    // wavefronts per CU that registers and the LDS row buffers allow (rows of up to 2 / 4 / 8 / 16 KiB); how
+    // many of them form a workgroup is the kernel's choice (fast::waves_per_wg)
     const uint32_t row_bytes = D * static_cast<uint32_t>(es);
-    const uint32_t per_cu = row_bytes <= 2048u ? 8u : row_bytes <= 4096u ? 6u : row_bytes <= 8192u ? 4u : 2u;
-    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * per_cu;
-    if (fgrid > resident) fgrid = resident;
-    const dim3 g(fgrid), b(fast::kThreads);
+    const uint32_t waves_per_cu = row_bytes <= 2048u ? 32u : row_bytes <= 4096u ? 24u : row_bytes <= 8192u ? 16u : 8u;
+    const uint32_t cus = static_cast<uint32_t>(device_cu_count());
     const uint32_t vecs = D / epv;  // 16-byte vectors per row, spread over 64 lanes
 #define DCT_LAUNCH_ONCHIP(NVV, MK, F32V)                                                                        \
   do {                                                                                                          \
     using W = std::conditional_t<F32V, uint32_t, uint16_t>;                                                     \
+    constexpr uint32_t wg_waves = fast::waves_per_wg<NVV>();                                                    \
+    const dim3 g(std::min(ceil_div(B, wg_waves), cus * std::max(waves_per_cu / wg_waves, 1u))), b(wg_waves * kWave); \
     hipLaunchKernelGGL((fast::rowtopk_fwd_onchip_kernel<NVV, MK, F32V>), g, b, 0, s, static_cast<const W*>(x), B, \
                        D, row_stride_elems, k, io, static_cast<W*>(d_val_out), static_cast<W*>(d_tau_out));     \
   } while (0)

@@ -37,8 +37,16 @@
 namespace dct {
 namespace fast {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
+// Wavefronts per workgroup.  Rows of more than 4 KiB leave room for 16 (8 KiB) or 8 (16 KiB) wavefronts on a
+// CU, and ALL of them form one workgroup so that they can share a row counter in LDS: a SIMD serves its oldest
+// wavefront first, and with the rows dealt out in advance the wavefronts that were started first finished their
+// share at 2/3 of the kernel's time and the last ones set it (c5: 76 / 89 / 101 / 114 us for the four
+// wavefronts of a SIMD).  Narrower rows keep workgroups of four wavefronts: several of those fit a CU and a
+// counter per workgroup would not level them.
+template <int NV>
+constexpr int waves_per_wg() {
+  return NV == 8 ? 16 : NV == 16 ? 8 : 4;
+}
 constexpr uint32_t kWindow = 32;
 constexpr int kSampleRegs = 4;  // packed registers per lane in the first row's sample (8 keys per lane)
 
@@ -80,7 +88,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 // values are written either way.
 // F32: fp32 rows (the packed 16-bit keys are the upper halves of the fp32 keys).
 template <int NV, int ENC, bool F32>
-__global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
+__global__ __launch_bounds__(waves_per_wg<NV>() * kWave) void rowtopk_fwd_onchip_kernel(
     const std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride,
     uint32_t k, void* __restrict__ idx_out, std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ val_out,
     std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ tau_out) {
@@ -93,6 +101,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
   constexpr int WORDS = (REGS + 15) / 16;
   static_assert(WORDS <= 2 || (WORDS == 4 && !F32), "a lane owns at most 64 columns (bf16: 128)");
   constexpr int CHUNK = (NV + 1) * 16;              // LDS bytes per lane chunk (16 bytes of padding)
+  constexpr int kWaves = waves_per_wg<NV>();
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
   __shared__ uint32_t s_hist[kWaves][kWave];
   __shared__ uint32_t s_fix[F32 ? kWaves : 1][F32 ? kWave * WORDS : 1];  // fp32: decisions handed back to the owner lane
@@ -129,9 +138,22 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
 
   uint32_t guess = 0xFFFFFFFFu;  // tau of the previous row of this wavefront; none yet
 
+  // The workgroup's rows are blocks of kWaves consecutive rows, one block in every stripe of gridDim.x blocks
+  // (the grid as a whole reads a moving window of the matrix); its wavefronts take them one at a time, in
+  // order, from a counter in LDS, so that a wavefront the SIMD favours simply takes more of them.  The n-th
+  // row taken is a strictly increasing function of n: a wavefront that is handed a row past the end is done.
   // The next row's loads are issued while the current row is processed.
   const uint64_t row_step = static_cast<uint64_t>(gridDim.x) * kWaves;
-  uint64_t row = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
+  __shared__ uint32_t s_rows_taken;
+  if (threadIdx.x == 0) s_rows_taken = 0;
+  __syncthreads();
+  auto take_row = [&]() -> uint64_t {
+    uint32_t n = 0;
+    if (lane == 0) n = atomicAdd(&s_rows_taken, 1u);
+    n = __builtin_amdgcn_readfirstlane(n);
+    return static_cast<uint64_t>(blockIdx.x) * kWaves + (n % kWaves) + static_cast<uint64_t>(n / kWaves) * row_step;
+  };
+  uint64_t row = take_row();
   uint4 nxt[NV];
   const bool full_width = n_vec == static_cast<uint32_t>(NV * kWave);  // no lane runs past the row's end
   auto load_row = [&](uint64_t r) {
@@ -147,7 +169,8 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
   };
   if (row < B) load_row(row);
 
-  for (; row < B; row += row_step) {
+  uint64_t next_row = 0;
+  for (; row < B; row = next_row) {
     // ---- 1. row -> LDS (padded) -> registers, lane-contiguous
     wave_lds_fence();  // the previous row's readers are done with the buffer
 #pragma unroll
@@ -156,7 +179,8 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_onchip_kernel(
       *reinterpret_cast<uint4*>(row_lds + (q / NV) * CHUNK + (q % NV) * 16) = nxt[j];
     }
     wave_lds_fence();
-    if (row + row_step < B) load_row(row + row_step);
+    next_row = take_row();
+    if (next_row < B) load_row(next_row);
     uint32_t R[4 * NV];  // the lane's columns as loaded: two per word (bf16) or one per word (fp32)
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
