@@ -13,8 +13,9 @@
 // For large vectors the radix passes do not run over the vector.  A first kernel
 // gathers a stratified sample of 16384 keys, a second one brackets two of its
 // order statistics to get bounds lo <= tau <= hi that hold with overwhelming
-// probability.  One streaming pass over the vector (coalesced 16-byte loads, tiles
-// dealt round-robin to the workgroups) counts the keys above hi and appends the keys in [lo, hi] --
+// probability.  One streaming pass over the vector (coalesced 16-byte loads, one
+// workgroup of 16 wavefronts per CU, pieces of 8 KiB taken from a counter in LDS)
+// counts the keys above hi and appends the keys in [lo, hi] --
 // well under 1 % of the vector -- to a candidate buffer (64 regions, each with its own
 // counter) through LDS staging.  The
 // radix passes then run over the candidates only, so the vector is read from HBM
@@ -40,7 +41,6 @@ namespace {
 
 constexpr int kSelMaxPasses = 3;
 constexpr int kSelUnroll = 4;                   // 16-byte loads in flight per lane in the radix passes
-constexpr uint32_t kSelMaxGrid = 4096;            // workgroups of the partition pass (at most)
 constexpr int kTailThreads = 1024;                // the kernel of the radix passes: few, large workgroups
 constexpr uint32_t kTailMaxGrid = 256;
 constexpr uint32_t kTailWaiters = 64;              // workgroups of a launch that may wait at a grid barrier
@@ -51,9 +51,11 @@ constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes r
 constexpr int kSampleThreads = 1024;
 constexpr uint32_t kSampleSize = 16384;         // 64 KiB of LDS
 constexpr int kGatherThreads = 256;
-constexpr int kPartRows = 4;                    // 16-byte loads per lane per step of the partition pass
+constexpr int kPartThreads = 1024;              // the partition pass: the CU's 16 wavefronts form one workgroup
+constexpr int kPartWaves = kPartThreads / kWave;
+constexpr int kPartRows = 8;                    // 16-byte loads per lane per piece (two input streams: 4 each)
 constexpr uint32_t kPartStage = 1024;           // staged candidate keys per wavefront
-constexpr uint32_t kPartTileVecs = kSelThreads * kPartRows;
+constexpr uint32_t kPartPieceVecs = kWave * kPartRows;  // with error feedback half of that, of either stream
 
 // The candidate buffer is cut into kCandRegions regions with a counter each: workgroup w of the
 // partition pass appends to region w % kCandRegions.  (All workgroups finish together; their end-of-chunk
@@ -214,25 +216,31 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
 
 // ------------------------------------------------------------------ kernel 2
 // Streaming partition pass: count keys > hi, append keys in [lo, hi] to the
-// candidate buffer.  Tiles of 16 KiB go round-robin to the workgroups, a quarter of
-// each tile to a wavefront; candidates are staged in LDS per wavefront and written
-// to the workgroup's region of the buffer with one slot reservation per workgroup
-// at the end (and one per wavefront whenever its staging area fills up before that).
-// Their order is irrelevant: only the multiset of keys matters.
+// candidate buffer.  One workgroup per CU.  Its share of the vector are blocks of 16 consecutive
+// pieces of 8 KiB, one block in every stripe of the grid, so that the grid as a whole reads one
+// moving window; its 16 wavefronts take these pieces one at a time from a counter in LDS.  (A SIMD
+// serves its oldest wavefront first.  With the pieces dealt out in advance -- 2048 workgroups of 4
+// wavefronts, 8 per CU -- the first workgroup of every CU had finished its share after 60 us and the
+// eighth after 150 us, and the last third of the pass ran with too few loads in flight: 170 us
+// against 160 us now.)  Candidates are staged in LDS per wavefront and written to the workgroup's
+// region of the buffer with one slot reservation per workgroup at the end (and one per wavefront
+// whenever its staging area fills up before that).  Their order is irrelevant: only the multiset of
+// keys matters.
 struct PartGeom {
-  uint32_t head, n_vec, tail, grid, vecs_per_wg;
+  uint32_t head, n_vec, tail, grid;
 };
 
 template <int DT, bool EF>
-__global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
+__global__ __launch_bounds__(kPartThreads) void select_partition_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* __restrict__ e, PartGeom geo,
     SelWs* ws) {
   static_assert(!EF || DT == DCT_F32, "error feedback is an fp32 addition");
   using E = Elem<DT>;
   constexpr int V = E::kVec;
-  constexpr int ROWS = EF ? kPartRows / 2 : kPartRows;  // two input streams: half a tile per step
-  constexpr uint32_t PARTS = kPartRows / ROWS;
-  __shared__ uint32_t s_stage[kSelWaves][kPartStage];
+  constexpr int ROWS = EF ? kPartRows / 2 : kPartRows;  // rows of 64 vectors per piece
+  constexpr uint32_t PIECE = ROWS * kWave;               // vectors per piece
+  __shared__ uint32_t s_stage[kPartWaves][kPartStage];
+  __shared__ uint32_t s_taken;
   const uint32_t lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const uint32_t wg = blockIdx.x;
@@ -242,7 +250,9 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
   uint32_t* region_keys = ws->cand + static_cast<size_t>(wg % kCandRegions) * region_cap;
   uint32_t* stage = s_stage[wave];
   uint32_t staged = 0, above = 0;
-  __shared__ uint32_t s_cnt[kSelWaves], s_abv[kSelWaves], s_base;
+  __shared__ uint32_t s_cnt[kPartWaves], s_abv[kPartWaves], s_base;
+  if (threadIdx.x == 0) s_taken = 0;
+  __syncthreads();
 
   // Mid-chunk flush of one wavefront's staging region (only when it fills up).
   auto flush = [&]() {
@@ -298,32 +308,39 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
     }
   };
 
-  // Tiles of 16 KiB are dealt round-robin to the workgroups, so that at any time the
-  // grid reads one contiguous window of the vector (order is irrelevant here).
+  // Pieces of ROWS rows of 64 vectors.  The workgroup's pieces are blocks of 16 consecutive ones, one block
+  // in every stripe of gridDim.x blocks (the grid reads one moving window of the vector; order is irrelevant
+  // here); its wavefronts take them one at a time from a counter in LDS.
   const uint4* gv = reinterpret_cast<const uint4*>(g + geo.head);
-  const uint32_t tiles = (geo.n_vec + kPartTileVecs - 1) / kPartTileVecs;
+  const uint4* ev = EF ? reinterpret_cast<const uint4*>(e + geo.head) : nullptr;
+  const uint32_t pieces = (geo.n_vec + PIECE - 1) / PIECE;
   if (wg == 0 && wave == 0 && geo.head != 0) {
     const bool in = lane < geo.head;
     const uint32_t raw = in ? elem_raw<DT, EF>(g, e, lane) : 0u;
     take(&raw, in, std::integral_constant<int, 1>{});
   }
-  // Two register buffers: the next step's loads are in flight while the current one is processed.
-  // Step q of a workgroup covers part q % PARTS of its (q / PARTS)-th tile.
+  if (wg == 0 && wave == 1 && geo.tail != 0) {
+    const bool in = lane < geo.tail;
+    const uint32_t raw = in ? elem_raw<DT, EF>(g, e, geo.head + geo.n_vec * V + lane) : 0u;
+    take(&raw, in, std::integral_constant<int, 1>{});
+  }
+  constexpr uint32_t kNoPiece = 0xFFFFFFFFu;
+  const uint32_t stripe = gridDim.x * kPartWaves;
+  auto take_piece = [&]() -> uint32_t {
+    uint32_t n = 0;
+    if (lane == 0) n = atomicAdd(&s_taken, 1u);
+    n = __builtin_amdgcn_readfirstlane(n);
+    const uint64_t p = static_cast<uint64_t>(wg) * kPartWaves + (n % kPartWaves) + static_cast<uint64_t>(n / kPartWaves) * stripe;
+    return p < pieces ? static_cast<uint32_t>(p) : kNoPiece;  // increasing in n: nothing follows a piece past the end
+  };
+  // Two register buffers: the next piece's loads are in flight while the current one is processed.
   struct Rows {
     uint4 a[ROWS];
     uint4 b[EF ? ROWS : 1];
   };
-  const uint4* ev = EF ? reinterpret_cast<const uint4*>(e + geo.head) : nullptr;
-  const uint32_t my_tiles = wg < tiles ? (tiles - wg + geo.grid - 1) / geo.grid : 0u;
-  const uint32_t steps = my_tiles * PARTS;
-  auto first_vec = [&](uint32_t q) {
-    const uint32_t tile = wg + (q / PARTS) * geo.grid;
-    return tile * kPartTileVecs + (wave * kPartRows + (q % PARTS) * ROWS) * kWave + lane;
-  };
-  auto tile_is_full = [&](uint32_t q) { return (wg + (q / PARTS) * geo.grid + 1) * kPartTileVecs <= geo.n_vec; };
-  auto load_step = [&](Rows& buf, uint32_t q) {
-    const uint32_t vec0 = first_vec(q);
-    if (tile_is_full(q)) {  // uniform
+  auto load_piece = [&](Rows& buf, uint32_t p) {
+    const uint32_t vec0 = p * PIECE + lane;
+    if ((p + 1) * PIECE <= geo.n_vec) {  // uniform
 #pragma unroll
       for (int r = 0; r < ROWS; ++r) {
         buf.a[r] = ld_stream(&gv[vec0 + r * kWave]);
@@ -338,9 +355,9 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
       }
     }
   };
-  auto process_step = [&](const Rows& buf, uint32_t q) {
-    const uint32_t vec0 = first_vec(q);
-    const bool full = tile_is_full(q);
+  auto process_piece = [&](const Rows& buf, uint32_t p) {
+    const uint32_t vec0 = p * PIECE + lane;
+    const bool full = (p + 1) * PIECE <= geo.n_vec;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
       uint4 v = buf.a[r];
@@ -353,22 +370,17 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
   };
   {
     Rows va, vb;
-    uint32_t q = 0;
-    if (q < steps) load_step(va, q);
-    while (q < steps) {
-      if (q + 1 < steps) load_step(vb, q + 1);
-      process_step(va, q);
-      ++q;
-      if (q >= steps) break;
-      if (q + 1 < steps) load_step(va, q + 1);
-      process_step(vb, q);
-      ++q;
+    uint32_t p = take_piece();
+    if (p != kNoPiece) load_piece(va, p);
+    while (p != kNoPiece) {
+      uint32_t q = take_piece();
+      if (q != kNoPiece) load_piece(vb, q);
+      process_piece(va, p);
+      if (q == kNoPiece) break;
+      p = take_piece();
+      if (p != kNoPiece) load_piece(va, p);
+      process_piece(vb, q);
     }
-  }
-  if (wg == geo.grid - 1 && wave == kSelWaves - 1 && geo.tail != 0) {
-    const bool in = lane < geo.tail;
-    const uint32_t raw = in ? elem_raw<DT, EF>(g, e, geo.head + geo.n_vec * V + lane) : 0u;
-    take(&raw, in, std::integral_constant<int, 1>{});
   }
   // end of the chunk: one reservation for the whole workgroup (both counts in one 64-bit add)
   if (lane == 0) {
@@ -378,7 +390,7 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_partition_kernel(
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t c = 0, a = 0;
-    for (int w = 0; w < kSelWaves; ++w) {
+    for (int w = 0; w < kPartWaves; ++w) {
       c += s_cnt[w];
       a += s_abv[w];
     }
@@ -736,13 +748,11 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
     geo.head = static_cast<uint32_t>(head);
     geo.n_vec = static_cast<uint32_t>((n - head) / vec);
     geo.tail = static_cast<uint32_t>((n - head) % vec);
-    uint32_t tiles = (geo.n_vec + kPartTileVecs - 1) / kPartTileVecs;
-    if (tiles == 0) tiles = 1;
-    uint32_t max_grid = static_cast<uint32_t>(device_cu_count()) * 8u;
-    if (max_grid > kSelMaxGrid) max_grid = kSelMaxGrid;
-    geo.grid = tiles < max_grid ? tiles : max_grid;
-    geo.vecs_per_wg = 0;
-    const dim3 ggrid(kSampleSize / kGatherThreads), gblock(kGatherThreads), pgrid(geo.grid), pblock(kSelThreads);
+    uint32_t blocks = (geo.n_vec + kPartPieceVecs * kPartWaves - 1) / (kPartPieceVecs * kPartWaves);
+    if (blocks == 0) blocks = 1;
+    const uint32_t max_grid = static_cast<uint32_t>(device_cu_count());
+    geo.grid = blocks < max_grid ? blocks : max_grid;
+    const dim3 ggrid(kSampleSize / kGatherThreads), gblock(kGatherThreads), pgrid(geo.grid), pblock(kPartThreads);
     if (ef) {
       hipLaunchKernelGGL((select_gather_kernel<DCT_F32, true>), ggrid, gblock, 0, s, g32, e32, n32, ws);
       hipLaunchKernelGGL((select_bounds_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws, cand_cap);
