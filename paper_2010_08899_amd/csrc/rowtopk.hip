@@ -461,16 +461,25 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     const uint32_t vecs = D / 8;
     const uint32_t nv = vecs <= 16 ? 1u : vecs <= 32 ? 2u : vecs <= 64 ? 4u : 8u;
     const uint32_t groups = ceil_div(B, quad::kRows);
-    uint32_t qgrid = (groups + quad::kWaves - 1) / quad::kWaves;
-    // workgroups per CU that registers and the LDS row buffers allow
-    const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * (nv == 8 ? 4u : nv == 4 ? 6u : 8u);
-    if (qgrid > resident) qgrid = resident;
+    const uint32_t cus = static_cast<uint32_t>(device_cu_count());
+    // one large workgroup per CU when each of its wavefronts gets at least four groups, else small workgroups,
+    // as many per CU as registers and the LDS row buffers allow
+    const bool large = groups >= 4u * quad::kWavesLarge * cus;
+    const uint32_t wg_waves = large ? quad::kWavesLarge : quad::kWavesSmall;
+    const uint32_t resident = large ? cus : cus * (nv == 8 ? 4u : nv == 4 ? 6u : 8u);
+    const uint32_t qgrid = std::min(ceil_div(groups, wg_waves), resident);
     const auto* xq = static_cast<const uint16_t*>(x);
     auto* vq = static_cast<uint16_t*>(d_val_out);
     auto* tq = static_cast<uint16_t*>(d_tau_out);
 #define DCT_LAUNCH_QUAD(NVV, ENCV)                                                                              \
-  hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV>), dim3(qgrid), dim3(quad::kThreads), 0, s, xq, B, \
-                     D, row_stride_elems, k, io, vq, tq)
+  do {                                                                                                          \
+    if (large)                                                                                                  \
+      hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV, quad::kWavesLarge>), dim3(qgrid),             \
+                         dim3(quad::kWavesLarge * kWave), 0, s, xq, B, D, row_stride_elems, k, io, vq, tq);     \
+    else                                                                                                        \
+      hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV, quad::kWavesSmall>), dim3(qgrid),             \
+                         dim3(quad::kWavesSmall * kWave), 0, s, xq, B, D, row_stride_elems, k, io, vq, tq);     \
+  } while (0)
 #define DCT_LAUNCH_QUAD_NV(ENCV)                  \
   do {                                            \
     if (nv == 1) DCT_LAUNCH_QUAD(1, ENCV);        \

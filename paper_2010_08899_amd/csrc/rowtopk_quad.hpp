@@ -32,8 +32,13 @@ using fast::pk_lshr15_u16;
 using fast::pk_sub_u16;
 using fast::wave_lds_fence;
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
+// Wavefronts per workgroup: 4, or -- when every wavefront of a full chip has several groups to do -- 16, one
+// workgroup per CU whose wavefronts take the groups from a counter in LDS (a SIMD serves its oldest wavefront
+// first; dealt out in advance, the groups of the last wavefronts set the kernel's time.  512 MiB of rows:
+// D = 256 246 -> 233 us, 512 175 -> 157 us, 1024 154 -> 136 us; below 64 k rows the small workgroups, which
+// spread over all CUs, are as fast or faster).
+constexpr int kWavesSmall = 4;
+constexpr int kWavesLarge = 16;
 constexpr int kRows = 4;               // rows per wavefront
 constexpr int kLanes = kWave / kRows;  // lanes per row: one DPP row
 constexpr uint32_t kMaxD = 1024;
@@ -73,8 +78,8 @@ __device__ __forceinline__ uint32_t row_ballot(bool p, uint32_t lane) {
 
 // NV = 16-byte vectors per lane: a lane owns NV * 8 contiguous columns, a row 16 * NV * 8.
 // ENC (RowEnc): how the mask is written (32- or 16-bit column indices, or a bitmap of ceil(D/32) words per row).
-template <int NV, int ENC>
-__global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
+template <int NV, int ENC, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
     const uint16_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, void* __restrict__ idx_out,
     uint16_t* __restrict__ val_out, uint16_t* __restrict__ tau_out) {
   constexpr int COLS = NV * 8;                  // columns per lane
@@ -85,6 +90,7 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
   constexpr int CHUNK = (NV + 1) * 16;          // LDS bytes per lane chunk (16 bytes of padding)
   constexpr int kColsPerWord = 2 * RPW;
   constexpr int wB = WORDS - 1;
+  constexpr int kWaves = WAVES;
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
   __shared__ uint32_t s_hist[kWaves][kRows][kWindow];
 
@@ -113,7 +119,19 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
 
   const uint64_t n_groups = (static_cast<uint64_t>(B) + kRows - 1) / kRows;
   const uint64_t group_step = static_cast<uint64_t>(gridDim.x) * kWaves;
-  uint64_t grp = static_cast<uint64_t>(blockIdx.x) * kWaves + wave;
+  // The workgroup's groups are blocks of kWaves consecutive ones, one block in every stripe of the grid; its
+  // wavefronts take them one at a time, in order (the n-th group taken increases with n: a wavefront that is
+  // handed a group past the end is done).
+  __shared__ uint32_t s_taken;
+  if (threadIdx.x == 0) s_taken = 0;
+  __syncthreads();
+  auto take_group = [&]() -> uint64_t {
+    uint32_t n = 0;
+    if (lane == 0) n = atomicAdd(&s_taken, 1u);
+    n = __builtin_amdgcn_readfirstlane(n);
+    return static_cast<uint64_t>(blockIdx.x) * kWaves + (n % kWaves) + static_cast<uint64_t>(n / kWaves) * group_step;
+  };
+  uint64_t grp = take_group();
   uint4 nxt[NV];
   auto load_group = [&](uint64_t gi) {
     const uint64_t row = gi * kRows + g;
@@ -126,7 +144,8 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
   };
   if (grp < n_groups) load_group(grp);
 
-  for (; grp < n_groups; grp += group_step) {
+  uint64_t next_grp = 0;
+  for (; grp < n_groups; grp = next_grp) {
     const uint64_t my_row = grp * kRows + g;
     // ---- 1. rows -> LDS (padded) -> registers, lane-contiguous within each row
     wave_lds_fence();  // the previous group's readers are done with the buffer
@@ -136,7 +155,8 @@ __global__ __launch_bounds__(kThreads) void rowtopk_fwd_quad_kernel(
       *reinterpret_cast<uint4*>(row_lds + (g * kLanes + q / NV) * CHUNK + (q % NV) * 16) = nxt[j];
     }
     wave_lds_fence();
-    if (grp + group_step < n_groups) load_group(grp + group_step);
+    next_grp = take_group();
+    if (next_grp < n_groups) load_group(next_grp);
     uint32_t R[4 * NV];
 #pragma unroll
     for (int m = 0; m < NV; ++m) {

@@ -902,7 +902,10 @@ def test_mp_bf16_wide_rows(dct, B, D, k, enc):
 @pytest.mark.parametrize("B,D,k,pad,idx16", [
     (8192, 256, 12, 0, False), (8193, 512, 25, 0, False), (10_000, 1024, 51, 0, False), (8200, 128, 6, 0, True),
     (9001, 264, 13, 8, False), (8192, 1000, 128, 0, False), (8195, 64, 64, 0, True), (8190 + 9, 8, 3, 0, False),
-    (8192, 1024, 1, 0, False), (8194, 520, 100, 16, True)])
+    (8192, 1024, 1, 0, False), (8194, 520, 100, 16, True),
+    # 64 k rows and more: one workgroup of 16 wavefronts per CU takes the groups from a counter
+    (65536, 256, 12, 0, False), (65539, 512, 25, 0, True), (70_001, 1024, 51, 0, False), (131_075, 64, 3, 0, False),
+    (65_537, 264, 13, 8, False)])
 def test_mp_many_narrow_rows(dct, B, D, k, pad, idx16):
     x = si.relu_activations(B, D, DEV, 1900 + D + k, dtype=torch.bfloat16, row_stride=D + pad if pad else None)
     # hard rows among the ordinary ones, spread over the slots of a group of four: all equal, all zero, two
@@ -932,7 +935,8 @@ def test_mp_many_narrow_rows(dct, B, D, k, pad, idx16):
     assert np.array_equal(bits(host(tau)), bits(etau))
 
 
-@pytest.mark.parametrize("B,D,k", [(8192, 256, 12), (8199, 64, 5), (8193, 128, 9), (9000, 1024, 51), (8192, 520, 26)])
+@pytest.mark.parametrize("B,D,k", [(8192, 256, 12), (8199, 64, 5), (8193, 128, 9), (9000, 1024, 51), (8192, 520, 26),
+                                   (65541, 256, 12), (66000, 1024, 51)])
 def test_mp_many_narrow_rows_bitmask(dct, B, D, k):
     x = si.relu_activations(B, D, DEV, 1950 + D, dtype=torch.bfloat16)
     x[3] = 0.5
