@@ -171,6 +171,73 @@ __global__ __launch_bounds__(256) void rowtopk_bwd_gather_flat_kernel(const W* _
   dval[o] = c < D ? dy[static_cast<uint64_t>(b) * stride + c] : static_cast<W>(0);
 }
 
+// The same gather for rows of which the list touches nearly every 64-byte sector anyway (k >= D / 32):
+// the whole row is streamed into LDS with coalesced 16-byte loads and the picks are made there.  One
+// workgroup of 16 wavefronts per CU; its rows are blocks of 16 consecutive ones, one block in every
+// stripe of the grid, taken one at a time from a counter in LDS (a SIMD serves its oldest wavefront
+// first: rows dealt out in advance leave the youngest wavefronts behind).  The next row and the first
+// 256 entries of its list are on their way while the current row is gathered.  Rows of up to 8 KiB.
+constexpr uint32_t kBwdRowBytes = 8192;
+constexpr int kBwdWaves = 16;
+template <typename W, typename I>
+__global__ __launch_bounds__(kBwdWaves * kWave) void rowtopk_bwd_rows_kernel(
+    const W* __restrict__ dy, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, const I* __restrict__ idx,
+    W* __restrict__ dval) {
+  constexpr uint32_t EPV = 16 / sizeof(W);
+  constexpr int NV = kBwdRowBytes / 16 / kWave;  // 16-byte vectors per lane: 8
+  constexpr int NI = 4;                          // list entries per lane that are fetched ahead
+  __shared__ uint4 s_rows[kBwdWaves][kBwdRowBytes / 16];
+  __shared__ uint32_t s_taken;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane = lane_id();
+  uint4* row4 = s_rows[wave];
+  const W* row_lds = reinterpret_cast<const W*>(row4);
+  const uint32_t n_vec = D / EPV;  // the host guarantees whole vectors and aligned rows
+  if (threadIdx.x == 0) s_taken = 0;
+  __syncthreads();
+  const uint64_t stripe = static_cast<uint64_t>(gridDim.x) * kBwdWaves;
+  auto take_row = [&]() -> uint64_t {
+    uint32_t n = 0;
+    if (lane == 0) n = atomicAdd(&s_taken, 1u);
+    n = __builtin_amdgcn_readfirstlane(n);
+    return static_cast<uint64_t>(blockIdx.x) * kBwdWaves + (n % kBwdWaves) + static_cast<uint64_t>(n / kBwdWaves) * stripe;
+  };
+  uint4 nxt[NV];
+  uint32_t nidx[NI];
+  auto load_row = [&](uint64_t r) {
+    const uint4* src = reinterpret_cast<const uint4*>(dy + r * stride) + lane;
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+      nxt[j] = j * kWave + lane < n_vec ? ld_stream(&src[j * kWave]) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+      nidx[j] = j * kWave + lane < k ? static_cast<uint32_t>(idx[r * k + j * kWave + lane]) : 0u;
+  };
+  uint64_t row = take_row(), next_row = 0;
+  if (row < B) load_row(row);
+  for (; row < B; row = next_row) {
+    fast::wave_lds_fence();  // the previous row's picks are done
+#pragma unroll
+    for (int j = 0; j < NV; ++j) row4[j * kWave + lane] = nxt[j];
+    uint32_t cur[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) cur[j] = nidx[j];
+    fast::wave_lds_fence();
+    next_row = take_row();
+    if (next_row < B) load_row(next_row);
+    W* out = dval + row * k;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const uint32_t o = j * kWave + lane;
+      if (o < k) out[o] = cur[j] < D ? row_lds[cur[j]] : static_cast<W>(0);
+    }
+    for (uint32_t o = NI * kWave + lane; o < k; o += kWave) {
+      const uint32_t c = static_cast<uint32_t>(idx[row * k + o]);
+      out[o] = c < D ? row_lds[c] : static_cast<W>(0);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Consumers of the bitmap form, one wavefront per row: column c of a 64-column
 // group belongs to lane c % 64; a ballot of the mask bits ranks the kept columns.
@@ -664,6 +731,20 @@ int launch_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row_stri
   if (!is_aligned(dy, es) || !is_aligned(d_idx, sizeof(I)) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint64_t n_out = static_cast<uint64_t>(B) * k;
+  // dense lists over rows of 4 to 8 KiB, enough rows for every wavefront of the chip: stream the rows through LDS
+  const uint32_t cus = static_cast<uint32_t>(device_cu_count());
+  if (static_cast<uint64_t>(D) * es <= kBwdRowBytes && D * es >= kBwdRowBytes / 2 && (D * es) % 16 == 0 && is_aligned(dy, 16) &&
+      (row_stride_elems * es) % 16 == 0 && static_cast<uint64_t>(k) * 32 >= D && B >= 4u * kBwdWaves * cus) {
+    const dim3 rgrid(std::min(ceil_div(B, static_cast<uint32_t>(kBwdWaves)), cus)), rblock(kBwdWaves * kWave);
+    if (dt == DCT_F32) {
+      hipLaunchKernelGGL((rowtopk_bwd_rows_kernel<uint32_t, I>), rgrid, rblock, 0, s, static_cast<const uint32_t*>(dy),
+                         B, D, row_stride_elems, k, d_idx, static_cast<uint32_t*>(d_dval_out));
+    } else {
+      hipLaunchKernelGGL((rowtopk_bwd_rows_kernel<uint16_t, I>), rgrid, rblock, 0, s, static_cast<const uint16_t*>(dy),
+                         B, D, row_stride_elems, k, d_idx, static_cast<uint16_t*>(d_dval_out));
+    }
+    return launch_status();
+  }
   // few outputs per row: one thread per output over all rows (a grid holds fewer than 2^32 threads)
   if (k < 192u && n_out + 255 <= 0xFFFFFFFFull) {
     const dim3 fgrid(static_cast<uint32_t>((n_out + 255) / 256));

@@ -382,6 +382,34 @@ def test_mp_bwd_out_of_range_index_is_not_dereferenced(dct):
     assert d[1, 1] == 0 and d[2, 0] == 0 and d[3, 2] == 0 and d[1, 0] == dyh[1, 1]
 
 
+@pytest.mark.parametrize("dtype,B,D,k,pad,idx16", [
+    (torch.bfloat16, 16384, 4096, 204, 0, False), (torch.bfloat16, 16391, 2048, 300, 0, True),
+    (torch.float32, 16385, 1024, 40, 8, False), (torch.float32, 16400, 2048, 700, 0, True),
+    (torch.bfloat16, 20000, 3000, 100, 8, False)])
+def test_mp_bwd_many_rows_dense_lists(dct, dtype, B, D, k, pad, idx16):
+    """Backward over many rows of 4 to 8 KiB with k >= D / 32: the rows are streamed through LDS (bad indices
+    give 0 there too; lists longer than the 256 entries that are fetched ahead; padded rows; both index widths)."""
+    dy = si.normal_matrix(B, D, DEV, 2700 + D, dtype=dtype, row_stride=D + pad if pad else None)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(2701 + D)
+    idx = torch.rand(B, D, device=DEV, generator=g).argsort(1)[:, :k].sort(1).values.to(torch.int32)
+    clean = idx.clone()     # the oracle takes valid lists only: the three bad entries are checked by hand
+    idx[5, 0] = D           # just past the row
+    idx[7, k - 1] = 65535 if idx16 else -1
+    idx[B - 1, k // 2] = D + 7
+    dval = torch.full((B, k), 3.0, device=DEV).to(dtype)
+    if idx16:
+        dct.dct_rowtopk_bwd_idx16(dy, idx.to(torch.int16), dval)
+        want = oracle.rowtopk_bwd_idx16(oracle.as_numpy(dy.cpu()), clean.to(torch.int16).cpu().numpy().view(np.uint16))
+    else:
+        dct.dct_rowtopk_bwd(dy, idx, dval)
+        want = oracle.rowtopk_bwd(oracle.as_numpy(dy.cpu()), clean.cpu().numpy())
+    want[5, 0] = want[7, k - 1] = want[B - 1, k // 2] = 0
+    got = host(dval)
+    assert np.array_equal(bits(got.reshape(-1)), bits(want.reshape(-1)))
+    assert got[5, 0] == 0 and got[7, k - 1] == 0 and got[B - 1, k // 2] == 0
+
+
 def test_mp_argument_errors(dct):
     x = si.relu_activations(4, 100, DEV, 61)
     idx = torch.zeros(4, 101, dtype=torch.int32, device=DEV)
