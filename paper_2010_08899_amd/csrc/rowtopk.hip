@@ -568,13 +568,20 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
     const uint32_t waves_per_cu = row_bytes <= 2048u ? 32u : row_bytes <= 4096u ? 24u : row_bytes <= 8192u ? 16u : 8u;
     const uint32_t cus = static_cast<uint32_t>(device_cu_count());
     const uint32_t vecs = D / epv;  // 16-byte vectors per row, spread over 64 lanes
-#define DCT_LAUNCH_ONCHIP(NVV, MK, F32V)                                                                        \
+#define DCT_LAUNCH_ONCHIP_W(NVV, MK, F32V, WV)                                                                   \
   do {                                                                                                          \
     using W = std::conditional_t<F32V, uint32_t, uint16_t>;                                                     \
-    constexpr uint32_t wg_waves = fast::waves_per_wg<NVV>();                                                    \
-    const dim3 g(std::min(ceil_div(B, wg_waves), cus * std::max(waves_per_cu / wg_waves, 1u))), b(wg_waves * kWave); \
-    hipLaunchKernelGGL((fast::rowtopk_fwd_onchip_kernel<NVV, MK, F32V>), g, b, 0, s, static_cast<const W*>(x), B, \
-                       D, row_stride_elems, k, io, static_cast<W*>(d_val_out), static_cast<W*>(d_tau_out));     \
+    const dim3 g(std::min(ceil_div(B, static_cast<uint32_t>(WV)), cus * std::max(waves_per_cu / (WV), 1u))),     \
+        b((WV) * kWave);                                                                                        \
+    hipLaunchKernelGGL((fast::rowtopk_fwd_onchip_kernel<NVV, MK, F32V, WV>), g, b, 0, s, static_cast<const W*>(x), \
+                       B, D, row_stride_elems, k, io, static_cast<W*>(d_val_out), static_cast<W*>(d_tau_out));  \
+  } while (0)
+  // the large workgroup (see fast::waves_per_wg) when each of its wavefronts gets at least four rows
+#define DCT_LAUNCH_ONCHIP(NVV, MK, F32V)                                                         \
+  do {                                                                                           \
+    constexpr uint32_t wl = fast::waves_per_wg<NVV>();                                           \
+    if (wl != fast::kWavesSmall && B >= 4u * wl * cus) DCT_LAUNCH_ONCHIP_W(NVV, MK, F32V, wl);   \
+    else DCT_LAUNCH_ONCHIP_W(NVV, MK, F32V, fast::kWavesSmall);                                  \
   } while (0)
 #define DCT_LAUNCH_ONCHIP_NV(MK, F32V)                       \
   do {                                                       \
@@ -595,6 +602,7 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
 #undef DCT_LAUNCH_ONCHIP_ENC
 #undef DCT_LAUNCH_ONCHIP_NV
 #undef DCT_LAUNCH_ONCHIP
+#undef DCT_LAUNCH_ONCHIP_W
     return launch_status();
   }
 #define DCT_LAUNCH_GENERIC(DTV, MK)                                                                       \

@@ -37,15 +37,17 @@
 namespace dct {
 namespace fast {
 
-// Wavefronts per workgroup.  Rows of more than 4 KiB leave room for 16 (8 KiB) or 8 (16 KiB) wavefronts on a
-// CU, and ALL of them form one workgroup so that they can share a row counter in LDS: a SIMD serves its oldest
-// wavefront first, and with the rows dealt out in advance the wavefronts that were started first finished their
-// share at 2/3 of the kernel's time and the last ones set it (c5: 76 / 89 / 101 / 114 us for the four
-// wavefronts of a SIMD).  Narrower rows keep workgroups of four wavefronts: several of those fit a CU and a
-// counter per workgroup would not level them.
+// Wavefronts per workgroup: 4, or -- for rows of more than 4 KiB, when every wavefront of a full chip has
+// several rows to do -- ALL the wavefronts a CU has room for, 16 (8 KiB rows) or 8 (16 KiB rows), so that they can
+// share a row counter in LDS: a SIMD serves its oldest wavefront first, and with the rows dealt out in advance
+// the wavefronts that were started first finished their share at 2/3 of the kernel's time and the last ones
+// set it (c5: 76 / 89 / 101 / 114 us for the four wavefronts of a SIMD).  Narrower rows keep workgroups of four
+// wavefronts: several of those fit a CU and a counter per workgroup would not level them; so do small batches,
+// whose few large workgroups would leave CUs idle (8 KiB rows: the large workgroup wins from 16 k rows on).
+constexpr int kWavesSmall = 4;
 template <int NV>
 constexpr int waves_per_wg() {
-  return NV == 8 ? 16 : NV == 16 ? 8 : 4;
+  return NV == 8 ? 16 : NV == 16 ? 8 : kWavesSmall;
 }
 constexpr uint32_t kWindow = 32;
 constexpr int kSampleRegs = 4;  // packed registers per lane in the first row's sample (8 keys per lane)
@@ -87,8 +89,8 @@ __device__ __forceinline__ void wave_lds_fence() {
 // 16 bits, or as a bitmap (ceil(D/32) words per row, bit c%32 of word c/32 = column c kept); the
 // values are written either way.
 // F32: fp32 rows (the packed 16-bit keys are the upper halves of the fp32 keys).
-template <int NV, int ENC, bool F32>
-__global__ __launch_bounds__(waves_per_wg<NV>() * kWave) void rowtopk_fwd_onchip_kernel(
+template <int NV, int ENC, bool F32, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_onchip_kernel(
     const std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride,
     uint32_t k, void* __restrict__ idx_out, std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ val_out,
     std::conditional_t<F32, uint32_t, uint16_t>* __restrict__ tau_out) {
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(waves_per_wg<NV>() * kWave) void rowtopk_fwd_onchip
   constexpr int WORDS = (REGS + 15) / 16;
   static_assert(WORDS <= 2 || (WORDS == 4 && !F32), "a lane owns at most 64 columns (bf16: 128)");
   constexpr int CHUNK = (NV + 1) * 16;              // LDS bytes per lane chunk (16 bytes of padding)
-  constexpr int kWaves = waves_per_wg<NV>();
+  constexpr int kWaves = WAVES;
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
   __shared__ uint32_t s_hist[kWaves][kWave];
   __shared__ uint32_t s_fix[F32 ? kWaves : 1][F32 ? kWave * WORDS : 1];  // fp32: decisions handed back to the owner lane

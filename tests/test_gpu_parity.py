@@ -899,7 +899,9 @@ def test_mp_bitmask_c5_block(dct):
 
 # ------------------------------------------------------------------ MP: bf16 rows of 4096 ... 8192 columns (four bitmap words per lane)
 @pytest.mark.parametrize("B,D,k,enc", [(37, 8192, 409, 0), (20, 5120, 256, 1), (9, 6144, 300, 2), (5, 8192, 512, 0),
-                                       (6, 4104, 1, 0), (4, 8192, 8192, 0), (11, 7168, 1000, 2)])
+                                       (6, 4104, 1, 0), (4, 8192, 8192, 0), (11, 7168, 1000, 2),
+                                       # enough rows for the workgroups of 8 wavefronts that share a row counter
+                                       (8200, 8192, 409, 0), (8195, 5120, 256, 1), (8192, 6144, 300, 2)])
 def test_mp_bf16_wide_rows(dct, B, D, k, enc):
     x = si.relu_activations(B, D, DEV, 1980 + D + k, dtype=torch.bfloat16)
     cols = torch.arange(D, device=DEV)
