@@ -37,17 +37,18 @@
 namespace dct {
 namespace fast {
 
-// Wavefronts per workgroup: 4, or -- for rows of more than 4 KiB, when every wavefront of a full chip has
-// several rows to do -- ALL the wavefronts a CU has room for, 16 (8 KiB rows) or 8 (16 KiB rows), so that they can
-// share a row counter in LDS: a SIMD serves its oldest wavefront first, and with the rows dealt out in advance
-// the wavefronts that were started first finished their share at 2/3 of the kernel's time and the last ones
-// set it (c5: 76 / 89 / 101 / 114 us for the four wavefronts of a SIMD).  Narrower rows keep workgroups of four
-// wavefronts: several of those fit a CU and a counter per workgroup would not level them; so do small batches,
-// whose few large workgroups would leave CUs idle (8 KiB rows: the large workgroup wins from 16 k rows on).
+// Wavefronts per workgroup: 4, or -- when every wavefront of a full chip has several rows to do -- 16 (8 for
+// rows of 16 KiB, all a CU has room for), one workgroup per CU whose wavefronts share a row counter in LDS: a
+// SIMD serves its oldest wavefront first, and with the rows dealt out in advance the wavefronts that were
+// started first finished their share at 2/3 of the kernel's time and the last ones set it (c5: 76 / 89 / 101 /
+// 114 us for the four wavefronts of a SIMD).  Measured per 512 MiB: 8 KiB rows 122 -> 114 us, 16 KiB rows
+// 145 -> 139 us, fp32 rows of 2 KiB 173 -> 155 us, of 1 KiB 329 -> 292 us; rows of 4 KiB gain nothing (six small
+// workgroups per CU do as well there) and keep the small workgroups, as do small batches, whose few large
+// workgroups would leave CUs idle (8 KiB rows: the large workgroup wins from 16 k rows on).
 constexpr int kWavesSmall = 4;
 template <int NV>
 constexpr int waves_per_wg() {
-  return NV == 8 ? 16 : NV == 16 ? 8 : kWavesSmall;
+  return NV == 16 ? 8 : NV == 4 ? kWavesSmall : 16;
 }
 constexpr uint32_t kWindow = 32;
 constexpr int kSampleRegs = 4;  // packed registers per lane in the first row's sample (8 keys per lane)

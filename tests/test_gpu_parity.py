@@ -324,6 +324,19 @@ def test_mp_bf16_on_chip_kernel_hard_rows(dct, D):
         check_mp(dct, x, dy, k)
 
 
+@pytest.mark.parametrize("dtype,B,D,k", [
+    (torch.float32, 16390, 256, 12), (torch.float32, 16384, 512, 25), (torch.float32, 20000, 200, 10),
+    (torch.bfloat16, 16400, 1024, 200), (torch.bfloat16, 16385, 2048, 102), (torch.float32, 16401, 1024, 51)])
+def test_mp_many_rows_of_up_to_4_kib(dct, dtype, B, D, k):
+    """From 16 k rows on the one-row-per-wavefront kernel runs as one workgroup of 16 wavefronts per CU that take
+    their rows from a counter (rows of up to 2 KiB; 4 KiB rows keep the small workgroups)."""
+    x = si.relu_activations(B, D, DEV, 2800 + D, dtype=dtype)
+    x[3] = 0.5
+    x[B - 2] = 0.0
+    dy = si.normal_matrix(B, D, DEV, 2801 + D, dtype=dtype)
+    check_mp(dct, x, dy, k)
+
+
 @pytest.mark.parametrize("D", [256, 1024, 2048, 4096])
 def test_mp_fp32_on_chip_kernel_hard_rows(dct, D):
     """fp32 rows for the on-chip kernel: its search runs on the upper halves of the keys, so the hard
