@@ -119,7 +119,7 @@ int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_thre
  *                stream.  Two calls that share a workspace must not overlap.
  *
  * Concurrency.  The kernel's workgroups exchange their counts while they run, so its
- * whole grid (at most four workgroups per CU) has to be on the chip together.  Run
+ * whole grid (three or four workgroups per CU) has to be on the chip together.  Run
  * alone on the device that is always so.  When other kernels hold CUs at the same
  * time (another stream), a call that needs several rounds -- more than about four
  * million survivors, or any dct_ef_threshold_compact on a large vector -- may find
