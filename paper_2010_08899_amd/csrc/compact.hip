@@ -67,9 +67,10 @@ constexpr uint32_t kCtTileVecs = kCtThreads * kCtRows;  // granule of the chunki
 // Workgroups per CU and staged pairs per wavefront (each pair 8 bytes of LDS; 144 KiB per CU either way).  Three
 // larger workgroups stream better than four (c4 179 -> 174 us; 2^28 dense fp32 with 1 % kept: 206 -> 184 us; a CU
 // serves its oldest workgroup first and the youngest sets the kernel's time); with error feedback, which writes a
-// third of what it reads, four do (597 against 622 us).
-constexpr int ct_wg_per_cu(bool ef) { return ef ? 4 : 3; }
-constexpr uint32_t ct_stage_cap(bool ef) { return ef ? 1152u : 1536u; }
+// third of what it reads, four do (597 against 622 us), and so do bf16 vectors, whose eight elements per vector
+// need the wavefronts (2^29 elements, exactly-k: 237 against 251 us).
+constexpr int ct_wg_per_cu(bool ef, int dt) { return ef || dt == DCT_BF16 ? 4 : 3; }
+constexpr uint32_t ct_stage_cap(bool ef, int dt) { return ef || dt == DCT_BF16 ? 1152u : 1536u; }
 constexpr uint32_t kCtMaxGrid = 2048;
 constexpr uint32_t kCtGroup = 64;                       // (virtual) workgroups per descriptor group
 constexpr uint32_t kCtMaxRounds = 12;                   // slices a dense vector is cut into (at most)
@@ -174,7 +175,7 @@ struct CompactGeom {
 
 // EF: g is W_grad, e_in the residual E_grad (may be the same buffer as e_out), e_out the new residual.
 template <int DT, bool EXACT, bool EF>
-__global__ __launch_bounds__(kCtThreads, ct_wg_per_cu(EF)) void compact_kernel(
+__global__ __launch_bounds__(kCtThreads, ct_wg_per_cu(EF, DT)) void compact_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* e_in,
     typename Elem<DT>::word_t* e_out, CompactGeom geo, const dct_threshold* __restrict__ thr,
     int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out, uint32_t capacity,
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(kCtThreads, ct_wg_per_cu(EF)) void compact_kernel(
   using word_t = typename E::word_t;
   constexpr int V = E::kVec;
   constexpr int ROWS = EF ? kCtRows / 2 : kCtRows;  // two input streams: half the rows per iteration
-  constexpr uint32_t kCtStageCap = ct_stage_cap(EF);
+  constexpr uint32_t kCtStageCap = ct_stage_cap(EF, DT);
   __shared__ uint32_t s_idx[kCtWaves][kCtStageCap];
   __shared__ word_t s_val[kCtWaves][kCtStageCap];
   __shared__ uint32_t s_wave_a[kCtWaves], s_wave_e[kCtWaves];
@@ -591,7 +592,7 @@ uint32_t resident_per_cu() {
     int nb = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, compact_kernel<DT, EXACT, EF>, kCtThreads, 0) != hipSuccess)
       nb = 0;
-    return static_cast<uint32_t>(std::min(std::max(nb, 0), ct_wg_per_cu(EF)));
+    return static_cast<uint32_t>(std::min(std::max(nb, 0), ct_wg_per_cu(EF, DT)));
   }();
   return cached;
 }
