@@ -64,13 +64,16 @@ constexpr int kCtThreads = 256;
 constexpr int kCtWaves = kCtThreads / kWave;
 constexpr int kCtRows = 8;                              // 16-byte loads per lane per iteration
 constexpr uint32_t kCtTileVecs = kCtThreads * kCtRows;  // granule of the chunking: 32 KiB
-// Workgroups per CU and staged pairs per wavefront (each pair 8 bytes of LDS; 144 KiB per CU either way).  Three
-// larger workgroups stream better than four (c4 179 -> 174 us; 2^28 dense fp32 with 1 % kept: 206 -> 184 us; a CU
-// serves its oldest workgroup first and the youngest sets the kernel's time); with error feedback, which writes a
-// third of what it reads, four do (597 against 622 us), and so do bf16 vectors, whose eight elements per vector
-// need the wavefronts (2^29 elements, exactly-k: 237 against 251 us).
-constexpr int ct_wg_per_cu(bool ef, int dt) { return ef || dt == DCT_BF16 ? 4 : 3; }
-constexpr uint32_t ct_stage_cap(bool ef, int dt) { return ef || dt == DCT_BF16 ? 1152u : 1536u; }
+// Workgroups per CU (WG, a template argument of the kernel) and staged pairs per wavefront (each pair 8 bytes of
+// LDS; 144 KiB per CU either way).  Three larger workgroups stream better than four (c4 179 -> 174 us; 2^28 dense
+// fp32 with 1 % kept: 206 -> 184 us; a CU serves its oldest workgroup first and the youngest sets the kernel's
+// time), and on short vectors two do better still (25 M elements: 27.0 -> 26.0 us); with error feedback, which
+// writes a third of what it reads, four do (597 against 622 us), and so do bf16 vectors, whose eight elements
+// per vector need the wavefronts (2^29 elements, exactly-k: 237 against 251 us).
+constexpr int ct_wg_per_cu(bool ef, int dt, uint64_t n) {
+  return ef || dt == DCT_BF16 ? 4 : n < (1ull << 26) ? 2 : 3;
+}
+constexpr uint32_t ct_stage_cap(int wg) { return 4608u / static_cast<uint32_t>(wg); }
 constexpr uint32_t kCtMaxGrid = 2048;
 constexpr uint32_t kCtGroup = 64;                       // (virtual) workgroups per descriptor group
 constexpr uint32_t kCtMaxRounds = 12;                   // slices a dense vector is cut into (at most)
@@ -174,8 +177,8 @@ struct CompactGeom {
 };
 
 // EF: g is W_grad, e_in the residual E_grad (may be the same buffer as e_out), e_out the new residual.
-template <int DT, bool EXACT, bool EF>
-__global__ __launch_bounds__(kCtThreads, ct_wg_per_cu(EF, DT)) void compact_kernel(
+template <int DT, bool EXACT, bool EF, int WG>
+__global__ __launch_bounds__(kCtThreads, WG) void compact_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* e_in,
     typename Elem<DT>::word_t* e_out, CompactGeom geo, const dct_threshold* __restrict__ thr,
     int32_t* __restrict__ idx_out, typename Elem<DT>::word_t* __restrict__ val_out, uint32_t capacity,
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(kCtThreads, ct_wg_per_cu(EF, DT)) void compact_kern
   using word_t = typename E::word_t;
   constexpr int V = E::kVec;
   constexpr int ROWS = EF ? kCtRows / 2 : kCtRows;  // two input streams: half the rows per iteration
-  constexpr uint32_t kCtStageCap = ct_stage_cap(EF, DT);
+  constexpr uint32_t kCtStageCap = ct_stage_cap(WG);
   __shared__ uint32_t s_idx[kCtWaves][kCtStageCap];
   __shared__ word_t s_val[kCtWaves][kCtStageCap];
   __shared__ uint32_t s_wave_a[kCtWaves], s_wave_e[kCtWaves];
@@ -583,16 +586,16 @@ CompactGeom make_geom(uintptr_t addr, uint64_t n, int dt, uint32_t wg_per_cu) {
   return geo;
 }
 
-// Workgroups of one instantiation that a CU holds at once, at most ct_wg_per_cu (asked of the runtime once).
+// Workgroups of one instantiation that a CU holds at once, at most WG (asked of the runtime once).
 // The kernel's waits are on lower-numbered workgroups of the same launch, and with several rounds a
 // workgroup also waits on every workgroup's earlier rounds: the whole grid has to be resident.
-template <int DT, bool EXACT, bool EF>
+template <int DT, bool EXACT, bool EF, int WG>
 uint32_t resident_per_cu() {
   static const uint32_t cached = [] {
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, compact_kernel<DT, EXACT, EF>, kCtThreads, 0) != hipSuccess)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, compact_kernel<DT, EXACT, EF, WG>, kCtThreads, 0) != hipSuccess)
       nb = 0;
-    return static_cast<uint32_t>(std::min(std::max(nb, 0), ct_wg_per_cu(EF, DT)));
+    return static_cast<uint32_t>(std::min(std::max(nb, 0), WG));
   }();
   return cached;
 }
@@ -641,29 +644,36 @@ int launch_compact(const void* g, const void* e_in, void* e_out, int dt, uint64_
   if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < kCtWsBytes) return DCT_ERR_WORKSPACE;
 
   const bool exact = mode == DCT_EXACT_K;
-  const uint32_t per_cu = ef ? (exact ? resident_per_cu<DCT_F32, true, true>() : resident_per_cu<DCT_F32, false, true>())
-                          : dt == DCT_F32
-                              ? (exact ? resident_per_cu<DCT_F32, true, false>() : resident_per_cu<DCT_F32, false, false>())
-                              : (exact ? resident_per_cu<DCT_BF16, true, false>() : resident_per_cu<DCT_BF16, false, false>());
-  if (per_cu == 0) return DCT_ERR_HIP;
-  const CompactGeom geo = make_geom(reinterpret_cast<uintptr_t>(g), n, dt, per_cu);
   const uint32_t cap = capacity > 0xFFFFFFFFull ? 0xFFFFFFFFu : static_cast<uint32_t>(capacity);
   auto* hdr = static_cast<CompactHeader*>(d_ws);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const dim3 grid(geo.grid), block(kCtThreads);
 
-#define DCT_LAUNCH_COMPACT(DTV, EX, EFV)                                                                        \
-  hipLaunchKernelGGL((compact_kernel<DTV, EX, EFV>), grid, block, 0, s,                                         \
-                     static_cast<const Elem<DTV>::word_t*>(g), static_cast<const Elem<DTV>::word_t*>(e_in),     \
-                     static_cast<Elem<DTV>::word_t*>(e_out), geo, d_thr, d_idx_out,                             \
-                     static_cast<Elem<DTV>::word_t*>(d_val_out), cap, d_count_out, hdr)
+#define DCT_LAUNCH_COMPACT(DTV, EX, EFV, WGV)                                                                   \
+  do {                                                                                                          \
+    const uint32_t per_cu = resident_per_cu<DTV, EX, EFV, WGV>();                                               \
+    if (per_cu == 0) return DCT_ERR_HIP;                                                                        \
+    const CompactGeom geo = make_geom(reinterpret_cast<uintptr_t>(g), n, dt, per_cu);                           \
+    hipLaunchKernelGGL((compact_kernel<DTV, EX, EFV, WGV>), dim3(geo.grid), dim3(kCtThreads), 0, s,              \
+                       static_cast<const Elem<DTV>::word_t*>(g), static_cast<const Elem<DTV>::word_t*>(e_in),   \
+                       static_cast<Elem<DTV>::word_t*>(e_out), geo, d_thr, d_idx_out,                           \
+                       static_cast<Elem<DTV>::word_t*>(d_val_out), cap, d_count_out, hdr);                      \
+  } while (0)
+#define DCT_LAUNCH_COMPACT_MODE(DTV, EFV, WGV)                  \
+  do {                                                          \
+    if (exact) DCT_LAUNCH_COMPACT(DTV, true, EFV, WGV);         \
+    else DCT_LAUNCH_COMPACT(DTV, false, EFV, WGV);              \
+  } while (0)
+  const int wg = ct_wg_per_cu(ef, dt, n);
   if (ef) {
-    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_F32, true, true); else DCT_LAUNCH_COMPACT(DCT_F32, false, true);
-  } else if (dt == DCT_F32) {
-    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_F32, true, false); else DCT_LAUNCH_COMPACT(DCT_F32, false, false);
+    DCT_LAUNCH_COMPACT_MODE(DCT_F32, true, 4);
+  } else if (dt == DCT_BF16) {
+    DCT_LAUNCH_COMPACT_MODE(DCT_BF16, false, 4);
+  } else if (wg == 2) {
+    DCT_LAUNCH_COMPACT_MODE(DCT_F32, false, 2);
   } else {
-    if (mode == DCT_EXACT_K) DCT_LAUNCH_COMPACT(DCT_BF16, true, false); else DCT_LAUNCH_COMPACT(DCT_BF16, false, false);
+    DCT_LAUNCH_COMPACT_MODE(DCT_F32, false, 3);
   }
+#undef DCT_LAUNCH_COMPACT_MODE
 #undef DCT_LAUNCH_COMPACT
   return launch_status();
 }
