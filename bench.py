@@ -50,7 +50,7 @@ CALL_KERNELS = {
     "dct_scatter[c4,add]": [("dct::scatter_pairs_kernel<unsigned int, true>", 1)],
     "dct_rowtopk_scatter[c5]": [("dct::rowscatter_lds_kernel<unsigned short, int>", 1)],
     "dct_rowtopk_fwd_bitmask[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 1, false, 16>", 1)],
-    "dct_rowtopk_bwd_bitmask[c5]": [("dct::rowtopk_bitmask_lanes_kernel<unsigned short, true>", 1)],
+    "dct_rowtopk_bwd_bitmask[c5]": [("dct::rowtopk_bwd_rows_bitmask_kernel<unsigned short>", 1)],
     "dct_rowtopk_scatter_bitmask[c5]": [("dct::rowtopk_bitmask_lanes_kernel<unsigned short, false>", 1)],
     "dct_rowtopk_fwd_idx16[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 2, false, 16>", 1)],
     "dct_rowtopk_bwd_idx16[c5]": [("dct::rowtopk_bwd_rows_kernel<unsigned short, unsigned short>", 1)],

@@ -409,6 +409,79 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
   }
 }
 
+// The backward gather through a bitmap for many rows of 4 to 8 KiB with dense masks: as rowtopk_bwd_rows_kernel,
+// the row is streamed into LDS; the lanes turn their two mask words (64 columns each) into the ordered list of
+// kept columns, also in LDS, and lane j then picks the values of slots j, j + 64, ...  k <= kBwdListCap.
+constexpr uint32_t kBwdListCap = 512;
+template <typename W>
+__global__ __launch_bounds__(kBwdWaves * kWave) void rowtopk_bwd_rows_bitmask_kernel(
+    const W* __restrict__ dy, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, const uint32_t* __restrict__ mask,
+    W* __restrict__ dval) {
+  constexpr uint32_t EPV = 16 / sizeof(W);
+  constexpr int NV = kBwdRowBytes / 16 / kWave;
+  __shared__ uint4 s_rows[kBwdWaves][kBwdRowBytes / 16];
+  __shared__ uint16_t s_list[kBwdWaves][kBwdListCap];
+  __shared__ uint32_t s_taken;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane = lane_id();
+  uint4* row4 = s_rows[wave];
+  const W* row_lds = reinterpret_cast<const W*>(row4);
+  uint16_t* list = s_list[wave];
+  const uint32_t n_vec = D / EPV;            // the host guarantees whole vectors and aligned rows
+  const uint32_t n_words = (D + 31) / 32;    // D <= 4096: a lane's two words cover the row
+  if (threadIdx.x == 0) s_taken = 0;
+  __syncthreads();
+  const uint64_t stripe = static_cast<uint64_t>(gridDim.x) * kBwdWaves;
+  auto take_row = [&]() -> uint64_t {
+    uint32_t n = 0;
+    if (lane == 0) n = atomicAdd(&s_taken, 1u);
+    n = __builtin_amdgcn_readfirstlane(n);
+    return static_cast<uint64_t>(blockIdx.x) * kBwdWaves + (n % kBwdWaves) + static_cast<uint64_t>(n / kBwdWaves) * stripe;
+  };
+  uint4 nxt[NV];
+  uint64_t m_next = 0;
+  auto load_row = [&](uint64_t r) {
+    const uint4* src = reinterpret_cast<const uint4*>(dy + r * stride) + lane;
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+      nxt[j] = j * kWave + lane < n_vec ? ld_stream(&src[j * kWave]) : make_uint4(0, 0, 0, 0);
+    const uint32_t* mr = mask + r * n_words;
+    const uint32_t w0 = lane * 2;
+    uint64_t m = 0;
+    if (w0 < n_words) m = mr[w0];
+    if (w0 + 1 < n_words) m |= static_cast<uint64_t>(mr[w0 + 1]) << 32;
+    const uint32_t col0 = lane * 64;
+    if (col0 >= D) m = 0;
+    else if (D - col0 < 64) m &= (1ull << (D - col0)) - 1ull;  // bits past the row's end do not count
+    m_next = m;
+  };
+  uint64_t row = take_row(), next_row = 0;
+  if (row < B) load_row(row);
+  for (; row < B; row = next_row) {
+    fast::wave_lds_fence();  // the previous row's picks are done
+#pragma unroll
+    for (int j = 0; j < NV; ++j) row4[j * kWave + lane] = nxt[j];
+    uint64_t m = m_next;
+    next_row = take_row();
+    if (next_row < B) load_row(next_row);
+    const uint32_t pc = __popcll(m);
+    const uint32_t incl = fast::wave_incl_scan(pc);
+    uint32_t slot = incl - pc;
+    const uint32_t base = min(static_cast<uint32_t>(__builtin_amdgcn_readlane(incl, kWave - 1)), k);  // kept columns listed
+    while (ballot64(m != 0) != 0) {
+      if (m != 0) {
+        const uint32_t c = lane * 64 + __builtin_ctzll(m);
+        m &= m - 1;
+        if (slot < k) list[slot] = static_cast<uint16_t>(c);  // k <= kBwdListCap, c < 4096
+        ++slot;
+      }
+    }
+    fast::wave_lds_fence();  // row and list are in place
+    W* out = dval + row * k;
+    for (uint32_t o = lane; o < k; o += kWave) out[o] = o < base ? row_lds[list[o]] : static_cast<W>(0);
+  }
+}
+
 // The two consumers for NARROW rows whose mask is a power of two of words, at most 32 (D = 32 ... 1024 in
 // powers of two): one lane per mask word, so a wavefront covers 64 / WPR rows at once.  One wave scan of the
 // popcounts, less its value at the row's first lane, ranks every word's kept columns within its row.
@@ -645,7 +718,24 @@ extern "C" int dct_rowtopk_bwd_bitmask(const void* dy, int dt, uint32_t B, uint3
   const size_t es = dt == DCT_F32 ? 4 : 2;
   if (!is_aligned(dy, es) || !is_aligned(d_mask, 4) || !is_aligned(d_dval_out, es)) return DCT_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const uint32_t resident = static_cast<uint32_t>(device_cu_count()) * 8u;
+  const uint32_t cus = static_cast<uint32_t>(device_cu_count());
+  const uint32_t resident = cus * 8u;
+  // dense masks over many rows of 4 to 8 KiB: stream the rows through LDS
+  if (static_cast<uint64_t>(D) * es <= kBwdRowBytes && D * es >= kBwdRowBytes / 2 && D <= 4096u && (D * es) % 16 == 0 &&
+      is_aligned(dy, 16) && (row_stride_elems * es) % 16 == 0 && static_cast<uint64_t>(k) * 32 >= D &&
+      k <= kBwdListCap && B >= 4u * kBwdWaves * cus) {
+    const dim3 rgrid(std::min(ceil_div(B, static_cast<uint32_t>(kBwdWaves)), cus)), rblock(kBwdWaves * kWave);
+    if (dt == DCT_F32) {
+      hipLaunchKernelGGL((rowtopk_bwd_rows_bitmask_kernel<uint32_t>), rgrid, rblock, 0, s,
+                         static_cast<const uint32_t*>(dy), B, D, row_stride_elems, k, d_mask,
+                         static_cast<uint32_t*>(d_dval_out));
+    } else {
+      hipLaunchKernelGGL((rowtopk_bwd_rows_bitmask_kernel<uint16_t>), rgrid, rblock, 0, s,
+                         static_cast<const uint16_t*>(dy), B, D, row_stride_elems, k, d_mask,
+                         static_cast<uint16_t*>(d_dval_out));
+    }
+    return launch_status();
+  }
   const uint32_t wpr = D / 32;
   if (D % 32 == 0 && wpr <= 32 && (wpr & (wpr - 1)) == 0) {  // narrow rows: several per wavefront, one lane per word
     const uint32_t steps = ceil_div(B, kWave / wpr);

@@ -423,6 +423,27 @@ def test_mp_bwd_many_rows_dense_lists(dct, dtype, B, D, k, pad, idx16):
     assert got[5, 0] == 0 and got[7, k - 1] == 0 and got[B - 1, k // 2] == 0
 
 
+@pytest.mark.parametrize("dtype,B,D,k", [
+    (torch.bfloat16, 16384, 4096, 204), (torch.float32, 16390, 1024, 51), (torch.bfloat16, 16400, 2048, 512),
+    (torch.bfloat16, 16385, 3008, 100), (torch.float32, 16384, 2048, 64)])
+def test_mp_bwd_bitmask_many_rows_dense_masks(dct, dtype, B, D, k):
+    """Backward through the bitmap over many rows of 4 to 8 KiB: the rows are streamed through LDS.  Masks with
+    fewer set bits than k (zeros at the end of the list) and with more (the first k count) are among them."""
+    x = si.relu_activations(B, D, DEV, 2900 + D, dtype=dtype)
+    dy = si.normal_matrix(B, D, DEV, 2901 + D, dtype=dtype)
+    mask = torch.zeros(B, (D + 31) // 32, dtype=torch.int32, device=DEV)
+    val = torch.zeros(B, k, dtype=dtype, device=DEV)
+    dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, None)
+    mask[5, 0] = 0                      # fewer kept columns than k
+    mask[9] = 0                         # none at all
+    mask[7, -1] = -1                    # more than k
+    mask[B - 1, 1] |= 0x0F0F0F0F
+    dval = torch.full((B, k), 3.0, device=DEV).to(dtype)
+    dct.dct_rowtopk_bwd_bitmask(dy, mask, dval)
+    want = oracle.rowtopk_bwd_bitmask(host(dy), mask.cpu().numpy().view(np.uint32), k)
+    assert np.array_equal(bits(host(dval).reshape(-1)), bits(want.reshape(-1)))
+
+
 def test_mp_argument_errors(dct):
     x = si.relu_activations(4, 100, DEV, 61)
     idx = torch.zeros(4, 101, dtype=torch.int32, device=DEV)
