@@ -735,6 +735,34 @@ def test_rowtopk_scatter(dct, dtype, B, D, k, pad):
                        val.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
 
 
+@pytest.mark.parametrize("dtype,B,D,k,pad,idx16", [
+    (torch.bfloat16, 16390, 4096, 300, 8, False), (torch.float32, 16384, 1024, 51, 0, False),
+    (torch.bfloat16, 16385, 2048, 102, 0, True), (torch.float32, 16400, 2048, 400, 4, True)])
+def test_rowtopk_scatter_many_rows(dct, dtype, B, D, k, pad, idx16):
+    """Decompression of many rows of 4 to 8 KiB: long lists, padded output rows, out-of-range columns (dropped),
+    both index widths."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3000 + D)
+    idx = torch.rand(B, D, device=DEV, generator=g).argsort(1)[:, :k].sort(1).values.to(torch.int32)
+    val = si.normal_matrix(B, k, DEV, 3001 + D, dtype=dtype)
+    clean = idx.clone()
+    bad = [(5, 0, D), (7, k - 1, 65535 if idx16 else -1), (B - 1, k // 2, D + 9)]
+    for r, c, v in bad:
+        idx[r, c] = v
+    buf = torch.full((B, D + pad), 3.0, device=DEV).to(dtype)
+    out = buf[:, :D]
+    if idx16:
+        dct.dct_rowtopk_scatter_idx16(idx.to(torch.int16), val, out)
+    else:
+        dct.dct_rowtopk_scatter(idx, val, out)
+    want = oracle.rowscatter(clean.cpu().numpy(), host(val), D)
+    for r, c, _ in bad:                       # the oracle takes valid lists only: a dropped pair leaves a zero
+        want[r, int(clean[r, c])] = 0
+    assert np.array_equal(bits(host(out.contiguous()).reshape(-1)), bits(want.reshape(-1)))
+    if pad:
+        assert torch.all(buf[:, D:] == 3.0)
+
+
 def test_rowtopk_scatter_c5_block(dct):
     x, dy, k = si.config_c5(DEV, b=2048)
     B, D = x.shape
