@@ -77,7 +77,7 @@ template <typename StartOf>
 __device__ uint32_t owner_segment(uint32_t n_seg, uint32_t item, StartOf start_of) {
   bool le = false;
   uint32_t cnt = 0;
-  for (uint32_t base = 0; base < n_seg; base += kBtThreads) {  // uniform trip count
+  for (uint32_t base = 0; base < n_seg; base += blockDim.x) {  // uniform trip count
     const uint32_t s = base + threadIdx.x;
     le = s < n_seg && start_of(s) <= item;
     cnt += __syncthreads_count(le);
@@ -86,13 +86,16 @@ __device__ uint32_t owner_segment(uint32_t n_seg, uint32_t item, StartOf start_o
 }
 
 // ------------------------------------------------------------------ select
+// (1024 threads per unit of 16384 elements: a unit's workgroup is often alone on its CU, and with four
+// wavefronts nothing hid the latency of its loads and of the LDS updates: 23 us per pass against 11.)
+constexpr int kBtPassThreads = 1024;
 template <int DT>
-__global__ __launch_bounds__(kBtThreads) void bt_select_pass_kernel(const typename Elem<DT>::word_t* __restrict__ g,
+__global__ __launch_bounds__(kBtPassThreads) void bt_select_pass_kernel(const typename Elem<DT>::word_t* __restrict__ g,
                                                                     const BtSeg* __restrict__ segs, uint32_t n_seg,
                                                                     SelState* states, uint32_t* hist, int pass) {
   using E = Elem<DT>;
   __shared__ uint32_t h[kSelBins];
-  __shared__ uint32_t s_tmp[kSelWaves + 4];
+  __shared__ uint32_t s_tmp[kBtPassThreads / kWave + 4];
   const uint32_t seg = owner_segment(n_seg, blockIdx.x, [&](uint32_t s) { return segs[s].unit_start; });
   const BtSeg sg = segs[seg];
   const uint32_t unit = blockIdx.x - sg.unit_start;
@@ -108,8 +111,9 @@ __global__ __launch_bounds__(kBtThreads) void bt_select_pass_kernel(const typena
     st.width = min(kDigitBits, st.rem_bits);
     st.last_count = sg.n;
   } else {
-    st = advance_state(states[static_cast<size_t>(pass - 1) * n_seg + seg],
-                       hist + (static_cast<size_t>(pass - 1) * n_seg + seg) * kSelBins, s_tmp);
+    const uint32_t* prev_hist = hist + (static_cast<size_t>(pass - 1) * n_seg + seg) * kSelBins;
+    st = advance_state_with<kBtPassThreads>(states[static_cast<size_t>(pass - 1) * n_seg + seg],
+                                            [&](uint32_t b) { return prev_hist[b]; }, s_tmp);
   }
   if (unit == 0 && threadIdx.x == 0) states[static_cast<size_t>(pass) * n_seg + seg] = st;
   if (st.width == 0) return;  // uniform: every digit is fixed already
@@ -118,18 +122,18 @@ __global__ __launch_bounds__(kBtThreads) void bt_select_pass_kernel(const typena
   const uint32_t dmask = (1u << st.width) - 1u;
   const uint32_t fixed_mask = E::kKeyMask & ~((st.rem_bits >= 32u ? 0u : (1u << st.rem_bits)) - 1u);
   const uint32_t prefix = st.prefix;
-  for (int i = threadIdx.x; i < kSelBins; i += kBtThreads) h[i] = 0;
+  for (int i = threadIdx.x; i < kSelBins; i += kBtPassThreads) h[i] = 0;
   __syncthreads();
   const typename E::word_t* src = g + sg.offset;
   const uint32_t lo = unit * kBtUnit;
   const uint32_t hi = min(lo + kBtUnit, sg.n);  // lo < n by construction of the grid
   constexpr int kUnroll = 8;
-  for (uint32_t base = lo; base < hi; base += kBtThreads * kUnroll) {
+  for (uint32_t base = lo; base < hi; base += kBtPassThreads * kUnroll) {
     uint32_t key[kUnroll];
     bool in[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const uint32_t i = base + u * kBtThreads + threadIdx.x;
+      const uint32_t i = base + u * kBtPassThreads + threadIdx.x;
       in[u] = i < hi;
       key[u] = in[u] ? (static_cast<uint32_t>(src[i]) & E::kKeyMask) : 0u;
     }
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(kBtThreads) void bt_select_pass_kernel(const typena
   }
   __syncthreads();
   uint32_t* gh = hist + (static_cast<size_t>(pass) * n_seg + seg) * kSelBins;
-  for (int i = threadIdx.x; i < kSelBins; i += kBtThreads) {
+  for (int i = threadIdx.x; i < kSelBins; i += kBtPassThreads) {
     const uint32_t c = h[i];
     if (c) atomicAdd(&gh[i], c);
   }
@@ -372,10 +376,10 @@ extern "C" int dct_select_threshold_batched(const void* g, int dt, const dct_seg
   bt_upload(segs, d_segs, d_hist, static_cast<uint32_t>(static_cast<size_t>(n_pass) * n_seg * kSelBins), s);
   for (int p = 0; p < n_pass; ++p) {
     if (dt == DCT_F32) {
-      hipLaunchKernelGGL((bt_select_pass_kernel<DCT_F32>), dim3(static_cast<uint32_t>(units)), dim3(kBtThreads), 0, s,
+      hipLaunchKernelGGL((bt_select_pass_kernel<DCT_F32>), dim3(static_cast<uint32_t>(units)), dim3(kBtPassThreads), 0, s,
                          static_cast<const uint32_t*>(g), d_segs, n_seg, d_states, d_hist, p);
     } else {
-      hipLaunchKernelGGL((bt_select_pass_kernel<DCT_BF16>), dim3(static_cast<uint32_t>(units)), dim3(kBtThreads), 0,
+      hipLaunchKernelGGL((bt_select_pass_kernel<DCT_BF16>), dim3(static_cast<uint32_t>(units)), dim3(kBtPassThreads), 0,
                          s, static_cast<const uint16_t*>(g), d_segs, n_seg, d_states, d_hist, p);
     }
   }
