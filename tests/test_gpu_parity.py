@@ -214,6 +214,26 @@ def test_dp_sampled_select_and_fallback(dct, case):
     assert thr == oracle.select_threshold(host(g), k, method="sort")
 
 
+@pytest.mark.parametrize("case", ["gauss", "all_equal", "few_levels", "mostly_zero", "misaligned"])
+def test_dp_sampled_select_long_vectors(dct, case):
+    """The same from 2^26 elements on, where the partition pass takes 8 KiB pieces: candidates, candidate overflow
+    (the passes then run over the keys of the vector inside the bounds) and a misaligned base."""
+    n = (1 << 26) + 12345
+    g = si.gaussian_gradient(n, DEV, 4343)
+    k = n // 200
+    if case == "all_equal":
+        g = torch.full((n,), 0.375, device=DEV)
+    elif case == "few_levels":
+        g = (torch.randint(0, 5, (n,), device=DEV, generator=torch.Generator(device=DEV).manual_seed(8)).float() - 2.0)
+        k = n // 3
+    elif case == "mostly_zero":
+        g[torch.rand(n, device=DEV, generator=torch.Generator(device=DEV).manual_seed(9)) < 0.9] = 0.0
+        k = n // 5       # beyond the non-zeros: tau = 0
+    elif case == "misaligned":
+        g = g[1:]
+    check_dp(dct, g, k, select_method="nth")
+
+
 # ------------------------------------------------------------------ DP: c3 (select once, reuse on fresh draws)
 @pytest.mark.parametrize("chunk", range(4))
 def test_dp_c3_reuse(dct, chunk):
@@ -326,10 +346,12 @@ def test_mp_bf16_on_chip_kernel_hard_rows(dct, D):
 
 @pytest.mark.parametrize("dtype,B,D,k", [
     (torch.float32, 16390, 256, 12), (torch.float32, 16384, 512, 25), (torch.float32, 20000, 200, 10),
-    (torch.bfloat16, 16400, 1024, 200), (torch.bfloat16, 16385, 2048, 102), (torch.float32, 16401, 1024, 51)])
+    (torch.bfloat16, 16400, 1024, 200), (torch.bfloat16, 16385, 2048, 102), (torch.float32, 16401, 1024, 51),
+    # 8 KiB rows on both sides of the batch size from which the large workgroups are used
+    (torch.bfloat16, 16383, 4096, 204), (torch.bfloat16, 16385, 4096, 204), (torch.float32, 16390, 2048, 102)])
 def test_mp_many_rows_of_up_to_4_kib(dct, dtype, B, D, k):
     """From 16 k rows on the one-row-per-wavefront kernel runs as one workgroup of 16 wavefronts per CU that take
-    their rows from a counter (rows of up to 2 KiB; 4 KiB rows keep the small workgroups)."""
+    their rows from a counter (rows of up to 2 KiB and of 8 KiB; 4 KiB rows keep the small workgroups)."""
     x = si.relu_activations(B, D, DEV, 2800 + D, dtype=dtype)
     x[3] = 0.5
     x[B - 2] = 0.0
