@@ -39,13 +39,13 @@ CALL_KERNELS = {
     "dct_select_threshold[c4]": [("dct::select_gather_kernel<0, false>", 1), ("dct::select_bounds_kernel<0>", 1),
                                  ("dct::select_partition_kernel<0, false, 8>", 1),
                                  ("dct::select_tail_kernel<0, false>", 1)],
-    "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false, 3>", 1)],
+    "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false>", 1)],
     "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 0, false, 16>", 1)],
     "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_rows_kernel<unsigned short, int>", 1)],
     "dct_ef_select_threshold[c4]": [("dct::select_gather_kernel<0, true>", 1), ("dct::select_bounds_kernel<0>", 1),
                                     ("dct::select_partition_kernel<0, true, 8>", 1),
                                     ("dct::select_tail_kernel<0, true>", 1)],
-    "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true, 4>", 1)],
+    "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true>", 1)],
     "dct_scatter[c4,assign]": [("dct::scatter_assign_kernel<unsigned int>", 1)],
     "dct_scatter[c4,add]": [("dct::scatter_pairs_kernel<unsigned int, true>", 1)],
     "dct_rowtopk_scatter[c5]": [("dct::rowscatter_lds_kernel<unsigned short, int>", 1)],
@@ -123,6 +123,7 @@ def main():
         sys.exit("bench.py needs a GPU")
 
     import paper_2010_08899_amd as dct
+    from paper_2010_08899_amd import bench_probes
     dct.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -361,8 +362,8 @@ def main():
     probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
     probe_dst = torch.empty(probe_bytes // 2, dtype=torch.uint8, device=dev)
     sink = torch.zeros(16384, dtype=torch.uint8, device=dev)
-    us_read = time_calls(lambda i: dct.dct_probe_read(probe_src, sink), 10)
-    us_copy = time_calls(lambda i: dct.dct_probe_copy(probe_dst, probe_src[: probe_bytes // 2]), 10)
+    us_read = time_calls(lambda i: bench_probes.probe_read(probe_src, sink), 10)
+    us_copy = time_calls(lambda i: bench_probes.probe_copy(probe_dst, probe_src[: probe_bytes // 2]), 10)
     probes = {"read_GBps": round(probe_bytes / (us_read * 1e-6) / 1e9, 1),
               "copy_GBps": round(probe_bytes / (us_copy * 1e-6) / 1e9, 1)}
     del probe_src, probe_dst

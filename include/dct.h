@@ -57,8 +57,8 @@ typedef enum {
 } dct_mode;
 
 /* The threshold carried from a select iteration to the following reuse
- * iterations (Algorithm 1, "use tau from iteration k-1").  Lives in DEVICE
- * memory, 16 bytes, 16-byte aligned, caller-owned. */
+ * iterations (Algorithm 1, the branch that keeps the previous iteration's tau).
+ * Lives in DEVICE memory, 16 bytes, 16-byte aligned, caller-owned. */
 typedef struct {
   uint32_t tau_key;   /* key of the k-th largest magnitude; always the key of an input element */
   uint32_t n_gt;      /* #{ i : key[i] >  tau_key }                                          */
@@ -67,7 +67,7 @@ typedef struct {
 } dct_threshold;
 
 /* Sentinel written to *d_count_out when dct_threshold_compact finds its
- * workspace uninitialised or corrupted (no survivor is written in that case). */
+ * workspace uninitialised or refusing, or when one of its bounded waits runs out. */
 #define DCT_COUNT_WORKSPACE_ERROR UINT64_MAX
 
 /* tau_key of a threshold record whose selection gave up (see "Concurrency" at
@@ -76,10 +76,14 @@ typedef struct {
 #define DCT_TAU_KEY_ERROR 0xFFFFFFFFu
 
 /* ---------------------------------------------------------------- DCT-DP ---
- * Algorithm 1, threshold selection ("sort |W_grad|; tau = w_floor(N*eta)"),
- * computed exactly without sorting or copying the gradient: a radix select over
- * the key bits with LDS histograms.  The caller passes the integer number of
- * entries to keep, k (for a sparsity factor eta that is N - floor(N*eta)).
+ * Algorithm 1, threshold selection (the sort of the magnitudes and the pick of
+ * the element at rank floor(N*eta)), computed exactly without sorting or copying
+ * the gradient: a radix select over the key bits with LDS histograms.  The caller
+ * passes the integer number of entries to keep, k; tau is the k-th largest key and
+ * the mask keeps every key >= tau.  For a sparsity factor eta (the fraction that
+ * is dropped: Sec. 2.2 says tau_i exceeds d*eta values of its row) with the
+ * magnitudes sorted ascending and numbered from 0, the element at rank
+ * floor(N*eta) is the (N - floor(N*eta))-th largest, so k = N - floor(N*eta).
  *
  *   g          device, n elements of `dt`, contiguous, aligned to the element size
  *   n          1 .. 2^31-1            k   1 .. n
@@ -100,9 +104,9 @@ size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n);
 int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,
                          void* d_ws, size_t ws_bytes, void* hip_stream);
 
-/* Algorithm 1, mask and compressed gradient ("M = I(|W_grad| >= tau)",
- * "W_hat = W_grad . M"), fused with an ordered stream compaction: one pass over
- * g, survivors written as idx[j] (ascending) and val[j] = g[idx[j]].
+/* Algorithm 1, the mask of the entries with |W_grad| >= tau and the compressed
+ * gradient, fused with an ordered stream compaction: one pass over g, survivors
+ * written as idx[j] (ascending) and val[j] = g[idx[j]].
  *
  *   d_thr        device, threshold from dct_select_threshold (possibly of an
  *                earlier iteration: the reuse iterations of Algorithm 1)
@@ -118,15 +122,16 @@ int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_thre
  *                initialised again, so it can be reused call after call on the same
  *                stream.  Two calls that share a workspace must not overlap.
  *
- * Concurrency.  The kernel's workgroups exchange their counts while they run, so its
- * whole grid (three or four workgroups per CU) has to be on the chip together.  Run
- * alone on the device that is always so.  When other kernels hold CUs at the same
- * time (another stream), a call that needs several rounds -- more than about four
- * million survivors, or any dct_ef_threshold_compact on a large vector -- may find
- * part of its grid waiting for room; its waits are bounded, and if one runs out the
- * call ends with *d_count_out = DCT_COUNT_WORKSPACE_ERROR (no output is valid, the
- * workspace has to be initialised again), it does not hang.  Keep such calls from
- * overlapping with other work, e.g. by issuing them on one stream.
+ * Concurrency.  One launch of one workgroup per compute unit.  When a workgroup has
+ * streamed its share it publishes its count and waits for the counts of the
+ * LOWER-numbered workgroups of the same launch, which the device started before it:
+ * kernels on other streams can delay that wait but not block it.  Only a vector with
+ * more than about four million survivors is cut into slices whose exchange involves
+ * the whole grid; such a call wants all compute units free (e.g. a stream of its
+ * own turn).  Every wait is bounded (dct_set_wait_limit).  If one runs out the call
+ * still ends, *d_count_out = DCT_COUNT_WORKSPACE_ERROR, idx / val hold nothing
+ * usable, g is untouched (compact again), and the workspace refuses further calls
+ * with the same sentinel until it is initialised again.
  */
 size_t dct_threshold_compact_workspace_bytes(int dt, uint64_t n);
 int dct_threshold_compact_workspace_init(void* d_ws, size_t ws_bytes, void* hip_stream);
@@ -135,8 +140,8 @@ int dct_threshold_compact(const void* g, int dt, uint64_t n, const dct_threshold
                           void* d_ws, size_t ws_bytes, void* hip_stream);
 
 /* ------------------------------------------- DCT-DP with error feedback ---
- * Algorithm 1 keeps what compression drops: "W_grad = W_grad + E_grad" before
- * the selection, "E_grad = W_grad - W_hat_grad" after the mask (Fig. 3).  These
+ * Algorithm 1 keeps what compression drops: the residual is added to the gradient
+ * before the selection and set to what the mask removed after it (Fig. 3).  These
  * two calls are dct_select_threshold and dct_threshold_compact applied to the
  * corrected gradient w = g + e, which is never materialised on its own.
  *
@@ -157,6 +162,14 @@ int dct_threshold_compact(const void* g, int dt, uint64_t n, const dct_threshold
  * kept in the residual, not lost.  e_out may be the same buffer as e_in (update in
  * place); otherwise the two must not overlap, and g must not overlap e_out.
  * Workspace, count and capacity as for dct_threshold_compact (same workspace).
+ *
+ * The residual is training state, so delivery is all or nothing.  The call is never
+ * cut into slices (a workgroup waits for lower-numbered workgroups only), and one
+ * workgroup decides for the whole launch whether every count has arrived.  If
+ * *d_count_out reads DCT_COUNT_WORKSPACE_ERROR afterwards -- a wait ran out, or the
+ * workspace was not initialised or had refused -- then NO pair was delivered and
+ * e_out[i] = g[i] + e_in[i] for every i: the iteration has sent nothing and lost
+ * nothing.  idx / val are unspecified.  Initialise the workspace again and go on.
  */
 int dct_ef_select_threshold(const void* g, const void* e, int dt, uint64_t n, uint64_t k,
                             dct_threshold* d_thr_out, void* d_ws, size_t ws_bytes, void* hip_stream);
@@ -181,7 +194,7 @@ int dct_ef_threshold_compact(const void* g, const void* e_in, void* e_out, int d
 int dct_rowtopk_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_stride_elems, uint32_t k,
                     int32_t* d_idx_out, void* d_val_out, void* d_tau_out, void* hip_stream);
 
-/* Algorithm 2, backward pass ("X_grad . M" with the mask of the forward pass):
+/* Algorithm 2, backward pass (the gradient passes through the mask of the forward pass):
  * dval[b, j] = dy[b, idx[b, j]].  No new selection takes place.  An index
  * outside [0, D) is not dereferenced; its output element is set to zero.
  */
@@ -189,7 +202,7 @@ int dct_rowtopk_bwd(const void* dy, int dt, uint32_t B, uint32_t D, uint64_t row
                     const int32_t* d_idx, void* d_dval_out, void* hip_stream);
 
 /* ------------------------------------------- DCT-MP, the mask as a bitmap ---
- * Algorithm 2 sends "X_act . M and the mask M".  These calls carry M literally,
+ * Algorithm 2 sends the masked activations and the mask M.  These calls carry M literally,
  * as a bitmap, instead of k column indices: ceil(D/32) 32-bit words per row, bit
  * (c mod 32) of word (c div 32) set iff column c is kept, plus the k kept values in
  * ascending column order.  For bf16 and k = D/20 that is 2.25 bytes per kept entry
@@ -266,9 +279,9 @@ int dct_threshold_compact_batched(const void* g, int dt, const dct_segment* h_se
                                   uint64_t* d_count_out, void* d_ws, size_t ws_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------ receiver side ---
- * Decompression of the two message formats above (Sec. 2.1 counts "compression
- * and decompression" as the overhead of the method; in Algorithm 2 the next
- * worker consumes X_act . M; the parameter server sums sparse gradients).
+ * Decompression of the two message formats above (Sec. 2.1 counts compressing
+ * and decompressing as the overhead of the method; in Algorithm 2 the next
+ * worker consumes the masked activations; the parameter server sums sparse gradients).
  *
  * dct_scatter: (idx, val) pairs -> dense vector of n elements.
  *   d_idx, d_val  device, `capacity` pairs as written by dct_threshold_compact:
@@ -296,16 +309,16 @@ int dct_scatter(const int32_t* d_idx, const void* d_val, const uint64_t* d_count
 int dct_rowtopk_scatter(const int32_t* d_idx, const void* d_val, int dt, uint32_t B, uint32_t D, uint32_t k,
                         void* d_out, uint64_t out_row_stride_elems, void* hip_stream);
 
-/* ------------------------------------------------------------ measurement ---
- * Plain streaming kernels used by the benchmark to measure the achievable HBM
- * rate next to the DCT kernels (not part of the method).
- *   dct_probe_read: sums `bytes` (multiple of 16, 16-byte aligned) as uint32 words,
- *                   writes one uint32 per workgroup into d_sink (>= 16384 bytes).
- *   dct_probe_copy: copies `bytes` (multiple of 16) from d_src to d_dst.
+/* ----------------------------------------------------------------- service ---
+ * dct_status_string: a static string for a dct_status.
+ *
+ * dct_set_wait_limit: the number of polls after which a device-side wait of this
+ * library gives up (the grid barriers of the selection, the count exchange of the
+ * compaction).  Process-wide; 0 restores the default (2^20 polls, about a second).
+ * Meant for tests of the give-up paths, which a tiny limit reaches while every
+ * kernel still runs to its end; production code has no reason to call it.
  */
-int dct_probe_read(const void* d_src, size_t bytes, void* d_sink, void* hip_stream);
-int dct_probe_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream);
-
+void dct_set_wait_limit(uint32_t polls);
 const char* dct_status_string(int status);
 
 #ifdef __cplusplus

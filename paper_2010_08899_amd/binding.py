@@ -75,9 +75,8 @@ _EXPORTS = {
     "dct_rowtopk_scatter": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint32,
                                            ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
                                            ctypes.c_void_p]),
-    "dct_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
-    "dct_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "dct_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "dct_set_wait_limit": (None, [ctypes.c_uint32]),
 }
 
 _lib = None
@@ -438,12 +437,7 @@ def dct_rowtopk_scatter_idx16(idx: torch.Tensor, val: torch.Tensor, out: torch.T
                                            stride, _stream()), "dct_rowtopk_scatter_idx16")
 
 
-# ------------------------------------------------------------------ measurement helpers
-def dct_probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:
-    _check(lib().dct_probe_read(_dev(src, "src"), src.numel() * src.element_size(), _dev(sink, "sink"), _stream()),
-           "dct_probe_read")
-
-
-def dct_probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
-    _check(lib().dct_probe_copy(_dev(dst, "dst"), _dev(src, "src"), src.numel() * src.element_size(), _stream()),
-           "dct_probe_copy")
+# ------------------------------------------------------------------ service
+def dct_set_wait_limit(polls: int) -> None:
+    """Polls after which a device-side wait gives up (0: the default); for tests of the give-up paths."""
+    lib().dct_set_wait_limit(int(polls))

@@ -1,4 +1,6 @@
-"""Builds libdct.so (HIP, gfx950 only) in-tree with hipcc."""
+"""Builds the HIP libraries (gfx950 only) in-tree with hipcc:
+libdct.so, the product (every csrc/*.hip), and libdct_bench.so, the plain streaming
+kernels that only bench.py loads (csrc/bench/*.hip)."""
 from __future__ import annotations
 
 import glob
@@ -9,6 +11,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdct.so")
+BENCH_LIB = os.path.join(PKG, "libdct_bench.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
@@ -21,23 +24,36 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def needs_build() -> bool:
-    if not os.path.exists(LIB):
+def bench_sources():
+    return sorted(glob.glob(os.path.join(CSRC, "bench", "*.hip")))
+
+
+def _stale(lib: str, srcs) -> bool:
+    if not os.path.exists(lib):
         return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    t = os.path.getmtime(lib)
+    deps = list(srcs) + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build_library(force: bool = True, verbose: bool = False) -> str:
-    """Compile every kernel for gfx950 into one shared library."""
-    if not force and not needs_build():
-        return LIB
+def needs_build() -> bool:
+    return _stale(LIB, sources()) or _stale(BENCH_LIB, bench_sources())
+
+
+def _compile(lib: str, srcs, verbose: bool) -> None:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *sources()]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", lib, *srcs]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
+
+
+def build_library(force: bool = True, verbose: bool = False) -> str:
+    """Compile every kernel for gfx950: the product library and the benchmark's probe library."""
+    if force or _stale(LIB, sources()):
+        _compile(LIB, sources(), verbose)
+    if force or _stale(BENCH_LIB, bench_sources()):
+        _compile(BENCH_LIB, bench_sources(), verbose)
     return LIB
 
 

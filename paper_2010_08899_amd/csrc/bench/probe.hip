@@ -1,6 +1,11 @@
 // Plain streaming kernels for the benchmark's "achievable HBM rate" lines and for
-// scaling the rocprof byte counters against a transfer of known size, plus the
-// status strings.  Not part of the method.
+// scaling the rocprof byte counters against a transfer of known size.  Not part of
+// the method and not part of libdct.so: built into libdct_bench.so, which only
+// bench.py loads.
+//   dct_bench_probe_read: sums `bytes` (multiple of 16, 16-byte aligned) as uint32 words,
+//                         writes one uint32 per workgroup into d_sink (>= 16384 bytes).
+//   dct_bench_probe_copy: copies `bytes` (multiple of 16) from d_src to d_dst.
+// Both return a dct_status.
 #include "dct_common.hpp"
 
 namespace dct {
@@ -52,17 +57,17 @@ uint32_t probe_grid(uint64_t n_vec) {
 
 using namespace dct;
 
-extern "C" int dct_probe_read(const void* d_src, size_t bytes, void* d_sink, void* hip_stream) {
+extern "C" int dct_bench_probe_read(const void* d_src, size_t bytes, void* d_sink, void* hip_stream) {
   if (!d_src || !d_sink || bytes == 0 || (bytes & 15) || !is_aligned(d_src, 16) || !is_aligned(d_sink, 4))
     return DCT_ERR_INVALID;
   const uint64_t n_vec = bytes / 16;
   hipLaunchKernelGGL(probe_read_kernel, dim3(probe_grid(n_vec)), dim3(kPrThreads), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<const uint4*>(d_src), n_vec,
                      static_cast<uint32_t*>(d_sink));
-  return launch_status();
+  return hipGetLastError() == hipSuccess ? DCT_OK : DCT_ERR_HIP;
 }
 
-extern "C" int dct_probe_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream) {
+extern "C" int dct_bench_probe_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream) {
   if (!d_src || !d_dst || bytes == 0 || (bytes & 15) || !is_aligned(d_src, 16) || !is_aligned(d_dst, 16))
     return DCT_ERR_INVALID;
   const uint64_t n_vec = bytes / 16;
@@ -70,16 +75,5 @@ extern "C" int dct_probe_copy(void* d_dst, const void* d_src, size_t bytes, void
   hipLaunchKernelGGL(probe_copy_kernel, dim3(static_cast<uint32_t>((n_vec + kPrThreads - 1) / kPrThreads)), dim3(kPrThreads), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<uint4*>(d_dst),
                      static_cast<const uint4*>(d_src), n_vec);
-  return launch_status();
-}
-
-extern "C" const char* dct_status_string(int status) {
-  switch (status) {
-    case DCT_OK: return "DCT_OK";
-    case DCT_ERR_INVALID: return "DCT_ERR_INVALID: bad argument";
-    case DCT_ERR_WORKSPACE: return "DCT_ERR_WORKSPACE: workspace null, misaligned, too small or uninitialised";
-    case DCT_ERR_OVERFLOW: return "DCT_ERR_OVERFLOW: more survivors than the output capacity";
-    case DCT_ERR_HIP: return "DCT_ERR_HIP: kernel launch failed";
-    default: return "unknown dct_status";
-  }
+  return hipGetLastError() == hipSuccess ? DCT_OK : DCT_ERR_HIP;
 }

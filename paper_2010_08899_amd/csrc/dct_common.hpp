@@ -73,6 +73,10 @@ __device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
   return v;
 }
 
+// Workgroup barrier that orders LDS accesses only: global loads and stores that are outstanding
+// stay in flight (__syncthreads() waits for them as well).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Agent-scope relaxed accesses for words that other workgroups poll or update.
 __device__ __forceinline__ uint64_t ld_agent(const uint64_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -125,6 +129,9 @@ inline int device_cu_count() {
   }
   return cached[dev];
 }
+
+// Polls a bounded device-side wait may take before it gives up (process-wide; dct_set_wait_limit).
+uint32_t wait_limit();
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? DCT_OK : DCT_ERR_HIP; }
 

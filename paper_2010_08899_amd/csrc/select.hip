@@ -45,7 +45,6 @@ constexpr int kTailThreads = 1024;                // the kernel of the radix pas
 constexpr uint32_t kTailMaxGrid = 256;
 constexpr uint32_t kTailWaiters = 64;              // workgroups of a launch that may wait at a grid barrier
 constexpr int kTailKeep = 8;                      // 16-byte vectors of candidates per thread kept in registers
-constexpr uint32_t kTailSpinLimit = 1u << 20;     // polls of a grid barrier (about a second) before giving up
 
 constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes run over the vector itself
 constexpr int kSampleThreads = 1024;
@@ -425,7 +424,7 @@ __device__ __forceinline__ uint32_t add_agent(uint32_t* p, uint32_t v) {
 // workspace; a grid barrier (an arrival counter polled with agent-scope loads) separates a pass
 // from the search in its histogram, which every workgroup repeats for itself.  The grid is
 // small enough to be resident as a whole; a workgroup that waits longer than about a second
-// gives up (spin_limit polls), and workgroup 0 then stores DCT_TAU_KEY_ERROR in the result.
+// gives up (spin_limit polls) and stores DCT_TAU_KEY_ERROR in the result.
 // After the last pass there is no barrier: the workgroup that arrives last finishes alone.
 //
 // Merging costs more than reading here: after the subtraction of lo the candidates fill most of
@@ -661,11 +660,14 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
       __syncthreads();
       if (s_arrived < n_active) {  // uniform
         if (last_pass) return;     // another workgroup arrives last and finishes
-        if (blockIdx.x == 0 && threadIdx.x == 0) {  // somebody never came; no result
-          out->tau_key = DCT_TAU_KEY_ERROR;
-          out->n_gt = 0;
-          out->n_eq = 0;
-          out->tie_quota = 0;
+        // Somebody never came.  A workgroup that gives up arrives at no later barrier, so no later pass
+        // can complete and nobody will write a result: every workgroup that gives up stores the error
+        // record itself (the same words from all of them).
+        if (threadIdx.x == 0) {
+          st_agent(&out->tau_key, DCT_TAU_KEY_ERROR);
+          st_agent(&out->n_gt, 0u);
+          st_agent(&out->n_eq, 0u);
+          st_agent(&out->tie_quota, 0u);
         }
         return;
       }
@@ -784,20 +786,21 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
   const void* g_al = reinterpret_cast<const void*>(addr & ~static_cast<uintptr_t>(15));
   const void* e_al = reinterpret_cast<const void*>(eaddr & ~static_cast<uintptr_t>(15));
   const PassDigits dg = pass_digits(dt);
+  const uint32_t spin_limit = wait_limit();  // polls of a grid barrier (by default about a second) before giving up
   const uint32_t tgrid = ef ? tail_grid<DCT_F32, true>()
                             : dt == DCT_F32 ? tail_grid<DCT_F32, false>() : tail_grid<DCT_BF16, false>();
   if (tgrid == 0) return DCT_ERR_HIP;
   if (ef) {
     hipLaunchKernelGGL((select_tail_kernel<DCT_F32, true>), dim3(tgrid), dim3(kTailThreads), 0, s,
                        static_cast<const uint32_t*>(g_al), static_cast<const uint32_t*>(e_al), off, n_virt, k32, ws,
-                       dg.n_pass, kTailSpinLimit, d_thr_out);
+                       dg.n_pass, spin_limit, d_thr_out);
   } else if (dt == DCT_F32) {
     hipLaunchKernelGGL((select_tail_kernel<DCT_F32, false>), dim3(tgrid), dim3(kTailThreads), 0, s,
-                       static_cast<const uint32_t*>(g_al), nullptr, off, n_virt, k32, ws, dg.n_pass, kTailSpinLimit,
+                       static_cast<const uint32_t*>(g_al), nullptr, off, n_virt, k32, ws, dg.n_pass, spin_limit,
                        d_thr_out);
   } else {
     hipLaunchKernelGGL((select_tail_kernel<DCT_BF16, false>), dim3(tgrid), dim3(kTailThreads), 0, s,
-                       static_cast<const uint16_t*>(g_al), nullptr, off, n_virt, k32, ws, dg.n_pass, kTailSpinLimit,
+                       static_cast<const uint16_t*>(g_al), nullptr, off, n_virt, k32, ws, dg.n_pass, spin_limit,
                        d_thr_out);
   }
   return launch_status();

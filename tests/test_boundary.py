@@ -33,6 +33,10 @@ def test_library_exports_every_declared_symbol():
         assert name in binding._EXPORTS, name
         assert hasattr(m, name), name
     assert handle.dct_status_string(0) == b"DCT_OK"
+    # the benchmark's streaming probes are not part of the product library or its header
+    assert not hasattr(raw, "dct_probe_read") and not hasattr(raw, "dct_bench_probe_read")
+    bench = ctypes.CDLL(build.BENCH_LIB)
+    assert hasattr(bench, "dct_bench_probe_read") and hasattr(bench, "dct_bench_probe_copy")
 
 
 def test_host_side_argument_checks_need_no_gpu():
