@@ -144,57 +144,73 @@ struct DescLoad {
   }
 };
 
-// Sum of the descriptors of workgroups 0..w-1 of this round plus the running total of the previous
-// round, once all of them are published.  One wavefront; one round trip when nobody is late.
-__device__ uint64_t prefix_of(const uint64_t* round_wg, uint32_t w, const uint64_t* prev_total, uint32_t limit,
-                              const uint32_t* error_flag, bool& failed) {
-  uint32_t spins = 0;
-  for (;;) {
-    DescLoad dl;
-    dl.load(round_wg, w);
-    const uint64_t pt = prev_total ? ld_agent(prev_total) : kStValid;
-    if (dl.all_published() && (pt >> 62) != 0) return dl.sum() + (pt & kPayload);
-    if (!keep_waiting(spins, limit, error_flag)) {
-      failed = true;
-      return 0;
-    }
+// A wait has used up its budget: raise the workspace's failure flag, and return only when that has been
+// performed.  Whoever waits afterwards polls once more, so that the order is fixed: either the last poll
+// already finds everything published (then this workgroup's outputs are right, and the call is merely reported
+// as failed), or the workgroup that writes the count, which needs the same descriptors, finds the flag set.
+__device__ __forceinline__ void raise_failure(uint32_t* error_flag) {
+  if (lane_id() == 0) {
+    const uint32_t old = __hip_atomic_fetch_or(error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::"v"(old) : "memory");
   }
 }
 
-// Error feedback, workgroup 0: all `grid` descriptors published?  (Bounded.)
-__device__ bool all_workgroups_published(const uint64_t* round_wg, uint32_t grid, uint32_t limit,
-                                         const uint32_t* error_flag) {
+// Sum of the descriptors of workgroups 0..w-1 of this round plus the running total of the previous
+// round, once all of them are published.  One wavefront; one round trip when nobody is late.
+__device__ uint64_t prefix_of(const uint64_t* round_wg, uint32_t w, const uint64_t* prev_total, uint32_t limit,
+                              uint32_t* error_flag, bool& failed) {
   uint32_t spins = 0;
-  for (;;) {
+  for (bool last = false;; last = true) {
+    do {
+      DescLoad dl;
+      dl.load(round_wg, w);
+      const uint64_t pt = prev_total ? ld_agent(prev_total) : kStValid;
+      if (dl.all_published() && (pt >> 62) != 0) return dl.sum() + (pt & kPayload);
+    } while (!last && keep_waiting(spins, limit, error_flag));
+    if (last) break;
+    raise_failure(error_flag);
+  }
+  failed = true;
+  return 0;
+}
+
+// Error feedback, workgroup 0: all `grid` descriptors published?  (Bounded; a wait that runs out raises the
+// failure flag, so that workgroups that start later deliver nothing either.)
+__device__ bool all_workgroups_published(const uint64_t* round_wg, uint32_t grid, uint32_t limit, uint32_t* error_flag) {
+  uint32_t spins = 0;
+  do {
     DescLoad dl;
     dl.load(round_wg, grid);
     if (dl.all_published()) return true;
-    if (!keep_waiting(spins, limit, error_flag)) return false;
-  }
+  } while (keep_waiting(spins, limit, error_flag));
+  raise_failure(error_flag);
+  return false;
 }
 
 // Error feedback, the other workgroups: workgroup 0's decision and, on commit, the exclusive prefix.
 __device__ uint64_t decided_prefix(const uint64_t* round_wg, uint32_t w, const uint64_t* decision, uint32_t limit,
-                                   const uint32_t* error_flag, bool& commit, bool& failed) {
+                                   uint32_t* error_flag, bool& commit, bool& failed) {
   uint32_t spins = 0;
-  for (;;) {
-    DescLoad dl;
-    dl.load(round_wg, w);
-    const uint64_t dec = ld_agent(decision);
-    if (dec == kAbort) {
-      commit = false;
-      return 0;
-    }
-    if (dec == kCommit && dl.all_published()) {  // (after a commit every descriptor is published)
-      commit = true;
-      return dl.sum();
-    }
-    if (!keep_waiting(spins, limit, error_flag)) {  // workgroup 0 never decided
-      commit = false;
-      failed = true;
-      return 0;
-    }
+  for (bool last = false;; last = true) {
+    do {
+      DescLoad dl;
+      dl.load(round_wg, w);
+      const uint64_t dec = ld_agent(decision);
+      if (dec == kAbort) {
+        commit = false;
+        return 0;
+      }
+      if (dec == kCommit && dl.all_published()) {  // (after a commit every descriptor is published)
+        commit = true;
+        return dl.sum();
+      }
+    } while (!last && keep_waiting(spins, limit, error_flag));
+    if (last) break;
+    raise_failure(error_flag);  // workgroup 0 has not decided within four times its own budget
   }
+  commit = false;
+  failed = true;
+  return 0;
 }
 
 // Work description shared by all workgroups (computed on the host).
@@ -586,7 +602,7 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
       const uint32_t magic = s_hdr[0], poisoned = s_hdr[2], used0 = s_hdr[3], used1 = s_hdr[4];
       epoch = s_hdr[1];
       if (magic != kCtMagic || poisoned != 0) {  // uniform over the workgroup
-        if (wg == 0 && threadIdx.x == 0) *count_out = DCT_COUNT_WORKSPACE_ERROR;
+        if (chunk == geo.grid - 1 && threadIdx.x == 0) *count_out = DCT_COUNT_WORKSPACE_ERROR;  // (the count's one writer)
         return;
       }
       DescSet* sets = reinterpret_cast<DescSet*>(reinterpret_cast<char*>(hdr) + kCtHeaderBytes);
@@ -652,7 +668,6 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
         // all or nothing: workgroup 0 decides for the whole grid
         if (wg == 0) {
           commit = all_workgroups_published(round_wg, geo.grid, spin_limit, &hdr->error);
-          failed = !commit;
           if (lane == 0) st_agent(&mine_set->decision, commit ? kCommit : kAbort);
           excl = 0;
         } else {
@@ -665,19 +680,18 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
       }
       excl &= kPayload;
       if (lane == 0) {
-        if (failed) {  // a wait ran out: report it (the workspace has to be initialised again)
-          atomicOr(&hdr->error, 1u);
-          *count_out = DCT_COUNT_WORKSPACE_ERROR;
-        }
-        if (!EF && chunk == geo.grid - 1) st_agent(&mine_set->round_total[round], kStValid | ((excl + mine) & kPayload));
+        if (!EF && chunk == geo.grid - 1 && !failed)
+          st_agent(&mine_set->round_total[round], kStValid | ((excl + mine) & kPayload));
         s_excl = excl;
-        s_commit = commit ? 1u : 0u;
-        if (round == rounds - 1 && chunk == geo.grid - 1 && commit) {  // every other workgroup has read the epoch and published: finish the call
+        s_commit = commit && !failed ? 1u : 0u;
+        // The count has ONE writer, the workgroup of the last chunk: after its last round (every other
+        // workgroup has read the epoch and published by then), or when it gives up.
+        if (chunk == geo.grid - 1 && (round == rounds - 1 || failed || !commit)) {
           const uint64_t total = (excl + mine) & kPayload;
           uint64_t c = cnt_a(total);
           if (EXACT) c += min(cnt_e(total), quota);
           const uint32_t err = __builtin_amdgcn_readfirstlane(ld_agent(&hdr->error));
-          if (failed || err != 0) {
+          if (failed || !commit || err != 0) {  // a wait ran out somewhere: the workspace refuses from now on
             *count_out = DCT_COUNT_WORKSPACE_ERROR;
           } else {
             *count_out = c;
@@ -690,9 +704,9 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     __syncthreads();
 
     // ---- 4: final slots
-    if constexpr (EF) {
-      if (s_commit == 0) return;  // uniform over the grid: every pair stays in the residual
-    }
+    // A wait ran out, or (error feedback) workgroup 0 decided that nobody delivers: every pair stays where it
+    // is -- with error feedback in the residual.  (Uniform over the workgroup.)
+    if (s_commit == 0) return;
     a_excl = cnt_a(s_excl);
     e_excl = cnt_e(s_excl);
     bool overflow = false;

@@ -1279,6 +1279,134 @@ def test_dp_selections_on_four_streams_at_once(dct):
             thr[i].zero_()
 
 
+def _raw_count(cnt):
+    return int(cnt.cpu().item()) & ((1 << 64) - 1)
+
+
+COUNT_ERROR = (1 << 64) - 1
+
+
+def test_dp_ef_compaction_next_to_long_kernels_on_another_stream(dct):
+    """Algorithm 1 with error feedback while unrelated kernels hold compute units on another stream (a trainer
+    that overlaps compression with its backward pass).  The residual is training state: the call must give the
+    oracle's result, or -- had one of its bounded waits run out -- report so through the count with NO pair
+    delivered and the corrected gradient g + e left in the residual.  Sparse and dense survivors (the dense
+    case streams its chunks a second time), residual updated in place, five rounds each."""
+    n = 6_000_011
+    side = torch.cuda.Stream()
+    a = torch.randn(4096, 4096, device=DEV)
+    b = torch.randn(4096, 4096, device=DEV)
+    for keep in (0.01, 0.30):
+        k = int(n * keep)
+        ef = EF(dct, n, capacity=n)
+        for rnd in range(5):
+            g = si.gaussian_gradient(n, DEV, 4100 + rnd)
+            e = si.residual_vector(n, DEV, 4200 + rnd)
+            gh, eh = host(g), host(e)
+            thr = ef.select(g, e, k)
+            exp = oracle.ef_select_threshold(gh, eh, k)
+            assert thr == exp
+            eidx, eval_, ecnt, e_exp = oracle.ef_threshold_compact(gh, eh, exp, oracle.GE_TAU)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):       # a few hundred microseconds of matrix products per launch
+                for _ in range(6):
+                    a = torch.tanh(a @ b)
+            ef.idx.fill_(-7)
+            dct.dct_ef_threshold_compact(g, e, e, ef.thr, dct.DCT_GE_TAU, ef.idx, ef.val, ef.count, ef.ws)
+            torch.cuda.synchronize()
+            c = _raw_count(ef.count)
+            if c == COUNT_ERROR:                # the documented state: nothing sent, nothing lost
+                assert np.array_equal(bits(host(e)), bits(oracle.ef_accumulate(gh, eh)))
+                pytest.fail("a bounded wait of dct_ef_threshold_compact ran out next to ordinary kernels")
+            assert c == ecnt
+            assert np.array_equal(host(ef.idx[:c]), eidx) and np.array_equal(bits(host(ef.val[:c])), bits(eval_))
+            assert np.array_equal(bits(host(e)), bits(e_exp))
+
+
+def test_dp_ef_give_up_delivers_nothing_and_keeps_the_corrected_gradient(dct):
+    """The give-up path of the error-feedback compaction, reached from the host with a wait limit of one poll
+    (every kernel still runs to its end).  Whatever the outcome, the documented state must hold: either the
+    oracle's result, or count = DCT_COUNT_WORKSPACE_ERROR with e_out = g + e_in bit for bit (nothing delivered);
+    the workspace then refuses further calls the same way, without losing anything, until it is initialised
+    again."""
+    n, k = 2_000_003, 20_000
+    g = si.gaussian_gradient(n, DEV, 4300)
+    e0 = si.residual_vector(n, DEV, 4301)
+    gh, eh = host(g), host(e0)
+    w = oracle.ef_accumulate(gh, eh)
+    ef = EF(dct, n, capacity=n)
+    exp = oracle.ef_select_threshold(gh, eh, k)
+    assert ef.select(g, e0, k) == exp
+    eidx, eval_, ecnt, e_exp = oracle.ef_threshold_compact(gh, eh, exp, oracle.EXACT_K)
+    gave_up = 0
+    try:
+        dct.dct_set_wait_limit(1)
+        for attempt in range(4):
+            e = e0.clone()
+            dct.dct_ef_threshold_compact(g, e, e, ef.thr, dct.DCT_EXACT_K, ef.idx, ef.val, ef.count, ef.ws)
+            torch.cuda.synchronize()
+            c = _raw_count(ef.count)
+            if c != COUNT_ERROR:
+                assert c == ecnt and np.array_equal(host(ef.idx[:c]), eidx)
+                assert np.array_equal(bits(host(e)), bits(e_exp))
+                continue
+            gave_up += 1
+            assert np.array_equal(bits(host(e)), bits(w))
+            # the workspace now refuses: again nothing delivered, nothing lost (not in place this time)
+            e_out = torch.full((n,), 5.0, device=DEV)
+            dct.dct_ef_threshold_compact(g, e0, e_out, ef.thr, dct.DCT_EXACT_K, ef.idx, ef.val, ef.count, ef.ws)
+            torch.cuda.synchronize()
+            assert _raw_count(ef.count) == COUNT_ERROR
+            assert np.array_equal(bits(host(e_out)), bits(w))
+            cnt2 = torch.zeros(1, dtype=torch.int64, device=DEV)
+            dct.dct_threshold_compact(g, ef.thr, dct.DCT_GE_TAU, ef.idx, ef.val, cnt2, ef.ws)
+            assert _raw_count(cnt2) == COUNT_ERROR
+            dct.dct_threshold_compact_workspace_init(ef.ws)
+    finally:
+        dct.dct_set_wait_limit(0)
+    # back to the default limit and an initialised workspace: the call works
+    e = e0.clone()
+    idx, val, cnt, _ = ef.compact(g, e, e, dct.DCT_EXACT_K)
+    assert cnt == ecnt and np.array_equal(idx, eidx) and np.array_equal(bits(val), bits(eval_))
+    assert np.array_equal(bits(host(e)), bits(e_exp))
+    print(f"gave up in {gave_up} of 4 attempts")
+
+
+def test_dp_give_up_paths_of_select_and_compact_leave_a_verdict(dct):
+    """With a wait limit of one poll the grid barriers of the selection and the count exchange of the
+    compaction may give up.  Every kernel still ends, and the outputs always carry a verdict: the oracle's
+    result or the error sentinel, never what the buffers held before."""
+    cases = [(si.gaussian_gradient(1_000_003, DEV, 4400), 10_000),     # radix passes over the vector: grid barriers
+             (si.student_t3_gradient(5_000_001, DEV, 4401), 5_000)]   # sample, partition, passes over candidates
+    try:
+        dct.dct_set_wait_limit(1)
+        for g, k in cases:
+            gh = host(g)
+            exp = oracle.select_threshold(gh, k, method="nth")
+            sws, cws = dct.new_select_workspace(g), dct.new_compact_workspace(g)
+            good = torch.tensor([exp.tau_key, exp.n_gt, exp.n_eq, exp.tie_quota], dtype=torch.int64).to(torch.int32).to(DEV)
+            eidx, eval_, ecnt = oracle.threshold_compact(gh, exp, oracle.GE_TAU)
+            idx = torch.zeros(ecnt + 8, dtype=torch.int32, device=DEV)
+            val = torch.zeros(ecnt + 8, device=DEV)
+            for attempt in range(3):
+                thr = torch.full((4,), 0x12345678, dtype=torch.int32, device=DEV)
+                dct.dct_select_threshold(g, k, thr, sws)
+                torch.cuda.synchronize()
+                rec = [v & 0xFFFFFFFF for v in thr.cpu().tolist()]
+                assert rec == [exp.tau_key, exp.n_gt, exp.n_eq, exp.tie_quota] or rec == [0xFFFFFFFF, 0, 0, 0], rec
+                cnt = torch.full((1,), 77, dtype=torch.int64, device=DEV)
+                dct.dct_threshold_compact(g, good, dct.DCT_GE_TAU, idx, val, cnt, cws)
+                torch.cuda.synchronize()
+                c = _raw_count(cnt)
+                assert c in (ecnt, COUNT_ERROR)
+                if c == ecnt:
+                    assert np.array_equal(host(idx[:c]), eidx) and np.array_equal(bits(host(val[:c])), bits(eval_))
+                else:
+                    dct.dct_threshold_compact_workspace_init(cws)
+    finally:
+        dct.dct_set_wait_limit(0)
+
+
 def test_random_mp_configurations(dct):
     """Forty seeded draws of (dtype, B, D, k, encoding, value structure): every forward kernel and every
     consumer against the oracle.  Value structures: post-ReLU, signed, four distinct values (ties everywhere),
