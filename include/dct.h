@@ -139,6 +139,24 @@ int dct_threshold_compact(const void* g, int dt, uint64_t n, const dct_threshold
                           int32_t* d_idx_out, void* d_val_out, uint64_t capacity, uint64_t* d_count_out,
                           void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* dct_threshold_compact for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as dct_threshold_compact, minus the workspace: the exchange
+ * area (dct_threshold_compact_static_scratch_bytes() = about 49 KB, whatever n is)
+ * is a static array in device memory that each GPU the library runs on holds until
+ * the process ends.  The call allocates and frees nothing and needs no
+ * initialisation call: it clears the array itself, with a small fill kernel ahead of
+ * the compaction on `hip_stream` (two launches per call).  n beyond 2^31 - 1 is
+ * DCT_ERR_INVALID as everywhere.  All calls on one GPU share that GPU's array: two
+ * calls that overlap in time on one GPU (different streams, no ordering between
+ * them) race and give undefined counts; order them.  The first call on a device
+ * looks up the array's address (hipGetSymbolAddress); make it outside a graph capture.
+ */
+size_t dct_threshold_compact_static_scratch_bytes(void);
+int dct_threshold_compact_static(const void* g, int dt, uint64_t n, const dct_threshold* d_thr, int mode,
+                                 int32_t* d_idx_out, void* d_val_out, uint64_t capacity, uint64_t* d_count_out,
+                                 void* hip_stream);
+
 /* ------------------------------------------- DCT-DP with error feedback ---
  * Algorithm 1 keeps what compression drops: the residual is added to the gradient
  * before the selection and set to what the mask removed after it (Fig. 3).  These

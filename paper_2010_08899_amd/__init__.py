@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     read_threshold, Segment, segment_table, dct_batched_workspace_bytes, new_batched_workspace,
     dct_select_threshold_batched, dct_threshold_compact_batched, dct_rowtopk_fwd_bitmask,
     dct_rowtopk_bwd_bitmask, dct_rowtopk_scatter_bitmask, dct_rowtopk_fwd_idx16, dct_rowtopk_bwd_idx16,
-    dct_rowtopk_scatter_idx16, dct_set_wait_limit,
+    dct_rowtopk_scatter_idx16, dct_set_wait_limit, dct_threshold_compact_static,
+    dct_threshold_compact_static_scratch_bytes,
 )

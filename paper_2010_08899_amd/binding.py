@@ -31,6 +31,10 @@ _EXPORTS = {
     "dct_threshold_compact": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_void_p,
                                              ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "dct_threshold_compact_static_scratch_bytes": (ctypes.c_size_t, []),
+    "dct_threshold_compact_static": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_void_p,
+                                                    ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                                    ctypes.c_void_p, ctypes.c_void_p]),
     "dct_ef_select_threshold": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64,
                                                ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                                ctypes.c_void_p]),
@@ -198,6 +202,25 @@ def dct_threshold_compact(g: torch.Tensor, thr: torch.Tensor, mode: int, idx_out
                                        _dev(count_out, "count_out"), _dev(ws, "ws"),
                                        ws.numel() * ws.element_size(), _stream()),
            "dct_threshold_compact")
+
+
+def dct_threshold_compact_static_scratch_bytes() -> int:
+    return lib().dct_threshold_compact_static_scratch_bytes()
+
+
+def dct_threshold_compact_static(g: torch.Tensor, thr: torch.Tensor, mode: int, idx_out: torch.Tensor,
+                                 val_out: torch.Tensor, count_out: torch.Tensor, capacity: int | None = None) -> None:
+    """dct_threshold_compact without a workspace argument (the library's static device array serves)."""
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > min(idx_out.numel(), val_out.numel()):
+        raise ValueError("capacity exceeds the output tensors")
+    if idx_out.dtype != torch.int32 or val_out.dtype != g.dtype or count_out.dtype != torch.int64:
+        raise TypeError("idx_out must be int32, val_out must match g, count_out must be int64")
+    _check(lib().dct_threshold_compact_static(_flat(g, "g"), _dt(g), g.numel(), _dev(thr, "thr"), int(mode),
+                                              _flat(idx_out, "idx_out") if cap else None,
+                                              _flat(val_out, "val_out") if cap else None, cap,
+                                              _dev(count_out, "count_out"), _stream()),
+           "dct_threshold_compact_static")
 
 
 def dct_ef_select_threshold(g: torch.Tensor, e: torch.Tensor, k: int, thr_out: torch.Tensor,

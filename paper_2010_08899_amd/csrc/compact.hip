@@ -61,6 +61,7 @@
 // calls (an epoch word picks the set): every call clears the other set for its
 // successor and the last workgroup advances the epoch, so a call is one launch.
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "dct_common.hpp"
@@ -893,4 +894,48 @@ extern "C" int dct_ef_threshold_compact(const void* g, const void* e_in, void* e
   if (!e_in || !e_out) return DCT_ERR_INVALID;
   return launch_compact(g, e_in, e_out, dt, n, d_thr, mode, d_idx_out, d_val_out, capacity, d_count_out, d_ws,
                         ws_bytes, hip_stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dct_threshold_compact_static: the same call for callers that can hand over no workspace.  The
+// descriptor sets live in a file-scope device array; every GPU the library runs on holds its own copy
+// until the process ends.  In host code the array's NAME is a stand-in, not a device address: the address
+// on the current device comes from hipGetSymbolAddress, once per device, and only that pointer is passed
+// to kernels.
+static __device__ __align__(256) unsigned char scratch[kCtWsBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (nullptr on failure).
+void* scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" size_t dct_threshold_compact_static_scratch_bytes(void) { return kCtWsBytes; }
+
+extern "C" int dct_threshold_compact_static(const void* g, int dt, uint64_t n, const dct_threshold* d_thr, int mode,
+                                            int32_t* d_idx_out, void* d_val_out, uint64_t capacity,
+                                            uint64_t* d_count_out, void* hip_stream) {
+  if (n == 0 || n > 0x7FFFFFFFull) return DCT_ERR_INVALID;  // beyond the int32 index range: no call of this library takes it
+  void* ws = scratch_on_current_device();
+  if (ws == nullptr) return DCT_ERR_HIP;
+  // The array keeps what the last call on this GPU left there -- possibly a refused state after a wait that
+  // ran out -- so every call starts from a freshly initialised workspace (a fill kernel ahead of the
+  // compaction on the same stream; no memset node, which callers under graph capture could not replay).
+  const int rc = dct_threshold_compact_workspace_init(ws, kCtWsBytes, hip_stream);
+  if (rc != DCT_OK) return rc;
+  return launch_compact(g, nullptr, nullptr, dt, n, d_thr, mode, d_idx_out, d_val_out, capacity, d_count_out, ws,
+                        kCtWsBytes, hip_stream);
 }
