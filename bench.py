@@ -9,19 +9,23 @@ One step = one pass of the whole hot path over one batch of synthetic input:
 Inputs are resident in HBM before the timed region; two copies of every input
 alternate so that no step re-reads what the previous one left in cache.
 
-Prints ONE JSON line: whole-step throughput in elements/s, per-call times and
-HBM fractions, the roofline entry of the dominant kernel, the c3 reuse loop
-(threshold selected once, applied to fresh draws), the two DCT-DP calls with
-error feedback fused in and the receiver-side decompression calls (timed on the
-same c4 / c5 data; not part of the step) and the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: whole-step throughput in elements/s; per-call times, elements/s and
+HBM fractions for all five configurations (c1 and c2 are a few MB and run out of cache: latency,
+not bandwidth; c3 is the reuse loop, the threshold selected once and applied to 1000 fresh draws);
+the roofline entry of the dominant kernel; the calls of the further rows (error feedback,
+decompression, other encodings, many tensors per call; none is part of the step); and the CPU
+oracle timed on the same step's input, on one thread and spread over the host's cores.
+The last lines on stderr repeat the figures that matter in short form.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import torch
@@ -58,20 +62,31 @@ CALL_KERNELS = {
 }
 
 
-def measured_traffic(call):
-    """HBM bytes per call from the committed rocprofv3 counter summary (profiles/), or None."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
-    try:
-        table = {}
-        with open(path) as f:
-            for line in f:
-                if line.startswith("#") or not line.strip():
-                    continue
-                name, fb, wb = line.rstrip("\n").split("\t")
-                table[name] = float(fb) + float(wb)
-        return int(sum(table[k] * n for k, n in CALL_KERNELS[call]))
-    except (OSError, KeyError, ValueError):
-        return None
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic_per_launch.txt")
+
+
+def traffic_table():
+    """{kernel name: HBM bytes per launch} from the committed rocprofv3 counter summary, and where it came from."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
+    table = {}
+    with open(path) as f:
+        text = f.read()
+    for line in text.splitlines():
+        if line.startswith("#") or not line.strip():
+            continue
+        name, fb, wb = line.split("\t")
+        table[name] = float(fb) + float(wb)
+    return table, f"{TRAFFIC_FILE}#sha1:{hashlib.sha1(text.encode()).hexdigest()[:12]}"
+
+
+def measured_traffic(call, table):
+    """HBM bytes per call: scaled FETCH_SIZE + WRITE_SIZE of its kernels.  A kernel the summary does not know
+    (renamed since the counters were collected) is an error, not a silent null."""
+    missing = [k for k, _ in CALL_KERNELS[call] if k not in table]
+    if missing:
+        sys.exit(f"bench.py: {TRAFFIC_FILE} has no entry for {missing} (call {call}): collect the counters again "
+                 f"(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this benchmark) and refresh the summary")
+    return int(sum(table[k] * n for k, n in CALL_KERNELS[call]))
 
 
 def log(*a):
@@ -115,6 +130,12 @@ def main():
                     help="skip the small-tensor comparison (its per-tensor calls launch the same kernels as the "
                          "large configurations, which blurs per-kernel profiles)")
     ap.add_argument("--small", action="store_true", help="shrink c4/c5 by 16x (debugging only, not a valid number)")
+    ap.add_argument("--no-small-configs", action="store_true",
+                    help="skip c1 and c2 (they launch the same kernels as the large configurations, which blurs "
+                         "per-kernel profiles)")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="leave roofline.traffic null instead of looking it up in profiles/ (for the rocprofv3 runs "
+                         "that collect the counters the lookup is made from)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every box has one); --gpus N with N > 1 is not supported. "
@@ -226,9 +247,39 @@ def main():
     gran128 = int(B5 * lines128) + B5 * k5 * 6
     gran64 = int(B5 * sect64) + B5 * k5 * 6
     calls.append(entry("dct_rowtopk_bwd[c5]", us, gran128, B5 * D5, extra={
+        "frac_of_hbm_peak_strict": round(strict / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_strict": strict, "GBps_strict": round(strict / (us * 1e-6) / 1e9, 1),
         "algorithmic_bytes_64B_sectors": gran64, "GBps_64B_sectors": round(gran64 / (us * 1e-6) / 1e9, 1),
-        "note": "algorithmic_bytes counts the 128-byte lines the gather touches"}))
+        "note": "frac_of_hbm_peak counts the 128-byte lines the gather touches (a 5 % gather of bf16 touches 96 % of them: "
+                "the memory moves whole lines); frac_of_hbm_peak_strict counts B*k*(4+2e) bytes only"}))
+
+    # ------------------------------------------------------------ the small configurations (parity cases; latency-bound)
+    # c1 (4 MiB) and c2 (8 MiB) live in the caches and take a microsecond of memory traffic: what is measured
+    # is launch latency.  Reported because the metric asks for every configuration's elements/s.
+    small_calls = []
+    if not args.small and not args.no_small_configs:
+        g1, k1 = si.config_c1(dev)
+        ws1s, ws1c = dct.new_select_workspace(g1), dct.new_compact_workspace(g1)
+        thr1 = torch.zeros(4, dtype=torch.int32, device=dev)
+        idx1 = torch.zeros(k1, dtype=torch.int32, device=dev)
+        val1 = torch.zeros(k1, dtype=torch.float32, device=dev)
+        us = time_calls(lambda i: dct.dct_select_threshold(g1, k1, thr1, ws1s), 200)
+        small_calls.append(entry("dct_select_threshold[c1]", us, si.C1_N * 4 + 16, si.C1_N, launches=2))
+        us = time_calls(lambda i: dct.dct_threshold_compact(g1, thr1, dct.DCT_EXACT_K, idx1, val1, cnt4, ws1c), 200)
+        small_calls.append(entry("dct_threshold_compact[c1,exact_k]", us, si.C1_N * 4 + k1 * 8 + 8, si.C1_N))
+        x2, dy2, k2 = si.config_c2(dev)
+        idx2 = torch.zeros(si.C2_B, k2, dtype=torch.int32, device=dev)
+        val2 = torch.zeros(si.C2_B, k2, dtype=torch.float32, device=dev)
+        dval2 = torch.zeros_like(val2)
+        us = time_calls(lambda i: dct.dct_rowtopk_fwd(x2, k2, idx2, val2, None), 200)
+        small_calls.append(entry("dct_rowtopk_fwd[c2]", us, si.C2_B * si.C2_D * 4 + si.C2_B * k2 * 8, si.C2_B * si.C2_D))
+        us = time_calls(lambda i: dct.dct_rowtopk_bwd(dy2, idx2, dval2), 200)
+        small_calls.append(entry("dct_rowtopk_bwd[c2]", us, si.C2_B * k2 * 12, si.C2_B * si.C2_D,
+                                 extra={"note": "strict bytes (idx, gathered values, output); the input sits in cache"}))
+        for c in small_calls:
+            c["note"] = (c.get("note", "") + " cache-resident input, repeated calls: launch latency, not HBM bandwidth").strip()
+        del g1, x2, dy2
+    call_select(0)
 
     # ------------------------------------------------------------ error feedback fused in (not part of the step)
     # Same c4 gradients plus a resident residual per copy; the new residual goes to a third buffer so
@@ -372,22 +423,6 @@ def main():
         log(f"[bench] {c['call']}: {c['us']} us, {c['GBps']} GB/s = {c['frac_of_hbm_peak']:.1%} of 8 TB/s")
     log(f"[bench] probes: {probes}")
 
-    # The dominant KERNEL of the step: among the calls that are one launch each, the longest.  (The
-    # selection call is seven launches; its largest kernel, the partition pass, is shorter than the
-    # compaction kernel -- see profiles/bench_kernel_trace.txt -- and the call as a whole is reported
-    # separately below.)
-    dom = max((c for c in calls if c["launches"] == 1), key=lambda c: c["us"])
-    roofline = {"bound": "hbm", "kernel": CALL_KERNELS[dom["call"]][0][0], "call": dom["call"],
-                "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom["call"]),
-                "algorithmic_bytes": dom["algorithmic_bytes"], "launch_us": dom["us"],
-                "note": "achieved = algorithmic bytes of one launch / average time of one launch (HIP events around the region of back-to-back launches); traffic = "
-                        "scaled FETCH_SIZE + WRITE_SIZE of the kernel from profiles/bench_hbm_counters.txt",
-                "longest_call": {k_: v for k_, v in max(calls, key=lambda c: c["us"]).items()
-                                 if k_ in ("call", "us", "GBps", "frac_of_hbm_peak", "launches", "algorithmic_bytes")}}
-    for c in calls + ef_calls + rx_calls + bm_calls:
-        c["traffic"] = measured_traffic(c["call"])
-
     # ------------------------------------------------------------ c3: select once, reuse on fresh draws
     c3 = None
     free_b, _ = torch.cuda.mem_get_info()
@@ -409,7 +444,9 @@ def main():
         cnt3 = torch.zeros(1, dtype=torch.int64, device=dev)
         torch.cuda.synchronize()
         log(f"[bench] c3: {draws} draws resident in {time.time() - t0:.1f}s")
-        us_sel3 = time_calls(lambda i: dct.dct_select_threshold(g0, k3, thr3, ws3s), 10)
+        # the selection runs once per threshold life-span; timed over distinct draws as well
+        us_sel3 = time_calls(lambda i: dct.dct_select_threshold(bank[i % draws], k3, thr3, ws3s), 50)
+        dct.dct_select_threshold(g0, k3, thr3, ws3s)
         iters = si.C3_DRAWS
         # the loop as a training run issues it: iterations back to back, two events around all of them
         us_c3 = time_calls(lambda i: dct.dct_threshold_compact(bank[i % draws], thr3, dct.DCT_GE_TAU, idx3, val3,
@@ -418,6 +455,9 @@ def main():
         us_c3_events = time_calls(lambda i: dct.dct_threshold_compact(bank[i % draws], thr3, dct.DCT_GE_TAU, idx3,
                                                                       val3, cnt3, ws3), min(iters, 200), warmup=5, per_call=True)
         alg3 = n3 * 4 + k3 * 8 + 8
+        calls.append(entry("dct_select_threshold[c3]", us_sel3, n3 * 4 + 16, n3, launches=sel_launches))
+        calls.append(entry("dct_threshold_compact[c3,ge_tau,reuse]", us_c3, alg3, n3, extra={
+            "note": f"per iteration of {iters} back-to-back calls over {draws} distinct resident draws"}))
         c3 = {"n": n3, "k": k3, "distinct_draws": draws, "iterations": iters, "select_us": round(us_sel3, 2),
               "compact_us_per_iteration": round(us_c3, 2),
               "compact_us_median_with_an_event_per_call": round(us_c3_events, 2),
@@ -430,7 +470,34 @@ def main():
     except torch.cuda.OutOfMemoryError:
         log("[bench] c3 reuse loop skipped: not enough free HBM")
 
-    # ------------------------------------------------------------ CPU oracle on a bounded sample
+    # The dominant KERNEL of the step: among the step's calls that are one launch each, the longest.  (The
+    # selection call is four launches; its largest kernel, the partition pass, is shorter than the
+    # compaction kernel -- see profiles/bench_kernel_trace.txt -- and the call as a whole is reported
+    # in `calls` and, flat, below.)
+    with_traffic = not (args.no_traffic or args.small)
+    table, traffic_source = traffic_table() if with_traffic else ({}, None)
+    by_name = {c["call"]: c for c in calls}
+    dom = max((c for c in calls[:4] if c["launches"] == 1), key=lambda c: c["us"])
+    roofline = {"bound": "hbm", "kernel": CALL_KERNELS[dom["call"]][0][0], "call": dom["call"],
+                "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4),
+                "traffic": measured_traffic(dom["call"], table) if with_traffic else None,
+                "traffic_source": traffic_source,
+                "algorithmic_bytes": dom["algorithmic_bytes"], "launch_us": dom["us"],
+                "note": "achieved = algorithmic bytes of one launch / average launch time (HIP events); traffic = scaled "
+                        "FETCH_SIZE + WRITE_SIZE per launch"}
+    # the other calls of the metric, flat (a reader of a trimmed record still sees them)
+    for key, name in (("select_c4", "dct_select_threshold[c4]"), ("fwd_c5", "dct_rowtopk_fwd[c5]"),
+                      ("bwd_c5", "dct_rowtopk_bwd[c5]"), ("select_c3", "dct_select_threshold[c3]"),
+                      ("compact_c3_reuse", "dct_threshold_compact[c3,ge_tau,reuse]")):
+        if name in by_name:
+            roofline[key + "_us"] = by_name[name]["us"]
+            roofline[key + "_frac"] = by_name[name]["frac_of_hbm_peak"]
+    roofline["bwd_c5_frac_strict"] = by_name["dct_rowtopk_bwd[c5]"]["frac_of_hbm_peak_strict"]
+    for c in calls[:4] + ef_calls + rx_calls + bm_calls + i16_calls:
+        c["traffic"] = measured_traffic(c["call"], table) if with_traffic else None
+
+    # ------------------------------------------------------------ CPU oracle on the same step's input
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -442,21 +509,58 @@ def main():
         dys = oracle.as_numpy(dy5[0][:b_s].cpu())
         t = {}
         t0 = time.perf_counter(); thr_s = oracle.select_threshold(gs, k_s); t["select_full_sort"] = time.perf_counter() - t0
-        t0 = time.perf_counter(); oracle.threshold_compact(gs, thr_s, oracle.EXACT_K, capacity=k_s); t["compact"] = time.perf_counter() - t0
-        t0 = time.perf_counter(); ei, _, _ = oracle.rowtopk_fwd(xs, k5); t["rowtopk_fwd"] = time.perf_counter() - t0
-        t0 = time.perf_counter(); oracle.rowtopk_bwd(dys, ei); t["rowtopk_bwd"] = time.perf_counter() - t0
+        t0 = time.perf_counter(); ci, cv, cc = oracle.threshold_compact(gs, thr_s, oracle.EXACT_K, capacity=k_s); t["compact"] = time.perf_counter() - t0
+        t0 = time.perf_counter(); ei, ev, _ = oracle.rowtopk_fwd(xs, k5); t["rowtopk_fwd"] = time.perf_counter() - t0
+        t0 = time.perf_counter(); ed = oracle.rowtopk_bwd(dys, ei); t["rowtopk_bwd"] = time.perf_counter() - t0
         total = sum(t.values())
         t0 = time.perf_counter(); oracle.select_threshold(gs, k_s, method="nth"); t_nth = time.perf_counter() - t0
+
+        # The same oracle spread trivially over the host's cores where the work is independent: rows for the
+        # row top-k, chunks + ordered concatenation for the compaction (the mask of Algorithm 1 per chunk; the
+        # ties beyond the quota are dropped afterwards).  The selection stays ONE full sort: its time is the
+        # single-thread one.  (The oracle's C routines release the interpreter lock, so threads do.)
+        cores = max(1, min(16, os.cpu_count() or 1))
+        tp = {}
+        with ThreadPoolExecutor(cores) as pool:
+            bounds = [n_s * j // cores for j in range(cores + 1)]
+            t0 = time.perf_counter()
+            parts = list(pool.map(lambda j: oracle.threshold_compact(gs[bounds[j]:bounds[j + 1]], thr_s, oracle.GE_TAU),
+                                  range(cores)))
+            pidx = np.concatenate([p_[0].astype(np.int64) + bounds[j] for j, p_ in enumerate(parts)])
+            pval = np.concatenate([p_[1] for p_ in parts])
+            tie = (pval.view(np.uint32) & 0x7FFFFFFF) == thr_s.tau_key
+            keep = ~tie | (np.cumsum(tie) <= thr_s.tie_quota)
+            pidx, pval = pidx[keep], pval[keep]
+            tp["compact"] = time.perf_counter() - t0
+            rb = [b_s * j // cores for j in range(cores + 1)]
+            t0 = time.perf_counter()
+            fparts = list(pool.map(lambda j: oracle.rowtopk_fwd(xs[rb[j]:rb[j + 1]], k5), range(cores)))
+            pei = np.concatenate([f_[0] for f_ in fparts])
+            tp["rowtopk_fwd"] = time.perf_counter() - t0
+            t0 = time.perf_counter()
+            ped = np.concatenate(list(pool.map(lambda j: oracle.rowtopk_bwd(dys[rb[j]:rb[j + 1]], pei[rb[j]:rb[j + 1]]),
+                                               range(cores))))
+            tp["rowtopk_bwd"] = time.perf_counter() - t0
+        assert np.array_equal(pidx, ci[:cc].astype(np.int64)) and np.array_equal(pei, ei) and np.array_equal(ped, ed)
+        total_par = t["select_full_sort"] + sum(tp.values())
         model = ""
         try:
             with open("/proc/cpuinfo") as f:
                 model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
         except OSError:
             pass
-        cpu = {"value": (n_s + b_s * D5) / total, "unit": "elements/s", "cores": 1, "kind": "oracle",
-               "sample": f"first {n_s} elements of the c4 gradient (k={k_s}) + first {b_s} rows of c5; "
-                         f"one step = full-sort select + scalar compact + partial-sort row top-k + gather",
-               "seconds": {k_: round(v, 3) for k_, v in t.items()}, "select_nth_element_seconds": round(t_nth, 3),
+        elems = n_s + b_s * D5
+        cpu = {"value": elems / total, "unit": "elements/s", "cores": 1, "kind": "oracle",
+               "sample": f"one whole step: {n_s} elements of c4 (k={k_s}), {b_s} rows of c5; full-sort select + scalar "
+                         f"compact + partial-sort row top-k + gather",
+               "seconds_select_full_sort": round(t["select_full_sort"], 3), "seconds_compact": round(t["compact"], 3),
+               "seconds_rowtopk_fwd": round(t["rowtopk_fwd"], 3), "seconds_rowtopk_bwd": round(t["rowtopk_bwd"], 3),
+               "select_nth_element_seconds": round(t_nth, 3),
+               "all_cores_value": elems / total_par, "all_cores": cores,
+               "all_cores_seconds_compact": round(tp["compact"], 3), "all_cores_seconds_rowtopk_fwd": round(tp["rowtopk_fwd"], 3),
+               "all_cores_seconds_rowtopk_bwd": round(tp["rowtopk_bwd"], 3),
+               "all_cores_without_select_value": elems / sum(tp.values()),
+               "all_cores_note": "rows / chunks over threads; the selection stays one full sort on one core",
                "host_cpus": os.cpu_count(), "cpu_model": model}
         log(f"[bench] cpu oracle: {cpu}")
 
@@ -469,11 +573,24 @@ def main():
         "config": {"workload": "c4 DP select+compact (N=2^28 fp32, keep 0.5%) + c5 MP row top-k fwd+bwd "
                                "(65536x4096 bf16, k=204)" + (" [SHRUNK 16x: not a valid number]" if args.small else ""),
                    "elements_per_step": elems_per_step, "dp_n": n4, "dp_k": k4, "mp_B": B5, "mp_D": D5, "mp_k": k5},
-        "roofline": roofline, "calls": calls, "error_feedback_calls": ef_calls, "decompression_calls": rx_calls, "bitmask_calls": bm_calls, "idx16_calls": i16_calls,
+        "roofline": roofline, "calls": calls, "small_config_calls": small_calls, "error_feedback_calls": ef_calls,
+        "decompression_calls": rx_calls, "bitmask_calls": bm_calls, "idx16_calls": i16_calls,
         "paper_mp_widths": narrow, "batched_small_tensors": batched, "probes": probes, "c3_reuse": c3, "cpu_baseline": cpu,
         "inputs": inputs,
     }
     print(json.dumps(out), flush=True)
+
+    # ------------------------------------------------------------ the short form, last on stderr
+    log("[bench] ---- summary (us, fraction of the 8 TB/s peak, elements/s)")
+    for c in calls + small_calls:
+        log(f"[bench] {c['call']}: {c['us']} us {c['frac_of_hbm_peak']:.3f} {c['elements_per_s']:.3g}")
+    for w in narrow:
+        log(f"[bench] MP bf16 D={w['D']} k={w['k']} B={w['B']}: fwd {w['fwd_us']} us {w['fwd_frac_of_hbm_peak']:.3f}, "
+            f"bwd {w['bwd_us']} us, scatter {w['scatter_us']} us")
+    log(f"[bench] step {ms_per_step:.4f} ms = {value:.4g} elements/s; probes {probes}")
+    if cpu:
+        log(f"[bench] cpu oracle: 1 core {cpu['value']:.3g} el/s; {cpu['all_cores']} cores {cpu['all_cores_value']:.3g} el/s "
+            f"(without the one-core sort {cpu['all_cores_without_select_value']:.3g})")
 
 
 if __name__ == "__main__":

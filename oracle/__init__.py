@@ -32,14 +32,26 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (errors abort), written to `path`.
+    A process loads it instead of the plain build when DCT_ORACLE_LIB names it; it needs gcc's libasan
+    preloaded (the interpreter is not instrumented)."""
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Wextra", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-o", path, _SRC]
+    subprocess.run(cmd, check=True)
+    return path
+
+
 _lib = None
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        override = os.environ.get("DCT_ORACLE_LIB")
+        if not override:
+            build()
+        lib = ctypes.CDLL(override or _LIB)
         vp, u64, u32, i32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int
         lib.oracle_select_threshold.argtypes = [vp, i32, u64, u64, vp]
         lib.oracle_select_threshold_nth.argtypes = [vp, i32, u64, u64, vp]

@@ -78,3 +78,18 @@ def test_binding_reports_the_error_sentinels():
         m.read_threshold(torch.tensor([-1, 0, 0, 0], dtype=torch.int32))
     with pytest.raises(m.DctError):
         m.read_count(torch.tensor([-1], dtype=torch.int64))
+
+
+def test_every_kernel_the_benchmark_prices_has_counter_traffic_on_file():
+    """bench.py looks the HBM traffic of its calls up in profiles/hbm_traffic_per_launch.txt by kernel name and
+    refuses to run when a name is missing: a renamed kernel must come with fresh counters."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    table, source = bench.traffic_table()
+    assert source.startswith("profiles/hbm_traffic_per_launch.txt#sha1:")
+    for call, kernels in bench.CALL_KERNELS.items():
+        assert bench.measured_traffic(call, table) > 0, call
+        for name, launches in kernels:
+            assert name in table and launches >= 1, (call, name)
