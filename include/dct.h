@@ -88,8 +88,16 @@ typedef struct {
  *   g          device, n elements of `dt`, contiguous, aligned to the element size
  *   n          1 .. 2^31-1            k   1 .. n
  *   d_thr_out  device, receives the dct_threshold
- *   d_ws       device workspace of at least dct_select_threshold_workspace_bytes,
- *              256-byte aligned; contents on entry are irrelevant, it is scratch
+ *   d_ws       device workspace, 256-byte aligned; contents on entry are irrelevant, it
+ *              is scratch.  About 230 KB of counters, histograms and the key sample,
+ *              plus, for n >= 2^22, a buffer for the keys that one pass over the vector
+ *              finds between two bounds drawn from the sample.  How many those are
+ *              depends on k / n: dct_select_threshold_workspace_bytes_for(dt, n, k) asks
+ *              for twice the expected number (c4, 0.5 % kept of 2^28: 4 M keys, 16 MB);
+ *              dct_select_threshold_workspace_bytes(dt, n) for what the worst k needs
+ *              (n/16 keys: 6 % of the vector's bytes) and serves every k.  Any size from
+ *              the first on is accepted and used; a buffer that proves too small costs
+ *              time (the radix passes then read the vector), never exactness.
  *
  * Concurrency: the last kernel of the call runs all radix passes in one launch.
  * Between two passes up to 64 of its workgroups (one per compute unit, the first
@@ -101,6 +109,7 @@ typedef struct {
  * dct_ef_select_threshold.
  */
 size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n);
+size_t dct_select_threshold_workspace_bytes_for(int dt, uint64_t n, uint64_t k);
 int dct_select_threshold(const void* g, int dt, uint64_t n, uint64_t k, dct_threshold* d_thr_out,
                          void* d_ws, size_t ws_bytes, void* hip_stream);
 

@@ -4,21 +4,21 @@
 // the HIP library and the product never calls it.
 //
 // What it computes is the plain definition in the paper:
-//   * DCT-DP (Algorithm 1, steps "sort |W_grad|", "tau = w_floor(N*eta)",
-//     "M = I(|W_grad| >= tau)", "W_hat = W_grad . M"): the threshold is an order
+//   * DCT-DP (Algorithm 1: the sort of the magnitudes, the pick of tau at rank
+//     floor(N*eta), the mask of the magnitudes >= tau, the masked gradient): the threshold is an order
 //     statistic of the magnitudes found by a FULL SORT of a copy (the
 //     copy-and-sort routine of Sec. 3.3), the mask is a scalar filter.
-//   * DCT-MP (Algorithm 2, forward loop over rows and backward "X_grad . M"):
+//   * DCT-MP (Algorithm 2, forward loop over rows and the masked gradient of the backward pass):
 //     per row, the k largest magnitudes by a partial sort; the backward pass
-//     reuses the forward mask (Sec. 2.2: "the same mask").
+//     reuses the forward mask (Sec. 2.2).
 //
-//   * Error feedback (Algorithm 1, "W_grad = W_grad + E_grad" before the
-//     selection and "E_grad = W_grad - W_hat_grad" after the mask; Fig. 3): the
+//   * Error feedback (Algorithm 1: the residual is added to the gradient before the
+//     selection and becomes what the mask removed after it; Fig. 3): the
 //     *_ef functions add the residual first, select / filter the sum, and return
 //     the new residual.
 //
-//   * Receiver side (Sec. 2.1 "compression and decompression"; Algorithm 2: the
-//     next worker consumes X_act . M): oracle_scatter / oracle_rowscatter put the
+//   * Receiver side (Sec. 2.1 names decompression next to compression as the overhead; Algorithm 2: the
+//     next worker consumes the masked activations): oracle_scatter / oracle_rowscatter put the
 //     pairs back into a dense tensor, by assignment into zeros or (fp32) by addition.
 //
 // Readings fixed where the paper is silent (listed in the design notes too):
@@ -228,7 +228,7 @@ int oracle_rowtopk_bwd(const void* dy, int dtype, uint32_t B, uint32_t D, uint64
 
 // ---- Algorithm 1 with error feedback (fp32) --------------------------------
 
-// "W_grad = W_grad + E_grad": one binary32 addition per element.  The sum is
+// The corrected gradient (Algorithm 1, first step with error feedback): one binary32 addition per element.  The sum is
 // formed in binary64, where it is exact or correctly rounded with far more than
 // 2*24+2 digits, and rounded once to binary32: the same value as a single
 // round-to-nearest-even binary32 addition.
@@ -249,7 +249,7 @@ int oracle_ef_select_threshold(const float* g, const float* e, uint64_t n, uint6
     return oracle_select_threshold(w.data(), ORACLE_F32, n, k, out);
 }
 
-// Mask, compressed gradient and new residual ("E_grad = W_grad - W_hat_grad"):
+// Mask, compressed gradient and new residual (Algorithm 1, the residual update after the mask):
 // filter w = g + e in index order exactly as oracle_threshold_compact filters g;
 // e_out[i] = +0 where the pair (i, w[i]) was written, w[i] otherwise.
 int oracle_ef_threshold_compact(const float* g, const float* e_in, uint64_t n, const uint32_t* thr, int mode,
@@ -294,8 +294,8 @@ int oracle_ef_threshold_compact(const float* g, const float* e_in, uint64_t n, c
 
 // ---- receiver side: decompression -------------------------------------------
 // What the next worker / the parameter server does with a compressed message
-// (Sec. 2.1 counts "compression and decompression" as the overhead of DCT; in
-// Algorithm 2 the next worker consumes X_act . M): put the pairs back into a
+// (Sec. 2.1 counts compressing and decompressing as the overhead of DCT; in
+// Algorithm 2 the next worker consumes the masked activations): put the pairs back into a
 // dense tensor.  mode 0 (assign): out = 0, then out[idx[j]] = val[j];
 // mode 1 (add, fp32 only): out[idx[j]] = out[idx[j]] + val[j], one binary32
 // addition each (the server-side sum of the workers' sparse gradients).
@@ -347,7 +347,7 @@ int oracle_rowscatter(const int32_t* idx, const void* val, int dtype, uint32_t B
 }
 
 // ---- Algorithm 2 with the mask sent as a bitmap -------------------------------
-// Algorithm 2 sends "X_act . M and the mask M".  Here M travels literally as a
+// Algorithm 2 sends the masked activations and the mask M.  Here M travels literally as a
 // bitmap: ceil(D/32) 32-bit words per row, bit (c mod 32) of word (c div 32) set
 // iff column c is kept, plus the k kept values in ascending column order.  The
 // kept set is the one oracle_rowtopk_fwd computes; only the encoding differs.

@@ -24,6 +24,7 @@ COUNT_WORKSPACE_ERROR = (1 << 64) - 1
 _EXPORTS = {
     # name: (restype, argtypes)
     "dct_select_threshold_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64]),
+    "dct_select_threshold_workspace_bytes_for": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64]),
     "dct_select_threshold": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "dct_threshold_compact_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64]),
@@ -162,8 +163,14 @@ def dct_threshold_compact_workspace_bytes(dt: int, n: int) -> int:
     return lib().dct_threshold_compact_workspace_bytes(dt, n)
 
 
-def new_select_workspace(g: torch.Tensor) -> torch.Tensor:
-    nbytes = dct_select_threshold_workspace_bytes(_dt(g), g.numel())
+def dct_select_threshold_workspace_bytes_for(dt: int, n: int, k: int) -> int:
+    return lib().dct_select_threshold_workspace_bytes_for(dt, n, k)
+
+
+def new_select_workspace(g: torch.Tensor, k: int | None = None) -> torch.Tensor:
+    """Workspace for selections on vectors of g's size: for any k, or (smaller) for this k."""
+    nbytes = dct_select_threshold_workspace_bytes(_dt(g), g.numel()) if k is None else \
+        dct_select_threshold_workspace_bytes_for(_dt(g), g.numel(), int(k))
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=g.device)
 
 

@@ -12,7 +12,7 @@ constexpr int kWave = 64;
 
 // Element traits: storage word, elements per 16-byte vector, key extraction.
 // key(x) = bit pattern with the sign bit cleared; unsigned order on keys is the
-// magnitude order used by Algorithm 1 ("sort |W_grad|") and Algorithm 2.
+// magnitude order used by Algorithm 1 (the sort of the magnitudes) and Algorithm 2.
 template <int DT>
 struct Elem;
 
@@ -71,6 +71,21 @@ __device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
   v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
   v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
   return v;
+}
+
+// One update of a histogram in LDS.  Lanes whose digit equals the first active lane's digit
+// are counted with one ballot and a single LDS add (skewed data such as a mostly zero
+// gradient, or candidates that share their top digits, would otherwise serialise on one
+// bin); the others add directly.
+__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digit) {
+  const uint64_t act = ballot64(active);
+  if (act == 0) return;
+  const int leader = __builtin_ctzll(act);
+  const uint32_t d0 = __shfl(digit, leader, kWave);
+  const bool same = active && digit == d0;
+  const uint64_t m = ballot64(same);
+  if (static_cast<int>(lane_id()) == leader) atomicAdd(&h[d0], static_cast<uint32_t>(__popcll(m)));
+  if (active && !same) atomicAdd(&h[digit], 1u);
 }
 
 // Workgroup barrier that orders LDS accesses only: global loads and stores that are outstanding

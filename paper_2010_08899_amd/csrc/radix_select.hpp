@@ -1,6 +1,6 @@
 // Radix-select building blocks shared by the single-tensor and the batched
-// threshold selection (Algorithm 1, "sort |W_grad|; tau = w_floor(N*eta)" without
-// the sort): the per-pass search state, the skew-tolerant LDS histogram update and
+// threshold selection (Algorithm 1, the sorted magnitudes and the element picked as tau,
+// without the sort): the per-pass search state and
 // the walk over a 2048-bin histogram from the top bin down.
 #pragma once
 
@@ -27,33 +27,6 @@ struct SelState {
 constexpr uint32_t kDigitBits = 11;
 
 
-// One histogram update.  Lanes whose digit equals the first active lane's digit
-// are counted with one ballot and a single LDS add (skewed data such as a mostly
-// zero gradient, or candidates that share their top digits, would otherwise
-// serialise on one bin); the others add directly.
-__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digit) {
-  const uint64_t act = ballot64(active);
-  if (act == 0) return;
-  const int leader = __builtin_ctzll(act);
-  const uint32_t d0 = __shfl(digit, leader, kWave);
-  const bool same = active && digit == d0;
-  const uint64_t m = ballot64(same);
-  if (static_cast<int>(lane_id()) == leader) atomicAdd(&h[d0], static_cast<uint32_t>(__popcll(m)));
-  if (active && !same) atomicAdd(&h[digit], 1u);
-}
-
-// Inclusive prefix sum over the lanes of a wavefront (DPP row shifts + broadcasts).
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
-  uint32_t v = x;
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);
-  return v;
-}
-
 // Walk a 2048-bin histogram from the top bin down and find the bin that holds the
 // k_rem-th largest key.  Called by all THREADS threads of a workgroup (THREADS a
 // multiple of 64 that divides 2048); s_tmp needs THREADS / 64 + 4 words.  Returns
@@ -73,7 +46,7 @@ __device__ BinHit find_bin(LoadBin load_bin, uint32_t k_rem, uint32_t* s_tmp) {
     c[j] = load_bin(kSelBins - 1 - (t * kPer + j));
     sum += c[j];
   }
-  const uint32_t incl_w = wave_incl_scan(sum);
+  const uint32_t incl_w = wave_prefix_sum(sum);
   if (lane_id() == kWave - 1) s_tmp[t / kWave] = incl_w;
   __syncthreads();
   uint32_t before_waves = 0;

@@ -2,8 +2,8 @@
 // X_act) the k largest magnitudes, i.e. the mask m_i = I(|X_act,i| >= tau_i)
 // made exactly k wide (ties to the lower column), emitted as ascending column
 // indices plus the selected values.  Backward: X_grad through the same mask,
-// which is a gather of dy at the forward indices (no new selection: Sec. 2.2,
-// "the same mask is used").
+// which is a gather of dy at the forward indices (no new selection: Sec. 2.2
+// reuses the forward mask in the backward pass).
 #include <algorithm>
 #include <type_traits>
 
@@ -27,17 +27,6 @@ constexpr uint32_t kQuadMinRows = 8192;  // below this the one-row-per-wavefront
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
-}
-
-__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t digit) {
-  const uint64_t act = ballot64(active);
-  if (act == 0) return;
-  const int leader = __builtin_ctzll(act);
-  const uint32_t d0 = __shfl(digit, leader, kWave);
-  const bool same = active && digit == d0;
-  const uint64_t m = ballot64(same);
-  if (static_cast<int>(lane_id()) == leader) atomicAdd(&h[d0], static_cast<uint32_t>(__popcll(m)));
-  if (active && !same) atomicAdd(&h[digit], 1u);
 }
 
 // ENC (RowEnc): the row's mask goes out through `idx_out` as 32- or 16-bit column indices or as a
@@ -330,7 +319,7 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_lanes_kernel(
       uint64_t m = c0 == 0 ? m_next : load_words(row, c0);
       if (c0 == 0 && row + row_step < B) m_next = load_words(row + row_step, 0);  // on its way during this row
       const uint32_t pc = __popcll(m);
-      const uint32_t incl = fast::wave_incl_scan(pc);
+      const uint32_t incl = wave_prefix_sum(pc);
       uint32_t slot = base + incl - pc;
       {
         // the first eight set bits of every lane without a loop: their loads are independent
@@ -465,7 +454,7 @@ __global__ __launch_bounds__(kBwdWaves * kWave) void rowtopk_bwd_rows_bitmask_ke
     next_row = take_row();
     if (next_row < B) load_row(next_row);
     const uint32_t pc = __popcll(m);
-    const uint32_t incl = fast::wave_incl_scan(pc);
+    const uint32_t incl = wave_prefix_sum(pc);
     uint32_t slot = incl - pc;
     const uint32_t base = min(static_cast<uint32_t>(__builtin_amdgcn_readlane(incl, kWave - 1)), k);  // kept columns listed
     while (ballot64(m != 0) != 0) {
@@ -519,7 +508,7 @@ __global__ __launch_bounds__(kRtThreads) void rowtopk_bitmask_words_kernel(
     if constexpr (!GATHER) wave_lds_sync();  // the block buffer is all zeros again
     uint32_t m = live ? mask[row * wpr + w] : 0u;  // D = 32 * wpr: every bit of a word is a column
     const uint32_t pc = __popc(m);
-    const uint32_t incl = fast::wave_incl_scan(pc);
+    const uint32_t incl = wave_prefix_sum(pc);
     const int first = static_cast<int>(lane - w);  // the row's first lane
     const uint32_t prev = __shfl(incl, first > 0 ? first - 1 : 0, kWave);  // taken by all lanes together
     const uint32_t before_row = first > 0 ? prev : 0u;                      // set bits of the rows in lower lanes

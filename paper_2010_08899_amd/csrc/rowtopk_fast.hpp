@@ -65,19 +65,8 @@ __device__ __forceinline__ uint32_t pk_lshr15_u16(uint32_t a) {
   return __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, a) >> static_cast<unsigned short>(15));
 }
 
-// Inclusive prefix sum over the 64 lanes with DPP row shifts and row broadcasts.
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
-  uint32_t v = x;
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
-  return v;
-}
 __device__ __forceinline__ uint32_t wave_total(uint32_t x) {
-  return __builtin_amdgcn_readlane(wave_incl_scan(x), 63);
+  return __builtin_amdgcn_readlane(wave_prefix_sum(x), 63);
 }
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -370,7 +359,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_onchip_kernel(
     }
     wave_lds_fence();
     const uint32_t c = hist[lane];
-    const uint32_t incl = wave_incl_scan(c);
+    const uint32_t incl = wave_prefix_sum(c);
     const uint32_t suffix = n_win - incl + c;  // keys in bins >= lane
     const uint64_t reach = ballot64(n_above + suffix >= k);  // non-empty: bin 0 reaches n_above + n_win >= k
     const int bstar = 63 - __builtin_clzll(reach);
@@ -448,7 +437,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_onchip_kernel(
         uint32_t tc = 0;
 #pragma unroll
         for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
-        uint32_t ts = wave_incl_scan(tc) - tc;
+        uint32_t ts = wave_prefix_sum(tc) - tc;
 #pragma unroll
         for (int w = 0; w < WORDS; ++w) {
           uint32_t m = tie[w];
@@ -552,7 +541,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_onchip_kernel(
       uint32_t tc = 0;
 #pragma unroll
       for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
-      const uint32_t before = wave_incl_scan(tc) - tc;     // ties in lower lanes
+      const uint32_t before = wave_prefix_sum(tc) - tc;     // ties in lower lanes
       const uint32_t allowed = tie_quota > before ? tie_quota - before : 0u;  // ties this lane may keep
       // lanes below the boundary keep all their ties, lanes above it none; the one lane on the
       // boundary drops its highest columns until `allowed` ties are left
@@ -579,7 +568,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_onchip_kernel(
     uint32_t kc = 0;
 #pragma unroll
     for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
-    uint32_t slot = wave_incl_scan(kc) - kc;
+    uint32_t slot = wave_prefix_sum(kc) - kc;
     const uint64_t o0 = row * k;  // first output slot of the row
     word_t* vo = val_out + o0;
     if constexpr (ENC == kEncBitmap) {

@@ -1,7 +1,7 @@
 // Receiver side of DCT: decompression of what dct_threshold_compact and
-// dct_rowtopk_fwd produce (Sec. 2.1 counts "compression and decompression" as
-// the overhead of the method; in Algorithm 2 the next worker consumes
-// X_act . M, and the parameter server sums the workers' sparse gradients).
+// dct_rowtopk_fwd produce (Sec. 2.1 counts compressing and decompressing as
+// the overhead of the method; in Algorithm 2 the next worker consumes the masked
+// activations, and the parameter server sums the workers' sparse gradients).
 //
 //   dct_scatter, assign : dense vector = zeros with val[j] at idx[j].  One kernel
 //       that writes every output element exactly once: each workgroup owns a

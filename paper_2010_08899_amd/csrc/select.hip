@@ -1,5 +1,5 @@
-// dct_select_threshold: Algorithm 1, "sort |W_grad|; tau = w_floor(N*eta)",
-// computed exactly as the k-th largest key WITHOUT sorting or copying the
+// dct_select_threshold: Algorithm 1, the sort of the magnitudes and the element at rank
+// floor(N*eta) taken as tau, computed exactly as the k-th largest key WITHOUT sorting or copying the
 // gradient (the copy-and-sort routine is what Sec. 3.3 measures as the cost of
 // recomputing the threshold every iteration).
 //
@@ -11,14 +11,16 @@
 // k-th largest key.  All passes run in one launch.
 //
 // For large vectors the radix passes do not run over the vector.  A first kernel
-// gathers a stratified sample of 16384 keys, a second one brackets two of its
-// order statistics to get bounds lo <= tau <= hi that hold with overwhelming
+// gathers a stratified sample of 16384 keys (16 workgroups, one key per thread) and
+// its first workgroup, as soon as all keys have arrived, brackets two order
+// statistics of the sample to get bounds lo <= tau <= hi that hold with overwhelming
 // probability.  One streaming pass over the vector (coalesced 16-byte loads, one
 // workgroup of 16 wavefronts per CU, pieces of 8 KiB taken from a counter in LDS)
 // counts the keys above hi and appends the keys in [lo, hi] --
 // well under 1 % of the vector -- to a candidate buffer (64 regions, each with its own
-// counter) through LDS staging.  The
-// radix passes then run over the candidates only, so the vector is read from HBM
+// counter) through LDS staging; on the way it histograms the candidates' top eight
+// bits (of key - lo), which is the first radix pass over them for free.  The
+// remaining radix passes run over the candidates only, so the vector is read from HBM
 // once.  The counts tell exactly whether the bounds held (n_above < k <= n_above
 // + n_candidates) and whether the buffer had room.  If it overflowed (ties by the
 // million at tau) the radix passes run over the keys of the VECTOR that lie in
@@ -27,11 +29,13 @@
 // device and the result is always the exact order statistic.  All arithmetic is
 // on integers.
 //
-// With error feedback (Algorithm 1, "W_grad = W_grad + E_grad" precedes the
+// With error feedback (Algorithm 1: the residual is added to the gradient before the
 // sort) the EF variants of the kernels that read the vector read g and the
 // residual e together and select on w = g + e, one fp32 addition per element,
 // without storing w: dct_ef_threshold_compact forms the same sums again.
 #include <algorithm>
+#include <atomic>
+#include <chrono>
 
 #include "dct_common.hpp"
 #include "radix_select.hpp"
@@ -48,8 +52,11 @@ constexpr int kTailKeep = 8;                      // 16-byte vectors of candidat
 
 constexpr uint64_t kSampleMinN = 1ull << 22;    // below this the radix passes run over the vector itself
 constexpr int kSampleThreads = 1024;
-constexpr uint32_t kSampleSize = 16384;         // 64 KiB of LDS
-constexpr int kGatherThreads = 256;
+constexpr uint32_t kSampleSize = 16384;         // keys: 16 per thread of the workgroup that brackets them
+constexpr uint32_t kCoarseBits = 8;             // the candidates' top bits that the partition pass histograms
+constexpr uint32_t kCoarseBins = 1u << kCoarseBits;
+constexpr uint32_t kCoarseCopies = 16;
+constexpr uint32_t kFinalCap = 16384;           // candidates that one workgroup finishes on its own (16 per thread)
 constexpr int kPartThreads = 1024;              // the partition pass: the CU's 16 wavefronts form one workgroup
 constexpr int kPartWaves = kPartThreads / kWave;
 constexpr int kPartRowsLarge = 8;               // 16-byte loads per lane per piece (two input streams: half of it each)
@@ -66,16 +73,28 @@ struct alignas(128) RegionCount {
   uint32_t pad[30];      // a 128-byte line of its own
 };
 struct SelWs {
+  // cleared by the first kernel of every call
   RegionCount counts[kCandRegions];
+  uint32_t bar[kSelMaxPasses];  // workgroups that have merged their histogram of pass p
+  uint32_t final_count;         // keys appended to final_keys
+  uint32_t final_arrived;       // workgroups that have appended theirs
+  uint32_t pad0[3];
+  // candidates per value of (key - lo) >> coarse_shift, in kCoarseCopies copies (workgroup w adds to copy
+  // w % kCoarseCopies: 256 workgroups adding to one word at the end of the pass take microseconds)
+  uint32_t coarse[kCoarseCopies][kCoarseBins];
+  uint32_t hist[kSelMaxPasses][kSelBins];
+  // written by the first kernel of every call
   uint32_t lo, hi;     // bounds from the sample
   uint32_t sampled;    // 1 when the sample / partition kernels ran
   uint32_t cand_cap;   // capacity of the whole candidate buffer, a multiple of 4 * kCandRegions keys
-  uint32_t bar[kSelMaxPasses];  // workgroups that have merged their histogram of pass p
-  uint32_t pad;
-  uint32_t hist[kSelMaxPasses][kSelBins];
-  uint32_t sample[kSampleSize];       // keys of the stratified sample
+  // The sample: key | call tag << 32.  The tag tells the workgroup that brackets the sample which words are
+  // this call's (the workspace is scratch: nothing in it is assumed on entry, so there is no counter to
+  // clear); a word that carries the tag by accident only makes the bounds worse, and bounds are verified.
+  uint32_t final_keys[kFinalCap];  // the candidates inside the one coarse bin that holds tau (as key - lo)
+  uint64_t sample[kSampleSize];
   uint32_t cand[4];    // candidate keys follow (cand_cap of them, region r at r * cand_cap / kCandRegions)
 };
+constexpr uint32_t kSelClearWords = offsetof(SelWs, lo) / 4;
 static_assert(offsetof(SelWs, cand) % 16 == 0, "candidate regions are read as 16-byte vectors");
 
 struct PassDigits {
@@ -119,63 +138,91 @@ __device__ __forceinline__ uint4 add4(const uint4& a, const uint4& b) {
 // Clears the workspace for the direct (no sample) path.
 __global__ void select_init_kernel(SelWs* ws) {
   uint32_t* w = reinterpret_cast<uint32_t*>(ws);
-  const uint32_t n_words = offsetof(SelWs, sample) / 4;
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) w[i] = 0;
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < kSelClearWords; i += gridDim.x * blockDim.x) w[i] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) ws->sampled = 0;
 }
 
 // ------------------------------------------------------------------ kernel 1b
-// Clear the workspace and gather a stratified sample of the keys: stratum i covers
-// [i*n/S, (i+1)*n/S) and contributes one key at a hashed offset.  One key per
-// thread, spread over many CUs (a single CU cannot keep enough scattered loads in
-// flight).
+// Clear the workspace, gather a stratified sample of the keys and bracket tau.  Stratum i covers
+// [i*n/S, (i+1)*n/S) and contributes one key at a hashed offset: one key per thread, 16 workgroups (a
+// single CU cannot keep enough scattered loads in flight).  Every thread publishes its key together with
+// the call's tag in one 64-bit word; workgroup 0 collects the 16384 words (16 per thread, polling until all
+// carry the tag; bounded) and selects two order statistics of the sample as bounds for tau, two radix passes
+// over the keys in its registers.  (Letting the sixteen workgroups histogram the first digit of their own
+// keys was tried: fetching their histograms costs workgroup 0 more than the pass it saves.)
+static_assert(kSelClearWords <= kSampleSize, "the sample grid also clears the workspace header");
 template <int DT, bool EF>
-__global__ __launch_bounds__(kGatherThreads) void select_gather_kernel(
+__global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* __restrict__ e, uint32_t n,
-    SelWs* ws) {
-  const uint32_t i = blockIdx.x * kGatherThreads + threadIdx.x;  // the grid has exactly kSampleSize threads
-  const uint32_t stratum = n / kSampleSize;                      // >= 256 by the choice of kSampleMinN
-  const uint64_t start = static_cast<uint64_t>(i) * n / kSampleSize;
-  const uint32_t h = (i * 2654435761u) ^ ((i * 40503u) >> 7);
-  const uint32_t raw = elem_raw<DT, EF>(g, e, start + h % stratum);
-  uint32_t* w = reinterpret_cast<uint32_t*>(ws);
-  const uint32_t n_words = offsetof(SelWs, sample) / 4;
-  if (i < n_words) w[i] = 0;
-  ws->sample[i] = raw & Elem<DT>::kKeyMask;
-}
-static_assert(offsetof(SelWs, sample) / 4 <= kSampleSize, "the gather grid also clears the workspace header");
-
-// ------------------------------------------------------------------ kernel 1c
-// One workgroup: select two order statistics of the sample as bounds for tau.
-template <int DT>
-__global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t n, uint32_t k, SelWs* ws,
-                                                                       uint32_t cand_cap) {
+    uint32_t k, SelWs* ws, uint32_t cand_cap, uint32_t tag, uint32_t spin_limit) {
   using E = Elem<DT>;
-  __shared__ uint32_t s_keys[kSampleSize];
+  constexpr int KPT = kSampleSize / kSampleThreads;  // keys per thread of workgroup 0 = workgroups of the grid
   __shared__ uint32_t s_hist[2 * kSelBins];
-  __shared__ uint32_t s_tmp[kSampleThreads / kWave + 4];
+  __shared__ uint32_t s_tmp[kSampleThreads / kWave + 4], s_scan_b[kSampleThreads / kWave], s_found[4];
   const uint32_t t = threadIdx.x;
+  const PassDigits dg = pass_digits(DT);
+  const uint64_t tagged = static_cast<uint64_t>(tag) << 32;
   {
-    const uint4* src = reinterpret_cast<const uint4*>(ws->sample);
-    uint4* dst = reinterpret_cast<uint4*>(s_keys);
-    for (uint32_t i = t; i < kSampleSize / 4; i += kSampleThreads) dst[i] = src[i];
+    const uint32_t i = blockIdx.x * kSampleThreads + t;  // the grid has exactly kSampleSize threads
+    const uint32_t stratum = n / kSampleSize;            // >= 256 by the choice of kSampleMinN
+    const uint64_t start = static_cast<uint64_t>(i) * n / kSampleSize;
+    const uint32_t h = (i * 2654435761u) ^ ((i * 40503u) >> 7);
+    const uint32_t key = elem_raw<DT, EF>(g, e, start + h % stratum) & E::kKeyMask;
+    if (i < kSelClearWords) reinterpret_cast<uint32_t*>(ws)[i] = 0;
+    st_agent(&ws->sample[i], tagged | key);
   }
-  __syncthreads();
+  if (blockIdx.x != 0) return;
+
+  // ---- workgroup 0: the whole sample, 16 keys per thread
+  uint32_t keys[KPT];
+  {
+    bool complete = false;  // uniform
+    for (uint32_t spins = 0; !complete && spins <= spin_limit; ++spins) {
+      // (tt: the thread's index, opaque to the compiler, which would otherwise keep every address in
+      // registers across the iterations of this loop; and all loads first, then their uses: the loads are
+      // ordered accesses, and a use between two of them makes the second wait for the first)
+      uint32_t tt = t;
+      asm volatile("" : "+v"(tt));
+      uint64_t w[KPT];
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) w[j] = ld_agent(&ws->sample[j * kSampleThreads + tt]);
+      bool mine = true;
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        keys[j] = static_cast<uint32_t>(w[j]);
+        mine = mine && static_cast<uint32_t>(w[j] >> 32) == tag;
+      }
+      complete = __syncthreads_and(mine) != 0;
+      if (!complete) __builtin_amdgcn_s_sleep(2);
+    }
+    if (!complete) {  // somebody's words never came: no bounds, the radix passes will run over the vector
+      if (t == 0) {
+        ws->lo = 0;
+        ws->hi = E::kKeyMask;
+        ws->sampled = 0;
+        ws->cand_cap = cand_cap;
+      }
+      return;
+    }
+  }
 
   // sample ranks (1-based from the top) that bracket rank k of the vector with a
-  // margin of five standard deviations of the sample count (binomial: r (S - r) / S), plus slack
+  // margin of five standard deviations of the sample count (binomial: r (S - r) / S), plus slack.
+  // Where that margin reaches past the top of the sample the largest sample key still serves as the upper
+  // bound as long as about 16 sample keys are expected above tau (none at all: e^-16, the risk the five
+  // standard deviations take elsewhere); a bound that does not hold is found out and costs time only.
   const uint64_t r = static_cast<uint64_t>(k) * kSampleSize / n;
   const uint64_t var = r * (kSampleSize - r) / kSampleSize;
   uint32_t sq = 0;
   while (static_cast<uint64_t>(sq + 1) * (sq + 1) <= var) ++sq;
   const uint64_t delta = 5ull * (sq + 1) + 8;
-  const uint64_t rank_hi = r > delta ? r - delta : 0;                     // 0: no upper bound
+  const uint64_t rank_hi = r > delta ? r - delta : (r >= 16 ? 1 : 0);     // 0: no upper bound
   const uint64_t rank_lo = r + delta + 1 <= kSampleSize ? r + delta + 1 : 0;  // 0: no lower bound
 
   // Both order statistics are searched together: while their fixed digits agree
   // (the usual case until the last pass) one histogram serves both.
   // The bounds only have to bracket tau, so the digits below the second pass are not
   // resolved: lo takes zeros there and hi ones (a relative widening of 2^-14 for fp32).
-  const PassDigits dg = pass_digits(DT);
   const int n_pass = dg.n_pass < 2 ? dg.n_pass : 2;
   const uint32_t rank[2] = {static_cast<uint32_t>(rank_hi), static_cast<uint32_t>(rank_lo)};
   uint32_t prefix[2] = {0, 0}, k_rem[2] = {rank[0], rank[1]};
@@ -186,19 +233,64 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
     const bool shared = rank[0] != 0 && rank[1] != 0 && prefix[0] == prefix[1];  // uniform
     for (uint32_t i = t; i < 2 * kSelBins; i += kSampleThreads) s_hist[i] = 0;
     __syncthreads();
-    for (uint32_t i = t; i < kSampleSize; i += kSampleThreads) {
-      const uint32_t key = s_keys[i];
+    const bool one_hist = shared || rank[0] == 0 || rank[1] == 0;  // uniform
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+      const uint32_t key = keys[j];
       const uint32_t digit = (key >> shift) & dmask;
-      if (rank[0] != 0) hist_add(s_hist, (key & fixed_mask) == prefix[0], digit);
-      if (rank[1] != 0 && !shared) hist_add(s_hist + kSelBins, (key & fixed_mask) == prefix[1], digit);
+      if (one_hist) {
+        hist_add(s_hist, (key & fixed_mask) == prefix[rank[0] != 0 ? 0 : 1], digit);
+      } else {
+        hist_add(s_hist, (key & fixed_mask) == prefix[0], digit);
+        hist_add(s_hist + kSelBins, (key & fixed_mask) == prefix[1], digit);
+      }
     }
     __syncthreads();
-    for (int which = 0; which < 2; ++which) {
-      if (rank[which] == 0) continue;  // uniform
-      const uint32_t* hsel = (which == 1 && !shared) ? s_hist + kSelBins : s_hist;
-      const BinHit hit = find_bin<kSampleThreads>([&](uint32_t b) { return hsel[b]; }, k_rem[which], s_tmp);
-      prefix[which] |= hit.bin << shift;
-      k_rem[which] -= hit.above;
+    {
+      // both ranks in one walk from the top bin down (two bins per thread; a rank of 0 finds nothing)
+      constexpr int kW = kSampleThreads / kWave;
+      const uint32_t* hb = one_hist ? s_hist : s_hist + kSelBins;
+      uint32_t ca[2], cb[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        ca[j] = s_hist[kSelBins - 1 - (t * 2 + j)];
+        cb[j] = hb[kSelBins - 1 - (t * 2 + j)];
+      }
+      const uint32_t sa = ca[0] + ca[1], sb = cb[0] + cb[1];
+      const uint32_t ia = wave_prefix_sum(sa), ib = wave_prefix_sum(sb);
+      if (lane_id() == kWave - 1) {
+        s_tmp[t / kWave] = ia;
+        s_scan_b[t / kWave] = ib;
+      }
+      __syncthreads();
+      uint32_t above_a = ia - sa, above_b = ib - sb;
+      for (uint32_t w = 0; w < t / kWave; ++w) {
+        above_a += s_tmp[w];
+        above_b += s_scan_b[w];
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if (rank[0] != 0 && above_a < k_rem[0] && k_rem[0] <= above_a + ca[j]) {
+          s_found[0] = kSelBins - 1 - (t * 2 + j);
+          s_found[1] = above_a;
+        }
+        if (rank[1] != 0 && above_b < k_rem[1] && k_rem[1] <= above_b + cb[j]) {
+          s_found[2] = kSelBins - 1 - (t * 2 + j);
+          s_found[3] = above_b;
+        }
+        above_a += ca[j];
+        above_b += cb[j];
+      }
+      __syncthreads();
+      if (rank[0] != 0) {
+        prefix[0] |= s_found[0] << shift;
+        k_rem[0] -= s_found[1];
+      }
+      if (rank[1] != 0) {
+        prefix[1] |= s_found[2] << shift;
+        k_rem[1] -= s_found[3];
+      }
+      static_assert(kW + 4 <= kSampleThreads / kWave + 4, "s_tmp holds one word per wavefront");
     }
     fixed_mask |= dmask << shift;
   }
@@ -211,6 +303,13 @@ __global__ __launch_bounds__(kSampleThreads) void select_bounds_kernel(uint32_t 
     ws->sampled = 1;
     ws->cand_cap = cand_cap;
   }
+}
+
+// Shift that maps key - lo, for keys in [lo, hi], onto kCoarseBins values.
+__device__ __forceinline__ uint32_t coarse_shift(uint32_t lo, uint32_t hi) {
+  const uint32_t span = hi - lo;
+  const uint32_t bits = span ? 32u - static_cast<uint32_t>(__builtin_clz(span)) : 0u;
+  return bits > kCoarseBits ? bits - kCoarseBits : 0u;
 }
 
 // ------------------------------------------------------------------ kernel 2
@@ -239,11 +338,13 @@ __global__ __launch_bounds__(kPartThreads) void select_partition_kernel(
   constexpr int ROWS = EF ? PR / 2 : PR;  // rows of 64 vectors per piece
   constexpr uint32_t PIECE = ROWS * kWave;               // vectors per piece
   __shared__ uint32_t s_stage[kPartWaves][kPartStage];
+  __shared__ uint32_t s_coarse[kCoarseBins];
   __shared__ uint32_t s_taken;
   const uint32_t lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const uint32_t wg = blockIdx.x;
   const uint32_t lo = ws->lo, hi = ws->hi;
+  const uint32_t cshift = coarse_shift(lo, hi);
   const uint32_t region_cap = ws->cand_cap / kCandRegions;
   unsigned long long* region_count = &ws->counts[wg % kCandRegions].c;
   uint32_t* region_keys = ws->cand + static_cast<size_t>(wg % kCandRegions) * region_cap;
@@ -251,6 +352,7 @@ __global__ __launch_bounds__(kPartThreads) void select_partition_kernel(
   uint32_t staged = 0, above = 0;
   __shared__ uint32_t s_cnt[kPartWaves], s_abv[kPartWaves], s_base;
   if (threadIdx.x == 0) s_taken = 0;
+  if (threadIdx.x < kCoarseBins) s_coarse[threadIdx.x] = 0;
   __syncthreads();
 
   // Mid-chunk flush of one wavefront's staging region (only when it fills up).
@@ -300,7 +402,11 @@ __global__ __launch_bounds__(kPartThreads) void select_partition_kernel(
         uint32_t slot = staged + before;
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
-          if ((c_bits >> e) & 1u) stage[slot++] = raw[e] & E::kKeyMask;
+          if ((c_bits >> e) & 1u) {
+            const uint32_t key = raw[e] & E::kKeyMask;
+            stage[slot++] = key;
+            atomicAdd(&s_coarse[(key - lo) >> cshift], 1u);  // the candidates' first radix pass, on the way
+          }
         }
       }
       staged += n_c;
@@ -403,6 +509,12 @@ __global__ __launch_bounds__(kPartThreads) void select_partition_kernel(
   for (int w = 0; w < wave; ++w) base += s_cnt[w];
   for (uint32_t i = lane; i < staged; i += kWave)
     if (base + i < region_cap) region_keys[base + i] = stage[i];
+  // (the barriers above have waited for every wavefront's last LDS add)
+  if (threadIdx.x < kCoarseBins) {
+    const uint32_t c = s_coarse[threadIdx.x];
+    if (c != 0)
+      __hip_atomic_fetch_add(&ws->coarse[wg % kCoarseCopies][threadIdx.x], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 // ------------------------------------------------------------------ kernel 3
@@ -446,7 +558,7 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
   constexpr int V = E::kVec;
   __shared__ uint32_t h[kSelBins];
   __shared__ uint32_t s_tmp[kTailThreads / kWave + 4];
-  __shared__ uint32_t s_tot[3];
+  __shared__ uint32_t s_tot[3], s_cb[3];
   __shared__ uint32_t s_arrived;
   const uint32_t span = kTailThreads * kSelUnroll;  // vectors per workgroup per iteration
   const uint32_t region_cap = ws->cand_cap / kCandRegions;
@@ -508,6 +620,43 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
     range_span = held ? ws->hi - lo_key : E::kKeyMask;
     st.rem_bits = range_span ? 32u - __builtin_clz(range_span) : 0u;
     st.prefix = 0u;
+    if (st.from_cand) {  // uniform
+      // The partition pass has histogrammed the top kCoarseBits bits of the candidates (of key - lo): walk
+      // that histogram from the top (the first wavefront, four bins per lane) and fix those bits at once.
+      const uint32_t cshift = st.rem_bits > kCoarseBits ? st.rem_bits - kCoarseBits : 0u;  // = coarse_shift(lo, hi)
+      if (threadIdx.x < kWave) {
+        static_assert(kCoarseBins == 4 * kWave, "four bins per lane");
+        uint32_t c[4], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          c[j] = 0;
+#pragma unroll
+          for (uint32_t q = 0; q < kCoarseCopies; ++q) c[j] += ws->coarse[q][kCoarseBins - 1 - (threadIdx.x * 4 + j)];
+          sum += c[j];
+        }
+        const uint32_t incl = wave_prefix_sum(sum);
+        uint32_t above = incl - sum;
+        if (above < st.k_rem && st.k_rem <= incl) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (above < st.k_rem && st.k_rem <= above + c[j]) {
+              s_cb[0] = kCoarseBins - 1 - (threadIdx.x * 4 + j);
+              s_cb[1] = above;
+              s_cb[2] = c[j];
+              above = 0xFFFFFFFFu;
+            } else if (above != 0xFFFFFFFFu) {
+              above += c[j];
+            }
+          }
+        }
+      }
+      __syncthreads();
+      st.prefix = s_cb[0] << cshift;
+      st.k_rem -= s_cb[1];
+      st.n_gt += s_cb[1];
+      st.last_count = s_cb[2];
+      st.rem_bits = cshift;
+    }
     st.width = min(kDigitBits, st.rem_bits);
   }
   // Workgroups that take part (the same number in every workgroup's view: it decides the barriers).
@@ -521,6 +670,117 @@ __global__ __launch_bounds__(kTailThreads) void select_tail_kernel(
                    : min(st.rem_bits <= kDigitBits ? gridDim.x : min(gridDim.x, kTailWaiters), (src_vecs + span - 1) / span);
   if (blockIdx.x >= n_active) return;
   bool finisher = blockIdx.x == 0;  // writes the result
+
+  // ---- the short way.  The coarse histogram has left one bin of the candidates; when that bin holds few
+  // keys (the rule: a few thousand of c4's 1.6 million candidates) every workgroup hands the keys of its
+  // region that fall into the bin to a common list, and the workgroup that arrives last selects among them on
+  // its own, in LDS, however many bits are left: no grid barrier, no histogram merged through memory.  (Keys
+  // and the arrival are returning agent-scope atomics, so a key has been performed before its workgroup's
+  // arrival is.)  A bin with more keys than the list holds -- ties, coarse data -- takes the passes below.
+  if (st.from_cand && st.rem_bits != 0 && st.last_count <= kFinalCap) {  // uniform over the grid
+    const uint32_t fixed_all = ~((1u << st.rem_bits) - 1u);
+    const uint32_t prefix = st.prefix;
+    const uint32_t low_mask = (1u << st.rem_bits) - 1u;
+    constexpr int kFinalPer = kFinalCap / kTailThreads;
+    __shared__ uint32_t s_base;
+    // this workgroup's keys in the bin: count, place, append
+    auto for_each_key = [&](auto&& f) {
+      for (uint32_t region = blockIdx.x; region < kCandRegions; region += n_active) {
+        const uint4* cv = reinterpret_cast<const uint4*>(ws->cand + static_cast<size_t>(region) * region_cap);
+        const bool first = region == blockIdx.x;  // its head is in registers
+        const uint32_t n_src = first ? cnt0 : min(static_cast<uint32_t>(ws->counts[region].c), region_cap);
+        const uint32_t reg_vecs = (n_src + 3) / 4;
+        if (first) {
+#pragma unroll
+          for (int u = 0; u < kTailKeep; ++u) {
+            f(keep[u].x);
+            f(keep[u].y);
+            f(keep[u].z);
+            f(keep[u].w);
+          }
+        }
+        for (uint32_t vi = (first ? kTailKeep * kTailThreads : 0u) + threadIdx.x; vi < reg_vecs; vi += kTailThreads) {
+          const uint4 v = offset_keys(cv[vi], vi, n_src, lo_key);
+          f(v.x);
+          f(v.y);
+          f(v.z);
+          f(v.w);
+        }
+      }
+    };
+    uint32_t mine = 0;
+    for_each_key([&](uint32_t key) { mine += (key & fixed_all) == prefix ? 1u : 0u; });
+    const uint32_t incl = wave_prefix_sum(mine);
+    if (lane_id() == kWave - 1) s_tmp[threadIdx.x / kWave] = incl;
+    __syncthreads();
+    uint32_t before = incl - mine, total = 0;
+    for (uint32_t w = 0; w < kTailThreads / kWave; ++w) {
+      const uint32_t c = s_tmp[w];
+      before += w < threadIdx.x / kWave ? c : 0u;
+      total += c;
+    }
+    if (threadIdx.x == 0) s_base = total ? add_agent(&ws->final_count, total) : 0u;
+    // The keys go out in two steps: into a list in LDS at their ranks, then one key per thread and round from
+    // that list to the common list.  (A thread that appends its own matches one after the other waits a
+    // memory round trip for each returning atomic: 6 us on c4, where some threads hold four.)
+    uint32_t seen = 0;
+    for (uint32_t done = 0; done < total; done += kSelBins) {  // uniform; one round unless ties abound
+      __syncthreads();  // s_base is set; h is free
+      uint32_t rank = before;
+      for_each_key([&](uint32_t key) {
+        if ((key & fixed_all) == prefix) {
+          if (rank >= done && rank < done + kSelBins) h[rank - done] = key & low_mask;
+          ++rank;
+        }
+      });
+      __syncthreads();
+      const uint32_t chunk = min(total - done, static_cast<uint32_t>(kSelBins));
+      for (uint32_t i = threadIdx.x; i < chunk; i += kTailThreads) {
+        const uint32_t pos = s_base + done + i;
+        if (pos < kFinalCap)
+          seen += __hip_atomic_exchange(&ws->final_keys[pos], h[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::"v"(seen) : "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) s_arrived = add_agent(&ws->final_arrived, 1u) + 1u;
+    __syncthreads();
+    if (s_arrived < n_active) return;  // uniform: another workgroup arrives last
+
+    // ---- the last workgroup: the k_rem-th largest of the listed keys, radix passes in LDS
+    const uint32_t n_final = st.last_count;  // exactly what the coarse histogram counted in the bin
+    uint32_t fk[kFinalPer];
+#pragma unroll
+    for (int j = 0; j < kFinalPer; ++j) {
+      const uint32_t i = j * kTailThreads + threadIdx.x;
+      fk[j] = i < n_final ? ld_agent(&ws->final_keys[i]) : 0xFFFFFFFFu;  // fillers match no prefix
+    }
+    uint32_t rem = st.rem_bits, low_prefix = 0, k_rem = st.k_rem, n_gt = st.n_gt, count = n_final;
+    while (rem != 0) {  // uniform
+      const uint32_t width = min(kDigitBits, rem);
+      const uint32_t shift = rem - width;
+      const uint32_t fixed = ~((1u << rem) - 1u);
+      for (int i = threadIdx.x; i < kSelBins; i += kTailThreads) h[i] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < kFinalPer; ++j)
+        hist_add(h, (fk[j] & fixed) == low_prefix, (fk[j] >> shift) & ((1u << width) - 1u));
+      __syncthreads();
+      const BinHit hit = find_bin<kTailThreads>([&](uint32_t b) { return h[b]; }, k_rem, s_tmp);
+      low_prefix |= hit.bin << shift;
+      k_rem -= hit.above;
+      n_gt += hit.above;
+      count = hit.count;
+      rem = shift;
+    }
+    if (threadIdx.x == 0) {
+      out->tau_key = (st.prefix | low_prefix) + range_lo;
+      out->n_gt = n_gt;
+      out->n_eq = count;
+      out->tie_quota = k_rem;
+    }
+    return;
+  }
 
   for (int pass = 0; pass < n_pass && st.width != 0; ++pass) {  // uniform over the grid
     const uint32_t shift = st.rem_bits - st.width;
@@ -701,10 +961,32 @@ uint32_t tail_grid() {
   return grid;
 }
 
-// Room for the keys between the sample bounds: about 10 sqrt(p (1 - p) / 16384) of the vector when a
-// fraction p is kept, i.e. at most 4 % (p = 1/2).
+// Room for the keys between the sample bounds.  The bounds are 5 standard deviations of the sample count on
+// either side of rank k, so about 10 sqrt(p (1 - p) / 16384) of the vector lies between them when a fraction
+// p is kept: at most 4 % (p = 1/2).  cand_capacity(n) serves any k; cand_capacity_for(n, k) is twice the
+// expected number for this k plus slack (0.6 % of c4 is expected, 1.4 % + 64 Ki keys are asked for).  A buffer
+// that turns out too small costs time, not exactness (the passes then run over the vector).
 uint32_t cand_capacity(uint64_t n) {
   return n >= kSampleMinN ? static_cast<uint32_t>(n / 16 + 65536) & ~(4u * kCandRegions - 1u) : 0u;
+}
+uint32_t cand_capacity_for(uint64_t n, uint64_t k) {
+  if (n < kSampleMinN) return 0u;
+  const uint64_t r = k * kSampleSize / n;  // the same arithmetic as the kernel that brackets the sample
+  const uint64_t var = r * (kSampleSize - r) / kSampleSize;
+  uint64_t sq = 0;
+  while ((sq + 1) * (sq + 1) <= var) ++sq;
+  const uint64_t window = 2 * (5 * (sq + 1) + 8) + 1;  // sample ranks between the bounds
+  const uint64_t want = 2 * (n / kSampleSize + 1) * window + 65536;
+  const uint64_t rounded = (want + 4u * kCandRegions - 1u) & ~static_cast<uint64_t>(4u * kCandRegions - 1u);
+  return static_cast<uint32_t>(std::min<uint64_t>(rounded, cand_capacity(n)));
+}
+
+// Tag of a call (see SelWs::sample): unique within the process, starting from a value that differs
+// from process to process.
+uint32_t next_call_tag() {
+  static std::atomic<uint32_t> counter{static_cast<uint32_t>(
+      std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761ull >> 16)};
+  return counter.fetch_add(1, std::memory_order_relaxed);
 }
 
 }  // namespace
@@ -715,6 +997,11 @@ using namespace dct;
 extern "C" size_t dct_select_threshold_workspace_bytes(int dt, uint64_t n) {
   if ((dt != DCT_F32 && dt != DCT_BF16) || n == 0 || n > 0x7FFFFFFFull) return 0;
   return sizeof(SelWs) + static_cast<size_t>(cand_capacity(n)) * 4;
+}
+
+extern "C" size_t dct_select_threshold_workspace_bytes_for(int dt, uint64_t n, uint64_t k) {
+  if ((dt != DCT_F32 && dt != DCT_BF16) || n == 0 || n > 0x7FFFFFFFull || k == 0 || k > n) return 0;
+  return sizeof(SelWs) + static_cast<size_t>(cand_capacity_for(n, k)) * 4;
 }
 
 namespace {
@@ -730,11 +1017,15 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
   const uintptr_t eaddr = reinterpret_cast<uintptr_t>(e);
   // both vectors are walked with the same 16-byte vectors: same offset within 16 bytes
   if (ef && (dt != DCT_F32 || !is_aligned(e, es) || (eaddr & 15) != (addr & 15))) return DCT_ERR_INVALID;
-  const uint32_t cand_cap = cand_capacity(n);
-  if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < sizeof(SelWs) + static_cast<size_t>(cand_cap) * 4)
-    return DCT_ERR_WORKSPACE;
+  // the candidate buffer: whatever the workspace offers beyond the fixed part, between what this k needs and
+  // what any k needs
+  if (!d_ws || !is_aligned(d_ws, 256) || ws_bytes < sizeof(SelWs)) return DCT_ERR_WORKSPACE;
+  const uint64_t offered = ((ws_bytes - sizeof(SelWs)) / 4) & ~static_cast<uint64_t>(4u * kCandRegions - 1u);
+  if (offered < cand_capacity_for(n, k)) return DCT_ERR_WORKSPACE;
+  const uint32_t cand_cap = static_cast<uint32_t>(std::min<uint64_t>(offered, cand_capacity(n)));
 
   const int vec = dt == DCT_F32 ? 4 : 8;
+  const uint32_t spin_limit = wait_limit();  // polls of a device-side wait (by default about a second) before giving up
   auto* ws = static_cast<SelWs*>(d_ws);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t n32 = static_cast<uint32_t>(n), k32 = static_cast<uint32_t>(k);
@@ -758,20 +1049,18 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
     if (blocks == 0) blocks = 1;
     const uint32_t max_grid = static_cast<uint32_t>(device_cu_count());
     geo.grid = blocks < max_grid ? blocks : max_grid;
-    const dim3 ggrid(kSampleSize / kGatherThreads), gblock(kGatherThreads), pgrid(geo.grid), pblock(kPartThreads);
+    const dim3 sgrid(kSampleSize / kSampleThreads), sblock(kSampleThreads), pgrid(geo.grid), pblock(kPartThreads);
+    const uint32_t tag = next_call_tag();
     if (ef) {
-      hipLaunchKernelGGL((select_gather_kernel<DCT_F32, true>), ggrid, gblock, 0, s, g32, e32, n32, ws);
-      hipLaunchKernelGGL((select_bounds_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_sample_kernel<DCT_F32, true>), sgrid, sblock, 0, s, g32, e32, n32, k32, ws, cand_cap, tag, spin_limit);
       if (large) hipLaunchKernelGGL((select_partition_kernel<DCT_F32, true, kPartRowsLarge>), pgrid, pblock, 0, s, g32, e32, geo, ws);
       else hipLaunchKernelGGL((select_partition_kernel<DCT_F32, true, kPartRowsSmall>), pgrid, pblock, 0, s, g32, e32, geo, ws);
     } else if (dt == DCT_F32) {
-      hipLaunchKernelGGL((select_gather_kernel<DCT_F32, false>), ggrid, gblock, 0, s, g32, nullptr, n32, ws);
-      hipLaunchKernelGGL((select_bounds_kernel<DCT_F32>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_sample_kernel<DCT_F32, false>), sgrid, sblock, 0, s, g32, nullptr, n32, k32, ws, cand_cap, tag, spin_limit);
       if (large) hipLaunchKernelGGL((select_partition_kernel<DCT_F32, false, kPartRowsLarge>), pgrid, pblock, 0, s, g32, nullptr, geo, ws);
       else hipLaunchKernelGGL((select_partition_kernel<DCT_F32, false, kPartRowsSmall>), pgrid, pblock, 0, s, g32, nullptr, geo, ws);
     } else {
-      hipLaunchKernelGGL((select_gather_kernel<DCT_BF16, false>), ggrid, gblock, 0, s, g16, nullptr, n32, ws);
-      hipLaunchKernelGGL((select_bounds_kernel<DCT_BF16>), dim3(1), dim3(kSampleThreads), 0, s, n32, k32, ws, cand_cap);
+      hipLaunchKernelGGL((select_sample_kernel<DCT_BF16, false>), sgrid, sblock, 0, s, g16, nullptr, n32, k32, ws, cand_cap, tag, spin_limit);
       if (large) hipLaunchKernelGGL((select_partition_kernel<DCT_BF16, false, kPartRowsLarge>), pgrid, pblock, 0, s, g16, nullptr, geo, ws);
       else hipLaunchKernelGGL((select_partition_kernel<DCT_BF16, false, kPartRowsSmall>), pgrid, pblock, 0, s, g16, nullptr, geo, ws);
     }
@@ -786,7 +1075,6 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
   const void* g_al = reinterpret_cast<const void*>(addr & ~static_cast<uintptr_t>(15));
   const void* e_al = reinterpret_cast<const void*>(eaddr & ~static_cast<uintptr_t>(15));
   const PassDigits dg = pass_digits(dt);
-  const uint32_t spin_limit = wait_limit();  // polls of a grid barrier (by default about a second) before giving up
   const uint32_t tgrid = ef ? tail_grid<DCT_F32, true>()
                             : dt == DCT_F32 ? tail_grid<DCT_F32, false>() : tail_grid<DCT_BF16, false>();
   if (tgrid == 0) return DCT_ERR_HIP;

@@ -49,6 +49,9 @@ def test_host_side_argument_checks_need_no_gpu():
     small = m.dct_select_threshold_workspace_bytes(m.DCT_F32, 1 << 20)
     big = m.dct_select_threshold_workspace_bytes(m.DCT_F32, 1 << 28)
     assert 0 < small < big <= (1 << 28) * 4 // 15  # a candidate buffer of 1/16 of the vector plus a fixed part
+    for_k = m.dct_select_threshold_workspace_bytes_for(m.DCT_F32, 1 << 28, 1342178)   # 0.5 % kept
+    assert small < for_k < big // 3 and m.dct_select_threshold_workspace_bytes_for(m.DCT_F32, 1 << 28, 0) == 0
+    assert m.dct_select_threshold_workspace_bytes_for(m.DCT_F32, 1 << 28, 1 << 27) == big       # half kept: the worst case
     # null pointers and bad sizes are rejected before anything is enqueued
     assert lib.dct_select_threshold(None, 0, 10, 1, None, None, 0, None) == 1
     assert lib.dct_threshold_compact(None, 0, 10, None, 0, None, None, 0, None, None, 0, None) == 1
