@@ -40,13 +40,13 @@ HBM_PEAK_GBPS = 8000.0
 
 # kernels behind each timed call (names as rocprofv3 prints them) and launches per call
 CALL_KERNELS = {
-    "dct_select_threshold[c4]": [("dct::select_gather_kernel<0, false>", 1), ("dct::select_bounds_kernel<0>", 1),
+    "dct_select_threshold[c4]": [("dct::select_sample_kernel<0, false>", 1),
                                  ("dct::select_partition_kernel<0, false, 8>", 1),
                                  ("dct::select_tail_kernel<0, false>", 1)],
     "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false>", 1)],
     "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 0, false, 16>", 1)],
     "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_rows_kernel<unsigned short, int>", 1)],
-    "dct_ef_select_threshold[c4]": [("dct::select_gather_kernel<0, true>", 1), ("dct::select_bounds_kernel<0>", 1),
+    "dct_ef_select_threshold[c4]": [("dct::select_sample_kernel<0, true>", 1),
                                     ("dct::select_partition_kernel<0, true, 8>", 1),
                                     ("dct::select_tail_kernel<0, true>", 1)],
     "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true>", 1)],
@@ -471,7 +471,7 @@ def main():
         log("[bench] c3 reuse loop skipped: not enough free HBM")
 
     # The dominant KERNEL of the step: among the step's calls that are one launch each, the longest.  (The
-    # selection call is four launches; its largest kernel, the partition pass, is shorter than the
+    # selection call is three launches; its largest kernel, the partition pass, is shorter than the
     # compaction kernel -- see profiles/bench_kernel_trace.txt -- and the call as a whole is reported
     # in `calls` and, flat, below.)
     with_traffic = not (args.no_traffic or args.small)
