@@ -417,7 +417,18 @@ def main():
     us_copy = time_calls(lambda i: bench_probes.probe_copy(probe_dst, probe_src[: probe_bytes // 2]), 10)
     probes = {"read_GBps": round(probe_bytes / (us_read * 1e-6) / 1e9, 1),
               "copy_GBps": round(probe_bytes / (us_copy * 1e-6) / 1e9, 1)}
-    del probe_src, probe_dst
+    # the traffic of the forward row kernel with none of its work: 8 KiB rows read by one wavefront each (the next
+    # row in flight), k (index, value) pairs' worth of bytes written per row.  Even a few per cent of writes mixed
+    # into a read stream cost this chip far more than their bytes (see the rows_* figures against read_GBps).
+    rows5 = (512 << 20) // shrink // 8192
+    out5 = (k5 * 6 + 15) // 16 * 16
+    row_src = probe_src[: rows5 * 8192]
+    us_rows0 = time_calls(lambda i: bench_probes.probe_rows(row_src, 8192, probe_dst, 0, sink), 10)
+    us_rows = time_calls(lambda i: bench_probes.probe_rows(row_src, 8192, probe_dst, out5, sink), 10)
+    probes["rows_c5_read_only_us"] = round(us_rows0, 2)
+    probes["rows_c5_read_write_us"] = round(us_rows, 2)
+    probes["rows_c5_write_bytes_per_row"] = out5
+    del probe_src, probe_dst, row_src
     for c in calls + ef_calls + rx_calls + bm_calls:
         c["frac_of_probe_read"] = round(c["GBps"] / probes["read_GBps"], 4)
         log(f"[bench] {c['call']}: {c['us']} us, {c['GBps']} GB/s = {c['frac_of_hbm_peak']:.1%} of 8 TB/s")
@@ -494,6 +505,9 @@ def main():
             roofline[key + "_us"] = by_name[name]["us"]
             roofline[key + "_frac"] = by_name[name]["frac_of_hbm_peak"]
     roofline["bwd_c5_frac_strict"] = by_name["dct_rowtopk_bwd[c5]"]["frac_of_hbm_peak_strict"]
+    # the forward call against a kernel that only moves its bytes (probes: rows_c5_read_write_us)
+    roofline["fwd_c5_traffic_only_us"] = probes["rows_c5_read_write_us"]
+    roofline["fwd_c5_frac_of_traffic_only"] = round(probes["rows_c5_read_write_us"] / by_name["dct_rowtopk_fwd[c5]"]["us"], 4)
     for c in calls[:4] + ef_calls + rx_calls + bm_calls + i16_calls:
         c["traffic"] = measured_traffic(c["call"], table) if with_traffic else None
 

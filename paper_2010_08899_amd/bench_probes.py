@@ -22,6 +22,9 @@ def lib() -> ctypes.CDLL:
         handle.dct_bench_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         handle.dct_bench_probe_copy.restype = ctypes.c_int
         handle.dct_bench_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        handle.dct_bench_probe_rows.restype = ctypes.c_int
+        handle.dct_bench_probe_rows.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p,
+                                                ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]
         _lib = handle
     return _lib
 
@@ -41,3 +44,16 @@ def probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     rc = lib().dct_bench_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _stream())
     if rc != 0:
         raise RuntimeError(f"dct_bench_probe_copy: status {rc}")
+
+
+def probe_rows(src: torch.Tensor, chunk_bytes: int, dst: torch.Tensor, out_bytes: int, sink: torch.Tensor) -> None:
+    """Read `src` in chunks of `chunk_bytes` (one wavefront per chunk, next chunk in flight) and write
+    `out_bytes` per chunk to consecutive places of `dst`: the traffic of a row kernel without its work."""
+    nbytes = src.numel() * src.element_size()
+    chunks = nbytes // chunk_bytes
+    if chunks * out_bytes > dst.numel() * dst.element_size():
+        raise ValueError("dst too small")
+    rc = lib().dct_bench_probe_rows(src.data_ptr(), chunks, chunk_bytes, dst.data_ptr(), out_bytes, sink.data_ptr(),
+                                    _stream())
+    if rc != 0:
+        raise RuntimeError(f"dct_bench_probe_rows: status {rc}")

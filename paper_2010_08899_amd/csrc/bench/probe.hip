@@ -5,7 +5,12 @@
 //   dct_bench_probe_read: sums `bytes` (multiple of 16, 16-byte aligned) as uint32 words,
 //                         writes one uint32 per workgroup into d_sink (>= 16384 bytes).
 //   dct_bench_probe_copy: copies `bytes` (multiple of 16) from d_src to d_dst.
-// Both return a dct_status.
+//   dct_bench_probe_rows: the memory traffic of a row kernel and nothing else: `chunks` consecutive chunks of
+//                         `chunk_bytes` (1024 * {1, 2, 4, 8, 16}) are read, one wavefront per chunk with the
+//                         next chunk in flight, and `out_bytes` (multiple of 16, <= chunk_bytes) are written
+//                         per chunk to consecutive places of d_dst.  What a read stream with a small write
+//                         stream mixed in can reach on this chip (it is well below a pure read).
+// All return a dct_status.
 #include "dct_common.hpp"
 
 namespace dct {
@@ -45,6 +50,35 @@ __global__ __launch_bounds__(kPrThreads) void probe_copy_kernel(uint4* __restric
   if (i < n_vec) dst[i] = ld_stream(&src[i]);
 }
 
+// NV 16-byte vectors per lane and chunk; 16 wavefronts per workgroup, one workgroup per CU.
+template <int NV>
+__global__ __launch_bounds__(1024) void probe_rows_kernel(const uint4* __restrict__ src, uint64_t chunks,
+                                                          uint4* __restrict__ dst, uint32_t out_vecs,
+                                                          uint32_t* __restrict__ sink) {
+  const uint32_t lane = lane_id(), wave = threadIdx.x / kWave;
+  const uint64_t step = static_cast<uint64_t>(gridDim.x) * 16;
+  uint64_t c = static_cast<uint64_t>(blockIdx.x) * 16 + wave;
+  uint4 v[NV], w[NV];
+  uint32_t acc = 0;
+  if (c < chunks) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j) v[j] = ld_stream(&src[c * (NV * kWave) + j * kWave + lane]);
+  }
+  for (; c < chunks; c += step) {
+    const uint64_t nc = c + step;
+    if (nc < chunks) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j) w[j] = ld_stream(&src[nc * (NV * kWave) + j * kWave + lane]);
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    for (uint32_t q = lane; q < out_vecs; q += kWave) dst[c * out_vecs + q] = make_uint4(acc, acc, acc, acc);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) v[j] = w[j];
+  }
+  if (acc == 0x9E3779B9u) sink[0] = acc;  // keeps the loads when nothing is written
+}
+
 uint32_t probe_grid(uint64_t n_vec) {
   const uint64_t span = static_cast<uint64_t>(kPrThreads) * kPrUnroll;
   uint64_t g = (n_vec + span - 1) / span;
@@ -75,5 +109,27 @@ extern "C" int dct_bench_probe_copy(void* d_dst, const void* d_src, size_t bytes
   hipLaunchKernelGGL(probe_copy_kernel, dim3(static_cast<uint32_t>((n_vec + kPrThreads - 1) / kPrThreads)), dim3(kPrThreads), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<uint4*>(d_dst),
                      static_cast<const uint4*>(d_src), n_vec);
+  return hipGetLastError() == hipSuccess ? DCT_OK : DCT_ERR_HIP;
+}
+
+extern "C" int dct_bench_probe_rows(const void* d_src, uint64_t chunks, uint32_t chunk_bytes, void* d_dst,
+                                    uint32_t out_bytes, void* d_sink, void* hip_stream) {
+  if (!d_src || !d_dst || !d_sink || chunks == 0 || (out_bytes & 15) || out_bytes > chunk_bytes ||
+      !is_aligned(d_src, 16) || !is_aligned(d_dst, 16) || !is_aligned(d_sink, 4))
+    return DCT_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const dim3 grid(static_cast<uint32_t>(device_cu_count())), block(1024);
+  const auto* src = static_cast<const uint4*>(d_src);
+  auto* dst = static_cast<uint4*>(d_dst);
+  auto* sink = static_cast<uint32_t*>(d_sink);
+  const uint32_t ov = out_bytes / 16;
+  switch (chunk_bytes) {
+    case 1024: hipLaunchKernelGGL(probe_rows_kernel<1>, grid, block, 0, s, src, chunks, dst, ov, sink); break;
+    case 2048: hipLaunchKernelGGL(probe_rows_kernel<2>, grid, block, 0, s, src, chunks, dst, ov, sink); break;
+    case 4096: hipLaunchKernelGGL(probe_rows_kernel<4>, grid, block, 0, s, src, chunks, dst, ov, sink); break;
+    case 8192: hipLaunchKernelGGL(probe_rows_kernel<8>, grid, block, 0, s, src, chunks, dst, ov, sink); break;
+    case 16384: hipLaunchKernelGGL(probe_rows_kernel<16>, grid, block, 0, s, src, chunks, dst, ov, sink); break;
+    default: return DCT_ERR_INVALID;
+  }
   return hipGetLastError() == hipSuccess ? DCT_OK : DCT_ERR_HIP;
 }

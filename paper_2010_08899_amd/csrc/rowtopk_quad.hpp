@@ -11,8 +11,9 @@
 // is held per lane, equal within a row.
 //
 // The search for tau_i is the windowed one of the wide kernel: the row four rows earlier (the
-// same slot of the previous group) predicts a window of 32 key values; two compare sweeps give
-// the bitmaps at its ends, the keys inside it are histogrammed (32 LDS bins per row).  The
+// same slot of the previous group) predicts a window of 32 to 128 key values (wider for narrower
+// rows, see window_width); two compare sweeps give the bitmaps at its ends, the keys inside it are
+// histogrammed (one LDS bin per key value and row, scanned by the row's 16 lanes).  The
 // prediction is a running mean of the slot's thresholds (narrow rows vary more from one to
 // the next than wide ones); a wavefront's first group predicts from a sample of each row.
 // Rows whose window misses gallop away from it and are then bracketed by bisection over the
@@ -26,7 +27,6 @@ namespace dct {
 namespace quad {
 
 using fast::kSampleRegs;
-using fast::kWindow;
 using fast::pk_add_u16;
 using fast::pk_lshr15_u16;
 using fast::pk_sub_u16;
@@ -43,6 +43,16 @@ constexpr int kRows = 4;               // rows per wavefront
 constexpr int kLanes = kWave / kRows;  // lanes per row: one DPP row
 constexpr uint32_t kMaxD = 1024;
 constexpr uint32_t kStageSlots = kWave * 8;  // survivor columns of the four rows: 4 k <= kStageSlots
+// Width of the prediction window in key values.  The threshold of a narrow row moves more from row to row
+// (the standard deviation of the k-th largest of D keys grows like 1/sqrt(D): about 17 key values at D = 256,
+// 12 at 512, 8 at 1024 for 5 % of post-ReLU normal values), and a window that misses costs a gallop and a
+// bisection for the whole group of four rows; a wider window costs more keys to histogram.  Measured on 512 MiB
+// of rows: D = 256 229 -> 206 us with 128 key values (192 us with the second compare sweep in place of the
+// remembered bins), D = 512 153 -> 134 us with 64; D = 1024 is better off with 32 (145 us against 150 with 64).
+template <int NV>
+constexpr uint32_t window_width() {
+  return NV <= 2 ? 128u : NV == 4 ? 64u : 32u;
+}
 
 // Sum over the 16 lanes of a DPP row, delivered to every lane of the row.
 __device__ __forceinline__ uint32_t row_sum(uint32_t x) {
@@ -91,8 +101,12 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
   constexpr int kColsPerWord = 2 * RPW;
   constexpr int wB = WORDS - 1;
   constexpr int kWaves = WAVES;
+  constexpr uint32_t kWindow = window_width<NV>();
+  constexpr int kBinBits = kWindow == 128 ? 7 : kWindow == 64 ? 6 : 5;
+  constexpr int kBinsPerLane = kWindow / kLanes;  // lane s of a row scans bins [s * kBinsPerLane, ...)
+  constexpr int kListMax = 32 / kBinBits;         // window keys a stream remembers (bin numbers in one register)
   __shared__ uint4 s_row[kWaves][kWave * (NV + 1)];
-  __shared__ uint32_t s_hist[kWaves][kRows][kWindow];
+  __shared__ __attribute__((aligned(16))) uint32_t s_hist[kWaves][kRows][kWindow];
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const uint32_t lane = lane_id();
@@ -103,15 +117,15 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
 
   // 16-bit key material of local column lc of this lane
   auto key_at = [&](uint32_t lc) {
-    return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(row_lds + lane * CHUNK + lc * 2));
+    return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(row_lds + __umul24(lane, CHUNK) + lc * 2));
   };
   // the stored element of column col of row rg of the group, bit for bit
   auto raw_at = [&](uint32_t rg, uint32_t col) -> uint32_t {
-    return *reinterpret_cast<const uint16_t*>(row_lds + (rg * kLanes + col / COLS) * CHUNK + (col % COLS) * 2);
+    return *reinterpret_cast<const uint16_t*>(row_lds + __umul24(rg * kLanes + col / COLS, CHUNK) + (col % COLS) * 2);
   };
   // the 16 padding bytes of every lane chunk hold the ordered lists of surviving columns (row rg at rg * k)
   auto stage_at = [&](uint32_t slot) {
-    return reinterpret_cast<uint16_t*>(row_lds + (slot >> 3) * CHUNK + NV * 16 + (slot & 7u) * 2);
+    return reinterpret_cast<uint16_t*>(row_lds + __umul24(slot >> 3, CHUNK) + NV * 16 + (slot & 7u) * 2);
   };
 
   constexpr uint32_t kNone = 0xFFFFFFFFu;
@@ -152,7 +166,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const uint32_t q = j * kLanes + s;
-      *reinterpret_cast<uint4*>(row_lds + (g * kLanes + q / NV) * CHUNK + (q % NV) * 16) = nxt[j];
+      *reinterpret_cast<uint4*>(row_lds + __umul24(g * kLanes + q / NV, CHUNK) + (q % NV) * 16) = nxt[j];
     }
     wave_lds_fence();
     next_grp = take_group();
@@ -160,7 +174,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
     uint32_t R[4 * NV];
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
-      const uint4 v = *reinterpret_cast<const uint4*>(row_lds + lane * CHUNK + m * 16);
+      const uint4 v = *reinterpret_cast<const uint4*>(row_lds + __umul24(lane, CHUNK) + m * 16);
       R[4 * m + 0] = v.x;
       R[4 * m + 1] = v.y;
       R[4 * m + 2] = v.z;
@@ -293,13 +307,21 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
       window_at(hit ? wlo : lo_u * kWindow);  // a row that had hit gets its window again
     }
 
-    // histogram of the keys inside the window: bin = key - wlo, 32 bins per row
-    s_hist[wave][lane / 32][lane % 32] = 0;
-    s_hist[wave][2 + lane / 32][lane % 32] = 0;
+    // histogram of the keys inside the window: bin = key - wlo, kWindow bins per row
+    {
+      uint4* hz = reinterpret_cast<uint4*>(&s_hist[wave][0][0]);  // 16 bytes per lane and step
+      constexpr uint32_t kHistVecs = kRows * kWindow / 4;
+#pragma unroll
+      for (uint32_t i = 0; i < (kHistVecs + kWave - 1) / kWave; ++i)
+        if (i * kWave + lane < kHistVecs) hz[i * kWave + lane] = make_uint4(0, 0, 0, 0);
+    }
     wave_lds_fence();
-    uint32_t listA = 0, listB = 0;
-    bool list_full = false;
-    uint32_t n_pops = 0;
+    // Lanes with few key registers (rows of up to 256 columns) compare them with tau once more at the end;
+    // the others remember the bins of their window keys per stream, so that the second walk needs no LDS reads.
+    constexpr bool kSweepAgain = REGS <= 8;
+    [[maybe_unused]] uint32_t listA = 0, listB = 0;
+    [[maybe_unused]] bool list_full = false;
+    [[maybe_unused]] uint32_t n_pops = 0;
     {
       uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
       uint32_t sh = 0;
@@ -310,28 +332,60 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
         const uint32_t bA = (key_at(cA) & 0x7FFFu) - wlo, bB = (key_at(cB) & 0x7FFFu) - wlo;
         if (vA) atomicAdd(&hist[bA], 1u);
         if (vB) atomicAdd(&hist[bB], 1u);
-        if (sh < 30u) {
-          listA |= (vA ? bA : 0u) << sh;
-          listB |= (vB ? bB : 0u) << sh;
-        } else {
-          list_full = true;
+        if constexpr (!kSweepAgain) {
+          if (sh < static_cast<uint32_t>(kListMax * kBinBits)) {
+            listA |= (vA ? bA : 0u) << sh;
+            listB |= (vB ? bB : 0u) << sh;
+          } else {
+            list_full = true;
+          }
+          sh += kBinBits;
+          ++n_pops;
         }
-        sh += 5u;
-        ++n_pops;
       }
     }
     wave_lds_fence();
-    // lane s of a row holds bins s and 16 + s; suffix sums over the 32 bins of the row
-    const uint32_t c_lo = hist[s], c_hi = hist[kLanes + s];
-    const uint32_t suf_hi = row_suffix_scan(c_hi);
-    const uint32_t suf_lo = row_sum(c_hi) + row_suffix_scan(c_lo);
-    const uint32_t m_hi = row_ballot(n_above + suf_hi >= k, lane);
-    const uint32_t m_lo = row_ballot(n_above + suf_lo >= k, lane);  // non-empty: bin 0 reaches n_above + n_win >= k
-    const bool upper = m_hi != 0;
-    const uint32_t bstar = upper ? kLanes + (31u - __builtin_clz(m_hi)) : 31u - __builtin_clz(m_lo | 1u);
-    const int src = static_cast<int>((lane & 48u) | (bstar & 15u));
-    const uint32_t n_eq = __shfl(upper ? c_hi : c_lo, src, kWave);
-    const uint32_t sfx = __shfl(upper ? suf_hi : suf_lo, src, kWave);
+    // lane s of a row scans bins [s * kBinsPerLane, (s + 1) * kBinsPerLane): its own count, the suffix sums over
+    // the lanes of the row, and -- were the answer among its bins -- where; the highest lane that reaches k has it
+    uint32_t cb[kBinsPerLane];
+    {
+      const uint32_t* hb = hist + s * kBinsPerLane;
+      if constexpr (kBinsPerLane == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(hb);
+        cb[0] = v.x;
+        cb[1] = v.y;
+      } else {
+#pragma unroll
+        for (int q = 0; q < kBinsPerLane / 4; ++q) {
+          const uint4 v = *reinterpret_cast<const uint4*>(hb + 4 * q);
+          cb[4 * q + 0] = v.x;
+          cb[4 * q + 1] = v.y;
+          cb[4 * q + 2] = v.z;
+          cb[4 * q + 3] = v.w;
+        }
+      }
+    }
+    uint32_t lane_sum = 0;
+#pragma unroll
+    for (int j = 0; j < kBinsPerLane; ++j) lane_sum += cb[j];
+    const uint32_t suf = row_suffix_scan(lane_sum);  // window keys in this lane's bins and above
+    const uint32_t m_reach = row_ballot(n_above + suf >= k, lane);  // non-empty: lane 0 reaches n_above + n_win >= k
+    // walk this lane's bins from the top: the first one at which the count reaches k
+    uint32_t acc = n_above + suf - lane_sum, loc = 0;
+    bool found = false;
+#pragma unroll
+    for (int j = kBinsPerLane - 1; j >= 0; --j) {
+      acc += cb[j];
+      if (!found && acc >= k) {
+        found = true;
+        loc = (s * kBinsPerLane + j) | (cb[j] << 8) | ((acc - n_above) << 20);  // bin, ties, window keys at or above
+      }
+    }
+    const int src = static_cast<int>((lane & 48u) | (31u - __builtin_clz(m_reach | 1u)));
+    loc = __shfl(loc, src, kWave);
+    const uint32_t bstar = loc & 0xFFu;
+    const uint32_t n_eq = (loc >> 8) & 0xFFFu;
+    const uint32_t sfx = loc >> 20;
     const uint32_t tau = wlo + bstar;
     const uint32_t n_gt = n_above + sfx - n_eq;
     const uint32_t quota = k - n_gt;  // ties at tau to keep, lowest columns first
@@ -346,7 +400,13 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
       tie[w] = 0;
     }
     const uint32_t bs = bstar;
-    if (ballot64(list_full) == 0) {
+    if constexpr (kSweepAgain) {
+      uint32_t ge_tau[WORDS];
+      ge_bitmap(tau + 1u, keep);  // tau + 1 <= 0x8000
+      ge_bitmap(tau, ge_tau);
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) tie[w] = ge_tau[w] & ~keep[w];
+    } else if (ballot64(list_full) == 0) {
       uint32_t mA = inwin[0], mB = WORDS == 2 ? inwin[wB] : 0u;
       for (uint32_t j = 0; j < n_pops; ++j) {
         const uint32_t bitA = mA & (0u - mA);  // 0 once the stream is exhausted: contributes nothing
@@ -359,9 +419,9 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
           bitB = mA != 0 ? 0x80000000u >> __builtin_clz(mA) : 0u;
           mA ^= bitB;
         }
-        const uint32_t bA = listA & 31u, bB = listB & 31u;
-        listA >>= 5;
-        listB >>= 5;
+        const uint32_t bA = listA & (kWindow - 1u), bB = listB & (kWindow - 1u);
+        listA >>= kBinBits;
+        listB >>= kBinBits;
         keep[0] |= bA > bs ? bitA : 0u;
         tie[0] |= bA == bs ? bitA : 0u;
         keep[wB] |= bB > bs ? bitB : 0u;
@@ -450,7 +510,35 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
     {
       const uint64_t row0 = grp * kRows;
       const uint32_t rows_here = static_cast<uint32_t>(min(static_cast<uint64_t>(kRows), B - row0));
-      if (k <= kWave) {
+      // the lists of the four rows follow one another in the staging slots as their outputs do in memory: entry e
+      // of the group belongs to row e / k
+      const uint32_t n_out = rows_here * k;
+      auto write_groups = [&](auto g_tag) {
+        constexpr int G = decltype(g_tag)::value;
+        uint32_t col[G], raw[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j) col[j] = j * kWave + lane < n_out ? *stage_at(j * kWave + lane) : 0u;
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          const uint32_t e = j * kWave + lane;
+          const uint32_t r = (e >= k ? 1u : 0u) + (e >= 2u * k ? 1u : 0u) + (e >= 3u * k ? 1u : 0u);
+          raw[j] = raw_at(r, col[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          const uint32_t e = j * kWave + lane;
+          if (e < n_out) {
+            put_col<ENC>(idx_out, row0 * k + e, col[j]);
+            val_out[row0 * k + e] = static_cast<uint16_t>(raw[j]);
+          }
+        }
+      };
+      if (n_out <= kWave) {
+        write_groups(std::integral_constant<int, 1>{});
+      } else if (n_out <= 2 * kWave) {
+        write_groups(std::integral_constant<int, 2>{});
+      } else if (k <= kWave) {
+        // one round per row: the row of an entry is known without comparing
         uint32_t col[kRows], raw[kRows];
 #pragma unroll
         for (int r = 0; r < kRows; ++r) col[r] = lane < k ? *stage_at(r * k + lane) : 0u;
@@ -465,13 +553,11 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
           }
         }
       } else {
-        for (uint32_t r = 0; r < rows_here; ++r) {
-          for (uint32_t j = lane; j < k; j += kWave) {
-            const uint32_t col = *stage_at(r * k + j);
-            const uint64_t o = (row0 + r) * k + j;
-            put_col<ENC>(idx_out, o, col);
-            val_out[o] = static_cast<uint16_t>(raw_at(r, col));
-          }
+        for (uint32_t e = lane; e < n_out; e += kWave) {
+          const uint32_t col = *stage_at(e);
+          const uint32_t r = (e >= k ? 1u : 0u) + (e >= 2u * k ? 1u : 0u) + (e >= 3u * k ? 1u : 0u);
+          put_col<ENC>(idx_out, row0 * k + e, col);
+          val_out[row0 * k + e] = static_cast<uint16_t>(raw_at(r, col));
         }
       }
     }
