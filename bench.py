@@ -43,15 +43,15 @@ CALL_KERNELS = {
     "dct_select_threshold[c4]": [("dct::select_sample_kernel<0, false>", 1),
                                  ("dct::select_partition_kernel<0, false, 8>", 1),
                                  ("dct::select_tail_kernel<0, false>", 1)],
-    "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false>", 1)],
+    "dct_threshold_compact[c4,exact_k]": [("dct::compact_kernel<0, true, false, true>", 1)],
     "dct_rowtopk_fwd[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 0, false, 16>", 1)],
     "dct_rowtopk_bwd[c5]": [("dct::rowtopk_bwd_rows_kernel<unsigned short, int>", 1)],
     "dct_ef_select_threshold[c4]": [("dct::select_sample_kernel<0, true>", 1),
                                     ("dct::select_partition_kernel<0, true, 8>", 1),
                                     ("dct::select_tail_kernel<0, true>", 1)],
-    "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true>", 1)],
+    "dct_ef_threshold_compact[c4,ge_tau]": [("dct::compact_kernel<0, false, true, false>", 1)],
     "dct_scatter[c4,assign]": [("dct::scatter_assign_kernel<unsigned int>", 1)],
-    "dct_scatter[c4,add]": [("dct::scatter_pairs_kernel<unsigned int, true>", 1)],
+    "dct_scatter[c4,add]": [("dct::scatter_add4_kernel", 1)],
     "dct_rowtopk_scatter[c5]": [("dct::rowscatter_lds_kernel<unsigned short, int>", 1)],
     "dct_rowtopk_fwd_bitmask[c5]": [("dct::fast::rowtopk_fwd_onchip_kernel<8, 1, false, 16>", 1)],
     "dct_rowtopk_bwd_bitmask[c5]": [("dct::rowtopk_bwd_rows_bitmask_kernel<unsigned short>", 1)],

@@ -224,7 +224,8 @@ struct CompactGeom {
 };
 
 // EF: g is W_grad, e_in the residual E_grad (may be the same buffer as e_out), e_out the new residual.
-template <int DT, bool EXACT, bool EF>
+// EARLY: wavefront 0 looks at the lower workgroups' descriptors before the workgroup's barrier (long chunks).
+template <int DT, bool EXACT, bool EF, bool EARLY>
 __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* e_in,
     typename Elem<DT>::word_t* e_out, CompactGeom geo, const dct_threshold* __restrict__ thr,
@@ -585,6 +586,20 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
 
     // ---- 1+2: stream the chunk, stage survivors in LDS
     const uint32_t staged = pass(std::false_type{}, round == 0);
+    // An early look at the descriptors of the lower-numbered workgroups, by wavefront 0 as soon as it has run out
+    // of pieces itself (the others may still be streaming): the workgroups that finish last -- and they set the
+    // kernel's time -- find everything published and save the round trip after the barrier (1 GiB: 165 -> 162 us).
+    [[maybe_unused]] DescLoad early;
+    [[maybe_unused]] bool early_ok = false;
+    // (An instantiation of its own, chosen by the host for long chunks: on a 100 MB vector, 95 pieces per
+    // workgroup, the look gains nothing, and its mere presence in the code cost 0.4 us of 20.8.)
+    if constexpr (EARLY) {
+      if (round == 0 && wave == 0 && s_hdr[0] == kCtMagic && s_hdr[2] == 0) {
+        DescSet* sets = reinterpret_cast<DescSet*>(reinterpret_cast<char*>(hdr) + kCtHeaderBytes);
+        early.load(&sets[s_hdr[1] & 1u].wg[0], chunk);
+        early_ok = true;
+      }
+    }
     // the residual stores of this pass have landed before anything (the +0 of a delivered pair, the
     // second pass's loads) touches the same addresses again
     if constexpr (EF) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -676,8 +691,11 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
           excl = decided_prefix(round_wg, chunk, &mine_set->decision, patient, &hdr->error, commit, failed);
         }
       } else {
-        excl = prefix_of(round_wg, chunk, round ? &mine_set->round_total[round - 1] : nullptr, spin_limit,
-                         &hdr->error, failed);
+        if (early_ok && early.all_published())
+          excl = early.sum();
+        else
+          excl = prefix_of(round_wg, chunk, round ? &mine_set->round_total[round - 1] : nullptr, spin_limit,
+                           &hdr->error, failed);
       }
       excl &= kPayload;
       if (lane == 0) {
@@ -856,22 +874,26 @@ int launch_compact(const void* g, const void* e_in, void* e_out, int dt, uint64_
   const CompactGeom geo = make_geom(reinterpret_cast<uintptr_t>(g), n, dt, ef);
   const uint32_t spin_limit = wait_limit();
 
-#define DCT_LAUNCH_COMPACT(DTV, EX, EFV)                                                                        \
-  hipLaunchKernelGGL((compact_kernel<DTV, EX, EFV>), dim3(geo.grid), dim3(kCtThreads), 0, s,                    \
+  // the early look at the descriptors pays from about 512 pieces per workgroup on (error feedback decides centrally)
+  const bool early = !ef && geo.pieces / geo.grid >= 512;
+#define DCT_LAUNCH_COMPACT(DTV, EX, EFV, EAV)                                                                   \
+  hipLaunchKernelGGL((compact_kernel<DTV, EX, EFV, EAV>), dim3(geo.grid), dim3(kCtThreads), 0, s,               \
                      static_cast<const Elem<DTV>::word_t*>(g), static_cast<const Elem<DTV>::word_t*>(e_in),     \
                      static_cast<Elem<DTV>::word_t*>(e_out), geo, d_thr, d_idx_out,                             \
                      static_cast<Elem<DTV>::word_t*>(d_val_out), cap, d_count_out, hdr, spin_limit)
-#define DCT_LAUNCH_COMPACT_MODE(DTV, EFV)                \
-  do {                                                   \
-    if (exact) DCT_LAUNCH_COMPACT(DTV, true, EFV);       \
-    else DCT_LAUNCH_COMPACT(DTV, false, EFV);            \
+#define DCT_LAUNCH_COMPACT_MODE(DTV, EFV, EAV)            \
+  do {                                                    \
+    if (exact) DCT_LAUNCH_COMPACT(DTV, true, EFV, EAV);   \
+    else DCT_LAUNCH_COMPACT(DTV, false, EFV, EAV);        \
   } while (0)
   if (ef) {
-    DCT_LAUNCH_COMPACT_MODE(DCT_F32, true);
+    DCT_LAUNCH_COMPACT_MODE(DCT_F32, true, false);
   } else if (dt == DCT_BF16) {
-    DCT_LAUNCH_COMPACT_MODE(DCT_BF16, false);
+    if (early) DCT_LAUNCH_COMPACT_MODE(DCT_BF16, false, true);
+    else DCT_LAUNCH_COMPACT_MODE(DCT_BF16, false, false);
   } else {
-    DCT_LAUNCH_COMPACT_MODE(DCT_F32, false);
+    if (early) DCT_LAUNCH_COMPACT_MODE(DCT_F32, false, true);
+    else DCT_LAUNCH_COMPACT_MODE(DCT_F32, false, false);
   }
 #undef DCT_LAUNCH_COMPACT_MODE
 #undef DCT_LAUNCH_COMPACT

@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stdint.h>
 
 #include "dct.h"
@@ -132,17 +134,18 @@ inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintp
 // ceil(a / b) for any a: a + b - 1 would wrap for a close to 2^32.
 inline uint32_t ceil_div(uint32_t a, uint32_t b) { return a / b + (a % b != 0 ? 1u : 0u); }
 
-// Compute units of the current device (cached per device).
+// Compute units of the current device.  The only thing the library remembers between calls besides the wait
+// limit: a per-device cache of this device attribute (atomic words; two threads racing store the same value).
 inline int device_cu_count() {
-  static int cached[64] = {0};
+  static std::atomic<int> cached[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached[dev];
+  return n;
 }
 
 // Polls a bounded device-side wait may take before it gives up (process-wide; dct_set_wait_limit).

@@ -172,6 +172,31 @@ __global__ void scatter_pairs_kernel(const int32_t* __restrict__ idx, const W* _
   }
 }
 
+// out[idx[j]] += val[j] (fp32), four pairs per thread and step, a workgroup's 256 threads taking neighbouring
+// pairs (pair j0 + 256 u + thread): the four read-modify-writes are independent (a compaction's indices are
+// distinct), so their loads are in flight together.
+__global__ __launch_bounds__(256) void scatter_add4_kernel(const int32_t* __restrict__ idx,
+                                                           const uint32_t* __restrict__ val,
+                                                           const uint64_t* __restrict__ count, uint64_t capacity,
+                                                           uint32_t* out, uint32_t n) {
+  const uint32_t m = valid_pairs(count, capacity);
+  for (uint64_t j0 = static_cast<uint64_t>(blockIdx.x) * 1024 + threadIdx.x; j0 < m;
+       j0 += static_cast<uint64_t>(gridDim.x) * 1024) {
+    uint32_t i[4], v[4], o[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool in = j0 + 256 * u < m;
+      i[u] = in ? static_cast<uint32_t>(idx[j0 + 256 * u]) : 0xFFFFFFFFu;  // out of range: skipped below
+      v[u] = in ? val[j0 + 256 * u] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) o[u] = i[u] < n ? out[i[u]] : 0u;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i[u] < n) out[i[u]] = __float_as_uint(__uint_as_float(o[u]) + __uint_as_float(v[u]));
+  }
+}
+
 // Dense rows, one wavefront per row, the row assembled in LDS (D * sizeof(W) <= kRowLdsBytes).
 template <typename W, typename I>
 __global__ __launch_bounds__(kScThreads) void rowscatter_lds_kernel(
@@ -292,7 +317,8 @@ extern "C" int dct_scatter(const int32_t* d_idx, const void* d_val, const uint64
 
   if (mode == DCT_SCATTER_ADD) {
     if (capacity == 0) return DCT_OK;
-    hipLaunchKernelGGL((scatter_pairs_kernel<uint32_t, true>), dim3(pair_grid), dim3(256), 0, s, d_idx,
+    const uint32_t add_grid = static_cast<uint32_t>(std::min<uint64_t>(4u * kScMaxGrid, (capacity + 1023) / 1024));
+    hipLaunchKernelGGL(scatter_add4_kernel, dim3(add_grid), dim3(256), 0, s, d_idx,
                        static_cast<const uint32_t*>(d_val), d_count, capacity, static_cast<uint32_t*>(d_out), n32);
     return launch_status();
   }

@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
     # the benchmark's streaming probes are not part of the product library or its header
     assert not hasattr(raw, "dct_probe_read") and not hasattr(raw, "dct_bench_probe_read")
     bench = ctypes.CDLL(build.BENCH_LIB)
-    assert hasattr(bench, "dct_bench_probe_read") and hasattr(bench, "dct_bench_probe_copy")
+    assert all(hasattr(bench, f"dct_bench_probe_{p}") for p in ("read", "copy", "rows"))
 
 
 def test_host_side_argument_checks_need_no_gpu():
