@@ -588,26 +588,50 @@ int launch_fwd(const void* x, int dt, uint32_t B, uint32_t D, uint64_t row_strid
   if (dt == DCT_BF16 && D % 8 == 0 && D <= quad::kMaxD && 4 * k <= quad::kStageSlots &&
       B >= kQuadMinRows && is_aligned(x, 16) && row_stride_elems % 8 == 0) {
     const uint32_t vecs = D / 8;
+    const uint32_t cus = static_cast<uint32_t>(device_cu_count());
+    const auto* xq = static_cast<const uint16_t*>(x);
+    auto* vq = static_cast<uint16_t*>(d_val_out);
+    auto* tq = static_cast<uint16_t*>(d_tau_out);
+    // rows of up to 256 columns, when every wavefront of a full chip gets several groups: eight rows per wavefront
+    const uint32_t groups8 = ceil_div(B, quad::kRowsNarrow);
+    if (D <= quad::kMaxDNarrow && quad::kRowsNarrow * k <= quad::kStageSlots &&
+        groups8 >= 4u * quad::kWavesLarge * cus) {
+      const uint32_t nv8 = vecs <= 8 ? 1u : vecs <= 16 ? 2u : 4u;
+      const uint32_t qgrid8 = std::min(ceil_div(groups8, static_cast<uint32_t>(quad::kWavesLarge)), cus);
+#define DCT_LAUNCH_OCT(NVV, ENCV)                                                                               \
+  hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV, quad::kWavesLarge, quad::kRowsNarrow>),          \
+                     dim3(qgrid8), dim3(quad::kWavesLarge * kWave), 0, s, xq, B, D, row_stride_elems, k, io, vq, tq)
+#define DCT_LAUNCH_OCT_NV(ENCV)                  \
+  do {                                           \
+    if (nv8 == 1) DCT_LAUNCH_OCT(1, ENCV);       \
+    else if (nv8 == 2) DCT_LAUNCH_OCT(2, ENCV);  \
+    else DCT_LAUNCH_OCT(4, ENCV);                \
+  } while (0)
+      if (enc == kEncIdx16) DCT_LAUNCH_OCT_NV(kEncIdx16);
+      else if (enc == kEncBitmap) DCT_LAUNCH_OCT_NV(kEncBitmap);
+      else DCT_LAUNCH_OCT_NV(kEncIdx32);
+#undef DCT_LAUNCH_OCT_NV
+#undef DCT_LAUNCH_OCT
+      return launch_status();
+    }
     const uint32_t nv = vecs <= 16 ? 1u : vecs <= 32 ? 2u : vecs <= 64 ? 4u : 8u;
     const uint32_t groups = ceil_div(B, quad::kRows);
-    const uint32_t cus = static_cast<uint32_t>(device_cu_count());
     // one large workgroup per CU when each of its wavefronts gets at least four groups, else small workgroups,
     // as many per CU as registers and the LDS row buffers allow
     const bool large = groups >= 4u * quad::kWavesLarge * cus;
     const uint32_t wg_waves = large ? quad::kWavesLarge : quad::kWavesSmall;
     const uint32_t resident = large ? cus : cus * (nv == 8 ? 4u : nv == 4 ? 6u : 8u);
     const uint32_t qgrid = std::min(ceil_div(groups, wg_waves), resident);
-    const auto* xq = static_cast<const uint16_t*>(x);
-    auto* vq = static_cast<uint16_t*>(d_val_out);
-    auto* tq = static_cast<uint16_t*>(d_tau_out);
 #define DCT_LAUNCH_QUAD(NVV, ENCV)                                                                              \
   do {                                                                                                          \
     if (large)                                                                                                  \
-      hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV, quad::kWavesLarge>), dim3(qgrid),             \
-                         dim3(quad::kWavesLarge * kWave), 0, s, xq, B, D, row_stride_elems, k, io, vq, tq);     \
+      hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV, quad::kWavesLarge, quad::kRows>),            \
+                         dim3(qgrid), dim3(quad::kWavesLarge * kWave), 0, s, xq, B, D, row_stride_elems, k, io, \
+                         vq, tq);                                                                               \
     else                                                                                                        \
-      hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV, quad::kWavesSmall>), dim3(qgrid),             \
-                         dim3(quad::kWavesSmall * kWave), 0, s, xq, B, D, row_stride_elems, k, io, vq, tq);     \
+      hipLaunchKernelGGL((quad::rowtopk_fwd_quad_kernel<NVV, ENCV, quad::kWavesSmall, quad::kRows>),            \
+                         dim3(qgrid), dim3(quad::kWavesSmall * kWave), 0, s, xq, B, D, row_stride_elems, k, io, \
+                         vq, tq);                                                                               \
   } while (0)
 #define DCT_LAUNCH_QUAD_NV(ENCV)                  \
   do {                                            \

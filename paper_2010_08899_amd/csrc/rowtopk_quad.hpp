@@ -1,23 +1,24 @@
 // Forward kernel of dct_rowtopk_fwd (Algorithm 2, forward loop: per row the k largest
-// |X_act,i|) for NARROW bf16 rows: up to 1024 columns, four rows per wavefront.
+// |X_act,i|) for NARROW bf16 rows: up to 1024 columns, four or eight rows per wavefront.
 //
 // The one-row-per-wavefront kernel (rowtopk_fast.hpp) spends about 250 vector instructions
 // per row on work that does not depend on the row's width (wave scans, the walks over the
 // window keys and the survivors, the output code), which is what limits it below 2048
 // columns.  Here every row of a group of four consecutive rows lives on one DPP row of 16
-// lanes: the per-lane work (packed 16-bit compares, bitmaps, bit walks) is the same code, the
-// per-row reductions and scans are DPP operations inside the 16 lanes, and the fixed work is
-// paid once per four rows.  What is uniform per row (the threshold, the counts, the window)
-// is held per lane, equal within a row.
+// lanes -- or, for rows of up to 256 columns when there are very many of them, every row of a
+// group of eight on half a DPP row: the per-lane work (packed 16-bit compares, bitmaps, bit
+// walks) is the same code, the per-row reductions and scans are DPP operations inside the
+// row's lanes, and the fixed work is paid once per group.  What is uniform per row (the
+// threshold, the counts, the window) is held per lane, equal within a row.
 //
-// The search for tau_i is the windowed one of the wide kernel: the row four rows earlier (the
-// same slot of the previous group) predicts a window of 32 to 128 key values (wider for narrower
-// rows, see window_width); two compare sweeps give the bitmaps at its ends, the keys inside it are
-// histogrammed (one LDS bin per key value and row, scanned by the row's 16 lanes).  The
+// The search for tau_i is the windowed one of the wide kernel: the row in the same slot of the
+// previous group predicts a window of 32 to 128 key values (wider for narrower rows, see
+// window_width); two compare sweeps give the bitmaps at its ends, the keys inside it are
+// histogrammed (one LDS bin per key value and row, scanned by the row's lanes).  The
 // prediction is a running mean of the slot's thresholds (narrow rows vary more from one to
 // the next than wide ones); a wavefront's first group predicts from a sample of each row.
 // Rows whose window misses gallop away from it and are then bracketed by bisection over the
-// window positions, in lock step for the four rows.
+// window positions, in lock step for the rows of the group.
 #pragma once
 
 #include "dct_common.hpp"
@@ -39,56 +40,83 @@ using fast::wave_lds_fence;
 // spread over all CUs, are as fast or faster).
 constexpr int kWavesSmall = 4;
 constexpr int kWavesLarge = 16;
-constexpr int kRows = 4;               // rows per wavefront
-constexpr int kLanes = kWave / kRows;  // lanes per row: one DPP row
+constexpr int kRows = 4;               // rows per wavefront: one DPP row of 16 lanes each ...
+constexpr int kRowsNarrow = 8;         // ... or, for rows of up to 256 columns, half a DPP row each
 constexpr uint32_t kMaxD = 1024;
-constexpr uint32_t kStageSlots = kWave * 8;  // survivor columns of the four rows: 4 k <= kStageSlots
+constexpr uint32_t kMaxDNarrow = 256;    // (eight rows of 512 columns, 14 wavefronts per CU for the LDS: 152 us against 135)
+constexpr uint32_t kStageSlots = kWave * 8;  // survivor columns of a group's rows: rows * k <= kStageSlots
 // Width of the prediction window in key values.  The threshold of a narrow row moves more from row to row
 // (the standard deviation of the k-th largest of D keys grows like 1/sqrt(D): about 17 key values at D = 256,
 // 12 at 512, 8 at 1024 for 5 % of post-ReLU normal values), and a window that misses costs a gallop and a
 // bisection for the whole group of four rows; a wider window costs more keys to histogram.  Measured on 512 MiB
 // of rows: D = 256 229 -> 206 us with 128 key values (192 us with the second compare sweep in place of the
 // remembered bins), D = 512 153 -> 134 us with 64; D = 1024 is better off with 32 (145 us against 150 with 64).
-template <int NV>
-constexpr uint32_t window_width() {
-  return NV <= 2 ? 128u : NV == 4 ? 64u : 32u;
+constexpr uint32_t window_width(int row_cols) {
+  return row_cols <= 256 ? 128u : row_cols <= 512 ? 64u : 32u;
 }
 
-// Sum over the 16 lanes of a DPP row, delivered to every lane of the row.
+// The reductions and scans of a row: LANES = 16 (a DPP row) or 8 (half a DPP row) neighbouring lanes.
+// Sum over the lanes of a row, delivered to every lane of the row.
+template <int LANES>
 __device__ __forceinline__ uint32_t row_sum(uint32_t x) {
   uint32_t v = x;
   v += __builtin_amdgcn_update_dpp(0u, v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
   v += __builtin_amdgcn_update_dpp(0u, v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
   v += __builtin_amdgcn_update_dpp(0u, v, 0x141, 0xf, 0xf, false);  // row_half_mirror
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x140, 0xf, 0xf, false);  // row_mirror
+  if constexpr (LANES == 16) v += __builtin_amdgcn_update_dpp(0u, v, 0x140, 0xf, 0xf, false);  // row_mirror
   return v;
 }
-// Inclusive prefix sum over the lanes of a DPP row (lower lanes first).
-__device__ __forceinline__ uint32_t row_incl_scan(uint32_t x) {
+// Inclusive prefix sum over the lanes of a row (lower lanes first); s = this lane's number in its row.  The DPP
+// shifts run over the 16 lanes of a DPP row: with 8-lane rows a lane drops what comes from the other half.
+template <int LANES>
+__device__ __forceinline__ uint32_t row_incl_scan(uint32_t x, uint32_t s) {
   uint32_t v = x;
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  if constexpr (LANES == 16) {
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  } else {
+    uint32_t t = __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);
+    v += s >= 1u ? t : 0u;
+    t = __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);
+    v += s >= 2u ? t : 0u;
+    t = __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);
+    v += s >= 4u ? t : 0u;
+  }
   return v;
 }
-// Inclusive suffix sum over the lanes of a DPP row (this lane and the higher ones).
-__device__ __forceinline__ uint32_t row_suffix_scan(uint32_t x) {
+// Inclusive suffix sum over the lanes of a row (this lane and the higher ones).
+template <int LANES>
+__device__ __forceinline__ uint32_t row_suffix_scan(uint32_t x, uint32_t s) {
   uint32_t v = x;
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x101, 0xf, 0xf, false);  // row_shl:1
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x102, 0xf, 0xf, false);  // row_shl:2
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x104, 0xf, 0xf, false);  // row_shl:4
-  v += __builtin_amdgcn_update_dpp(0u, v, 0x108, 0xf, 0xf, false);  // row_shl:8
+  if constexpr (LANES == 16) {
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x101, 0xf, 0xf, false);  // row_shl:1
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x102, 0xf, 0xf, false);  // row_shl:2
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x104, 0xf, 0xf, false);  // row_shl:4
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x108, 0xf, 0xf, false);  // row_shl:8
+  } else {
+    uint32_t t = __builtin_amdgcn_update_dpp(0u, v, 0x101, 0xf, 0xf, false);
+    v += s < 7u ? t : 0u;
+    t = __builtin_amdgcn_update_dpp(0u, v, 0x102, 0xf, 0xf, false);
+    v += s < 6u ? t : 0u;
+    t = __builtin_amdgcn_update_dpp(0u, v, 0x104, 0xf, 0xf, false);
+    v += s < 4u ? t : 0u;
+  }
   return v;
 }
-// The 16 ballot bits of this lane's row.
+// The ballot bits of this lane's row.
+template <int LANES>
 __device__ __forceinline__ uint32_t row_ballot(bool p, uint32_t lane) {
-  return static_cast<uint32_t>(ballot64(p) >> (lane & 48u)) & 0xFFFFu;
+  return static_cast<uint32_t>(ballot64(p) >> (lane & (64u - LANES))) & ((1u << LANES) - 1u);
 }
 
-// NV = 16-byte vectors per lane: a lane owns NV * 8 contiguous columns, a row 16 * NV * 8.
+// NV = 16-byte vectors per lane: a lane owns NV * 8 contiguous columns, a row (64 / ROWS) * NV * 8.
 // ENC (RowEnc): how the mask is written (32- or 16-bit column indices, or a bitmap of ceil(D/32) words per row).
-template <int NV, int ENC, int WAVES>
+// ROWS = rows per wavefront, 4 or 8.  The work that does not depend on the row's width (scans, the loops over
+// window keys and survivors, the output code) is paid per group: eight rows of 256 columns per wavefront cost
+// about what four rows of 512 do (512 MiB of 256-column rows: 192 -> 156 us).
+template <int NV, int ENC, int WAVES, int ROWS>
 __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
     const uint16_t* __restrict__ x, uint32_t B, uint32_t D, uint64_t stride, uint32_t k, void* __restrict__ idx_out,
     uint16_t* __restrict__ val_out, uint16_t* __restrict__ tau_out) {
@@ -101,7 +129,10 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
   constexpr int kColsPerWord = 2 * RPW;
   constexpr int wB = WORDS - 1;
   constexpr int kWaves = WAVES;
-  constexpr uint32_t kWindow = window_width<NV>();
+  constexpr int kRows = ROWS;
+  constexpr int kLanes = kWave / kRows;  // lanes per row
+  static_assert(ROWS == 4 || ROWS == 8, "a row is a DPP row of 16 lanes or half of one");
+  constexpr uint32_t kWindow = window_width(NV * 8 * kLanes);
   constexpr int kBinBits = kWindow == 128 ? 7 : kWindow == 64 ? 6 : 5;
   constexpr int kBinsPerLane = kWindow / kLanes;  // lane s of a row scans bins [s * kBinsPerLane, ...)
   constexpr int kListMax = 32 / kBinBits;         // window keys a stream remembers (bin numbers in one register)
@@ -210,7 +241,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
       uint32_t acc = 0;
 #pragma unroll
       for (int i = 0; i < REGS; ++i) acc = pk_add_u16(acc, pk_lshr15_u16(pk_sub_u16(K[i], t2)));
-      return row_sum((acc & 0xFFFFu) + (acc >> 16));
+      return row_sum<kLanes>((acc & 0xFFFFu) + (acc >> 16));
     };
     // two independent bit streams per step (see the wide kernel)
     auto pop2 = [&](uint32_t& mA, uint32_t& mB, bool& vA, uint32_t& cA, bool& vB, uint32_t& cB) {
@@ -243,7 +274,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
         ca += __popc(above[w]);
         cw += __popc(inwin[w]);
       }
-      const uint32_t both = row_sum(ca | (cw << 16));  // each count is at most 1024
+      const uint32_t both = row_sum<kLanes>(ca | (cw << 16));  // each count is at most 1024
       n_above = both & 0xFFFFu;
       n_win = both >> 16;
     };
@@ -258,7 +289,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
         uint32_t acc = 0;
 #pragma unroll
         for (int i = 0; i < kSampleRegs; ++i) acc = pk_add_u16(acc, pk_lshr15_u16(pk_sub_u16(K[i], t2)));
-        if (row_sum((acc & 0xFFFFu) + (acc >> 16)) >= ks) t = cand;
+        if (row_sum<kLanes>((acc & 0xFFFFu) + (acc >> 16)) >= ks) t = cand;
       }
       guess = t;
     }
@@ -318,7 +349,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
     wave_lds_fence();
     // Lanes with few key registers (rows of up to 256 columns) compare them with tau once more at the end;
     // the others remember the bins of their window keys per stream, so that the second walk needs no LDS reads.
-    constexpr bool kSweepAgain = REGS <= 8;
+    constexpr bool kSweepAgain = REGS <= 8 || ROWS == 8;
     [[maybe_unused]] uint32_t listA = 0, listB = 0;
     [[maybe_unused]] bool list_full = false;
     [[maybe_unused]] uint32_t n_pops = 0;
@@ -368,8 +399,8 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
     uint32_t lane_sum = 0;
 #pragma unroll
     for (int j = 0; j < kBinsPerLane; ++j) lane_sum += cb[j];
-    const uint32_t suf = row_suffix_scan(lane_sum);  // window keys in this lane's bins and above
-    const uint32_t m_reach = row_ballot(n_above + suf >= k, lane);  // non-empty: lane 0 reaches n_above + n_win >= k
+    const uint32_t suf = row_suffix_scan<kLanes>(lane_sum, s);  // window keys in this lane's bins and above
+    const uint32_t m_reach = row_ballot<kLanes>(n_above + suf >= k, lane);  // non-empty: lane 0 reaches n_above + n_win >= k
     // walk this lane's bins from the top: the first one at which the count reaches k
     uint32_t acc = n_above + suf - lane_sum, loc = 0;
     bool found = false;
@@ -381,7 +412,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
         loc = (s * kBinsPerLane + j) | (cb[j] << 8) | ((acc - n_above) << 20);  // bin, ties, window keys at or above
       }
     }
-    const int src = static_cast<int>((lane & 48u) | (31u - __builtin_clz(m_reach | 1u)));
+    const int src = static_cast<int>((lane & (64u - kLanes)) | (31u - __builtin_clz(m_reach | 1u)));
     loc = __shfl(loc, src, kWave);
     const uint32_t bstar = loc & 0xFFu;
     const uint32_t n_eq = (loc >> 8) & 0xFFFu;
@@ -449,7 +480,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
       for (int w = 0; w < WORDS; ++w) tc += __popc(tie[w]);
       const bool trim = quota < n_eq;  // per row
       if (ballot64(trim) != 0) {
-        const uint32_t before = row_incl_scan(tc) - tc;               // ties in lower lanes of the row
+        const uint32_t before = row_incl_scan<kLanes>(tc, s) - tc;               // ties in lower lanes of the row
         const uint32_t allowed = quota > before ? quota - before : 0u;  // ties this lane may keep
         if (trim) {
           // lanes below the boundary keep all their ties, lanes above it none; the one lane on the
@@ -474,7 +505,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
     uint32_t kc = 0;
 #pragma unroll
     for (int w = 0; w < WORDS; ++w) kc += __popc(keep[w]);
-    const uint32_t slot = row_incl_scan(kc) - kc;
+    const uint32_t slot = row_incl_scan<kLanes>(kc, s) - kc;
     if constexpr (ENC == kEncBitmap) {
       // the per-lane bitmaps ARE the mask: COLS bits per lane, packed into the row's 32-bit words
       const uint32_t n_words = (D + 31) / 32;
@@ -521,7 +552,9 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
 #pragma unroll
         for (int j = 0; j < G; ++j) {
           const uint32_t e = j * kWave + lane;
-          const uint32_t r = (e >= k ? 1u : 0u) + (e >= 2u * k ? 1u : 0u) + (e >= 3u * k ? 1u : 0u);
+          uint32_t r = 0;
+#pragma unroll
+          for (uint32_t m = 1; m < static_cast<uint32_t>(kRows); ++m) r += e >= m * k ? 1u : 0u;
           raw[j] = raw_at(r, col[j]);
         }
 #pragma unroll
@@ -555,7 +588,9 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
       } else {
         for (uint32_t e = lane; e < n_out; e += kWave) {
           const uint32_t col = *stage_at(e);
-          const uint32_t r = (e >= k ? 1u : 0u) + (e >= 2u * k ? 1u : 0u) + (e >= 3u * k ? 1u : 0u);
+          uint32_t r = 0;
+#pragma unroll
+          for (uint32_t m = 1; m < static_cast<uint32_t>(kRows); ++m) r += e >= m * k ? 1u : 0u;
           put_col<ENC>(idx_out, row0 * k + e, col);
           val_out[row0 * k + e] = static_cast<uint16_t>(raw_at(r, col));
         }

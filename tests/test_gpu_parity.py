@@ -1019,7 +1019,10 @@ def test_mp_bf16_wide_rows(dct, B, D, k, enc):
     (8192, 1024, 1, 0, False), (8194, 520, 100, 16, True),
     # 64 k rows and more: one workgroup of 16 wavefronts per CU takes the groups from a counter
     (65536, 256, 12, 0, False), (65539, 512, 25, 0, True), (70_001, 1024, 51, 0, False), (131_075, 64, 3, 0, False),
-    (65_537, 264, 13, 8, False)])
+    (65_537, 264, 13, 8, False),
+    # rows of up to 256 columns, 128 k rows and more: eight rows per wavefront
+    (131_083, 256, 12, 0, False), (140_001, 128, 6, 0, True), (131_073, 200, 64, 0, False),
+    (131_077, 256, 13, 8, True), (131_072, 8, 3, 0, False), (131_079, 256, 1, 0, False)])
 def test_mp_many_narrow_rows(dct, B, D, k, pad, idx16):
     x = si.relu_activations(B, D, DEV, 1900 + D + k, dtype=torch.bfloat16, row_stride=D + pad if pad else None)
     # hard rows among the ordinary ones, spread over the slots of a group of four: all equal, all zero, two
@@ -1050,7 +1053,8 @@ def test_mp_many_narrow_rows(dct, B, D, k, pad, idx16):
 
 
 @pytest.mark.parametrize("B,D,k", [(8192, 256, 12), (8199, 64, 5), (8193, 128, 9), (9000, 1024, 51), (8192, 520, 26),
-                                   (65541, 256, 12), (66000, 1024, 51)])
+                                   (65541, 256, 12), (66000, 1024, 51), (131_079, 256, 12), (131_075, 128, 9),
+                                   (131_073, 72, 5)])
 def test_mp_many_narrow_rows_bitmask(dct, B, D, k):
     x = si.relu_activations(B, D, DEV, 1950 + D, dtype=torch.bfloat16)
     x[3] = 0.5
