@@ -47,11 +47,17 @@ constexpr uint32_t kMaxDNarrow = 256;    // (eight rows of 512 columns, 14 wavef
 constexpr uint32_t kStageSlots = kWave * 8;  // survivor columns of a group's rows: rows * k <= kStageSlots
 // Width of the prediction window in key values.  The threshold of a narrow row moves more from row to row
 // (the standard deviation of the k-th largest of D keys grows like 1/sqrt(D): about 17 key values at D = 256,
-// 12 at 512, 8 at 1024 for 5 % of post-ReLU normal values), and a window that misses costs a gallop and a
-// bisection for the whole group of four rows; a wider window costs more keys to histogram.  Measured on 512 MiB
-// of rows: D = 256 229 -> 206 us with 128 key values (192 us with the second compare sweep in place of the
-// remembered bins), D = 512 153 -> 134 us with 64; D = 1024 is better off with 32 (145 us against 150 with 64).
-constexpr uint32_t window_width(int row_cols) {
+// 12 at 512, 8 at 1024 for 5 % of post-ReLU normal values).  A window that misses costs the whole group a
+// gallop and a bisection with a count sweep each plus a second pair of bitmaps; a wider window costs more keys
+// to histogram.  Lanes with 16 or more key registers first try the NEIGHBOURING window after a miss (one sweep:
+// it shares an end with the failed one), which makes a narrow window affordable again.  Measured on 512 MiB of
+// rows, four rows per wavefront: D = 256 229 -> 206 us with 128 key values instead of 32 (192 us with the second
+// compare sweep in place of the remembered bins); D = 512 153 -> 134 us with 64, 128 us with 32 and the
+// neighbour step; D = 1024 (32 key values) 126 -> 117 us with the neighbour step, 150 us with 64 and without.
+// Eight rows of 256 columns per wavefront: 156 us with 128 key values, 146 us with 64 and the neighbour step
+// (32: the same).
+constexpr uint32_t window_width(int row_cols, int regs) {
+  if (regs >= 16) return row_cols <= 256 ? 64u : 32u;  // a near miss is cheap there (the neighbouring window)
   return row_cols <= 256 ? 128u : row_cols <= 512 ? 64u : 32u;
 }
 
@@ -132,7 +138,7 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
   constexpr int kRows = ROWS;
   constexpr int kLanes = kWave / kRows;  // lanes per row
   static_assert(ROWS == 4 || ROWS == 8, "a row is a DPP row of 16 lanes or half of one");
-  constexpr uint32_t kWindow = window_width(NV * 8 * kLanes);
+  constexpr uint32_t kWindow = window_width(NV * 8 * kLanes, REGS);
   constexpr int kBinBits = kWindow == 128 ? 7 : kWindow == 64 ? 6 : 5;
   constexpr int kBinsPerLane = kWindow / kLanes;  // lane s of a row scans bins [s * kBinsPerLane, ...)
   constexpr int kListMax = 32 / kBinBits;         // window keys a stream remembers (bin numbers in one register)
@@ -300,6 +306,43 @@ __global__ __launch_bounds__(WAVES * kWave) void rowtopk_fwd_quad_kernel(
       window_at(lo_end);
     }
     bool hit = have && n_above < k && k <= n_above + n_win;
+    if (REGS >= 16 && ballot64(have && !hit) != 0) {
+      // Most misses are near misses: try the neighbouring window first.  It shares an end with the failed one, so
+      // one compare sweep (at its far end) and one count suffice; rows that hit keep what they have.  (Worth it
+      // for long lanes only, where the general path's count sweeps and second pair of bitmaps are expensive.)
+      const bool up = n_above >= k;
+      const bool can = have && !hit && (up ? wlo + 2u * kWindow <= 0x8000u : wlo >= kWindow);
+      uint32_t far[WORDS];
+      ge_bitmap(up ? wlo + 2u * kWindow : wlo - kWindow, far);
+      uint32_t cf = 0;
+#pragma unroll
+      for (int w = 0; w < WORDS; ++w) cf += __popc(far[w]);
+      const uint32_t n_far = row_sum<kLanes>(cf);  // keys at or above the neighbour's far end
+      if (can) {
+        if (up) {  // [wlo + W, wlo + 2 W): its lower end is the old upper end
+          n_win = n_above - n_far;
+          n_above = n_far;
+#pragma unroll
+          for (int w = 0; w < WORDS; ++w) {
+            inwin[w] = above[w] & ~far[w];
+            above[w] = far[w];
+          }
+          wlo += kWindow;
+        } else {   // [wlo - W, wlo): its upper end is the old lower end
+          const uint32_t n_lo_old = n_above + n_win;
+          n_win = n_far - n_lo_old;
+          n_above = n_lo_old;
+#pragma unroll
+          for (int w = 0; w < WORDS; ++w) {
+            const uint32_t lo_old = above[w] | inwin[w];
+            inwin[w] = far[w] & ~lo_old;
+            above[w] = lo_old;
+          }
+          wlo -= kWindow;
+        }
+        hit = n_above < k && k <= n_above + n_win;
+      }
+    }
     if (ballot64(!hit) != 0) {
       // Brackets in units of the window width, per row: count_ge(lo_u * width) >= k > count_ge(hi_u * width).
       // Rows that hit take no part (their bracket is closed from the start).  Every count is taken by all
