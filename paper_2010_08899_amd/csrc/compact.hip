@@ -410,21 +410,30 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
     wave_e = 0;
 
     // up to NE elements per lane: raw[e], validity, index of element 0
-    auto emit = [&](const uint32_t* raw, bool in, uint32_t index0, auto nelem_tag) {
+    auto emit = [&](const uint32_t* raw, bool in, uint32_t index0, auto nelem_tag, const uint4* packed = nullptr) {
       constexpr int NE = decltype(nelem_tag)::value;
+      constexpr bool kPacked = DT == DCT_BF16 && NE == 8;  // whole bf16 vectors: packed compares (`packed`)
       // Cheap common case first: one compare per element against tau (keys >= tau are the
       // survivors and, in exactly-k mode, the ties), collected in a per-lane bitmap; most rows
       // have none.
       uint32_t ge_bits = 0;
+      if constexpr (kPacked) {
+        ge_bits = bf16x8_ge_bits(*packed, tau);
+      } else {
 #pragma unroll
-      for (int e = 0; e < NE; ++e) ge_bits |= (raw[e] & E::kKeyMask) >= tau ? (1u << e) : 0u;
+        for (int e = 0; e < NE; ++e) ge_bits |= (raw[e] & E::kKeyMask) >= tau ? (1u << e) : 0u;
+      }
       if (!in) ge_bits = 0;
       const uint64_t m_any = ballot64(ge_bits != 0);
       if (m_any == 0) return;
       uint32_t e_bits = 0;
       if constexpr (EXACT) {
+        if constexpr (kPacked) {
+          e_bits = ~bf16x8_ge_bits(*packed, tau + 1u);  // (tau + 1 may be 0x8000: nothing is at or above it)
+        } else {
 #pragma unroll
-        for (int e = 0; e < NE; ++e) e_bits |= (raw[e] & E::kKeyMask) == tau ? (1u << e) : 0u;
+          for (int e = 0; e < NE; ++e) e_bits |= (raw[e] & E::kKeyMask) == tau ? (1u << e) : 0u;
+        }
         e_bits &= ge_bits;
       }
       const uint32_t a_bits = ge_bits & ~e_bits;
@@ -541,7 +550,7 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
             raw[e] = __float_as_uint(__uint_as_float(raw[e]) + __uint_as_float(E::raw(buf.b[r], e)));
           if (in) st_stream(&wv[vi], raw[0], raw[1], raw[2], raw[3]);
         }
-        emit(raw, in, geo.head + vi * V, std::integral_constant<int, V>{});
+        emit(raw, in, geo.head + vi * V, std::integral_constant<int, V>{}, &buf.a[r]);
       }
       if (p == geo.pieces - 1 && geo.tail != 0) {
         const bool in = lane < geo.tail;

@@ -41,6 +41,21 @@ struct Elem<DCT_BF16> {
   }
 };
 
+// bf16: which of the eight keys of a 16-byte vector are >= t (t <= 0x8000), as bits in element order.  The keys
+// are compared two at a time: with bit 15 of each half set (which also clears the sign), a packed 16-bit subtract
+// of t leaves that bit standing exactly where key >= t; the low halves' bits are gathered on even positions, the
+// high halves' 15 bits above them.
+__device__ __forceinline__ uint32_t bf16x8_ge_bits(const uint4& v, uint32_t t) {
+  typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+  const uint32_t t2 = t * 0x00010001u;
+  auto flags = [&](uint32_t w) {
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, w | 0x80008000u) - __builtin_bit_cast(u16x2, t2)) &
+           0x80008000u;
+  };
+  const uint32_t x = (flags(v.x) >> 15) | (flags(v.y) >> 13) | (flags(v.z) >> 11) | (flags(v.w) >> 9);
+  return (x | (x >> 15)) & 0xFFu;
+}
+
 __device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
 
 // Number of set bits of `m` in lanes below the calling lane.

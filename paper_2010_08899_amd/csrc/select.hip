@@ -366,18 +366,27 @@ __global__ __launch_bounds__(kPartThreads) void select_partition_kernel(
     staged = 0;
   };
   // NE keys per lane
-  auto take = [&](const uint32_t* raw, bool in, auto ne_tag) {
+  auto take = [&](const uint32_t* raw, bool in, auto ne_tag, const uint4* packed = nullptr) {
     constexpr int NE = decltype(ne_tag)::value;
+    constexpr bool kPacked = DT == DCT_BF16 && NE == 8;  // whole bf16 vectors: packed compares (`packed`)
     // one compare per element in the common case: keys >= lo are rare (per-lane bitmap)
     uint32_t ge_bits = 0;
+    if constexpr (kPacked) {
+      ge_bits = bf16x8_ge_bits(*packed, lo);
+    } else {
 #pragma unroll
-    for (int e = 0; e < NE; ++e) ge_bits |= (raw[e] & E::kKeyMask) >= lo ? (1u << e) : 0u;
+      for (int e = 0; e < NE; ++e) ge_bits |= (raw[e] & E::kKeyMask) >= lo ? (1u << e) : 0u;
+    }
     if (!in) ge_bits = 0;
     const uint64_t m_any = ballot64(ge_bits != 0);
     if (m_any == 0) return;
     uint32_t hi_bits = 0;
+    if constexpr (kPacked) {
+      hi_bits = bf16x8_ge_bits(*packed, hi + 1u);  // hi <= 0x7FFF
+    } else {
 #pragma unroll
-    for (int e = 0; e < NE; ++e) hi_bits |= (raw[e] & E::kKeyMask) > hi ? (1u << e) : 0u;
+      for (int e = 0; e < NE; ++e) hi_bits |= (raw[e] & E::kKeyMask) > hi ? (1u << e) : 0u;
+    }
     hi_bits &= ge_bits;
     const uint32_t c_bits = ge_bits & ~hi_bits;  // candidates: lo <= key <= hi
     // counts of the row and the candidates in lower lanes: a ballot when no lane holds two
@@ -470,7 +479,7 @@ __global__ __launch_bounds__(kPartThreads) void select_partition_kernel(
       uint32_t raw[V];
 #pragma unroll
       for (int i = 0; i < V; ++i) raw[i] = E::raw(v, i);
-      take(raw, full || vec0 + r * kWave < geo.n_vec, std::integral_constant<int, V>{});
+      take(raw, full || vec0 + r * kWave < geo.n_vec, std::integral_constant<int, V>{}, &v);
     }
   };
   {
