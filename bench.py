@@ -356,16 +356,24 @@ def main():
             valn = torch.zeros(Bn, kn, dtype=torch.bfloat16, device=dev)
             dvaln = torch.zeros_like(valn)
             outn = torch.empty_like(xn[0])
-            uf = time_calls(lambda i: dct.dct_rowtopk_fwd(xn[i & 1], kn, idxn, valn, None), 10)
+            uf = time_calls(lambda i: dct.dct_rowtopk_fwd(xn[i & 1], kn, idxn, valn, None), 30)
             ub = time_calls(lambda i: dct.dct_rowtopk_bwd(xn[i & 1], idxn, dvaln), 10)
             us_ = time_calls(lambda i: dct.dct_rowtopk_scatter(idxn, valn, outn), 10)
             fb = Bn * Dn * 2 + Bn * kn * 6
+            # the same traffic and nothing else: four rows (one group of the narrow-row kernel) read by a wavefront,
+            # their outputs' bytes written
+            chunk = 4 * Dn * 2
+            out_b = (4 * kn * 6 + 15) // 16 * 16
+            snk = torch.zeros(16384, dtype=torch.uint8, device=dev)
+            dstn = torch.empty((Bn // 4) * out_b + 16, dtype=torch.uint8, device=dev)
+            ut = time_calls(lambda i: bench_probes.probe_rows(xn[i & 1].view(torch.uint8).reshape(-1), chunk, dstn, out_b, snk), 10)
             narrow.append({"B": Bn, "D": Dn, "k": kn, "dtype": "bf16", "fwd_us": round(uf, 1),
                            "fwd_frac_of_hbm_peak": round(fb / (uf * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                           "traffic_only_us": round(ut, 1), "fwd_frac_of_traffic_only": round(ut / uf, 4),
                            "bwd_us": round(ub, 1), "scatter_us": round(us_, 1)})
-            log(f"[bench] MP {Bn}x{Dn} bf16 k={kn}: fwd {uf:.1f} us ({narrow[-1]['fwd_frac_of_hbm_peak'] * 100:.1f}% of peak), "
-                f"bwd {ub:.1f} us, scatter {us_:.1f} us")
-            del xn, idxn, valn, dvaln, outn
+            log(f"[bench] MP {Bn}x{Dn} bf16 k={kn}: fwd {uf:.1f} us ({narrow[-1]['fwd_frac_of_hbm_peak'] * 100:.1f}% of peak, "
+                f"traffic only {ut:.1f} us), bwd {ub:.1f} us, scatter {us_:.1f} us")
+            del xn, idxn, valn, dvaln, outn, dstn
 
     # ------------------------------------------------------------ many small tensors per call (not part of the step)
     # 24 tensors from 64 to 2^20 elements (the largest is c1-sized), 1 % kept: one batched select +
@@ -508,6 +516,9 @@ def main():
     # the forward call against a kernel that only moves its bytes (probes: rows_c5_read_write_us)
     roofline["fwd_c5_traffic_only_us"] = probes["rows_c5_read_write_us"]
     roofline["fwd_c5_frac_of_traffic_only"] = round(probes["rows_c5_read_write_us"] / by_name["dct_rowtopk_fwd[c5]"]["us"], 4)
+    for w in narrow:  # the paper's MP widths, flat as well
+        roofline[f"fwd_d{w['D']}_us"] = w["fwd_us"]
+        roofline[f"fwd_d{w['D']}_frac"] = w["fwd_frac_of_hbm_peak"]
     for c in calls[:4] + ef_calls + rx_calls + bm_calls + i16_calls:
         c["traffic"] = measured_traffic(c["call"], table) if with_traffic else None
 
@@ -599,8 +610,8 @@ def main():
     for c in calls + small_calls:
         log(f"[bench] {c['call']}: {c['us']} us {c['frac_of_hbm_peak']:.3f} {c['elements_per_s']:.3g}")
     for w in narrow:
-        log(f"[bench] MP bf16 D={w['D']} k={w['k']} B={w['B']}: fwd {w['fwd_us']} us {w['fwd_frac_of_hbm_peak']:.3f}, "
-            f"bwd {w['bwd_us']} us, scatter {w['scatter_us']} us")
+        log(f"[bench] MP bf16 D={w['D']} k={w['k']} B={w['B']}: fwd {w['fwd_us']} us {w['fwd_frac_of_hbm_peak']:.3f} "
+            f"(traffic only {w['traffic_only_us']} us), bwd {w['bwd_us']} us, scatter {w['scatter_us']} us")
     log(f"[bench] step {ms_per_step:.4f} ms = {value:.4g} elements/s; probes {probes}")
     if cpu:
         log(f"[bench] cpu oracle: 1 core {cpu['value']:.3g} el/s; {cpu['all_cores']} cores {cpu['all_cores_value']:.3g} el/s "
