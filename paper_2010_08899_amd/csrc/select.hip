@@ -154,7 +154,7 @@ static_assert(kSelClearWords <= kSampleSize, "the sample grid also clears the wo
 template <int DT, bool EF>
 __global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
     const typename Elem<DT>::word_t* __restrict__ g, const typename Elem<DT>::word_t* __restrict__ e, uint32_t n,
-    uint32_t k, SelWs* ws, uint32_t cand_cap, uint32_t tag, uint32_t spin_limit) {
+    uint32_t rank_hi, uint32_t rank_lo, SelWs* ws, uint32_t cand_cap, uint32_t tag, uint32_t spin_limit) {
   using E = Elem<DT>;
   constexpr int KPT = kSampleSize / kSampleThreads;  // keys per thread of workgroup 0 = workgroups of the grid
   __shared__ uint32_t s_hist[2 * kSelBins];
@@ -177,6 +177,9 @@ __global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
   uint32_t keys[KPT];
   {
     bool complete = false;  // uniform
+    // The other workgroups' words are on their way for as long as this workgroup's own were: a first look at
+    // once would find some missing and cost a whole round of 16 loads per thread.
+    __builtin_amdgcn_s_sleep(24);
     for (uint32_t spins = 0; !complete && spins <= spin_limit; ++spins) {
       // (tt: the thread's index, opaque to the compiler, which would otherwise keep every address in
       // registers across the iterations of this loop; and all loads first, then their uses: the loads are
@@ -206,18 +209,8 @@ __global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
     }
   }
 
-  // sample ranks (1-based from the top) that bracket rank k of the vector with a
-  // margin of five standard deviations of the sample count (binomial: r (S - r) / S), plus slack.
-  // Where that margin reaches past the top of the sample the largest sample key still serves as the upper
-  // bound as long as about 16 sample keys are expected above tau (none at all: e^-16, the risk the five
-  // standard deviations take elsewhere); a bound that does not hold is found out and costs time only.
-  const uint64_t r = static_cast<uint64_t>(k) * kSampleSize / n;
-  const uint64_t var = r * (kSampleSize - r) / kSampleSize;
-  uint32_t sq = 0;
-  while (static_cast<uint64_t>(sq + 1) * (sq + 1) <= var) ++sq;
-  const uint64_t delta = 5ull * (sq + 1) + 8;
-  const uint64_t rank_hi = r > delta ? r - delta : (r >= 16 ? 1 : 0);     // 0: no upper bound
-  const uint64_t rank_lo = r + delta + 1 <= kSampleSize ? r + delta + 1 : 0;  // 0: no lower bound
+  // rank_hi, rank_lo: the sample ranks (1-based from the top) that bracket rank k of the vector, from the host
+  // (sample_ranks); 0 = no bound on that side.
 
   // Both order statistics are searched together: while their fixed digits agree
   // (the usual case until the last pass) one histogram serves both.
@@ -234,15 +227,37 @@ __global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
     for (uint32_t i = t; i < 2 * kSelBins; i += kSampleThreads) s_hist[i] = 0;
     __syncthreads();
     const bool one_hist = shared || rank[0] == 0 || rank[1] == 0;  // uniform
+    if (p == 0) {
+      // first pass: every key takes part, so the lanes that share lane 0's digit (a mostly zero gradient: all of
+      // them) are counted with one ballot and one add, without the search for a leader
 #pragma unroll
-    for (int j = 0; j < KPT; ++j) {
-      const uint32_t key = keys[j];
-      const uint32_t digit = (key >> shift) & dmask;
-      if (one_hist) {
-        hist_add(s_hist, (key & fixed_mask) == prefix[rank[0] != 0 ? 0 : 1], digit);
-      } else {
-        hist_add(s_hist, (key & fixed_mask) == prefix[0], digit);
-        hist_add(s_hist + kSelBins, (key & fixed_mask) == prefix[1], digit);
+      for (int j = 0; j < KPT; ++j) {
+        const uint32_t digit = (keys[j] >> shift) & dmask;
+        const uint32_t d0 = __builtin_amdgcn_readfirstlane(digit);
+        const uint64_t m = ballot64(digit == d0);
+        if (lane_id() == 0) atomicAdd(&s_hist[d0], static_cast<uint32_t>(__popcll(m)));
+        if (digit != d0) atomicAdd(&s_hist[digit], 1u);
+        if (!one_hist) {
+          if (lane_id() == 0) atomicAdd(&s_hist[kSelBins + d0], static_cast<uint32_t>(__popcll(m)));
+          if (digit != d0) atomicAdd(&s_hist[kSelBins + digit], 1u);
+        }
+      }
+    } else {
+      // later passes: only the keys of the one or two bins that are followed take part, and most wavefronts hold
+      // none: which of a thread's keys do is collected first
+      uint32_t act0 = 0, act1 = 0;
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        act0 |= (keys[j] & fixed_mask) == prefix[one_hist && rank[0] == 0 ? 1 : 0] ? (1u << j) : 0u;
+        if (!one_hist) act1 |= (keys[j] & fixed_mask) == prefix[1] ? (1u << j) : 0u;
+      }
+      if (ballot64((act0 | act1) != 0) != 0) {
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+          const uint32_t digit = (keys[j] >> shift) & dmask;
+          hist_add(s_hist, (act0 >> j) & 1u, digit);  // (returns at once when no lane takes part)
+          if (!one_hist) hist_add(s_hist + kSelBins, (act1 >> j) & 1u, digit);
+        }
       }
     }
     __syncthreads();
@@ -257,16 +272,18 @@ __global__ __launch_bounds__(kSampleThreads) void select_sample_kernel(
         cb[j] = hb[kSelBins - 1 - (t * 2 + j)];
       }
       const uint32_t sa = ca[0] + ca[1], sb = cb[0] + cb[1];
-      const uint32_t ia = wave_prefix_sum(sa), ib = wave_prefix_sum(sb);
+      const uint32_t ia = wave_prefix_sum(sa), ib = one_hist ? ia : wave_prefix_sum(sb);
       if (lane_id() == kWave - 1) {
         s_tmp[t / kWave] = ia;
         s_scan_b[t / kWave] = ib;
       }
       __syncthreads();
       uint32_t above_a = ia - sa, above_b = ib - sb;
-      for (uint32_t w = 0; w < t / kWave; ++w) {
-        above_a += s_tmp[w];
-        above_b += s_scan_b[w];
+      for (uint32_t w = 0; w < t / kWave; ++w) above_a += s_tmp[w];
+      if (one_hist) {
+        above_b = above_a;
+      } else {
+        for (uint32_t w = 0; w < t / kWave; ++w) above_b += s_scan_b[w];
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
@@ -980,7 +997,7 @@ uint32_t cand_capacity(uint64_t n) {
 }
 uint32_t cand_capacity_for(uint64_t n, uint64_t k) {
   if (n < kSampleMinN) return 0u;
-  const uint64_t r = k * kSampleSize / n;  // the same arithmetic as the kernel that brackets the sample
+  const uint64_t r = k * kSampleSize / n;  // the same arithmetic as sample_ranks
   const uint64_t var = r * (kSampleSize - r) / kSampleSize;
   uint64_t sq = 0;
   while ((sq + 1) * (sq + 1) <= var) ++sq;
@@ -988,6 +1005,21 @@ uint32_t cand_capacity_for(uint64_t n, uint64_t k) {
   const uint64_t want = 2 * (n / kSampleSize + 1) * window + 65536;
   const uint64_t rounded = (want + 4u * kCandRegions - 1u) & ~static_cast<uint64_t>(4u * kCandRegions - 1u);
   return static_cast<uint32_t>(std::min<uint64_t>(rounded, cand_capacity(n)));
+}
+
+// Sample ranks (1-based from the top) that bracket rank k of the vector with a margin of five standard
+// deviations of the sample count (binomial: r (S - r) / S), plus slack; 0 = no bound on that side.  Where the
+// margin reaches past the top of the sample the largest sample key still serves as the upper bound as long as
+// about 16 sample keys are expected above tau (none at all: e^-16, the risk the five standard deviations take
+// elsewhere); a bound that does not hold is found out and costs time only.
+void sample_ranks(uint64_t n, uint64_t k, uint32_t& rank_hi, uint32_t& rank_lo) {
+  const uint64_t r = k * kSampleSize / n;
+  const uint64_t var = r * (kSampleSize - r) / kSampleSize;
+  uint64_t sq = 0;
+  while ((sq + 1) * (sq + 1) <= var) ++sq;
+  const uint64_t delta = 5ull * (sq + 1) + 8;
+  rank_hi = static_cast<uint32_t>(r > delta ? r - delta : (r >= 16 ? 1 : 0));
+  rank_lo = static_cast<uint32_t>(r + delta + 1 <= kSampleSize ? r + delta + 1 : 0);
 }
 
 // Tag of a call (see SelWs::sample): unique within the process, starting from a value that differs
@@ -1060,16 +1092,18 @@ int launch_select(const void* g, const void* e, int dt, uint64_t n, uint64_t k, 
     geo.grid = blocks < max_grid ? blocks : max_grid;
     const dim3 sgrid(kSampleSize / kSampleThreads), sblock(kSampleThreads), pgrid(geo.grid), pblock(kPartThreads);
     const uint32_t tag = next_call_tag();
+    uint32_t rank_hi = 0, rank_lo = 0;
+    sample_ranks(n, k, rank_hi, rank_lo);
     if (ef) {
-      hipLaunchKernelGGL((select_sample_kernel<DCT_F32, true>), sgrid, sblock, 0, s, g32, e32, n32, k32, ws, cand_cap, tag, spin_limit);
+      hipLaunchKernelGGL((select_sample_kernel<DCT_F32, true>), sgrid, sblock, 0, s, g32, e32, n32, rank_hi, rank_lo, ws, cand_cap, tag, spin_limit);
       if (large) hipLaunchKernelGGL((select_partition_kernel<DCT_F32, true, kPartRowsLarge>), pgrid, pblock, 0, s, g32, e32, geo, ws);
       else hipLaunchKernelGGL((select_partition_kernel<DCT_F32, true, kPartRowsSmall>), pgrid, pblock, 0, s, g32, e32, geo, ws);
     } else if (dt == DCT_F32) {
-      hipLaunchKernelGGL((select_sample_kernel<DCT_F32, false>), sgrid, sblock, 0, s, g32, nullptr, n32, k32, ws, cand_cap, tag, spin_limit);
+      hipLaunchKernelGGL((select_sample_kernel<DCT_F32, false>), sgrid, sblock, 0, s, g32, nullptr, n32, rank_hi, rank_lo, ws, cand_cap, tag, spin_limit);
       if (large) hipLaunchKernelGGL((select_partition_kernel<DCT_F32, false, kPartRowsLarge>), pgrid, pblock, 0, s, g32, nullptr, geo, ws);
       else hipLaunchKernelGGL((select_partition_kernel<DCT_F32, false, kPartRowsSmall>), pgrid, pblock, 0, s, g32, nullptr, geo, ws);
     } else {
-      hipLaunchKernelGGL((select_sample_kernel<DCT_BF16, false>), sgrid, sblock, 0, s, g16, nullptr, n32, k32, ws, cand_cap, tag, spin_limit);
+      hipLaunchKernelGGL((select_sample_kernel<DCT_BF16, false>), sgrid, sblock, 0, s, g16, nullptr, n32, rank_hi, rank_lo, ws, cand_cap, tag, spin_limit);
       if (large) hipLaunchKernelGGL((select_partition_kernel<DCT_BF16, false, kPartRowsLarge>), pgrid, pblock, 0, s, g16, nullptr, geo, ws);
       else hipLaunchKernelGGL((select_partition_kernel<DCT_BF16, false, kPartRowsSmall>), pgrid, pblock, 0, s, g16, nullptr, geo, ws);
     }
