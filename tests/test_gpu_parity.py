@@ -1052,6 +1052,53 @@ def test_mp_many_narrow_rows(dct, B, D, k, pad, idx16):
     assert np.array_equal(bits(host(tau)), bits(etau))
 
 
+def _hard_rows(kind, B, D, seed):
+    """Rows whose thresholds jump, tie, or sit at the ends of the key range: what the prediction window, its
+    neighbour step, the gallop and the clamps at both ends of the key space have to get right."""
+    gen = torch.Generator(device=DEV).manual_seed(seed)
+    x = torch.randn(B, D, device=DEV, generator=gen)
+    rows = torch.arange(B, device=DEV)
+    if kind == "scales":      # consecutive rows nine orders of magnitude apart
+        sc = torch.where(rows % 3 == 0, 1e-3, torch.where(rows % 3 == 1, 1.0, 3e4))
+        x = torch.relu(x) * sc[:, None]
+    elif kind == "quant":     # few distinct values: ties by the dozen at every threshold
+        x = torch.round(x * 2) / 2
+    elif kind == "tiny":      # denormals: the window is clamped at key 0
+        x = x * 1e-39
+    elif kind == "huge":      # the top of the key range, infinities and NaNs
+        x = x * 1e38
+        x[::7, ::5] = float("inf")
+        x[3::11, 1] = float("nan")
+    elif kind == "drift":     # thresholds drifting over 17 orders of magnitude
+        x = torch.relu(x) * torch.exp(torch.linspace(-20, 20, B, device=DEV))[:, None]
+    return x.to(torch.bfloat16).contiguous()
+
+
+@pytest.mark.parametrize("kind", ["scales", "quant", "tiny", "huge", "drift"])
+@pytest.mark.parametrize("B,D,k,enc", [(131_077, 256, 12, 0), (131_075, 128, 6, 2), (70_001, 512, 25, 0),
+                                       (66_003, 1024, 51, 1), (9_001, 512, 25, 2)])
+def test_mp_narrow_rows_hard_distributions(dct, kind, B, D, k, enc):
+    x = _hard_rows(kind, B, D, 4242 + D + enc)
+    val = torch.zeros(B, k, dtype=torch.bfloat16, device=DEV)
+    tau = torch.zeros(B, dtype=torch.bfloat16, device=DEV)
+    xh = host(x)
+    if enc == 1:
+        mask = torch.full((B, (D + 31) // 32), -1, dtype=torch.int32, device=DEV)
+        dct.dct_rowtopk_fwd_bitmask(x, k, mask, val, tau)
+        emask, eval_, etau = oracle.rowtopk_fwd_bitmask(xh, k)
+        assert np.array_equal(mask.cpu().numpy().view(np.uint32), emask)
+    else:
+        idx = torch.full((B, k), -1, dtype=torch.int16 if enc == 2 else torch.int32, device=DEV)
+        (dct.dct_rowtopk_fwd_idx16 if enc == 2 else dct.dct_rowtopk_fwd)(x, k, idx, val, tau)
+        eidx, eval_, etau = oracle.rowtopk_fwd(xh, k)
+        got = idx.cpu().numpy()
+        got = got.view(np.uint16).astype(np.int32) if enc == 2 else got
+        bad = np.nonzero((got != eidx).any(axis=1))[0]
+        assert bad.size == 0, (bad[:10], got[bad[0]], eidx[bad[0]])
+    assert np.array_equal(bits(host(val).reshape(-1)), bits(np.asarray(eval_).reshape(-1)))
+    assert np.array_equal(bits(host(tau)), bits(np.asarray(etau)))
+
+
 @pytest.mark.parametrize("B,D,k", [(8192, 256, 12), (8199, 64, 5), (8193, 128, 9), (9000, 1024, 51), (8192, 520, 26),
                                    (65541, 256, 12), (66000, 1024, 51), (131_079, 256, 12), (131_075, 128, 9),
                                    (131_073, 72, 5)])
