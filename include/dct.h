@@ -89,7 +89,7 @@ typedef struct {
  *   n          1 .. 2^31-1            k   1 .. n
  *   d_thr_out  device, receives the dct_threshold
  *   d_ws       device workspace, 256-byte aligned; contents on entry are irrelevant, it
- *              is scratch.  About 230 KB of counters, histograms and the key sample,
+ *              is scratch.  About 240 KB of counters, histograms and the key sample,
  *              plus, for n >= 2^22, a buffer for the keys that one pass over the vector
  *              finds between two bounds drawn from the sample.  How many those are
  *              depends on k / n: dct_select_threshold_workspace_bytes_for(dt, n, k) asks
