@@ -61,6 +61,7 @@
 // calls (an epoch word picks the set): every call clears the other set for its
 // successor and the last workgroup advances the epoch, so a call is one launch.
 #include <algorithm>
+#include <cstddef>
 #include <mutex>
 #include <type_traits>
 
@@ -361,11 +362,19 @@ __global__ __launch_bounds__(kCtThreads) void compact_kernel(
   // and leaves it in LDS for the others: a failure flag that is raised while the workgroup starts must not be
   // seen by some of its wavefronts only.  (That wavefront waits a microsecond here; the others stream on.)
   if (threadIdx.x == 0) {
-    s_hdr[0] = ld_agent(&hdr->magic);
-    s_hdr[1] = ld_agent(&hdr->epoch);
-    s_hdr[2] = ld_agent(&hdr->error);
-    s_hdr[3] = ld_agent(&hdr->used[0]);
-    s_hdr[4] = ld_agent(&hdr->used[1]);
+    // (all loads first, then their uses: these are ordered accesses, and a use between two of them makes the
+    // second wait for the first -- five round trips instead of one)
+    static_assert(offsetof(CompactHeader, magic) == 0 && offsetof(CompactHeader, epoch) == 4 &&
+                      offsetof(CompactHeader, error) == 8 && offsetof(CompactHeader, used) == 12,
+                  "the header's first five words are read as two 64-bit words and one of 32 bits");
+    const uint64_t* h64 = reinterpret_cast<const uint64_t*>(hdr);
+    const uint64_t me = ld_agent(h64), eu = ld_agent(h64 + 1);
+    const uint32_t u1 = ld_agent(&hdr->used[1]);
+    s_hdr[0] = static_cast<uint32_t>(me);
+    s_hdr[1] = static_cast<uint32_t>(me >> 32);
+    s_hdr[2] = static_cast<uint32_t>(eu);
+    s_hdr[3] = static_cast<uint32_t>(eu >> 32);
+    s_hdr[4] = u1;
   }
 
   // ---- rounds.  All survivors of a workgroup's chunk wait in LDS until the chunk's place in the output
